@@ -1,0 +1,156 @@
+/*
+ * adadim.h - C ABI of the MI355X (gfx950) AdaDim layer-search library.
+ *
+ * AdaDim (paper Sec. 3.3, Eq. 1; procedure `rtn_ada` in App. B) decides, for
+ * one linear layer, whether group-wise b-bit round-to-nearest quantization
+ * should form its groups inside each output channel (per-OC) or inside each
+ * input channel (per-IC, Sec. 3.2): it quantizes the weight both ways, scores
+ * each by the output reconstruction error on calibration activations and
+ * keeps the lower one.  This library is that search on one GPU.
+ *
+ * Conventions shared by every call
+ *   - W is the layer weight, fp16, row-major [out, in] (torch.nn.Linear
+ *     layout); X are calibration activations, fp16, row-major [tokens, in],
+ *     so the layer output is X W^T (Eq. 1 writes the same product as W X).
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless the
+ *     argument is documented as a host pointer.  The library never frees or
+ *     keeps caller memory.  Internal scratch lives in the context.
+ *   - Calls are asynchronous on the context's HIP stream; results are ready
+ *     when that stream has caught up.  Only adadim_select with a host output
+ *     synchronises.
+ *   - Return value: ADADIM_OK or a negative ADADIM_E* code; the library does
+ *     not throw or abort.  Arguments are validated before any device work, so
+ *     a rejected call has touched nothing.  adadim_last_error gives a text.
+ *   - Inf/NaN in W or X give undefined numbers, not an error.
+ *   - A context may be used from one host thread at a time.
+ */
+#ifndef ADADIM_H
+#define ADADIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADADIM_OK       0
+#define ADADIM_EINVAL  (-1)  /* bad dim/bits/group/clip/shape/leading dimension */
+#define ADADIM_ENULL   (-2)  /* a required pointer is NULL */
+#define ADADIM_EALIGN  (-3)  /* a pointer or row pitch is not aligned as documented */
+#define ADADIM_EHIP    (-4)  /* a HIP runtime call failed; see adadim_last_error */
+
+#define ADADIM_DIM_OC 0      /* groups of `group` consecutive input channels inside an output row */
+#define ADADIM_DIM_IC 1      /* groups of `group` consecutive output channels inside an input column */
+
+#define ADADIM_DW_F32        0  /* dW written / read as fp32 */
+#define ADADIM_DW_F16        1  /* dW written / read as fp16 (round to nearest even) */
+#define ADADIM_DW_F16_SCALED 2  /* fp16 of dW[o,j] * colscale[j]; see adadim_hessian_prepare */
+
+typedef struct adadim_ctx adadim_ctx;
+
+/* Creates a context bound to `hip_stream` (a hipStream_t passed as void*, NULL
+ * = the default stream) on the device that is current at the time of the first
+ * compute call.  Performs no device work itself.  *out receives the context. */
+int adadim_create(adadim_ctx** out, void* hip_stream);
+
+/* Frees the context and its device scratch.  NULL is allowed. */
+void adadim_destroy(adadim_ctx* ctx);
+
+/* Text for the last error recorded on this context (ctx == NULL: the text of
+ * the last error of a failed adadim_create).  Owned by the library. */
+const char* adadim_last_error(const adadim_ctx* ctx);
+
+/* Library version string, e.g. "adadim-gfx950 0.1". Host pointer, static. */
+const char* adadim_version(void);
+
+/*
+ * H (+)= X^T X, the Gram matrix that turns Eq. 1 into a quadratic form:
+ * ||X W^T - X Q(W)^T||_F^2 = tr(dW H dW^T), dW = W - Q(W).
+ *   X      fp16 [tokens, in], row pitch ldx >= in elements; X and ldx*2 must be
+ *          16-byte aligned (EALIGN), in a multiple of 8.
+ *   H      fp32 [in, in], full symmetric storage, 16-byte aligned.
+ *   accumulate  0: H is overwritten; 1: the product is added to H, so a long
+ *          calibration set can be fed in token chunks.
+ * Products are exact (fp16 x fp16), sums are fp32 on the matrix cores.
+ * tokens == 0 with accumulate == 0 zeroes H.
+ */
+int adadim_hessian(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx,
+                   float* H, int accumulate);
+
+/*
+ * Group-wise asymmetric round-to-nearest quantization of W (Sec. 2.1: groups
+ * of consecutive weights inside a channel share parameters; Sec. 3.2: the
+ * channel is an output row for per-OC and an input column for per-IC; Sec. 4.1:
+ * uniform asymmetric).  Per group, in fp32 with one rounding per operation:
+ *     mx = clip*max(max w, 0)   mn = clip*min(min w, 0)
+ *     scale = (mx-mn)/qmax, or 1 if mx == mn        qmax = 2^bits - 1
+ *     zero  = clamp(rint(-mn/scale), 0, qmax)
+ *     code  = clamp(rint(w/scale) + zero, 0, qmax)   (rint: ties to even)
+ *     What  = scale*(code-zero)                      dW = w - What
+ *   W      fp16 [out, in] contiguous, 16-byte aligned if in is a multiple of 8.
+ *   dim    ADADIM_DIM_OC or ADADIM_DIM_IC.   bits in [2, 8].
+ *   group  > 0 and dividing `in` (OC) / `out` (IC); 0 = the whole channel.
+ *   clip   in (0, 1]; 1 is the paper's plain min/max range.
+ * Outputs, each optional (NULL skips it):
+ *   codes  u8  [out, in]
+ *   scales f32 [out, in/g] (OC) or [out/g, in] (IC)
+ *   zeros  u8  same shape as scales
+ *   dW     [out, in] in the type named by dW_dtype.  ADADIM_DW_F16_SCALED
+ *          multiplies column j by colscale[j] (fp32 [in], powers of two from
+ *          adadim_hessian_prepare) before the fp16 rounding; colscale must
+ *          then be non-NULL, otherwise it is ignored.
+ *   packed u32 bitstream of the codes of each channel (row for OC, column for
+ *          IC): code k of the channel at bits [k*bits, (k+1)*bits) of the
+ *          channel's stream, little-endian 32-bit words, each channel padded
+ *          to a whole word: [channels, ceil(len*bits/32)].
+ */
+int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in,
+                    int dim, int bits, int group, float clip,
+                    uint8_t* codes, float* scales, uint8_t* zeros,
+                    void* dW, int dW_dtype, const float* colscale,
+                    uint32_t* packed);
+
+/*
+ * Prepares H for scoring on the matrix cores.  With the power-of-two column
+ * scales d_j ~ sqrt(H_jj):
+ *   Hs     fp16 [in, in]: Hs[n,k] = H[n,k]/(d_n d_k) for k < n, 0 elsewhere
+ *   hmeta  f32  [2, in]:  hmeta[0,j] = d_j (the colscale of adadim_quantize),
+ *                         hmeta[1,j] = H_jj
+ * so that tr(dW H dW^T) = sum_o ( sum_j H_jj dW_oj^2 + 2 sum_{k<n} dW'_ok Hs_nk dW'_on ),
+ * dW'_oj = dW_oj d_j.  The scaling keeps |Hs| <= 2 whatever the activation
+ * outliers are.  Hs 16-byte aligned; in a multiple of 8.
+ */
+int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs, float* hmeta);
+
+/*
+ * Reconstruction error of one candidate (Eq. 1, squared):
+ *   loss = tr(dW H dW^T) = ||X dW^T||_F^2,   loss_rows[o] = dW_o H dW_o^T.
+ *   dW        [out, in] of type dW_dtype (F32 or F16; not F16_SCALED).
+ *   H         fp32 [in, in] as written by adadim_hessian.
+ *   loss_rows optional fp32 [out];  loss  fp32 device scalar (required).
+ * Prepares H internally on every call; use the _prepared form to score many
+ * candidates against one H.
+ */
+int adadim_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in,
+                       const float* H, float* loss_rows, float* loss);
+
+/* Same result from a prepared H.  dW_dtype may also be ADADIM_DW_F16_SCALED
+ * (dW already multiplied by hmeta[0,:], as adadim_quantize can emit). */
+int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in,
+                                const void* Hs, const float* hmeta, float* loss_rows, float* loss);
+
+/*
+ * Eq. 1's argmin: index of the first minimum of losses[0..n) (a later
+ * candidate wins only if strictly lower, as in App. B where 'oc' is visited
+ * before 'ic').  NaN entries never win.
+ *   losses    fp32 device array.   best_dev  optional device int32.
+ *   host_best optional HOST int32*: if given, the call waits for the stream
+ *             and stores the index there.
+ */
+int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADADIM_H */

@@ -1,0 +1,150 @@
+"""ctypes binding of libadadim.so: same names as the C ABI (include/adadim.h).
+
+Argument marshalling only.  Tensors are torch CUDA(ROCm) tensors used purely as
+device memory; every step of the search runs in the library's HIP kernels.
+There is no fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, byref, c_char_p, c_float, c_int, c_int32, c_int64, c_void_p
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadadim.so")
+
+OK, EINVAL, ENULL, EALIGN, EHIP = 0, -1, -2, -3, -4
+DIM_OC, DIM_IC = 0, 1
+DW_F32, DW_F16, DW_F16_SCALED = 0, 1, 2
+
+EXPORTS = (
+    "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version",
+    "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
+    "adadim_layer_error", "adadim_layer_error_prepared", "adadim_select",
+)
+
+_lib = None
+
+
+class AdaDimError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"adadim error {code}: {text}")
+        self.code = code
+
+
+def load_library(path: str | None = None) -> ctypes.CDLL:
+    """Loads the built shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(
+            f"{p} is missing: build it with `python -m paper_2309_15531_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(p)
+    lib.adadim_create.argtypes = [POINTER(c_void_p), c_void_p]
+    lib.adadim_create.restype = c_int
+    lib.adadim_destroy.argtypes = [c_void_p]
+    lib.adadim_destroy.restype = None
+    lib.adadim_last_error.argtypes = [c_void_p]
+    lib.adadim_last_error.restype = c_char_p
+    lib.adadim_version.argtypes = []
+    lib.adadim_version.restype = c_char_p
+    lib.adadim_hessian.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int]
+    lib.adadim_hessian.restype = c_int
+    lib.adadim_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_float,
+                                    c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p]
+    lib.adadim_quantize.restype = c_int
+    lib.adadim_hessian_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
+    lib.adadim_hessian_prepare.restype = c_int
+    lib.adadim_layer_error.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
+    lib.adadim_layer_error.restype = c_int
+    lib.adadim_layer_error_prepared.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p,
+                                                c_void_p, c_void_p]
+    lib.adadim_layer_error_prepared.restype = c_int
+    lib.adadim_select.argtypes = [c_void_p, c_void_p, c_int, c_void_p, POINTER(c_int32)]
+    lib.adadim_select.restype = c_int
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _ptr(t):
+    """Device address of a torch tensor (None -> NULL); plain ints pass through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return c_void_p(t)
+    return c_void_p(t.data_ptr())
+
+
+class Context:
+    """One adadim_ctx bound to a HIP stream (default: torch's current stream)."""
+
+    def __init__(self, stream: int | None = None):
+        self._lib = load_library()
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else 0
+        self.stream = stream
+        h = c_void_p()
+        rc = self._lib.adadim_create(byref(h), c_void_p(stream))
+        if rc != OK:
+            raise AdaDimError(rc, self._lib.adadim_last_error(None).decode())
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.adadim_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return self._lib.adadim_last_error(self._h).decode()
+
+    def _check(self, rc: int):
+        if rc != OK:
+            raise AdaDimError(rc, self.last_error())
+
+    # -- raw calls: return the status code, never raise ------------------
+    def raw(self, name: str, *args) -> int:
+        return getattr(self._lib, name)(self._h, *args)
+
+    # -- the ABI, one method per entry point ----------------------------
+    def adadim_hessian(self, X, H, accumulate: bool = False, tokens: int | None = None):
+        t = X.shape[0] if tokens is None else tokens
+        self._check(self._lib.adadim_hessian(self._h, _ptr(X), t, X.shape[1], X.stride(0), _ptr(H),
+                                             1 if accumulate else 0))
+
+    def adadim_quantize(self, W, dim: int, bits: int, group: int, clip: float = 1.0, codes=None, scales=None,
+                        zeros=None, dW=None, dW_dtype: int = DW_F32, colscale=None, packed=None):
+        out_f, in_f = W.shape
+        self._check(self._lib.adadim_quantize(self._h, _ptr(W), out_f, in_f, dim, bits, group, c_float(clip),
+                                              _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(dW), dW_dtype,
+                                              _ptr(colscale), _ptr(packed)))
+
+    def adadim_hessian_prepare(self, H, Hs, hmeta):
+        self._check(self._lib.adadim_hessian_prepare(self._h, _ptr(H), H.shape[0], _ptr(Hs), _ptr(hmeta)))
+
+    def adadim_layer_error(self, dW, dW_dtype: int, H, loss, loss_rows=None):
+        out_f, in_f = dW.shape
+        self._check(self._lib.adadim_layer_error(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(H),
+                                                 _ptr(loss_rows), _ptr(loss)))
+
+    def adadim_layer_error_prepared(self, dW, dW_dtype: int, Hs, hmeta, loss, loss_rows=None):
+        out_f, in_f = dW.shape
+        self._check(self._lib.adadim_layer_error_prepared(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(Hs),
+                                                          _ptr(hmeta), _ptr(loss_rows), _ptr(loss)))
+
+    def adadim_select(self, losses, n: int | None = None, best_dev=None, to_host: bool = True):
+        n = losses.numel() if n is None else n
+        host = c_int32(-1)
+        self._check(self._lib.adadim_select(self._h, _ptr(losses), n, _ptr(best_dev),
+                                            byref(host) if to_host else None))
+        return host.value if to_host else None

@@ -1,0 +1,196 @@
+// C-ABI entry points: context handling and argument validation.  Every check
+// runs before the first HIP call so that a rejected call touches no device.
+#include "common.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+static char g_create_error[256] = "";
+
+int adadim_fail(adadim_ctx* ctx, int code, const char* fmt, ...) {
+    char* dst = ctx ? ctx->err : g_create_error;
+    size_t cap = ctx ? sizeof(ctx->err) : sizeof(g_create_error);
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, cap, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes) {
+    if (bytes == 0) bytes = 256;
+    if (ctx->ws_bytes[slot] >= bytes) return ctx->ws[slot];
+    if (ctx->ws[slot]) {
+        // Earlier kernels on the stream may still read the old buffer.
+        if (hipStreamSynchronize(ctx->stream) != hipSuccess || hipFree(ctx->ws[slot]) != hipSuccess) {
+            adadim_fail(ctx, ADADIM_EHIP, "releasing scratch slot %d failed", slot);
+            return nullptr;
+        }
+        ctx->ws[slot] = nullptr;
+        ctx->ws_bytes[slot] = 0;
+    }
+    size_t want = (bytes + 255) & ~size_t(255);
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, want);
+    if (e != hipSuccess) {
+        adadim_fail(ctx, ADADIM_EHIP, "hipMalloc(%zu bytes) for scratch slot %d: %s", want, slot,
+                    hipGetErrorString(e));
+        return nullptr;
+    }
+    ctx->ws[slot] = p;
+    ctx->ws_bytes[slot] = want;
+    return p;
+}
+
+extern "C" {
+
+const char* adadim_version(void) { return "adadim-gfx950 0.1"; }
+
+int adadim_create(adadim_ctx** out, void* hip_stream) {
+    if (!out) return adadim_fail(nullptr, ADADIM_ENULL, "adadim_create: out is NULL");
+    adadim_ctx* c = new (std::nothrow) adadim_ctx;
+    if (!c) return adadim_fail(nullptr, ADADIM_EINVAL, "adadim_create: out of host memory");
+    std::memset(c, 0, sizeof(*c));
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    std::strcpy(c->err, "no error");
+    *out = c;
+    return ADADIM_OK;
+}
+
+void adadim_destroy(adadim_ctx* ctx) {
+    if (!ctx) return;
+    bool any = false;
+    for (int i = 0; i < WS_COUNT; ++i) any = any || ctx->ws[i];
+    if (any) {
+        (void)hipStreamSynchronize(ctx->stream);
+        for (int i = 0; i < WS_COUNT; ++i)
+            if (ctx->ws[i]) (void)hipFree(ctx->ws[i]);
+    }
+    delete ctx;
+}
+
+const char* adadim_last_error(const adadim_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
+
+int adadim_hessian(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
+                   int accumulate) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!H) return adadim_fail(ctx, ADADIM_ENULL, "adadim_hessian: H is NULL");
+    if (tokens < 0 || in <= 0 || ldx < in || (accumulate != 0 && accumulate != 1))
+        return adadim_fail(ctx, ADADIM_EINVAL,
+                           "adadim_hessian: need tokens >= 0, in > 0, ldx >= in, accumulate in {0,1} "
+                           "(tokens=%lld in=%lld ldx=%lld accumulate=%d)",
+                           (long long)tokens, (long long)in, (long long)ldx, accumulate);
+    if (in > (int64_t(1) << 20) || tokens > (int64_t(1) << 40))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_hessian: size out of range");
+    if (tokens > 0 && !X) return adadim_fail(ctx, ADADIM_ENULL, "adadim_hessian: X is NULL");
+    if ((in % 8) != 0 || (ldx % 8) != 0 || !aligned16(X) || !aligned16(H))
+        return adadim_fail(ctx, ADADIM_EALIGN,
+                           "adadim_hessian: in and ldx must be multiples of 8, X and H 16-byte aligned");
+    return launch_hessian(ctx, static_cast<const __half*>(X), tokens, in, ldx, H, accumulate);
+}
+
+int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                    float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
+                    const float* colscale, uint32_t* packed) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!W) return adadim_fail(ctx, ADADIM_ENULL, "adadim_quantize: W is NULL");
+    if (out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 24))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: bad shape out=%lld in=%lld",
+                           (long long)out, (long long)in);
+    if (dim != ADADIM_DIM_OC && dim != ADADIM_DIM_IC)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: dim must be 0 (OC) or 1 (IC), got %d", dim);
+    if (bits < 2 || bits > 8)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: bits must be in [2,8], got %d", bits);
+    if (!(clip > 0.0f && clip <= 1.0f))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: clip must be in (0,1], got %g", (double)clip);
+    const int64_t axis = dim == ADADIM_DIM_OC ? in : out;
+    if (group < 0 || (group > 0 && (axis % group) != 0))
+        return adadim_fail(ctx, ADADIM_EINVAL,
+                           "adadim_quantize: group %d must be 0 or divide the grouped axis (%lld)", group,
+                           (long long)axis);
+    if (dW && dW_dtype != ADADIM_DW_F32 && dW_dtype != ADADIM_DW_F16 && dW_dtype != ADADIM_DW_F16_SCALED)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: unknown dW_dtype %d", dW_dtype);
+    if (dW && dW_dtype == ADADIM_DW_F16_SCALED && !colscale)
+        return adadim_fail(ctx, ADADIM_ENULL, "adadim_quantize: colscale is NULL with dW_dtype F16_SCALED");
+    if (dW && dW_dtype == ADADIM_DW_F16_SCALED && (in % 8) == 0 && !aligned16(colscale))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_quantize: colscale must be 16-byte aligned");
+    if ((in % 8) == 0 && (!aligned16(W) || (dW && !aligned16(dW)) || (codes && (reinterpret_cast<uintptr_t>(codes) & 7u))))
+        return adadim_fail(ctx, ADADIM_EALIGN,
+                           "adadim_quantize: W and dW must be 16-byte, codes 8-byte aligned");
+    const int g = group == 0 ? (int)axis : group;
+    return launch_quantize(ctx, static_cast<const __half*>(W), out, in, dim, bits, g, clip, codes, scales,
+                           zeros, dW, dW_dtype, colscale, packed);
+}
+
+int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs, float* hmeta) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!H || !Hs || !hmeta) return adadim_fail(ctx, ADADIM_ENULL, "adadim_hessian_prepare: NULL argument");
+    if (in <= 0 || in > (int64_t(1) << 20))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_hessian_prepare: bad in=%lld", (long long)in);
+    if ((in % 8) != 0 || !aligned16(H) || !aligned16(Hs) || !aligned16(hmeta))
+        return adadim_fail(ctx, ADADIM_EALIGN,
+                           "adadim_hessian_prepare: in must be a multiple of 8, H, Hs and hmeta 16-byte aligned");
+    return launch_hessian_prepare(ctx, H, in, static_cast<__half*>(Hs), hmeta);
+}
+
+static int check_error_args(adadim_ctx* ctx, const char* who, const void* dW, int dW_dtype, int64_t out,
+                            int64_t in, const void* Hany, const float* loss, bool allow_scaled) {
+    if (!dW || !Hany || !loss) return adadim_fail(ctx, ADADIM_ENULL, "%s: dW, H or loss is NULL", who);
+    if (out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 20))
+        return adadim_fail(ctx, ADADIM_EINVAL, "%s: bad shape out=%lld in=%lld", who, (long long)out,
+                           (long long)in);
+    const bool ok = dW_dtype == ADADIM_DW_F32 || dW_dtype == ADADIM_DW_F16 ||
+                    (allow_scaled && dW_dtype == ADADIM_DW_F16_SCALED);
+    if (!ok) return adadim_fail(ctx, ADADIM_EINVAL, "%s: dW_dtype %d not accepted here", who, dW_dtype);
+    if ((in % 8) != 0 || !aligned16(dW) || !aligned16(Hany))
+        return adadim_fail(ctx, ADADIM_EALIGN, "%s: in must be a multiple of 8, dW and H 16-byte aligned", who);
+    return ADADIM_OK;
+}
+
+int adadim_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in, const float* H,
+                       float* loss_rows, float* loss) {
+    if (!ctx) return ADADIM_ENULL;
+    int rc = check_error_args(ctx, "adadim_layer_error", dW, dW_dtype, out, in, H, loss, false);
+    if (rc != ADADIM_OK) return rc;
+    __half* Hs = static_cast<__half*>(adadim_workspace(ctx, WS_HS, size_t(in) * size_t(in) * sizeof(__half)));
+    float* hmeta = static_cast<float*>(adadim_workspace(ctx, WS_HMETA, size_t(in) * 2 * sizeof(float)));
+    if (!Hs || !hmeta) return ADADIM_EHIP;
+    rc = launch_hessian_prepare(ctx, H, in, Hs, hmeta);
+    if (rc != ADADIM_OK) return rc;
+    return launch_layer_error(ctx, dW, dW_dtype, out, in, Hs, hmeta, loss_rows, loss);
+}
+
+int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in,
+                                const void* Hs, const float* hmeta, float* loss_rows, float* loss) {
+    if (!ctx) return ADADIM_ENULL;
+    int rc = check_error_args(ctx, "adadim_layer_error_prepared", dW, dW_dtype, out, in, Hs, loss, true);
+    if (rc != ADADIM_OK) return rc;
+    if (!hmeta) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_prepared: hmeta is NULL");
+    if (!aligned16(hmeta))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_layer_error_prepared: hmeta must be 16-byte aligned");
+    return launch_layer_error(ctx, dW, dW_dtype, out, in, static_cast<const __half*>(Hs), hmeta, loss_rows,
+                              loss);
+}
+
+int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!losses) return adadim_fail(ctx, ADADIM_ENULL, "adadim_select: losses is NULL");
+    if (n <= 0 || n > (1 << 20)) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_select: bad n=%d", n);
+    if (!best_dev && !host_best) return adadim_fail(ctx, ADADIM_ENULL, "adadim_select: no output given");
+    int32_t* dst = best_dev;
+    if (!dst) {
+        dst = static_cast<int32_t*>(adadim_workspace(ctx, WS_SELECT, 256));
+        if (!dst) return ADADIM_EHIP;
+    }
+    int rc = launch_select(ctx, losses, n, dst);
+    if (rc != ADADIM_OK) return rc;
+    if (host_best) {
+        ADADIM_HIP_TRY(ctx, hipMemcpyAsync(host_best, dst, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
+        ADADIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    }
+    return ADADIM_OK;
+}
+
+}  // extern "C"

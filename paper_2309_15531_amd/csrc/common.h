@@ -1,0 +1,64 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "../../include/adadim.h"
+
+// Scratch slots owned by a context; each grows on demand and is reused.
+enum {
+    WS_HESS_PART = 0,   // split-K partial tiles of the Gram matrix
+    WS_ERR_PART,        // per-column-block partial row losses
+    WS_DW16,            // fp16 column-scaled copy of dW
+    WS_HS,              // prepared fp16 H when the caller passes the fp32 one
+    WS_HMETA,           // column scales and diagonal of the above
+    WS_CODES,           // u8 codes when only the packed stream is requested
+    WS_SELECT,          // device int for adadim_select without a device output
+    WS_COUNT
+};
+
+struct adadim_ctx {
+    hipStream_t stream;
+    char err[512];
+    void* ws[WS_COUNT];
+    size_t ws_bytes[WS_COUNT];
+};
+
+int adadim_fail(adadim_ctx* ctx, int code, const char* fmt, ...);
+
+// Returns a device buffer of at least `bytes` for `slot`, or nullptr (error recorded).
+void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes);
+
+#define ADADIM_HIP_TRY(ctx, expr)                                                          \
+    do {                                                                                   \
+        hipError_t e__ = (expr);                                                           \
+        if (e__ != hipSuccess)                                                             \
+            return adadim_fail((ctx), ADADIM_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+    } while (0)
+
+#define ADADIM_LAUNCH_CHECK(ctx, what)                                                     \
+    do {                                                                                   \
+        hipError_t e__ = hipGetLastError();                                                \
+        if (e__ != hipSuccess)                                                             \
+            return adadim_fail((ctx), ADADIM_EHIP, "launch %s: %s", (what), hipGetErrorString(e__)); \
+    } while (0)
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Launchers implemented in the .hip files.  All validate nothing: the API layer does.
+int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
+                    float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
+                    const float* colscale, uint32_t* packed);
+int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, int dim, int bits,
+                uint32_t* packed);
+int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
+                   int accumulate);
+int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* Hs, float* hmeta);
+int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in,
+                       const __half* Hs, const float* hmeta, float* loss_rows, float* loss);
+int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev);

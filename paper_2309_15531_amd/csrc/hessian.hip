@@ -1,0 +1,243 @@
+// H (+)= X^T X on the matrix cores, and the preparation of H for scoring.
+//
+// H is the Gram matrix that turns the reconstruction error of Eq. 1 (Sec. 3.3)
+// into a quadratic form in dW.  It is a symmetric rank-k update whose
+// contraction runs over the tokens, the slow axis of X, so both operands are
+// transposed on their way into LDS.  Only tiles on or above the diagonal are
+// computed; the token range is split over workgroups to fill the chip, each
+// (tile, split) writes an fp32 partial tile, and a second kernel adds the
+// partials in a fixed order, mirrors the result and stores or accumulates H.
+// No atomics: the result is bit-reproducible and exactly symmetric.
+#include "common.h"
+#include "mfma_tile.h"
+
+namespace {
+
+using namespace mfma;
+
+template <int BT>
+__global__ __launch_bounds__(THREADS) void gram_tiles(const __half* __restrict__ X, int64_t tokens, int64_t in,
+                                                      int64_t ldx, int nb, int64_t t_per_split,
+                                                      float* __restrict__ part) {
+    constexpr int WM = BT / 2, TM = WM / 32;
+    extern __shared__ __align__(16) char smem[];
+    constexpr int TILE_BYTES = BT * ROW_BYTES;
+    auto sA = [&](int b) { return smem + b * (2 * TILE_BYTES); };
+    auto sB = [&](int b) { return smem + b * (2 * TILE_BYTES) + TILE_BYTES; };
+
+    // linear index over tiles (I <= J), row-major over the upper triangle
+    int idx = blockIdx.x, I = 0;
+    while (idx >= nb - I) {
+        idx -= nb - I;
+        ++I;
+    }
+    const int J = I + idx;
+    const int64_t t_begin = int64_t(blockIdx.y) * t_per_split;
+    const int64_t t_end = min(tokens, t_begin + t_per_split);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    floatx16 acc[TM][TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    TransposeStage<BT> ga, gb;
+    const int64_t rowA = int64_t(I) * BT, rowB = int64_t(J) * BT;
+    if (t_begin < t_end) {
+        ga.load(X, ldx, rowA, in, t_begin, t_end, tid);
+        gb.load(X, ldx, rowB, in, t_begin, t_end, tid);
+        ga.store(sA(0), tid);
+        gb.store(sB(0), tid);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int64_t k0 = t_begin; k0 < t_end; k0 += KT) {
+        const bool more = k0 + KT < t_end;
+        if (more) {
+            ga.load(X, ldx, rowA, in, k0 + KT, t_end, tid);
+            gb.load(X, ldx, rowB, in, k0 + KT, t_end, tid);
+        }
+        mma_stage<TM, TM>(sA(buf), sB(buf), wm * WM, wn * WM, lane, acc);
+        if (more) {
+            ga.store(sA(buf ^ 1), tid);
+            gb.store(sB(buf ^ 1), tid);
+        }
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    float* dst = part + (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * (int64_t(BT) * BT);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = wm * WM + 32 * i + acc_row(r, lane);
+                const int col = wn * WM + 32 * j + (lane & 31);
+                dst[row * BT + col] = acc[i][j][r];
+            }
+}
+
+// Adds the split partials of one 32x32 sub-block, writes it to H and, off the
+// diagonal, its mirror image.  grid = tiles * (sub-blocks per tile side)^2.
+template <int BT>
+__global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ part, int n_tiles, int n_split,
+                                                   int nb, int64_t in, float* __restrict__ H, int accumulate) {
+    constexpr int SB = BT / 32;
+    __shared__ float s[32][33];
+    const int tile = blockIdx.x / (SB * SB), sub = blockIdx.x % (SB * SB);
+    int idx = tile, I = 0;
+    while (idx >= nb - I) {
+        idx -= nb - I;
+        ++I;
+    }
+    const int J = I + idx;
+    const int sr = sub / SB, sc = sub % SB;
+    const int64_t R0 = int64_t(I) * BT + sr * 32, C0 = int64_t(J) * BT + sc * 32;
+    if (R0 > C0 || R0 >= in || C0 >= in) return;  // below the diagonal or outside H
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const float* src = part + int64_t(tile) * (int64_t(BT) * BT);
+    const int64_t split_stride = int64_t(n_tiles) * BT * BT;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = ty * 4 + rr;
+        float v = 0.0f;
+        for (int sp = 0; sp < n_split; ++sp) v += src[sp * split_stride + (sr * 32 + r) * BT + sc * 32 + tx];
+        s[r][tx] = v;
+    }
+    __syncthreads();
+    const bool diag = R0 == C0;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int r = ty * 4 + rr;
+        // upper block: element (r, tx); on a diagonal block take the upper triangle for both halves
+        if (R0 + r < in && C0 + tx < in) {
+            const float v = (diag && r > tx) ? s[tx][r] : s[r][tx];
+            float* p = H + (R0 + r) * in + C0 + tx;
+            *p = accumulate ? *p + v : v;
+        }
+        // mirrored block: element (r, tx) of the transpose
+        if (!diag && C0 + r < in && R0 + tx < in) {
+            const float v = s[tx][r];
+            float* p = H + (C0 + r) * in + R0 + tx;
+            *p = accumulate ? *p + v : v;
+        }
+    }
+}
+
+__global__ void zero_f32(float* p, int64_t n) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+// hmeta[0,j] = d_j = 2^round(log2(H_jj)/2) (1 if H_jj <= 0), hmeta[1,j] = H_jj.
+__global__ void hprep_meta(const float* __restrict__ H, int64_t in, float* __restrict__ hmeta) {
+    const int64_t j = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (j >= in) return;
+    const float h = H[j * in + j];
+    float d = 1.0f;
+    if (h > 0.0f && h < 3.0e38f) {
+        // any power of two near sqrt(h) serves; the exponent is clamped so that
+        // d, 1/d and d*d stay normal fp32 numbers
+        int e = static_cast<int>(rintf(0.5f * log2f(h)));
+        e = max(-30, min(30, e));
+        d = ldexpf(1.0f, e);
+    }
+    hmeta[j] = d;
+    hmeta[in + j] = h;
+}
+
+// Hs[n,k] = fp16(H[n,k] / (d_n d_k)) for k < n, else 0.  8 elements per thread.
+__global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, int64_t in,
+                                                   const float* __restrict__ hmeta, __half* __restrict__ Hs) {
+    const int64_t chunks_per_row = in / 8;
+    const int64_t c = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (c >= in * chunks_per_row) return;
+    const int64_t n = c / chunks_per_row, k0 = (c % chunks_per_row) * 8;
+    uint4 o = make_uint4(0, 0, 0, 0);
+    if (k0 < n) {
+        const float rn = 1.0f / hmeta[n];  // exact: powers of two
+        const float4 a = *reinterpret_cast<const float4*>(H + n * in + k0);
+        const float4 b = *reinterpret_cast<const float4*>(H + n * in + k0 + 4);
+        const float4 da = *reinterpret_cast<const float4*>(hmeta + k0);
+        const float4 db = *reinterpret_cast<const float4*>(hmeta + k0 + 4);
+        float v[8] = {a.x * rn / da.x, a.y * rn / da.y, a.z * rn / da.z, a.w * rn / da.w,
+                      b.x * rn / db.x, b.y * rn / db.y, b.z * rn / db.z, b.w * rn / db.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (k0 + e >= n) v[e] = 0.0f;
+        __half2* h = reinterpret_cast<__half2*>(&o);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = __floats2half2_rn(v[2 * e], v[2 * e + 1]);
+    }
+    *reinterpret_cast<uint4*>(Hs + n * in + k0) = o;
+}
+
+template <int BT>
+int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H, int accumulate) {
+    const int nb = static_cast<int>((in + BT - 1) / BT);
+    const int n_tiles = nb * (nb + 1) / 2;
+    // Split the tokens so that there are a few workgroups per compute unit, in
+    // whole LDS stages, but never more than 32 ways.
+    const int64_t stages = (tokens + KT - 1) / KT;
+    int n_split = static_cast<int>((4 * 256 + n_tiles - 1) / n_tiles);
+    if (n_split > 32) n_split = 32;
+    if (n_split > stages) n_split = static_cast<int>(stages);
+    if (n_split < 1) n_split = 1;
+    const int64_t t_per_split = ((stages + n_split - 1) / n_split) * KT;
+    n_split = static_cast<int>((tokens + t_per_split - 1) / t_per_split);
+
+    const size_t part_bytes = size_t(n_split) * n_tiles * BT * BT * sizeof(float);
+    float* part = static_cast<float*>(adadim_workspace(ctx, WS_HESS_PART, part_bytes));
+    if (!part) return ADADIM_EHIP;
+
+    constexpr int smem = 4 * BT * ROW_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gram_tiles<BT>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(gram_tiles<BT>, dim3(n_tiles, n_split), dim3(THREADS), smem, ctx->stream, X, tokens, in,
+                       ldx, nb, t_per_split, part);
+    ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
+    constexpr int SB = BT / 32;
+    hipLaunchKernelGGL(gram_reduce<BT>, dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream, part, n_tiles,
+                       n_split, nb, in, H, accumulate);
+    ADADIM_LAUNCH_CHECK(ctx, "gram_reduce");
+    return ADADIM_OK;
+}
+
+}  // namespace
+
+int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
+                   int accumulate) {
+    if (tokens == 0) {
+        if (!accumulate) {
+            const int64_t n = in * in;
+            hipLaunchKernelGGL(zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                               H, n);
+            ADADIM_LAUNCH_CHECK(ctx, "zero_f32");
+        }
+        return ADADIM_OK;
+    }
+    if (in <= 1024) return run_gram<128>(ctx, X, tokens, in, ldx, H, accumulate);
+    return run_gram<256>(ctx, X, tokens, in, ldx, H, accumulate);
+}
+
+int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* Hs, float* hmeta) {
+    hipLaunchKernelGGL(hprep_meta, dim3(static_cast<unsigned>((in + 255) / 256)), dim3(256), 0, ctx->stream, H,
+                       in, hmeta);
+    ADADIM_LAUNCH_CHECK(ctx, "hprep_meta");
+    const int64_t chunks = in * (in / 8);
+    hipLaunchKernelGGL(hprep_scale, dim3(static_cast<unsigned>((chunks + 255) / 256)), dim3(256), 0, ctx->stream,
+                       H, in, hmeta, Hs);
+    ADADIM_LAUNCH_CHECK(ctx, "hprep_scale");
+    return ADADIM_OK;
+}

@@ -1,0 +1,84 @@
+"""The per-layer AdaDim search as a sequence of library calls (Sec. 3.3, App. B).
+
+Allocation and call order only; all arithmetic happens in libadadim.so.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def clip_grid(n: int = 20, lo: float = 0.5, hi: float = 1.0):
+    """n clip ratios in [lo, hi], ends included, fp64 then one rounding to fp32."""
+    if n == 1:
+        return [float(np.float32(hi))]
+    return [float(np.float32(lo + (hi - lo) * i / (n - 1))) for i in range(n)]
+
+
+class PreparedHessian:
+    """H = X^T X on the device plus the fp16 form the scoring kernel consumes."""
+
+    def __init__(self, ctx: B.Context, in_f: int, device="cuda"):
+        self.ctx = ctx
+        self.in_f = in_f
+        self.H = torch.empty((in_f, in_f), dtype=torch.float32, device=device)
+        self.Hs = torch.empty((in_f, in_f), dtype=torch.float16, device=device)
+        self.hmeta = torch.empty((2, in_f), dtype=torch.float32, device=device)
+        self.tokens = 0
+
+    def update(self, X, accumulate: bool = False):
+        self.ctx.adadim_hessian(X, self.H, accumulate=accumulate)
+        self.tokens = X.shape[0] + (self.tokens if accumulate else 0)
+        return self
+
+    def prepare(self):
+        self.ctx.adadim_hessian_prepare(self.H, self.Hs, self.hmeta)
+        return self
+
+    @property
+    def colscale(self):
+        return self.hmeta[0]
+
+
+class LayerSearch:
+    """Buffers for searching layers of one shape; reused across layers and candidates."""
+
+    def __init__(self, ctx: B.Context, out_f: int, in_f: int, bits: int, group: int, clips=(1.0,),
+                 keep_winner: bool = True, device="cuda"):
+        self.ctx, self.out_f, self.in_f, self.bits, self.group = ctx, out_f, in_f, bits, group
+        self.clips = [float(np.float32(c)) for c in clips]
+        self.cands = [(d, c) for d in (B.DIM_OC, B.DIM_IC) for c in self.clips]
+        self.dW = torch.empty((out_f, in_f), dtype=torch.float16, device=device)
+        self.losses = torch.empty(len(self.cands), dtype=torch.float32, device=device)
+        self.best = torch.empty(1, dtype=torch.int32, device=device)
+        self.keep_winner = keep_winner
+        g_oc = in_f if group == 0 else group
+        g_ic = out_f if group == 0 else group
+        self.meta_shape = {B.DIM_OC: (out_f, in_f // g_oc), B.DIM_IC: (out_f // g_ic, in_f)}
+        if keep_winner:
+            n_meta = max(out_f * (in_f // g_oc), (out_f // g_ic) * in_f)
+            self.scales = torch.empty(n_meta, dtype=torch.float32, device=device)
+            self.zeros = torch.empty(n_meta, dtype=torch.uint8, device=device)
+            words = max(out_f * ((in_f * bits + 31) // 32), in_f * ((out_f * bits + 31) // 32))
+            self.packed = torch.empty(words, dtype=torch.int32, device=device)
+
+    def score_all(self, W, hp: PreparedHessian):
+        """Quantizes and scores every candidate; losses stay on the device."""
+        for i, (dim, clip) in enumerate(self.cands):
+            self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, dW=self.dW,
+                                     dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
+            self.ctx.adadim_layer_error_prepared(self.dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta,
+                                                 self.losses[i:i + 1])
+
+    def run(self, W, hp: PreparedHessian):
+        """Whole search for one layer: returns (best index, dim, clip); with
+        keep_winner the winner's packed codes, scales and zeros are in self.*"""
+        self.score_all(W, hp)
+        best = self.ctx.adadim_select(self.losses, best_dev=self.best, to_host=True)
+        dim, clip = self.cands[best]
+        if self.keep_winner:
+            self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, scales=self.scales,
+                                     zeros=self.zeros, packed=self.packed)
+        return best, dim, clip

@@ -1,0 +1,127 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before any device
+work."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2309_15531_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2309_15531_amd.build import build
+        build(verbose=False)
+    c = B.Context(stream=0)
+    yield c
+    c.close()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "adadim.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adadim_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(ctx):
+    lib = B.load_library()
+    names = _declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.adadim_version().decode().startswith("adadim-gfx950")
+
+
+def test_no_torch_types_in_header():
+    text = open(os.path.join(ROOT, "include", "adadim.h")).read()
+    assert "torch" not in text.replace("torch.nn.Linear", "") and "at::" not in text
+    assert 'extern "C"' in text
+
+
+A16 = ctypes.c_void_p(0x1000)      # fake, aligned, never dereferenced: validation fails first
+ODD = ctypes.c_void_p(0x1004)
+F1 = ctypes.c_float(1.0)
+
+
+def test_quantize_validation(ctx):
+    q = lambda *a: ctx.raw("adadim_quantize", *a)
+    tail = (A16, None, None, None, 0, None, None)
+    assert q(None, 64, 64, 0, 3, 32, F1, *tail) == B.ENULL
+    assert q(A16, 0, 64, 0, 3, 32, F1, *tail) == B.EINVAL
+    assert q(A16, 64, 64, 2, 3, 32, F1, *tail) == B.EINVAL          # dim
+    assert "dim" in ctx.last_error()
+    assert q(A16, 64, 64, 0, 1, 32, F1, *tail) == B.EINVAL          # bits
+    assert q(A16, 64, 64, 0, 9, 32, F1, *tail) == B.EINVAL
+    assert q(A16, 64, 96, 0, 3, 64, F1, *tail) == B.EINVAL          # 96 % 64
+    assert q(A16, 96, 64, 1, 3, 64, F1, *tail) == B.EINVAL          # per-IC groups run along out
+    assert q(A16, 64, 64, 0, 3, -1, F1, *tail) == B.EINVAL
+    assert q(A16, 64, 64, 0, 3, 32, ctypes.c_float(0.0), *tail) == B.EINVAL
+    assert q(A16, 64, 64, 0, 3, 32, ctypes.c_float(1.5), *tail) == B.EINVAL
+    assert q(A16, 64, 64, 0, 3, 32, ctypes.c_float(float("nan")), *tail) == B.EINVAL
+    assert q(ODD, 64, 64, 0, 3, 32, F1, *tail) == B.EALIGN
+    # scaled fp16 dW needs the column scales
+    assert q(A16, 64, 64, 0, 3, 32, F1, None, None, None, A16, B.DW_F16_SCALED, None, None) == B.ENULL
+    assert q(A16, 64, 64, 0, 3, 32, F1, None, None, None, A16, 7, None, None) == B.EINVAL
+
+
+def test_hessian_validation(ctx):
+    h = lambda *a: ctx.raw("adadim_hessian", *a)
+    assert h(A16, 16, 64, 64, None, 0) == B.ENULL
+    assert h(None, 16, 64, 64, A16, 0) == B.ENULL
+    assert h(A16, -1, 64, 64, A16, 0) == B.EINVAL
+    assert h(A16, 16, 64, 32, A16, 0) == B.EINVAL                   # ldx < in
+    assert h(A16, 16, 64, 64, A16, 2) == B.EINVAL
+    assert h(A16, 16, 60, 64, A16, 0) == B.EALIGN                   # in % 8
+    assert h(ODD, 16, 64, 64, A16, 0) == B.EALIGN
+    p = lambda *a: ctx.raw("adadim_hessian_prepare", *a)
+    assert p(None, 64, A16, A16) == B.ENULL
+    assert p(A16, 0, A16, A16) == B.EINVAL
+    assert p(A16, 60, A16, A16) == B.EALIGN
+
+
+def test_error_and_select_validation(ctx):
+    e = lambda *a: ctx.raw("adadim_layer_error", *a)
+    assert e(None, 0, 64, 64, A16, None, A16) == B.ENULL
+    assert e(A16, 0, 64, 64, A16, None, None) == B.ENULL
+    assert e(A16, 0, 0, 64, A16, None, A16) == B.EINVAL
+    assert e(A16, B.DW_F16_SCALED, 64, 64, A16, None, A16) == B.EINVAL   # scaled dW needs the prepared form
+    assert e(A16, 0, 64, 60, A16, None, A16) == B.EALIGN
+    ep = lambda *a: ctx.raw("adadim_layer_error_prepared", *a)
+    assert ep(A16, B.DW_F16_SCALED, 64, 64, A16, None, None, A16) == B.ENULL
+    assert ep(A16, 5, 64, 64, A16, A16, None, A16) == B.EINVAL
+    s = lambda *a: ctx.raw("adadim_select", *a)
+    assert s(None, 2, A16, None) == B.ENULL
+    assert s(A16, 0, A16, None) == B.EINVAL
+    assert s(A16, 2, None, None) == B.ENULL
+    assert "adadim_select" in ctx.last_error()
+
+
+def test_create_destroy():
+    lib = B.load_library()
+    assert lib.adadim_create(None, None) == B.ENULL
+    assert b"NULL" in lib.adadim_last_error(None)
+    lib.adadim_destroy(None)
+    c = B.Context(stream=0)
+    assert c.last_error() == "no error"
+    c.close()
+    c.close()
+
+
+def test_product_does_not_import_oracle():
+    """The product package must never reach into the oracle (and vice versa)."""
+    pkg = os.path.join(ROOT, "paper_2309_15531_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", src, flags=re.M), f
+                assert "oracle/" not in src, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            src = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2309_15531_amd" not in src and "ctypes" not in src, f

@@ -1,0 +1,328 @@
+"""GPU parity: every library call against the CPU oracle on the same seeded inputs.
+
+Bars: codes, zeros, scales, packed streams and the chosen index are bit-exact;
+fp32 dW is bit-exact (same formulas, one rounding per operation); fp16 dW is
+the round-to-nearest-even of the oracle's fp32 dW; H within 2e-5*sqrt(H_ii H_jj)
+(fp32 accumulation of exact fp16 products); the layer error within 1e-3
+relative of the fp64 oracle; the winning dimension is compared only where the
+two losses differ by more than 1 %.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import OC, IC
+from paper_2309_15531_amd import binding as B
+from paper_2309_15531_amd import search as S
+from paper_2309_15531_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+LOSS_RTOL = 1e-3
+H_TOL = 2e-5
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = B.Context()
+    yield c
+    torch.cuda.synchronize()
+    c.close()
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def gpu_quantize(ctx, W, dim, bits, group, clip=1.0, dW_dtype=B.DW_F32, colscale=None, want_packed=True,
+                 want_codes=True):
+    out_f, in_f = W.shape
+    g = (in_f if dim == OC else out_f) if group == 0 else group
+    meta = (out_f, in_f // g) if dim == OC else (out_f // g, in_f)
+    Wd = dev(W)
+    codes = torch.full((out_f, in_f), 255, dtype=torch.uint8, device="cuda") if want_codes else None
+    scales = torch.full(meta, -1.0, dtype=torch.float32, device="cuda")
+    zeros = torch.full(meta, 255, dtype=torch.uint8, device="cuda")
+    dW = torch.full((out_f, in_f), float("nan"), dtype=torch.float32 if dW_dtype == B.DW_F32 else torch.float16,
+                    device="cuda")
+    n_ch, ln = (out_f, in_f) if dim == OC else (in_f, out_f)
+    packed = torch.full((n_ch, (ln * bits + 31) // 32), -1, dtype=torch.int32, device="cuda") if want_packed else None
+    ctx.adadim_quantize(Wd, dim, bits, group, clip, codes=codes, scales=scales, zeros=zeros, dW=dW,
+                        dW_dtype=dW_dtype, colscale=colscale, packed=packed)
+    torch.cuda.synchronize()
+    return {
+        "codes": codes.cpu().numpy() if want_codes else None,
+        "scales": scales.cpu().numpy(), "zeros": zeros.cpu().numpy(), "dW": dW.cpu().numpy(),
+        "packed": packed.cpu().numpy().view(np.uint32) if want_packed else None,
+    }
+
+
+def rand_w(out_f, in_f, seed):
+    return synth.make_weight(out_f, in_f, seed, heavy_cols=max(1, in_f // 100), heavy_scale=5.0)
+
+
+QUANT_CASES = [
+    # out, in, bits, group      (several tiles, ragged tails, every kernel path)
+    (512, 512, 3, 64),          # the toy workload's setting
+    (384, 640, 4, 128),
+    (256, 1024, 2, 64),
+    (640, 264, 3, 8),           # in not a multiple of the 256-column tile
+    (520, 328, 4, 0),           # whole-channel groups
+    (96, 1536, 8, 512),         # 64 lanes per group
+    (768, 768, 5, 256),
+    (240, 72, 3, 24),           # group not a power of two -> element-wise path
+    (100, 70, 4, 10),           # in % 8 != 0 -> scalar paths for both dims
+    (128, 128, 3, 16),
+    (64, 4096, 3, 32),
+]
+
+
+@pytest.mark.parametrize("dim", [OC, IC])
+@pytest.mark.parametrize("out_f,in_f,bits,group", QUANT_CASES)
+def test_quantize_bit_exact(ctx, dim, out_f, in_f, bits, group):
+    axis = in_f if dim == OC else out_f
+    if group and axis % group:
+        pytest.skip("group does not divide this axis")
+    W = rand_w(out_f, in_f, seed=out_f * 7 + in_f + bits)
+    ref = oracle.quantize(W, dim, bits, group)
+    got = gpu_quantize(ctx, W, dim, bits, group)
+    assert np.array_equal(got["scales"].view(np.uint32), ref["scales"].view(np.uint32))
+    assert np.array_equal(got["zeros"], ref["zeros"])
+    assert np.array_equal(got["codes"], ref["codes"])
+    assert np.array_equal(got["dW"], ref["dW"])
+    assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, bits))
+
+
+@pytest.mark.parametrize("dim", [OC, IC])
+@pytest.mark.parametrize("clip", [0.5, 0.7368421, 0.97])
+def test_quantize_clip_and_fp16_outputs(ctx, dim, clip):
+    W = rand_w(256, 512, seed=77)
+    clip = float(np.float32(clip))
+    ref = oracle.quantize(W, dim, 3, 64, clip)
+    got = gpu_quantize(ctx, W, dim, 3, 64, clip, dW_dtype=B.DW_F16)
+    assert np.array_equal(got["scales"].view(np.uint32), ref["scales"].view(np.uint32))
+    assert np.array_equal(got["zeros"], ref["zeros"])
+    assert np.array_equal(got["codes"], ref["codes"])
+    assert np.array_equal(got["dW"], ref["dW"].astype(np.float16))
+    # column-scaled fp16 dW: powers of two commute with the rounding
+    cs = np.ldexp(np.float32(1.0), np.random.default_rng(3).integers(-2, 9, size=512)).astype(np.float32)
+    got = gpu_quantize(ctx, W, dim, 3, 64, clip, dW_dtype=B.DW_F16_SCALED, colscale=dev(cs))
+    assert np.array_equal(got["dW"], (ref["dW"] * cs[None, :]).astype(np.float16))
+    # packed stream without a caller-side code buffer
+    got = gpu_quantize(ctx, W, dim, 3, 64, clip, want_codes=False)
+    assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, 3))
+
+
+@pytest.mark.parametrize("dim", [OC, IC])
+def test_quantize_degenerate_groups(ctx, dim):
+    """All-zero groups, one-sided groups, on-grid weights (exact fixed point)."""
+    W = rand_w(128, 256, seed=5)
+    W[:32] = 0
+    W[32:64] = np.abs(W[32:64])
+    W[64:96] = -np.abs(W[64:96])
+    ref = oracle.quantize(W, dim, 3, 32)
+    got = gpu_quantize(ctx, W, dim, 3, 32)
+    for k in ("scales", "zeros", "codes", "dW"):
+        assert np.array_equal(got[k], ref[k]), k
+    Wg, q, z, s = synth.on_grid_weight(128, 256, dim, 4, 64, seed=2)
+    got = gpu_quantize(ctx, Wg, dim, 4, 64)
+    assert np.array_equal(got["codes"], q) and np.array_equal(got["zeros"], z)
+    assert np.array_equal(got["scales"], s) and not got["dW"].any()
+
+
+def gpu_hessian(ctx, X, accumulate_chunks=None, ld_pad=0):
+    t, in_f = X.shape
+    if ld_pad:
+        Xp = torch.zeros((t, in_f + ld_pad), dtype=torch.float16, device="cuda")
+        Xp[:, :in_f] = dev(X)
+        Xd = Xp[:, :in_f]
+    else:
+        Xd = dev(X)
+    H = torch.full((in_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    if accumulate_chunks is None:
+        ctx.adadim_hessian(Xd, H)
+    else:
+        bounds = np.linspace(0, t, accumulate_chunks + 1).astype(int)
+        for i in range(accumulate_chunks):
+            ctx.adadim_hessian(Xd[bounds[i]:bounds[i + 1]], H, accumulate=i > 0)
+    torch.cuda.synchronize()
+    return H.cpu().numpy()
+
+
+def check_hessian(Hg, Href):
+    d = np.sqrt(np.maximum(np.diag(Href), 1e-30))
+    err = np.abs(Hg.astype(np.float64) - Href) / (d[:, None] * d[None, :])
+    assert err.max() <= H_TOL, err.max()
+    assert np.array_equal(Hg, Hg.T)
+
+
+@pytest.mark.parametrize("tokens,in_f", [(256, 512), (1000, 264), (77, 1288), (4096, 128), (3000, 2056), (1, 64)])
+def test_hessian(ctx, tokens, in_f):
+    X = synth.make_activations(tokens, in_f, seed=tokens + in_f, n_outliers=3, scale_lo=50, scale_hi=100)
+    check_hessian(gpu_hessian(ctx, X), oracle.hessian(X))
+
+
+def test_hessian_accumulate_and_pitch(ctx):
+    X = synth.make_activations(1500, 520, seed=9, n_outliers=4, scale_lo=30, scale_hi=60, relu=True)
+    Href = oracle.hessian(X)
+    check_hessian(gpu_hessian(ctx, X, accumulate_chunks=3), Href)
+    check_hessian(gpu_hessian(ctx, X, ld_pad=24), Href)
+    # tokens == 0 clears H
+    H = torch.ones((64, 64), dtype=torch.float32, device="cuda")
+    ctx.adadim_hessian(torch.empty((0, 64), dtype=torch.float16, device="cuda"), H)
+    torch.cuda.synchronize()
+    assert not H.cpu().numpy().any()
+
+
+def test_hessian_reproducible(ctx):
+    X = synth.make_activations(5000, 776, seed=4, n_outliers=2, scale_lo=50, scale_hi=50)
+    a, b = gpu_hessian(ctx, X), gpu_hessian(ctx, X)
+    assert np.array_equal(a, b)
+
+
+ERR_CASES = [(512, 512, 256), (384, 640, 1000), (264, 328, 300), (1288, 264, 500), (96, 2056, 2048)]
+
+
+@pytest.mark.parametrize("out_f,in_f,tokens", ERR_CASES)
+@pytest.mark.parametrize("dW_dtype", [B.DW_F32, B.DW_F16])
+def test_layer_error(ctx, out_f, in_f, tokens, dW_dtype):
+    W = rand_w(out_f, in_f, seed=out_f + in_f)
+    X = synth.make_activations(tokens, in_f, seed=in_f, n_outliers=4, scale_lo=50, scale_hi=100,
+                               relu=(in_f == 2056))
+    H64 = oracle.hessian(X)
+    Hg = dev(gpu_hessian(ctx, X))
+    for dim in (OC, IC):
+        group = 8
+        dw = oracle.quantize(W, dim, 3, group)["dW"]
+        if dW_dtype == B.DW_F16:
+            dw = dw.astype(np.float16)
+        rows_ref = oracle.layer_error_rows(dw, H64)
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        rows = torch.zeros(out_f, dtype=torch.float32, device="cuda")
+        ctx.adadim_layer_error(dev(dw), dW_dtype, Hg, loss, loss_rows=rows)
+        torch.cuda.synchronize()
+        assert loss.item() == pytest.approx(rows_ref.sum(), rel=LOSS_RTOL)
+        r = rows.cpu().numpy().astype(np.float64)
+        assert np.abs(r - rows_ref).max() <= LOSS_RTOL * rows_ref.max()
+        assert r.sum() == pytest.approx(loss.item(), rel=1e-5)
+
+
+def test_layer_error_prepared_matches_and_scaled_input(ctx):
+    out_f, in_f = 640, 520
+    W = rand_w(out_f, in_f, seed=1)
+    X = synth.make_activations(700, in_f, seed=2, n_outliers=3, scale_lo=60, scale_hi=60)
+    hp = S.PreparedHessian(ctx, in_f).update(dev(X)).prepare()
+    torch.cuda.synchronize()
+    hmeta = hp.hmeta.cpu().numpy()
+    Hg = hp.H.cpu().numpy()
+    # column scales are powers of two within a factor sqrt(2) of sqrt(H_jj)
+    m, e = np.frexp(hmeta[0])
+    assert (m == 0.5).all()
+    assert np.array_equal(hmeta[1], np.diag(Hg))
+    ratio = hmeta[0] / np.sqrt(np.diag(Hg))
+    assert (ratio > 0.70).all() and (ratio < 1.42).all()
+    Hs = hp.Hs.cpu().numpy().astype(np.float64)
+    assert not np.triu(Hs).any() and np.abs(Hs).max() <= 2.0
+    ref = oracle.layer_error(oracle.quantize(W, IC, 3, 64)["dW"], oracle.hessian(X))
+    Wd = dev(W)
+    dW = torch.empty((out_f, in_f), dtype=torch.float16, device="cuda")
+    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+    ctx.adadim_quantize(Wd, IC, 3, 64, dW=dW, dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
+    ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, losses[0:1])
+    dW32 = torch.empty((out_f, in_f), dtype=torch.float32, device="cuda")
+    ctx.adadim_quantize(Wd, IC, 3, 64, dW=dW32, dW_dtype=B.DW_F32)
+    ctx.adadim_layer_error_prepared(dW32, B.DW_F32, hp.Hs, hp.hmeta, losses[1:2])
+    ctx.adadim_layer_error(dW32, B.DW_F32, hp.H, losses[2:3])
+    torch.cuda.synchronize()
+    got = losses.cpu().numpy()
+    assert got[1] == got[2]
+    assert got == pytest.approx([ref] * 3, rel=LOSS_RTOL)
+
+
+def test_layer_error_zero_and_identity(ctx):
+    """dW = 0 gives exactly 0; H = I gives ||dW||_F^2."""
+    n = 256
+    H = torch.eye(n, dtype=torch.float32, device="cuda")
+    loss = torch.full((1,), -1.0, dtype=torch.float32, device="cuda")
+    ctx.adadim_layer_error(torch.zeros((128, n), dtype=torch.float32, device="cuda"), B.DW_F32, H, loss)
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0
+    d = np.random.default_rng(0).standard_normal((128, n)).astype(np.float32) * 0.01
+    ctx.adadim_layer_error(dev(d), B.DW_F32, H, loss)
+    torch.cuda.synchronize()
+    assert loss.item() == pytest.approx(float(np.sum(d.astype(np.float64) ** 2)), rel=1e-5)
+
+
+def test_select(ctx):
+    for vals, want in [([1.0, 1.0], 0), ([2.0, 1.0], 1), ([3.0, 2.0, 2.0, 5.0], 1),
+                       ([float("nan"), 4.0, 3.0], 2), ([5.0] * 40, 0)]:
+        t = torch.tensor(vals, dtype=torch.float32, device="cuda")
+        best_dev = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        assert ctx.adadim_select(t, best_dev=best_dev) == want
+        if not any(v != v for v in vals):
+            assert oracle.select(vals) == want
+        assert ctx.adadim_select(t) == want
+        assert best_dev.item() == want
+
+
+def run_search(ctx, W, X, bits, group, clips=(1.0,)):
+    in_f = W.shape[1]
+    hp = S.PreparedHessian(ctx, in_f).update(dev(X)).prepare()
+    ls = S.LayerSearch(ctx, W.shape[0], in_f, bits, group, clips)
+    best, dim, clip = ls.run(dev(W), hp)
+    torch.cuda.synchronize()
+    return ls, best, dim, clip
+
+
+def test_toy_workload_end_to_end(ctx):
+    """The 512x512 workload: full search against the full oracle."""
+    cfg = synth.CONFIGS[0]
+    W, X = synth.config_weight(0, "fc"), synth.config_activations(0, 512)
+    ref = oracle.search(W, X, cfg["bits"][0], cfg["group"])
+    ls, best, dim, clip = run_search(ctx, W, X, cfg["bits"][0], cfg["group"])
+    got = ls.losses.cpu().numpy()
+    assert got == pytest.approx(ref["losses"], rel=LOSS_RTOL)
+    # direct definition of Eq. 1 on this small case
+    assert got[0] == pytest.approx(oracle.layer_error_direct(X, W, oracle.quantize(W, OC, 3, 64)["What"]),
+                                   rel=LOSS_RTOL)
+    lo, hi = min(ref["losses"]), max(ref["losses"])
+    if (hi - lo) / lo > 0.01:
+        assert best == ref["best"] and dim == ref["dim"]
+    q = ref["quant"] if dim == ref["dim"] else oracle.quantize(W, dim, 3, 64)
+    n_meta = q["scales"].size
+    assert np.array_equal(ls.scales[:n_meta].cpu().numpy(), q["scales"].ravel())
+    assert np.array_equal(ls.zeros[:n_meta].cpu().numpy(), q["zeros"].ravel())
+    pk = oracle.pack(q["codes"], dim, 3)
+    assert np.array_equal(ls.packed[:pk.size].cpu().numpy().view(np.uint32), pk.ravel())
+
+
+def test_clip_grid_search(ctx):
+    W = rand_w(256, 512, seed=31)
+    X = synth.make_activations(512, 512, seed=32, n_outliers=4, scale_lo=100, scale_hi=100)
+    clips = oracle.clip_grid(20)
+    assert S.clip_grid(20) == [float(c) for c in clips]
+    ref = oracle.search(W, X, 2, 64, clips=clips)
+    ls, best, dim, clip = run_search(ctx, W, X, 2, 64, clips=S.clip_grid(20))
+    got = ls.losses.cpu().numpy()
+    assert len(got) == 40
+    assert got == pytest.approx(ref["losses"], rel=LOSS_RTOL)
+    srt = np.sort(ref["losses"])
+    if (srt[1] - srt[0]) / srt[0] > 0.01:
+        assert best == ref["best"] and (dim, np.float32(clip)) == (ref["dim"], np.float32(ref["clip"]))
+    else:
+        assert ref["losses"][best] <= srt[0] * 1.01
+
+
+def test_choice_flips_under_transpose_gpu(ctx):
+    n = 256
+    X = np.eye(n, dtype=np.float16)
+    rng = np.random.default_rng(13)
+    W = rng.standard_normal((n, n)).astype(np.float32) * 0.02
+    W[:, rng.choice(n, 8, replace=False)] *= 12.0
+    W = W.astype(np.float16)
+    _, _, dim_a, _ = run_search(ctx, W, X, 3, 32)
+    _, _, dim_b, _ = run_search(ctx, np.ascontiguousarray(W.T), X, 3, 32)
+    assert (dim_a, dim_b) == (IC, OC)
