@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdaDim layer search on one MI355X.
+
+A step is one pass of the whole hot path over one layer: Gram matrix of the
+calibration activations, its preparation, quantize + score for both grouping
+dimensions, selection, and the winner's packed codes / scales / zeros.
+Prints ONE JSON line (see README / DESIGN for the fields).
+
+    python bench.py [--steps K] [--warmup W] [--workload q_proj|down_proj|gate_proj|toy]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # B/s, MI355X HBM3E
+MFMA_F16_PEAK = 2.5e15     # flop/s, dense fp16 with fp32 accumulate
+
+WORKLOADS = {
+    # name: (config id in synth.CONFIGS, layer name)
+    "toy": (0, "fc"),
+    "q_proj": (1, "q_proj"),           # the workload the headline metric is quoted on
+    "gate_proj": (2, "gate_proj"),
+    "down_proj": (2, "down_proj"),
+}
+
+
+def gram_tiling(in_f: int):
+    bt = 128 if in_f <= 1024 else 256
+    nb = (in_f + bt - 1) // bt
+    return bt, nb * (nb + 1) // 2
+
+
+def cpu_baseline(W, X, bits, group, budget_tokens=4096):
+    """Times the CPU oracle, as it stands, on a bounded sample: the Gram matrix on
+    the first `budget_tokens` tokens (scaled linearly to all tokens), the two
+    quantizations and the two fp64 scorings in full."""
+    import oracle
+    t_sample = min(budget_tokens, X.shape[0])
+    t0 = time.perf_counter()
+    H = oracle.hessian(X[:t_sample])
+    t_h = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    losses = []
+    for dim in (oracle.OC, oracle.IC):
+        q = oracle.quantize(W, dim, bits, group)
+        losses.append(oracle.layer_error(q["dW"], H))
+    oracle.select(losses)
+    t_q = time.perf_counter() - t0
+    total = t_h * (X.shape[0] / t_sample) + t_q
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {
+        "value": W.size / total, "unit": "weights/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"fp64 Gram matrix on the first {t_sample} of {X.shape[0]} tokens ({t_h:.2f} s, scaled x"
+                  f"{X.shape[0] / t_sample:.0f}); both quantizations and both fp64 losses in full ({t_q:.2f} s)",
+        "seconds_extrapolated": total,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS))
+    ap.add_argument("--bits", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (layers are independent; see DESIGN.md for how the "
+              "search would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2309_15531_amd import binding as B
+    from paper_2309_15531_amd import search as S
+    from paper_2309_15531_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.load_library()  # fails loudly if the HIP library has not been built
+
+    cfg_id, layer = WORKLOADS[args.workload]
+    cfg = synth.CONFIGS[cfg_id]
+    out_f, in_f = cfg["layers"][layer]
+    bits = args.bits if args.bits is not None else (3 if 3 in cfg["bits"] else cfg["bits"][0])
+    group, tokens = cfg["group"], cfg["tokens"]
+
+    W = synth.config_weight(cfg_id, layer)
+    X = synth.config_activations(cfg_id, in_f)
+    Wd = torch.from_numpy(W).cuda()
+    Xd = torch.from_numpy(X).cuda()
+
+    ctx = B.Context()
+    hp = S.PreparedHessian(ctx, in_f)
+    ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,))
+
+    def step():
+        hp.update(Xd)
+        hp.prepare()
+        return ls.run(Wd, hp)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.adadim_profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        best, dim, clip = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.adadim_profile(False)
+    prof = ctx.adadim_profile_read()
+    losses = ls.losses.cpu().numpy().tolist()
+
+    ms_per_step = elapsed / args.steps * 1e3
+    kern = {k: {"avg_us": v[0] / max(v[1], 1) * 1e3, "launches": v[1]} for k, v in prof.items()}
+
+    # roofline of the dominant kernel: the Gram-matrix tiles.  MFMA flops
+    # actually issued = upper-triangular tiles x 2*BT*BT*tokens.
+    bt, n_tiles = gram_tiling(in_f)
+    gram_flops = 2.0 * n_tiles * bt * bt * tokens
+    gram_s = kern["gram_tiles"]["avg_us"] * 1e-6
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(f"gram_tiles/{args.workload}")
+    roofline = {
+        "kernel": "gram_tiles", "bound": "mfma", "achieved": gram_flops / gram_s / 1e12, "peak": MFMA_F16_PEAK / 1e12,
+        "unit": "TFLOP/s", "frac": gram_flops / gram_s / MFMA_F16_PEAK, "traffic": traffic,
+        "dense_equivalent": 2.0 * tokens * in_f * in_f / gram_s / 1e12,
+    }
+
+    # secondary kernels: error GEMM (MFMA) and quantizers (HBM)
+    comps = {}
+    if "error_tiles" in kern:
+        s = kern["error_tiles"]["avg_us"] * 1e-6
+        bn = 256
+        nbk = (in_f + bn - 1) // bn
+        issued = 2.0 * out_f * bn * bn * nbk * (nbk + 1) / 2  # k-range of column block nb is (nb+1)*BN
+        comps["error_tiles"] = {
+            "avg_us": s * 1e6, "tflops_issued": issued / s / 1e12, "frac_mfma": issued / s / MFMA_F16_PEAK,
+            "tflops_dense_equivalent": 2.0 * out_f * in_f * in_f / s / 1e12,
+        }
+    qbytes = out_f * in_f * (2 + 2) + 5.0 * out_f * in_f / group   # W read + fp16 dW written + scale/zero
+    for k in ("quant_oc_lanes", "quant_ic_tile"):
+        if k in kern:
+            s = kern[k]["avg_us"] * 1e-6
+            comps[k] = {"avg_us": s * 1e6, "GBps_algorithmic": qbytes / s / 1e9, "frac_hbm": qbytes / s / HBM_PEAK,
+                        "note": "average over scoring launches (W + fp16 dW) and the winner's repack launch"}
+    for k, v in kern.items():
+        comps.setdefault(k, {"avg_us": v["avg_us"]})
+        comps[k]["launches_per_step"] = v["launches"] / args.steps
+
+    result = {
+        "metric": "weight params quantized+scored (both dims)/s",
+        "value": out_f * in_f / (elapsed / args.steps),
+        "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 operands, f32 accumulate (quantizer f32)", "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}/{layer} W[{out_f},{in_f}] X[{tokens},{in_f}] int{bits} g{group} "
+                               "both dims + selection", "bits": bits, "group": group, "tokens": tokens},
+        "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
+        "roofline": roofline,
+        "kernels": comps,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(W, X, bits, group)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -150,6 +150,20 @@ int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, i
  */
 int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best);
 
+/*
+ * Measurement aid (not part of the method): per-kernel device timings.
+ * adadim_profile(ctx, 1) clears the records and starts bracketing every kernel
+ * the library launches on this context with a pair of HIP events on the
+ * context's stream; adadim_profile(ctx, 0) stops.  At most 8192 launches are
+ * recorded per enable; later ones are counted as `dropped`.
+ * adadim_profile_read waits for the stream and returns the idx-th kernel's
+ * record: name (host buffer of `cap` bytes), total milliseconds and number of
+ * recorded launches.  Returns ADADIM_OK, or ADADIM_EINVAL when idx is past the
+ * last record (use this to stop iterating).
+ */
+int adadim_profile(adadim_ctx* ctx, int enable);
+int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

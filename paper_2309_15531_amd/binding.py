@@ -21,6 +21,7 @@ EXPORTS = (
     "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version",
     "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_select",
+    "adadim_profile", "adadim_profile_read",
 )
 
 _lib = None
@@ -65,6 +66,11 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_layer_error_prepared.restype = c_int
     lib.adadim_select.argtypes = [c_void_p, c_void_p, c_int, c_void_p, POINTER(c_int32)]
     lib.adadim_select.restype = c_int
+    lib.adadim_profile.argtypes = [c_void_p, c_int]
+    lib.adadim_profile.restype = c_int
+    lib.adadim_profile_read.argtypes = [c_void_p, c_int, ctypes.c_char_p, c_int, POINTER(ctypes.c_double),
+                                        POINTER(c_int64)]
+    lib.adadim_profile_read.restype = c_int
     if path is None:
         _lib = lib
     return lib
@@ -148,3 +154,19 @@ class Context:
         self._check(self._lib.adadim_select(self._h, _ptr(losses), n, _ptr(best_dev),
                                             byref(host) if to_host else None))
         return host.value if to_host else None
+
+    def adadim_profile(self, enable: bool):
+        self._check(self._lib.adadim_profile(self._h, 1 if enable else 0))
+
+    def adadim_profile_read(self) -> dict:
+        """All per-kernel records: {kernel name: (total ms, launches)}."""
+        out, idx = {}, 0
+        while True:
+            name = ctypes.create_string_buffer(64)
+            ms, n = ctypes.c_double(0.0), c_int64(0)
+            rc = self._lib.adadim_profile_read(self._h, idx, name, 64, byref(ms), byref(n))
+            if rc == EINVAL:
+                return out
+            self._check(rc)
+            out[name.value.decode()] = (ms.value, n.value)
+            idx += 1

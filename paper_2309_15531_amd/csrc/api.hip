@@ -44,7 +44,79 @@ void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes) {
     return p;
 }
 
+ProfScope::ProfScope(adadim_ctx* c, const char* name) : ctx(c), pair(-1) {
+    adadim_prof& p = c->prof;
+    if (!p.enabled) return;
+    if (p.n_used >= p.n_events) {
+        ++p.dropped;
+        return;
+    }
+    int k = 0;
+    while (k < p.n_kernels && p.names[k] != name && std::strcmp(p.names[k], name) != 0) ++k;
+    if (k == p.n_kernels) {
+        if (k == PROF_MAX_KERNELS) {
+            ++p.dropped;
+            return;
+        }
+        p.names[p.n_kernels++] = name;
+    }
+    pair = p.n_used++;
+    p.kernel_of[pair] = k;
+    (void)hipEventRecord(p.start[pair], c->stream);
+}
+
+ProfScope::~ProfScope() {
+    if (pair >= 0) (void)hipEventRecord(ctx->prof.stop[pair], ctx->stream);
+}
+
 extern "C" {
+
+int adadim_profile(adadim_ctx* ctx, int enable) {
+    if (!ctx) return ADADIM_ENULL;
+    adadim_prof& p = ctx->prof;
+    if (enable && !p.start) {
+        p.start = new (std::nothrow) hipEvent_t[PROF_MAX_LAUNCHES];
+        p.stop = new (std::nothrow) hipEvent_t[PROF_MAX_LAUNCHES];
+        p.kernel_of = new (std::nothrow) int[PROF_MAX_LAUNCHES];
+        if (!p.start || !p.stop || !p.kernel_of) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_profile: out of host memory");
+        p.n_events = 0;
+        for (int i = 0; i < PROF_MAX_LAUNCHES; ++i) {
+            ADADIM_HIP_TRY(ctx, hipEventCreate(&p.start[i]));
+            ADADIM_HIP_TRY(ctx, hipEventCreate(&p.stop[i]));
+            p.n_events = i + 1;
+        }
+    }
+    if (enable) {
+        p.n_used = 0;
+        p.dropped = 0;
+        p.n_kernels = 0;
+    }
+    p.enabled = enable != 0;
+    return ADADIM_OK;
+}
+
+int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches) {
+    if (!ctx) return ADADIM_ENULL;
+    adadim_prof& p = ctx->prof;
+    if (idx < 0 || idx >= p.n_kernels) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_profile_read: no record %d", idx);
+    ADADIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    double tot = 0.0;
+    int64_t n = 0;
+    for (int i = 0; i < p.n_used; ++i) {
+        if (p.kernel_of[i] != idx) continue;
+        float ms = 0.0f;
+        ADADIM_HIP_TRY(ctx, hipEventElapsedTime(&ms, p.start[i], p.stop[i]));
+        tot += ms;
+        ++n;
+    }
+    if (name && cap > 0) {
+        std::strncpy(name, p.names[idx], cap - 1);
+        name[cap - 1] = 0;
+    }
+    if (total_ms) *total_ms = tot;
+    if (launches) *launches = n;
+    return ADADIM_OK;
+}
 
 const char* adadim_version(void) { return "adadim-gfx950 0.1"; }
 
@@ -67,6 +139,15 @@ void adadim_destroy(adadim_ctx* ctx) {
         (void)hipStreamSynchronize(ctx->stream);
         for (int i = 0; i < WS_COUNT; ++i)
             if (ctx->ws[i]) (void)hipFree(ctx->ws[i]);
+    }
+    if (ctx->prof.start) {
+        for (int i = 0; i < ctx->prof.n_events; ++i) {
+            (void)hipEventDestroy(ctx->prof.start[i]);
+            (void)hipEventDestroy(ctx->prof.stop[i]);
+        }
+        delete[] ctx->prof.start;
+        delete[] ctx->prof.stop;
+        delete[] ctx->prof.kernel_of;
     }
     delete ctx;
 }

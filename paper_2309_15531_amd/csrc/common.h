@@ -22,11 +22,36 @@ enum {
     WS_COUNT
 };
 
+// Per-kernel event timing (adadim_profile).  Events are created once, on the
+// first enable, and reused.
+constexpr int PROF_MAX_LAUNCHES = 8192;
+constexpr int PROF_MAX_KERNELS = 32;
+struct adadim_prof {
+    bool enabled;
+    int n_events;                    // event pairs created so far
+    int n_used;                      // pairs used since the last enable
+    int64_t dropped;
+    hipEvent_t* start;
+    hipEvent_t* stop;
+    int* kernel_of;                  // pair -> kernel slot
+    int n_kernels;
+    const char* names[PROF_MAX_KERNELS];
+};
+
 struct adadim_ctx {
     hipStream_t stream;
     char err[512];
     void* ws[WS_COUNT];
     size_t ws_bytes[WS_COUNT];
+    adadim_prof prof;
+};
+
+// Brackets one kernel launch with events when profiling is on.
+struct ProfScope {
+    adadim_ctx* ctx;
+    int pair;
+    ProfScope(adadim_ctx* c, const char* name);
+    ~ProfScope();
 };
 
 int adadim_fail(adadim_ctx* ctx, int code, const char* fmt, ...);

@@ -204,12 +204,18 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         attr_set = true;
     }
-    hipLaunchKernelGGL(gram_tiles<BT>, dim3(n_tiles, n_split), dim3(THREADS), smem, ctx->stream, X, tokens, in,
-                       ldx, nb, t_per_split, part);
+    {
+        ProfScope prof(ctx, "gram_tiles");
+        hipLaunchKernelGGL(gram_tiles<BT>, dim3(n_tiles, n_split), dim3(THREADS), smem, ctx->stream, X, tokens, in,
+                           ldx, nb, t_per_split, part);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     constexpr int SB = BT / 32;
-    hipLaunchKernelGGL(gram_reduce<BT>, dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream, part, n_tiles,
-                       n_split, nb, in, H, accumulate);
+    {
+        ProfScope prof(ctx, "gram_reduce");
+        hipLaunchKernelGGL(gram_reduce<BT>, dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream, part, n_tiles,
+                           n_split, nb, in, H, accumulate);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "gram_reduce");
     return ADADIM_OK;
 }
@@ -221,8 +227,11 @@ int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in,
     if (tokens == 0) {
         if (!accumulate) {
             const int64_t n = in * in;
-            hipLaunchKernelGGL(zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
-                               H, n);
+            {
+                ProfScope prof(ctx, "zero_f32");
+                hipLaunchKernelGGL(zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                                   H, n);
+            }
             ADADIM_LAUNCH_CHECK(ctx, "zero_f32");
         }
         return ADADIM_OK;
@@ -232,12 +241,18 @@ int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in,
 }
 
 int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* Hs, float* hmeta) {
-    hipLaunchKernelGGL(hprep_meta, dim3(static_cast<unsigned>((in + 255) / 256)), dim3(256), 0, ctx->stream, H,
-                       in, hmeta);
+    {
+        ProfScope prof(ctx, "hprep_meta");
+        hipLaunchKernelGGL(hprep_meta, dim3(static_cast<unsigned>((in + 255) / 256)), dim3(256), 0, ctx->stream, H,
+                           in, hmeta);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "hprep_meta");
     const int64_t chunks = in * (in / 8);
-    hipLaunchKernelGGL(hprep_scale, dim3(static_cast<unsigned>((chunks + 255) / 256)), dim3(256), 0, ctx->stream,
-                       H, in, hmeta, Hs);
+    {
+        ProfScope prof(ctx, "hprep_scale");
+        hipLaunchKernelGGL(hprep_scale, dim3(static_cast<unsigned>((chunks + 255) / 256)), dim3(256), 0, ctx->stream,
+                           H, in, hmeta, Hs);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "hprep_scale");
     return ADADIM_OK;
 }

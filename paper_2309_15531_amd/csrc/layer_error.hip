@@ -201,8 +201,11 @@ int run_error_tiles(adadim_ctx* ctx, const __half* A, const __half* Hs, int64_t 
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         attr_set = true;
     }
-    hipLaunchKernelGGL((error_tiles<BM, BN, WGM, WGN>), dim3(static_cast<unsigned>(int64_t(MB) * NB)),
-                       dim3(THREADS), smem, ctx->stream, A, Hs, out, in, MB, NB, part);
+    {
+        ProfScope prof(ctx, "error_tiles");
+        hipLaunchKernelGGL((error_tiles<BM, BN, WGM, WGN>), dim3(static_cast<unsigned>(int64_t(MB) * NB)),
+                           dim3(THREADS), smem, ctx->stream, A, Hs, out, in, MB, NB, part);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
     *NB_out = NB;
     return ADADIM_OK;
@@ -225,8 +228,11 @@ int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t ou
         if (!dW16) return ADADIM_EHIP;
         A = dW16;
     }
-    hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out)), dim3(256), 0, ctx->stream, dW, dW_dtype,
-                       in, hmeta, dW16, diag);
+    {
+        ProfScope prof(ctx, "error_prologue");
+        hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out)), dim3(256), 0, ctx->stream, dW, dW_dtype,
+                           in, hmeta, dW16, diag);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
     int nb_used = 0;
     int rc;
@@ -235,13 +241,19 @@ int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t ou
     else
         rc = run_error_tiles<256, BN, 2, 2>(ctx, A, Hs, out, in, part, &nb_used);
     if (rc != ADADIM_OK) return rc;
-    hipLaunchKernelGGL(error_finish, dim3(1), dim3(1024), 0, ctx->stream, diag, part, out, nb_used, loss_rows, loss);
+    {
+        ProfScope prof(ctx, "error_finish");
+        hipLaunchKernelGGL(error_finish, dim3(1), dim3(1024), 0, ctx->stream, diag, part, out, nb_used, loss_rows, loss);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "error_finish");
     return ADADIM_OK;
 }
 
 int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev) {
-    hipLaunchKernelGGL(select_first_min, dim3(1), dim3(64), 0, ctx->stream, losses, n, best_dev);
+    {
+        ProfScope prof(ctx, "select_first_min");
+        hipLaunchKernelGGL(select_first_min, dim3(1), dim3(64), 0, ctx->stream, losses, n, best_dev);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "select_first_min");
     return ADADIM_OK;
 }

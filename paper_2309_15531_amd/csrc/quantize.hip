@@ -317,9 +317,12 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
                      const float* colscale) {
     const int64_t n_chunks = out * in / 8;
     const unsigned blocks = static_cast<unsigned>((n_chunks + 255) / 256);
-    hipLaunchKernelGGL(quant_oc_lanes<LPG>, dim3(blocks), dim3(256), 0, ctx->stream,
-                       reinterpret_cast<const uint4*>(W), n_chunks, static_cast<int>(in / 8), clip, qmax, codes,
-                       scales, zeros, dW, dW_dtype, colscale);
+    {
+        ProfScope prof(ctx, "quant_oc_lanes");
+        hipLaunchKernelGGL(quant_oc_lanes<LPG>, dim3(blocks), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const uint4*>(W), n_chunks, static_cast<int>(in / 8), clip, qmax, codes,
+                           scales, zeros, dW, dW_dtype, colscale);
+    }
 }
 
 }  // namespace
@@ -331,9 +334,12 @@ int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, 
     const int64_t n_words = (len * bits + 31) / 32;
     const int64_t total = n_ch * n_words;
     const unsigned blocks = static_cast<unsigned>((total + 255) / 256);
-    hipLaunchKernelGGL(pack_words, dim3(blocks), dim3(256), 0, ctx->stream, codes, n_ch, len,
-                       dim == ADADIM_DIM_OC ? in : int64_t(1), dim == ADADIM_DIM_OC ? int64_t(1) : in, bits,
-                       n_words, dim == ADADIM_DIM_IC ? 1 : 0, packed);
+    {
+        ProfScope prof(ctx, "pack_words");
+        hipLaunchKernelGGL(pack_words, dim3(blocks), dim3(256), 0, ctx->stream, codes, n_ch, len,
+                           dim == ADADIM_DIM_OC ? in : int64_t(1), dim == ADADIM_DIM_OC ? int64_t(1) : in, bits,
+                           n_words, dim == ADADIM_DIM_IC ? 1 : 0, packed);
+    }
     ADADIM_LAUNCH_CHECK(ctx, "pack_words");
     return ADADIM_OK;
 }
@@ -360,8 +366,11 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
         } else {
             const int64_t n_groups = out * (in / g);
             const unsigned blocks = static_cast<unsigned>((n_groups + 3) / 4);
-            hipLaunchKernelGGL(quant_oc_generic, dim3(blocks), dim3(256), 0, ctx->stream, W, n_groups, g, in,
-                               clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+            {
+                ProfScope prof(ctx, "quant_oc_generic");
+                hipLaunchKernelGGL(quant_oc_generic, dim3(blocks), dim3(256), 0, ctx->stream, W, n_groups, g, in,
+                                   clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+            }
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_generic");
         }
     } else {
@@ -370,12 +379,18 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: more than 65535 row groups per column");
         if (vec) {
             dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(row_groups));
-            hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
-                               scales, zeros, dW, dW_dtype, colscale);
+            {
+                ProfScope prof(ctx, "quant_ic_tile");
+                hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
+                                   scales, zeros, dW, dW_dtype, colscale);
+            }
         } else {
             dim3 grid(static_cast<unsigned>((in + 31) / 32), static_cast<unsigned>(row_groups));
-            hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
-                               scales, zeros, dW, dW_dtype, colscale);
+            {
+                ProfScope prof(ctx, "quant_ic_tile");
+                hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
+                                   scales, zeros, dW, dW_dtype, colscale);
+            }
         }
         ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");
     }
