@@ -19,7 +19,7 @@ enum {
     WS_HMETA,           // column scales and diagonal of the above
     WS_CODES,           // u8 codes when only the packed stream is requested
     WS_SELECT,          // device int for adadim_select without a device output
-    WS_ZERO,            // 256 zero bytes: source of out-of-range rows/columns for LDS DMA
+    WS_ZERO,            // zero-filled buffer: source of out-of-range token rows for LDS DMA
     WS_COUNT
 };
 
@@ -44,7 +44,7 @@ struct adadim_ctx {
     char err[512];
     void* ws[WS_COUNT];
     size_t ws_bytes[WS_COUNT];
-    bool zero_ready;                 // WS_ZERO has been cleared
+    size_t zero_ready_bytes;         // size of WS_ZERO when it was last cleared
     adadim_prof prof;
 };
 

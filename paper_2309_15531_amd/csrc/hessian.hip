@@ -10,6 +10,7 @@
 // No atomics: the result is bit-reproducible and exactly symmetric.
 #include "common.h"
 #include "mfma_tile.h"
+#include "gram_dma.h"
 
 namespace {
 
@@ -83,191 +84,6 @@ __global__ __launch_bounds__(THREADS) void gram_tiles(const __half* __restrict__
                 dst[row * BT + col] = acc[i][j][r];
             }
 }
-
-// ---------------------------------------------------------------------------
-// 256x256 tiles with LDS-DMA staging.  X is copied global -> LDS without
-// passing through registers (global_load_lds_dwordx4, 1 KB per wavefront
-// instruction = two token rows of 256 columns) into a ring of four 32-token
-// stages, and the MFMA fragments are fetched with the transposing LDS read
-// (ds_read_b64_tr_b16), which turns the token-major tile into the
-// contraction-contiguous operand layout on the fly.
-//
-// LDS stage layout: operand A (row panel I) then operand B (column panel J),
-// each [32 tokens][256 columns] fp16, 512 bytes per token row.  The 16-byte
-// chunk c of token row r is stored at chunk slot c ^ ((r & 3) << 2): the four
-// token rows that one transposing read touches then fall into different
-// 64-byte bank groups.  The permutation is applied on the global side (the
-// LDS side of a DMA transfer is always lane-linear).
-//
-// ds_read_b64_tr_b16: within each block of 16 lanes, lane i receives the four
-// 16-bit elements {i, 16+i, 32+i, 48+i} of the 64 elements the block's lanes
-// address (lane L contributing elements 4L..4L+3).  Lane L therefore points at
-// token row L/4, columns 4*(L%4)..+3 of a 4-token x 16-column patch and lane i
-// ends up with column i of the patch for the four tokens.
-//
-// Pipeline per 32-token stage s (two 16-token MFMA sweeps, fragments double
-// buffered in registers):  sweep 0 | wait for stage s+1's DMA, barrier, start
-// the DMA of stage s+3 into the buffer stage s-1 used, prefetch the first
-// fragments of stage s+1 | sweep 1.
-namespace dma {
-
-constexpr int BT = 256, KT = 32, NST = 4;
-constexpr int ROWB = BT * 2;
-constexpr int OP_BYTES = KT * ROWB;
-constexpr int STAGE_BYTES = 2 * OP_BYTES;
-constexpr int SMEM_BYTES = NST * STAGE_BYTES;
-
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef short short8v __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ void g2l16(const void* g, uint32_t lds) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory", "m0");
-}
-
-__device__ __forceinline__ half8 tr_read8(uint32_t addr) {
-    typedef short4v __attribute__((address_space(3))) * lds_ptr;
-    const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_ptr>(uintptr_t(addr)));
-    const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_ptr>(uintptr_t(addr + 4 * ROWB)));
-    const short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(half8, v);
-}
-
-template <int TM, int TN>
-struct Frags {
-    half8 a[TM];
-    half8 b[TN];
-};
-
-template <int WGM, int WGN>
-__global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* __restrict__ X, int64_t tokens,
-                                                                 int64_t in, int64_t ldx, int nb,
-                                                                 int64_t t_per_split, const void* zero16,
-                                                                 float* __restrict__ part) {
-    constexpr int NW = WGM * WGN;
-    constexpr int WM = BT / WGM, WN = BT / WGN, TM = WM / 32, TN = WN / 32;
-    constexpr int LOADS = 32 / NW;  // 1-KB transfers per wavefront per stage
-    static_assert(32 % NW == 0, "wavefront count");
-    extern __shared__ __align__(16) char smem[];
-    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
-
-    int idx = blockIdx.x, I = 0;
-    while (idx >= nb - I) {
-        idx -= nb - I;
-        ++I;
-    }
-    const int J = I + idx;
-    const int64_t t_begin = int64_t(blockIdx.y) * t_per_split;
-    const int64_t t_end = min(tokens, t_begin + t_per_split);
-    const int t_len = static_cast<int>(t_end - t_begin);
-    const int n_st = (t_len + KT - 1) / KT;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    // ---- DMA descriptors: transfer j of this wavefront moves token rows 2*rp, 2*rp+1 of operand op
-    const int rl = lane >> 5, p = lane & 31;
-    const __half* gptr[LOADS];
-    int grow[LOADS];
-    bool gok[LOADS];
-    uint32_t gdst[LOADS];
-#pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        const int q = wave + NW * j;
-        const int op = q >> 4, rp = q & 15;
-        const int row = 2 * rp + rl;
-        const int c = p ^ ((row & 3) << 2);
-        const int64_t col = int64_t(op ? J : I) * BT + 8 * c;
-        gok[j] = col < in;
-        grow[j] = row;
-        gptr[j] = X + (t_begin + row) * ldx + (gok[j] ? col : 0);
-        gdst[j] = lds0 + op * OP_BYTES + rp * 1024;
-    }
-    const int64_t stage_step = int64_t(KT) * ldx;
-    int issued = 0;  // stages whose DMA has been started
-    auto issue_stage = [&]() {
-        const uint32_t sbase = (issued & (NST - 1)) * STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const bool ok = gok[j] && (issued * KT + grow[j] < t_len);
-            const void* g = ok ? static_cast<const void*>(gptr[j]) : zero16;
-            g2l16(g, gdst[j] + sbase);
-            gptr[j] += stage_step;
-        }
-        ++issued;
-    };
-
-    // ---- fragment addresses (stage-relative, first sweep)
-    const int f = ((lane & 15) >> 2) << 2;
-    const int lrow = 8 * (lane >> 5) + ((lane & 15) >> 2);
-    const int mlow = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-    uint32_t a_off[TM], b_off[TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-        a_off[i] = lds0 + lrow * ROWB + ((((wm * WM) / 8 + 4 * i + (mlow >> 3)) ^ f) << 4) + (mlow & 7) * 2;
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-        b_off[j] = lds0 + OP_BYTES + lrow * ROWB + ((((wn * WN) / 8 + 4 * j + (mlow >> 3)) ^ f) << 4) + (mlow & 7) * 2;
-
-    auto read_frags = [&](Frags<TM, TN>& F, int stage, int sweep) {
-        const uint32_t off = (stage & (NST - 1)) * STAGE_BYTES + sweep * 16 * ROWB;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) F.a[i] = tr_read8(a_off[i] + off);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) F.b[j] = tr_read8(b_off[j] + off);
-    };
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    auto sweep = [&](const Frags<TM, TN>& F) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(F.a[i], F.b[j], acc[i][j], 0, 0, 0);
-    };
-
-    Frags<TM, TN> F0, F1;
-    issue_stage();
-    issue_stage();
-    issue_stage();
-    // stage 0 landed (two later stages may still be in flight)
-    if constexpr (LOADS == 8) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    read_frags(F0, 0, 0);
-    for (int s = 0; s < n_st; ++s) {
-        read_frags(F1, s, 1);
-        sweep(F0);
-        if constexpr (LOADS == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        issue_stage();            // stage s+3 overwrites the buffer of stage s-1
-        read_frags(F0, s + 1, 0);
-        sweep(F1);
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
-
-    float* dst = part + (int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * (int64_t(BT) * BT);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * WM + 32 * i + acc_row(r, lane);
-                const int col = wn * WN + 32 * j + (lane & 31);
-                dst[row * BT + col] = acc[i][j][r];
-            }
-}
-
-}  // namespace dma
 
 // Adds the split partials of one 32x32 sub-block, writes it to H and, off the
 // diagonal, its mirror image.  grid = tiles * (sub-blocks per tile side)^2.
@@ -384,7 +200,10 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
     if (!part) return ADADIM_EHIP;
 
     if constexpr (BT == 256) {
-        void* zero16 = adadim_workspace(ctx, WS_ZERO, 256);
+        // zero-filled source for rows past the end of the token range: the DMA of a surplus stage
+        // reads up to 32 token rows of pitch ldx from it
+        const size_t zero_bytes = size_t(32) * size_t(ldx) * 2 + 512;
+        void* zero16 = adadim_workspace(ctx, WS_ZERO, zero_bytes);
         if (!zero16) return ADADIM_EHIP;
         static bool attr_set = false;
         if (!attr_set) {
@@ -392,15 +211,18 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, dma::SMEM_BYTES));
             attr_set = true;
         }
-        if (!ctx->zero_ready) {
-            hipLaunchKernelGGL(zero_f32, dim3(1), dim3(64), 0, ctx->stream, static_cast<float*>(zero16), int64_t(64));
+        if (ctx->zero_ready_bytes != ctx->ws_bytes[WS_ZERO]) {
+            const int64_t n = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
+            hipLaunchKernelGGL(zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                               static_cast<float*>(zero16), n);
             ADADIM_LAUNCH_CHECK(ctx, "zero_f32");
-            ctx->zero_ready = true;
+            ctx->zero_ready_bytes = ctx->ws_bytes[WS_ZERO];
         }
         {
             ProfScope prof(ctx, "gram_tiles");
-            hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2>), dim3(n_tiles, n_split), dim3(256), dma::SMEM_BYTES,
-                               ctx->stream, X, tokens, in, ldx, nb, t_per_split, zero16, part);
+            const unsigned grid = 8u * static_cast<unsigned>((n_tiles * n_split + 7) / 8);
+            hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2>), dim3(grid), dim3(256), dma::SMEM_BYTES, ctx->stream, X,
+                               tokens, in, ldx, nb, n_split, t_per_split, zero16, part);
         }
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     } else {
