@@ -14,6 +14,7 @@ FLAGS = [
     "-ffp-contract=off",                      # one rounding per operation in the quantizer
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Wno-inline-asm",                        # the LDS-DMA helper names m0 as clobbered on purpose
 ]
 
 

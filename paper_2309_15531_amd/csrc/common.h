@@ -19,6 +19,7 @@ enum {
     WS_HMETA,           // column scales and diagonal of the above
     WS_CODES,           // u8 codes when only the packed stream is requested
     WS_SELECT,          // device int for adadim_select without a device output
+    WS_ERR_FIN,         // block totals and ticket of the loss reduction
     WS_ZERO,            // zero-filled buffer: source of out-of-range token rows for LDS DMA
     WS_COUNT
 };

@@ -1,0 +1,282 @@
+// Error-GEMM tile kernel with LDS-DMA staging (gfx950).  Included by layer_error.hip.
+//
+// Computes, for one 256x256 tile (row block mb of dW', column block nb of E)
+// and one chunk of the contraction range, the partial row sums
+//     part[slot, o] = sum_{n in block nb} ( sum_{k in chunk} dW'[o,k] Hs[n,k] ) * dW'[o,n]
+// where Hs is the scaled strictly-lower triangle of H (zero for k >= n), so the
+// contraction of column block nb stops at its diagonal block.  Row sums are
+// linear in the contraction range, so chunks simply add up; cutting the long
+// contractions of the right-hand column blocks into chunks is what balances the
+// triangular work over the compute units.
+//
+// The MFMA's M index runs over the columns n of E (rows of Hs) and its N index
+// over the rows o (rows of dW'): each lane then owns one output row o per
+// 32-wide block and four consecutive n per accumulator quad, so the epilogue's
+// dW'[o,n] factors are 8-byte loads and the sum over n stays inside the lane.
+//
+// Both operands are contraction-contiguous in memory ([row][k]), so a DMA
+// transfer (global_load_lds_dwordx4, 1 KB per wavefront instruction) brings 16
+// rows x 32 k and the MFMA fragments are plain 16-byte LDS reads.  Stage layout:
+// operand 0 (256 rows of Hs) then operand 1 (256 rows of dW'), each [256 rows][64 bytes];
+// the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 2) & 3), which
+// makes the fragment reads (32 consecutive rows, one chunk) conflict-free.  The
+// permutation is applied on the global side of the transfer.
+//
+// The software pipeline is the one of the Gram kernel: a ring of four 32-k
+// stages, two 16-k MFMA sweeps per stage with register double buffering, one
+// barrier per stage, DMA and LDS reads interleaved with the MFMAs in a pinned
+// order, the ragged remainder of the contraction range taken by the first
+// stage through per-lane predicates.
+#pragma once
+
+#include "mfma_tile.h"
+
+#include <type_traits>
+
+namespace {
+
+using namespace mfma;
+
+namespace edma {
+
+constexpr int BT = 256, KT = 32, NST = 4;
+constexpr int ROWB = KT * 2;               // 64 bytes per tile row per stage
+constexpr int OP_BYTES = BT * ROWB;        // 16384
+constexpr int STAGE_BYTES = 2 * OP_BYTES;
+constexpr int SMEM_BYTES = NST * STAGE_BYTES;
+constexpr int NW = 4, WM = 128, WN = 128, TM = 4, TN = 4, LOADS = 8;
+
+__device__ __forceinline__ void g2l16(const void* g, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds), "v"(g) : "memory", "m0");
+}
+__device__ __forceinline__ void g2l16_s(const void* sbase, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+__device__ __forceinline__ half8 lds_read8(uint32_t addr) {
+    typedef half8 __attribute__((address_space(3))) * lds_ptr;
+    return *reinterpret_cast<lds_ptr>(uintptr_t(addr));
+}
+
+struct Frags {
+    half8 v[TM + TN];
+};
+
+// Column block nb contracts over k < kend(nb) = min(in, (nb+1)*256), cut into
+// chunks of kc_len (a multiple of 32).  Slots enumerate (nb, chunk) with nb
+// descending; slot_of_nb[] is not stored: the decode loop below recomputes it.
+__device__ __forceinline__ int chunks_of(int nb, int64_t in, int kc_len) {
+    const int64_t kend = min(in, int64_t(nb + 1) * BT);
+    return static_cast<int>((kend + kc_len - 1) / kc_len);
+}
+
+__global__ __launch_bounds__(256) void error_tiles_dma(const __half* __restrict__ A, const __half* __restrict__ Hs,
+                                                       int64_t out, int64_t in, int MB, int NB, int kc_len,
+                                                       int n_slots, const void* zero16,
+                                                       float* __restrict__ part) {
+    extern __shared__ __align__(16) char smem[];
+    __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+
+    // work item = slot * MB + mb; XCD x takes the x-th contiguous eighth of the list
+    const int total = n_slots * MB;
+    const int per_xcd = (total + 7) / 8;
+    const int item = static_cast<int>(blockIdx.x % 8) * per_xcd + static_cast<int>(blockIdx.x / 8);
+    if (static_cast<int>(blockIdx.x / 8) >= per_xcd || item >= total) return;
+    const int slot = item / MB, mb = item - slot * MB;
+    int nb = NB - 1, rem = slot;
+    for (;;) {
+        const int c = chunks_of(nb, in, kc_len);
+        if (rem < c) break;
+        rem -= c;
+        --nb;
+    }
+    const int64_t kend = min(in, int64_t(nb + 1) * BT);
+    const int64_t k_begin = int64_t(rem) * kc_len;
+    const int k_len = static_cast<int>(min(kend, k_begin + kc_len) - k_begin);   // > 0, multiple of 8
+    const int n_st = (k_len + KT - 1) / KT;
+    const int r0 = k_len - KT * (n_st - 1);                                       // k of stage 0: 8..32
+    const int64_t row0 = int64_t(mb) * BT, col0 = int64_t(nb) * BT;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- DMA descriptors.  Transfer j of this wavefront moves rows 16*rq .. 16*rq+15 of operand op
+    // (q = wave + 4j: op = q >> 4, rq = q & 15; operand 0 = Hs rows of column block nb, operand 1 =
+    // dW' rows of row block mb); lane l takes row l >> 2, chunk slot l & 3.  Rows past the end of a
+    // matrix re-read the block's first row: they only feed entries of E that the epilogue skips.
+    const int lr = lane >> 2, p = lane & 3;
+    uint32_t goff[LOADS], gdst[LOADS];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const int q = wave + NW * j;
+        const int op = q >> 4, rq = q & 15;
+        const int row = 16 * rq + lr;
+        const int c = p ^ ((row >> 2) & 3);
+        const int64_t blk0 = op ? row0 : col0, lim = op ? out : in;
+        int64_t grow = blk0 + row;
+        if (grow >= lim) grow = blk0;
+        const __half* base = op ? A : Hs;
+        goff[j] = static_cast<uint32_t>(((grow - blk0) * in + 8 * c) * 2);
+        gdst[j] = lds0 + op * OP_BYTES + rq * 1024;
+        // stage 0, predicated on the ragged length
+        const void* g = 8 * c < r0 ? static_cast<const void*>(base + grow * in + k_begin + 8 * c) : zero16;
+        g2l16(g, gdst[j]);
+    }
+    // scalar bases of the two operands for the next stage to issue
+    const char* baseA = reinterpret_cast<const char*>(Hs + col0 * in + k_begin + r0);   // operand 0
+    const char* baseB = reinterpret_cast<const char*>(A + row0 * in + k_begin + r0);    // operand 1
+    int issued = 1;
+    const char* curA = baseA;
+    const char* curB = baseB;
+    uint32_t cur_mask = 0;
+    auto uniform_ptr = [](const char* ptr) {
+        const uintptr_t b = reinterpret_cast<uintptr_t>(ptr);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b >> 32));
+        return reinterpret_cast<const char*>((uintptr_t(hi) << 32) | lo);
+    };
+    auto stage_begin = [&]() {
+        const bool real = issued < n_st;   // stages past the end read the 16 zero bytes
+        curA = uniform_ptr(real ? baseA : static_cast<const char*>(zero16));
+        curB = uniform_ptr(real ? baseB : static_cast<const char*>(zero16));
+        cur_mask = real ? 0xffffffffu : 0u;
+    };
+    auto issue_one = [&](int j, int buf) {
+        g2l16_s(j < LOADS / 2 ? curA : curB, goff[j] & cur_mask, gdst[j] + buf * STAGE_BYTES);
+    };
+    auto stage_issued = [&]() {
+        ++issued;
+        baseA += KT * 2;
+        baseB += KT * 2;
+    };
+    auto issue_stage = [&](int buf) {
+        stage_begin();
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) issue_one(j, buf);
+        stage_issued();
+    };
+
+    // ---- fragment addresses: lane l reads row (l & 31) of a 32-row block, chunk 2*sweep + (l >> 5)
+    const int fr = lane & 31, fh = lane >> 5;
+    uint32_t f_off[2][TM + TN], f_off_hi[2][TM + TN];   // [sweep][fragment]
+#pragma unroll
+    for (int sw = 0; sw < 2; ++sw) {
+#pragma unroll
+        for (int k = 0; k < TM + TN; ++k) {
+            const int row = (k < TM ? wm * WM + 32 * k : wn * WN + 32 * (k - TM)) + fr;
+            const int c = (2 * sw + fh) ^ ((row >> 2) & 3);
+            f_off[sw][k] = lds0 + (k < TM ? 0 : OP_BYTES) + row * ROWB + c * 16;
+            f_off_hi[sw][k] = f_off[sw][k] + 2 * STAGE_BYTES;
+            asm("" : "+v"(f_off_hi[sw][k]));
+        }
+    }
+    auto read_one = [&](Frags& F, int buf, int sw, int k) {
+        const uint32_t base = (buf & 2) ? f_off_hi[sw][k] : f_off[sw][k];
+        F.v[k] = lds_read8(base + (buf & 1) * STAGE_BYTES);
+    };
+    auto read_frags = [&](Frags& F, int buf, int sw) {
+#pragma unroll
+        for (int k = 0; k < TM + TN; ++k) read_one(F, buf, sw, k);
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    constexpr int NMMA = TM * TN, NRD = TM + TN;
+    auto mma = [&](const Frags& F, int m) {
+        const int i = m / TN, j = m % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(F.v[i], F.v[TM + j], acc[i][j], 0, 0, 0);
+    };
+
+    Frags F0, F1;
+    issue_stage(1);
+    issue_stage(2);
+    asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // stage 0 landed
+    __builtin_amdgcn_s_barrier();
+    read_frags(F0, 0, 0);
+    constexpr int PRE = NMMA / 4;
+    auto stage_body = [&](auto buf_tag) {
+        constexpr int B = decltype(buf_tag)::value;
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+#pragma unroll
+            for (int r = m * NRD / NMMA; r < (m + 1) * NRD / NMMA; ++r) read_one(F1, B, 1, r);
+            mma(F0, m);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int m = 0; m < PRE; ++m) mma(F1, m);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // next stage landed
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        stage_begin();
+#pragma unroll
+        for (int m = PRE; m < NMMA; ++m) {
+            constexpr int REST = NMMA - PRE;
+            const int q = m - PRE;
+#pragma unroll
+            for (int r = q * NRD / REST; r < (q + 1) * NRD / REST; ++r) read_one(F0, (B + 1) & 3, 0, r);
+#pragma unroll
+            for (int j = q * LOADS / REST; j < (q + 1) * LOADS / REST; ++j) issue_one(j, (B + 3) & 3);
+            mma(F1, m);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        stage_issued();
+    };
+    // four stages per trip (constant ring slots); surplus stages multiply zeros
+    for (int s = 0; s < n_st; s += 4) {
+        stage_body(std::integral_constant<int, 0>{});
+        stage_body(std::integral_constant<int, 1>{});
+        stage_body(std::integral_constant<int, 2>{});
+        stage_body(std::integral_constant<int, 3>{});
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
+
+    // ---- epilogue: acc[i][j][r] = E[o, n] with o = row0 + wn*WN + 32j + (lane & 31) and
+    // n = col0 + wm*WM + 32i + 8*(r/4) + 4*(lane >> 5) + (r & 3).  Multiply by dW'[o, n] (four
+    // consecutive n per 8-byte load) and add up over n inside the lane.
+    float v[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int64_t o = row0 + wn * WN + 32 * j + (lane & 31);
+        float sum = 0.0f;
+        if (o < out) {
+            const __half* arow = A + o * in;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int64_t n0 = col0 + wm * WM + 32 * i + 8 * g + 4 * (lane >> 5);
+                    if (n0 < in) {   // in % 8 == 0: the four columns are inside together
+                        const uint2 raw = *reinterpret_cast<const uint2*>(arow + n0);
+                        const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&raw.x));
+                        const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&raw.y));
+                        sum += acc[i][j][4 * g + 0] * a.x;
+                        sum += acc[i][j][4 * g + 1] * a.y;
+                        sum += acc[i][j][4 * g + 2] * b.x;
+                        sum += acc[i][j][4 * g + 3] * b.y;
+                    }
+                }
+            }
+        }
+        v[j] = sum + __shfl_xor(sum, 32, 64);
+    }
+    if (lane < 32) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) s_rows[wm][wn * WN + 32 * j + lane] = v[j];
+    }
+    __syncthreads();
+    if (tid < BT && row0 + tid < out) part[int64_t(slot) * out + row0 + tid] = s_rows[0][tid] + s_rows[1][tid];
+}
+
+}  // namespace edma
+
+}  // namespace

@@ -13,6 +13,7 @@
 // bit-reproducible.
 #include "common.h"
 #include "mfma_tile.h"
+#include "error_dma.h"
 
 namespace {
 
@@ -73,106 +74,56 @@ __global__ __launch_bounds__(256) void error_prologue(const void* __restrict__ d
     if (threadIdx.x == 0) diag[o] = s_red[0];
 }
 
-// One workgroup per (row block, column block) tile of E, longest contraction
-// first.  part[nb*out + o] = sum over the tile's columns n of E[o,n]*dW'[o,n].
-template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(THREADS) void error_tiles(const __half* __restrict__ A, const __half* __restrict__ Hs,
-                                                       int64_t out, int64_t in, int MB, int NB,
-                                                       float* __restrict__ part) {
-    static_assert(WGM * WGN == 4, "four wavefronts");
-    constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
-    extern __shared__ __align__(16) char smem[];
-    constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
-    auto sA = [&](int b) { return smem + b * (A_BYTES + B_BYTES); };
-    auto sB = [&](int b) { return smem + b * (A_BYTES + B_BYTES) + A_BYTES; };
-    __shared__ float s_rows[WGN][BM];
-
-    const int nb = NB - 1 - static_cast<int>(blockIdx.x / MB);
-    const int mb = static_cast<int>(blockIdx.x % MB);
-    const int64_t row0 = int64_t(mb) * BM, col0 = int64_t(nb) * BN;
-    const int64_t k_end = min(in, col0 + BN);  // Hs[n,k] = 0 for k >= n
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WGN, wn = wave % WGN;
-
-    floatx16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-    DirectStage<BM> ga;
-    DirectStage<BN> gb;
-    ga.load(A, in, row0, out, 0, k_end, tid);
-    gb.load(Hs, in, col0, in, 0, k_end, tid);
-    ga.store(sA(0), tid);
-    gb.store(sB(0), tid);
-    __syncthreads();
-    int buf = 0;
-    for (int64_t k0 = 0; k0 < k_end; k0 += KT) {
-        const bool more = k0 + KT < k_end;
-        if (more) {
-            ga.load(A, in, row0, out, k0 + KT, k_end, tid);
-            gb.load(Hs, in, col0, in, k0 + KT, k_end, tid);
-        }
-        mma_stage<TM, TN>(sA(buf), sB(buf), wm * WM, wn * WN, lane, acc);
-        if (more) {
-            ga.store(sA(buf ^ 1), tid);
-            gb.store(sB(buf ^ 1), tid);
-        }
-        __syncthreads();
-        buf ^= 1;
-    }
-
-    // epilogue: row sums of E .* dW' over this tile's columns
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int lrow = wm * WM + 32 * i + acc_row(r, lane);
-            const int64_t row = row0 + lrow;
-            float v = 0.0f;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int64_t col = col0 + wn * WN + 32 * j + (lane & 31);
-                if (row < out && col < in) v += acc[i][j][r] * __half2float(A[row * in + col]);
-            }
-#pragma unroll
-            for (int m = 1; m < 32; m <<= 1) v += __shfl_xor(v, m, 64);
-            if ((lane & 31) == 0) s_rows[wn][lrow] = v;
-        }
-    }
-    __syncthreads();
-    for (int r = tid; r < BM; r += THREADS) {
-        float v = s_rows[0][r];
-#pragma unroll
-        for (int w = 1; w < WGN; ++w) v += s_rows[w][r];
-        if (row0 + r < out) part[int64_t(nb) * out + row0 + r] = v;
-    }
-}
-
-// loss_rows[o] = diag[o] + 2*sum_nb part[nb,o];  loss = sum_o loss_rows[o].  One block.
-__global__ __launch_bounds__(1024) void error_finish(const float* __restrict__ diag, const float* __restrict__ part,
-                                                     int64_t out, int NB, float* __restrict__ loss_rows,
-                                                     float* __restrict__ loss) {
-    __shared__ double s_red[1024];
-    double tot = 0.0;
-    for (int64_t o = threadIdx.x; o < out; o += 1024) {
+// loss_rows[o] = diag[o] + 2*sum_slot part[slot,o] for 256 rows per block, a per-block total,
+// and, in the block that finishes last, loss = sum of the block totals in block order (so the
+// result does not depend on which block that is).  `ticket` must be zero on entry and is zero
+// again on exit.
+__global__ __launch_bounds__(256) void error_finish(const float* __restrict__ diag, const float* __restrict__ part,
+                                                    int64_t out, int n_slots, float* __restrict__ loss_rows,
+                                                    float* __restrict__ loss, double* __restrict__ block_tot,
+                                                    unsigned int* __restrict__ ticket) {
+    __shared__ double s_red[256];
+    __shared__ bool s_last;
+    const int64_t o = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    double mine = 0.0;
+    if (o < out) {
         float off = 0.0f;
-        for (int nb = 0; nb < NB; ++nb) off += part[int64_t(nb) * out + o];
+        for (int sl = 0; sl < n_slots; ++sl) off += part[int64_t(sl) * out + o];
         const float l = diag[o] + 2.0f * off;
         if (loss_rows) loss_rows[o] = l;
-        tot += static_cast<double>(l);
+        mine = static_cast<double>(l);
     }
-    s_red[threadIdx.x] = tot;
+    s_red[threadIdx.x] = mine;
     __syncthreads();
-    for (int s = 512; s > 0; s >>= 1) {
+    for (int s = 128; s > 0; s >>= 1) {
         if (threadIdx.x < s) s_red[threadIdx.x] += s_red[threadIdx.x + s];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *loss = static_cast<float>(s_red[0]);
+    if (threadIdx.x == 0) {
+        block_tot[blockIdx.x] = s_red[0];
+        __threadfence();
+        s_last = atomicAdd(ticket, 1u) == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    double tot = 0.0;
+    for (unsigned b = threadIdx.x; b < gridDim.x; b += 256) tot += __builtin_nontemporal_load(block_tot + b);
+    s_red[threadIdx.x] = tot;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) s_red[threadIdx.x] += s_red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        *loss = static_cast<float>(s_red[0]);
+        *ticket = 0u;
+    }
+}
+
+__global__ void fill_zero_f32(float* p, int64_t n) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
 }
 
 __global__ void select_first_min(const float* __restrict__ losses, int n, int32_t* __restrict__ best) {
@@ -190,37 +141,50 @@ __global__ void select_first_min(const float* __restrict__ losses, int n, int32_
     *best = b < 0 ? 0 : b;
 }
 
-template <int BM, int BN, int WGM, int WGN>
-int run_error_tiles(adadim_ctx* ctx, const __half* A, const __half* Hs, int64_t out, int64_t in, float* part,
-                    int* NB_out) {
-    const int MB = static_cast<int>((out + BM - 1) / BM), NB = static_cast<int>((in + BN - 1) / BN);
-    constexpr int smem = 2 * (BM + BN) * ROW_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(error_tiles<BM, BN, WGM, WGN>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        attr_set = true;
-    }
-    {
-        ProfScope prof(ctx, "error_tiles");
-        hipLaunchKernelGGL((error_tiles<BM, BN, WGM, WGN>), dim3(static_cast<unsigned>(int64_t(MB) * NB)),
-                           dim3(THREADS), smem, ctx->stream, A, Hs, out, in, MB, NB, part);
-    }
-    ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
-    *NB_out = NB;
-    return ADADIM_OK;
-}
-
 }  // namespace
 
 int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in, const __half* Hs,
                        const float* hmeta, float* loss_rows, float* loss) {
-    constexpr int BN = 256;
-    const int NB = static_cast<int>((in + BN - 1) / BN);
-    // scratch: [NB+1, out] floats: row partials per column block, then the diagonal term
-    float* part = static_cast<float*>(adadim_workspace(ctx, WS_ERR_PART, size_t(NB + 1) * size_t(out) * sizeof(float)));
+    constexpr int BT = edma::BT;
+    const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
+    // Contraction chunk: about half of the work one compute unit gets, in 256-k blocks,
+    // so that the triangular work balances without multiplying epilogues.
+    const int64_t total_blocks = int64_t(MB) * NB * (NB + 1) / 2;
+    int kb = static_cast<int>(total_blocks / (256 * 2));
+    kb = kb < 1 ? 1 : (kb > 16 ? 16 : kb);
+    const int kc_len = kb * BT;
+    int n_slots = 0;
+    for (int nb = 0; nb < NB; ++nb) {
+        const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
+        n_slots += static_cast<int>((kend + kc_len - 1) / kc_len);
+    }
+    // scratch: [n_slots+1, out] floats: row partials per (column block, chunk), then the diagonal term
+    float* part = static_cast<float*>(
+        adadim_workspace(ctx, WS_ERR_PART, size_t(n_slots + 1) * size_t(out) * sizeof(float)));
     if (!part) return ADADIM_EHIP;
-    float* diag = part + size_t(NB) * size_t(out);
+    float* diag = part + size_t(n_slots) * size_t(out);
+    // scratch of the final reduction: one double per 256 rows, then the (self-resetting) ticket
+    const unsigned fin_blocks = static_cast<unsigned>((out + 255) / 256);
+    const size_t fin_bytes = size_t(fin_blocks) * sizeof(double) + 256;
+    const bool fin_fresh = ctx->ws_bytes[WS_ERR_FIN] < fin_bytes;
+    double* block_tot = static_cast<double*>(adadim_workspace(ctx, WS_ERR_FIN, fin_bytes));
+    if (!block_tot) return ADADIM_EHIP;
+    unsigned int* ticket = reinterpret_cast<unsigned int*>(block_tot + (ctx->ws_bytes[WS_ERR_FIN] - 256) / sizeof(double));
+    if (fin_fresh) {
+        hipLaunchKernelGGL(fill_zero_f32, dim3(1), dim3(64), 0, ctx->stream, reinterpret_cast<float*>(ticket),
+                           int64_t(64));
+        ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
+    }
+    void* zero16 = adadim_workspace(ctx, WS_ZERO, 256);
+    if (!zero16) return ADADIM_EHIP;
+    if (ctx->zero_ready_bytes != ctx->ws_bytes[WS_ZERO]) {
+        // a fill kernel rather than a memset node, so that the call stays safe to capture in a graph
+        const int64_t n = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
+        hipLaunchKernelGGL(fill_zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                           static_cast<float*>(zero16), n);
+        ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
+        ctx->zero_ready_bytes = ctx->ws_bytes[WS_ZERO];
+    }
     const __half* A = static_cast<const __half*>(dW);
     __half* dW16 = nullptr;
     if (dW_dtype != ADADIM_DW_F16_SCALED) {
@@ -234,16 +198,23 @@ int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t ou
                            in, hmeta, dW16, diag);
     }
     ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
-    int nb_used = 0;
-    int rc;
-    if (out <= 2048 || (out / 256) * NB < 512)
-        rc = run_error_tiles<128, BN, 1, 4>(ctx, A, Hs, out, in, part, &nb_used);
-    else
-        rc = run_error_tiles<256, BN, 2, 2>(ctx, A, Hs, out, in, part, &nb_used);
-    if (rc != ADADIM_OK) return rc;
+    static bool attr_set = false;
+    if (!attr_set) {
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(edma::error_tiles_dma),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, edma::SMEM_BYTES));
+        attr_set = true;
+    }
+    {
+        ProfScope prof(ctx, "error_tiles");
+        const unsigned grid = 8u * static_cast<unsigned>((int64_t(n_slots) * MB + 7) / 8);
+        hipLaunchKernelGGL(edma::error_tiles_dma, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, A, Hs, out,
+                           in, MB, NB, kc_len, n_slots, zero16, part);
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
     {
         ProfScope prof(ctx, "error_finish");
-        hipLaunchKernelGGL(error_finish, dim3(1), dim3(1024), 0, ctx->stream, diag, part, out, nb_used, loss_rows, loss);
+        hipLaunchKernelGGL(error_finish, dim3(fin_blocks), dim3(256), 0, ctx->stream, diag, part, out, n_slots,
+                           loss_rows, loss, block_tot, ticket);
     }
     ADADIM_LAUNCH_CHECK(ctx, "error_finish");
     return ADADIM_OK;
