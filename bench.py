@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy, the reference dispatch that scales "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (layers are independent; see DESIGN.md for how the "
@@ -116,6 +119,13 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ctx.adadim_profile(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -156,7 +166,7 @@ def main():
             "tflops_dense_equivalent": 2.0 * out_f * in_f * in_f / s / 1e12,
         }
     qbytes = out_f * in_f * (2 + 2) + 5.0 * out_f * in_f / group   # W read + fp16 dW written + scale/zero
-    for k in ("quant_oc_lanes", "quant_ic_tile"):
+    for k in ("quant_oc", "quant_ic"):
         if k in kern:
             s = kern[k]["avg_us"] * 1e-6
             comps[k] = {"avg_us": s * 1e6, "GBps_algorithmic": qbytes / s / 1e9, "frac_hbm": qbytes / s / HBM_PEAK,

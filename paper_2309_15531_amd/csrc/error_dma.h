@@ -78,12 +78,12 @@ __global__ __launch_bounds__(256) void error_tiles_dma(const __half* __restrict_
     __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
-    // work item = slot * MB + mb; XCD x takes the x-th contiguous eighth of the list
-    const int total = n_slots * MB;
-    const int per_xcd = (total + 7) / 8;
-    const int item = static_cast<int>(blockIdx.x % 8) * per_xcd + static_cast<int>(blockIdx.x / 8);
-    if (static_cast<int>(blockIdx.x / 8) >= per_xcd || item >= total) return;
-    const int slot = item / MB, mb = item - slot * MB;
+    // Workgroups go to the eight XCDs round-robin by launch index.  Slots are sorted by
+    // decreasing contraction length, so XCD x takes slots x, x+8, x+16, ... (a balanced share,
+    // longest first) and all MB row blocks of a slot run on the same XCD, sharing its Hs tile in L2.
+    const int xcd = static_cast<int>(blockIdx.x % 8), seq = static_cast<int>(blockIdx.x / 8);
+    const int slot = (seq / MB) * 8 + xcd, mb = seq % MB;
+    if (slot >= n_slots) return;
     int nb = NB - 1, rem = slot;
     for (;;) {
         const int c = chunks_of(nb, in, kc_len);

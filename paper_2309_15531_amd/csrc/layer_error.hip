@@ -206,7 +206,7 @@ int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t ou
     }
     {
         ProfScope prof(ctx, "error_tiles");
-        const unsigned grid = 8u * static_cast<unsigned>((int64_t(n_slots) * MB + 7) / 8);
+        const unsigned grid = 8u * static_cast<unsigned>((n_slots + 7) / 8) * static_cast<unsigned>(MB);
         hipLaunchKernelGGL(edma::error_tiles_dma, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, A, Hs, out,
                            in, MB, NB, kc_len, n_slots, zero16, part);
     }

@@ -10,6 +10,7 @@
 // kernel re-reads its tile from cache) with 16-byte loads and writes each
 // output once.
 #include "common.h"
+#include "fastdiv.h"
 
 namespace {
 
@@ -87,61 +88,6 @@ __device__ __forceinline__ void store_dw1(void* dW, int dW_dtype, const float* _
     }
 }
 
-// ---------------------------------------------------------------------------
-// per-OC, group = 8*LPG contiguous halfs: LPG adjacent lanes own one group,
-// each lane 8 halfs (one 16-byte load).  W is addressed as a flat array of
-// 16-byte chunks because groups never straddle rows.
-template <int LPG>
-__global__ __launch_bounds__(256) void quant_oc_lanes(const uint4* __restrict__ W, int64_t n_chunks,
-                                                      int chunks_per_row, float clip, float qmax,
-                                                      uint8_t* __restrict__ codes, float* __restrict__ scales,
-                                                      uint8_t* __restrict__ zeros, void* __restrict__ dW,
-                                                      int dW_dtype, const float* __restrict__ colscale) {
-    const int64_t c = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    const bool valid = c < n_chunks;
-    float w[8];
-    uint4 raw = make_uint4(0, 0, 0, 0);
-    if (valid) raw = W[c];
-    unpack8(raw, w);
-    float mn = w[0], mx = w[0];
-#pragma unroll
-    for (int i = 1; i < 8; ++i) {
-        mn = fminf(mn, w[i]);
-        mx = fmaxf(mx, w[i]);
-    }
-#pragma unroll
-    for (int m = 1; m < LPG; m <<= 1) {
-        mn = fminf(mn, __shfl_xor(mn, m, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-    }
-    if (!valid) return;
-    const GroupParams gp = group_params(mn, mx, clip, qmax);
-    if ((c & (LPG - 1)) == 0) {
-        const int64_t grp = c / LPG;
-        if (scales) scales[grp] = gp.scale;
-        if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
-    }
-    float q[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = quant_code(w[i], gp.scale, gp.zero, qmax);
-    if (codes) {
-        uint32_t lo = 0, hi = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            lo |= static_cast<uint32_t>(q[i]) << (8 * i);
-            hi |= static_cast<uint32_t>(q[4 + i]) << (8 * i);
-        }
-        reinterpret_cast<uint2*>(codes)[c] = make_uint2(lo, hi);
-    }
-    if (dW) {
-        float d[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) d[i] = weight_error(w[i], q[i], gp.scale, gp.zero);
-        const int64_t col = (c % chunks_per_row) * 8;
-        store_dw8(dW, dW_dtype, colscale, c * 8, col, d);
-    }
-}
-
 // per-OC, any group length: one wavefront per group, element-wise accesses.
 __global__ __launch_bounds__(256) void quant_oc_generic(const __half* __restrict__ W, int64_t n_groups, int g,
                                                         int64_t in, float clip, float qmax,
@@ -173,6 +119,202 @@ __global__ __launch_bounds__(256) void quant_oc_generic(const __half* __restrict
         const float q = quant_code(w, gp.scale, gp.zero, qmax);
         if (codes) codes[base + i] = static_cast<uint8_t>(q);
         if (dW) store_dw1(dW, dW_dtype, colscale, base + i, (base + i) % in, weight_error(w, q, gp.scale, gp.zero));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fast paths.  Same arithmetic, organised for bandwidth:
+//  * the per-weight division uses the group's correctly rounded reciprocal
+//    (fastdiv.h: three operations, bit-identical to the IEEE quotient);
+//  * min/max across the lanes of a group go through DPP row operations
+//    instead of LDS permutes;
+//  * several 16-byte chunks per thread are in flight at once;
+//  * the bit stream is assembled in registers (2, 3, 4 and 8 bits).
+
+struct GroupParamsR {
+    float scale, zero, rcp;
+    bool fast;
+};
+
+// IEEE division that the optimiser may not hoist out of the (rarely taken, wave-uniform)
+// branch it sits in: the empty volatile asm pins it there.
+__device__ __forceinline__ float pinned_div(float a, float b) {
+    asm volatile("" : "+v"(a));
+    return a / b;
+}
+
+// Same results as group_params, with the divisions replaced by fastdiv where its
+// preconditions hold: range/qmax through the reciprocal of qmax (exact for every
+// range, see fastdiv_check.cpp), -mn/scale through the reciprocal of the scale when
+// mn is an fp16 value (clip == 1).  The plain divisions sit behind wave-uniform
+// branches so that they cost nothing when no lane needs them.
+__device__ __forceinline__ GroupParamsR group_params_r(float mn, float mx, float clip, float qmax, float rqmax) {
+    mx = fmaxf(mx, 0.0f);
+    mn = fminf(mn, 0.0f);
+    mx = clip * mx;
+    mn = clip * mn;
+    const float range = mx - mn;
+    float scale = fastdiv(range, qmax, rqmax);
+    if (__any(!(range >= 8.6736174e-19f) && range != 0.0f)) scale = pinned_div(range, qmax);   // below 2^-60: tiny clip
+    if (range == 0.0f) scale = 1.0f;
+    const float rcp = 1.0f / scale;
+    const bool fast = fastdiv_ok(scale);
+    float zq = fastdiv(-mn, scale, rcp);
+    if (__any(!fast || clip != 1.0f)) zq = pinned_div(-mn, scale);
+    const float z = __builtin_amdgcn_fmed3f(rintf(zq), 0.0f, qmax);
+    return {scale, z, rcp, fast};
+}
+
+// 8 codes of one lane; the plain division only runs if some lane of the wave needs it
+__device__ __forceinline__ void quant_codes8(const float (&w)[8], const float (&sc)[8], const float (&zp)[8],
+                                             const float (&rc)[8], bool all_fast, float qmax, float (&q)[8]) {
+    float quo[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) quo[i] = fastdiv(w[i], sc[i], rc[i]);
+    if (__any(!all_fast)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) quo[i] = pinned_div(w[i], sc[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) q[i] = __builtin_amdgcn_fmed3f(rintf(quo[i]) + zp[i], 0.0f, qmax);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
+}
+
+// min and max over clusters of LPG adjacent lanes (LPG a power of two, aligned).
+// quad_perm [1,0,3,2] and [2,3,0,1] exchange inside a quad, row_half_mirror
+// pairs the two quads of 8 lanes, row_mirror the two halves of a 16-lane row.
+template <int LPG>
+__device__ __forceinline__ void cluster_minmax(float& mn, float& mx) {
+    if constexpr (LPG >= 2) {
+        mn = fminf(mn, dpp_f<0xB1>(mn));
+        mx = fmaxf(mx, dpp_f<0xB1>(mx));
+    }
+    if constexpr (LPG >= 4) {
+        mn = fminf(mn, dpp_f<0x4E>(mn));
+        mx = fmaxf(mx, dpp_f<0x4E>(mx));
+    }
+    if constexpr (LPG >= 8) {
+        mn = fminf(mn, dpp_f<0x141>(mn));
+        mx = fmaxf(mx, dpp_f<0x141>(mx));
+    }
+    if constexpr (LPG >= 16) {
+        mn = fminf(mn, dpp_f<0x140>(mn));
+        mx = fmaxf(mx, dpp_f<0x140>(mx));
+    }
+    if constexpr (LPG >= 32) {
+        mn = fminf(mn, __shfl_xor(mn, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    }
+    if constexpr (LPG >= 64) {
+        mn = fminf(mn, __shfl_xor(mn, 32, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    }
+}
+
+// Bit stream of 8 codes held by one lane, for chunk c of a flat [out, in] weight.
+// PB = bits per code (2, 3, 4 or 8).  Words are written straight to `packed`
+// (rows are whole numbers of words because in % 32 == 0).
+template <int PB>
+__device__ __forceinline__ void pack8_store(const float (&q)[8], int64_t c, bool valid,
+                                            uint32_t* __restrict__ packed) {
+    uint32_t lo = 0, hi = 0;  // 8*PB bits, little end first
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t code = static_cast<uint32_t>(q[i]);
+        const int bit = i * PB;
+        if (bit < 32) lo |= code << bit;
+        if (bit + PB > 32) hi |= bit >= 32 ? code << (bit - 32) : code >> (32 - bit);
+    }
+    if constexpr (PB == 8) {
+        if (valid) reinterpret_cast<uint2*>(packed)[c] = make_uint2(lo, hi);
+    } else if constexpr (PB == 4) {
+        if (valid) packed[c] = lo;
+    } else if constexpr (PB == 2) {
+        const uint32_t other = dpp_u<0xB1>(lo);       // partner lane's 16 bits
+        if (valid && (c & 1) == 0) packed[c >> 1] = lo | (other << 16);
+    } else {                                           // PB == 3: four lanes -> three words
+        const uint32_t next = dpp_u<0xF9>(lo);        // quad_perm [1,2,3,3]: the next lane's 24 bits
+        const int j = static_cast<int>(c & 3);
+        if (valid && j < 3) packed[(c >> 2) * 3 + j] = (lo >> (8 * j)) | (next << (24 - 8 * j));
+    }
+}
+
+// per-OC fast path: LPG lanes per group, U chunks per thread.
+template <int LPG, int PB>
+__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t n_chunks,
+                                                     int chunks_per_row, float clip, float qmax, float rqmax,
+                                                     uint8_t* __restrict__ codes, float* __restrict__ scales,
+                                                     uint8_t* __restrict__ zeros, void* __restrict__ dW,
+                                                     int dW_dtype, const float* __restrict__ colscale,
+                                                     uint32_t* __restrict__ packed) {
+    constexpr int U = 4;
+    const int64_t base = int64_t(blockIdx.x) * (256 * U) + threadIdx.x;
+    // column chunk of the first chunk (32-bit arithmetic: the launcher keeps n_chunks below 2^31);
+    // later chunks follow by adding 256 and wrapping
+    uint32_t cc = dW_dtype == ADADIM_DW_F16_SCALED
+                      ? static_cast<uint32_t>(base) % static_cast<uint32_t>(chunks_per_row)
+                      : 0u;
+    uint4 raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * 256;
+        raw[u] = c < n_chunks ? W[c] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + u * 256;
+        float w[8];
+        unpack8(raw[u], w);
+        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
+        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
+        cluster_minmax<LPG>(mn, mx);
+        const GroupParamsR gp = group_params_r(mn, mx, clip, qmax, rqmax);
+        float q[8];
+        {
+            float sc[8], zp[8], rc[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                sc[i] = gp.scale;
+                zp[i] = gp.zero;
+                rc[i] = gp.rcp;
+            }
+            quant_codes8(w, sc, zp, rc, gp.fast, qmax, q);
+        }
+        if constexpr (PB != 0) {
+            if (packed) pack8_store<PB>(q, c, c < n_chunks, packed);   // all lanes take part in the DPP
+        }
+        if (c >= n_chunks) continue;
+        if ((c & (LPG - 1)) == 0) {
+            const int64_t grp = c / LPG;
+            if (scales) scales[grp] = gp.scale;
+            if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
+        }
+        if (codes) {
+            uint32_t lo = 0, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo |= static_cast<uint32_t>(q[i]) << (8 * i);
+                hi |= static_cast<uint32_t>(q[4 + i]) << (8 * i);
+            }
+            reinterpret_cast<uint2*>(codes)[c] = make_uint2(lo, hi);
+        }
+        if (dW) {
+            float d[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) d[i] = weight_error(w[i], q[i], gp.scale, gp.zero);
+            uint32_t ccu = cc + u * 256;
+            while (ccu >= static_cast<uint32_t>(chunks_per_row)) ccu -= chunks_per_row;
+            store_dw8(dW, dW_dtype, colscale, c * 8, int64_t(ccu) * 8, d);
+        }
     }
 }
 
@@ -283,6 +425,104 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
     }
 }
 
+// per-IC fast path: group = 8*RPT rows.  A block of 8*TXW threads owns one row group x 8*TXW
+// columns; thread (tx, ty) keeps rows ty*RPT .. ty*RPT+RPT-1 of its 8 columns in registers, so W
+// is read once.  TXW = 64 makes every wavefront access one whole 1 KB row segment.
+template <int RPT, int TXW>
+__global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restrict__ W, int64_t in, float clip,
+                                                     float qmax, float rqmax, uint8_t* __restrict__ codes,
+                                                     float* __restrict__ scales, uint8_t* __restrict__ zeros,
+                                                     void* __restrict__ dW, int dW_dtype,
+                                                     const float* __restrict__ colscale) {
+    constexpr int G = 8 * RPT, COLS = 8 * TXW, NT = 8 * TXW;
+    __shared__ float s_mn[8][COLS];
+    __shared__ float s_mx[8][COLS];
+    __shared__ float s_scale[COLS];
+    __shared__ float s_zero[COLS];
+    __shared__ float s_rcp[COLS];
+
+    const int tx = threadIdx.x % TXW, ty = threadIdx.x / TXW;
+    const int64_t col0 = int64_t(blockIdx.x) * COLS + tx * 8;
+    const int64_t row0 = int64_t(blockIdx.y) * G + ty * RPT;
+    const bool col_ok = col0 < in;
+
+    uint4 raw[RPT];
+#pragma unroll
+    for (int r = 0; r < RPT; ++r)
+        raw[r] = col_ok ? *reinterpret_cast<const uint4*>(W + (row0 + r) * in + col0) : make_uint4(0, 0, 0, 0);
+    float mn[8], mx[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v) mn[v] = mx[v] = 0.0f;
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        float w[8];
+        unpack8(raw[r], w);
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            mn[v] = fminf(mn[v], w[v]);
+            mx[v] = fmaxf(mx[v], w[v]);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        s_mn[ty][tx * 8 + v] = mn[v];
+        s_mx[ty][tx * 8 + v] = mx[v];
+    }
+    __syncthreads();
+    for (int cidx = threadIdx.x; cidx < COLS; cidx += NT) {   // COLS == NT: one column per thread, all lanes active
+        float a = s_mn[0][cidx], b = s_mx[0][cidx];
+#pragma unroll
+        for (int y = 1; y < 8; ++y) {
+            a = fminf(a, s_mn[y][cidx]);
+            b = fmaxf(b, s_mx[y][cidx]);
+        }
+        const GroupParamsR gp = group_params_r(a, b, clip, qmax, rqmax);
+        s_scale[cidx] = gp.scale;
+        s_zero[cidx] = gp.zero;
+        s_rcp[cidx] = gp.rcp;
+        const int64_t col = int64_t(blockIdx.x) * COLS + cidx;
+        if (col < in) {
+            const int64_t gi = int64_t(blockIdx.y) * in + col;
+            if (scales) scales[gi] = gp.scale;
+            if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
+        }
+    }
+    __syncthreads();
+    if (!codes && !dW) return;
+    float sc[8], zp[8], rc[8];
+    bool all_fast = true;
+#pragma unroll
+    for (int v = 0; v < 8; ++v) {
+        sc[v] = s_scale[tx * 8 + v];
+        zp[v] = s_zero[tx * 8 + v];
+        rc[v] = s_rcp[tx * 8 + v];
+        all_fast = all_fast && fastdiv_ok(sc[v]);
+    }
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+        const int64_t elem = (row0 + r) * in + col0;
+        float w[8], q[8];
+        unpack8(raw[r], w);
+        quant_codes8(w, sc, zp, rc, all_fast, qmax, q);   // every lane reaches the wave-wide test inside
+        if (!col_ok) continue;
+        if (codes) {
+            uint32_t lo = 0, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo |= static_cast<uint32_t>(q[i]) << (8 * i);
+                hi |= static_cast<uint32_t>(q[4 + i]) << (8 * i);
+            }
+            *reinterpret_cast<uint2*>(codes + elem) = make_uint2(lo, hi);
+        }
+        if (dW) {
+            float d[8];
+#pragma unroll
+            for (int v = 0; v < 8; ++v) d[v] = weight_error(w[v], q[v], sc[v], zp[v]);
+            store_dw8(dW, dW_dtype, colscale, elem, col0, d);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Bit-packing: one thread assembles one 32-bit word of a channel's stream.
 // channel stride / element stride describe where code k of channel ch lives:
@@ -312,17 +552,36 @@ __global__ __launch_bounds__(256) void pack_words(const uint8_t* __restrict__ co
 }
 
 template <int LPG>
-void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax,
+void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
                      uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
-                     const float* colscale) {
+                     const float* colscale, uint32_t* packed) {
     const int64_t n_chunks = out * in / 8;
-    const unsigned blocks = static_cast<unsigned>((n_chunks + 255) / 256);
-    {
-        ProfScope prof(ctx, "quant_oc_lanes");
-        hipLaunchKernelGGL(quant_oc_lanes<LPG>, dim3(blocks), dim3(256), 0, ctx->stream,
-                           reinterpret_cast<const uint4*>(W), n_chunks, static_cast<int>(in / 8), clip, qmax, codes,
-                           scales, zeros, dW, dW_dtype, colscale);
+    const unsigned blocks = static_cast<unsigned>((n_chunks + 1023) / 1024);
+    const uint4* W4 = reinterpret_cast<const uint4*>(W);
+    const int cpr = static_cast<int>(in / 8);
+    ProfScope prof(ctx, "quant_oc");
+#define OC_GO(PB)                                                                                                  \
+    hipLaunchKernelGGL((quant_oc_fast<LPG, PB>), dim3(blocks), dim3(256), 0, ctx->stream, W4, n_chunks, cpr, clip, \
+                       qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed)
+    switch (pb) {
+        case 2: OC_GO(2); break;
+        case 3: OC_GO(3); break;
+        case 4: OC_GO(4); break;
+        case 8: OC_GO(8); break;
+        default: OC_GO(0); break;
     }
+#undef OC_GO
+}
+
+template <int RPT>
+void launch_ic_regs(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax,
+                    uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
+                    const float* colscale) {
+    constexpr int TXW = 32;
+    dim3 grid(static_cast<unsigned>((in + 8 * TXW - 1) / (8 * TXW)), static_cast<unsigned>(out / (8 * RPT)));
+    ProfScope prof(ctx, "quant_ic");
+    hipLaunchKernelGGL((quant_ic_regs<RPT, TXW>), grid, dim3(8 * TXW), 0, ctx->stream, W, in, clip, qmax,
+                       1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale);
 }
 
 }  // namespace
@@ -348,21 +607,27 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
                     float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
                     const float* colscale, uint32_t* packed) {
     const float qmax = static_cast<float>((1 << bits) - 1);
-    if (packed && !codes) {
+    const bool vec = (in % 8) == 0;
+    const int lpg = g / 8;
+    const bool oc_lanes = dim == ADADIM_DIM_OC && vec && (g % 8) == 0 && lpg <= 64 && (lpg & (lpg - 1)) == 0 &&
+                          out * in / 8 < (int64_t(1) << 31);
+    // the per-OC fast kernel assembles the bit stream itself for these widths
+    const bool fused_pack =
+        packed && oc_lanes && (in % 32) == 0 && (bits == 2 || bits == 3 || bits == 4 || bits == 8);
+    if (packed && !fused_pack && !codes) {
         codes = static_cast<uint8_t*>(adadim_workspace(ctx, WS_CODES, size_t(out) * size_t(in)));
         if (!codes) return ADADIM_EHIP;
     }
-    const bool vec = (in % 8) == 0;
     if (dim == ADADIM_DIM_OC) {
-        const int lpg = g / 8;
-        const bool lanes = vec && (g % 8) == 0 && lpg <= 64 && (lpg & (lpg - 1)) == 0;
-        if (lanes) {
+        if (oc_lanes) {
+            const int pb = fused_pack ? bits : 0;
+            uint32_t* pk = fused_pack ? packed : nullptr;
             switch (lpg) {
-#define OC_CASE(n) case n: launch_oc_lanes<n>(ctx, W, out, in, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale); break;
+#define OC_CASE(n) case n: launch_oc_lanes<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk); break;
                 OC_CASE(1) OC_CASE(2) OC_CASE(4) OC_CASE(8) OC_CASE(16) OC_CASE(32) OC_CASE(64)
 #undef OC_CASE
             }
-            ADADIM_LAUNCH_CHECK(ctx, "quant_oc_lanes");
+            ADADIM_LAUNCH_CHECK(ctx, "quant_oc_fast");
         } else {
             const int64_t n_groups = out * (in / g);
             const unsigned blocks = static_cast<unsigned>((n_groups + 3) / 4);
@@ -377,13 +642,22 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
         const int64_t row_groups = out / g;
         if (row_groups > 65535)
             return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: more than 65535 row groups per column");
-        if (vec) {
+        const bool regs = vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
+        if (regs) {
+            switch (lpg) {
+#define IC_CASE(n) case n: launch_ic_regs<n>(ctx, W, out, in, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale); break;
+                IC_CASE(1) IC_CASE(2) IC_CASE(4) IC_CASE(8) IC_CASE(16) IC_CASE(32)
+#undef IC_CASE
+            }
+            ADADIM_LAUNCH_CHECK(ctx, "quant_ic_regs");
+        } else if (vec) {
             dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(row_groups));
             {
                 ProfScope prof(ctx, "quant_ic_tile");
                 hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
                                    scales, zeros, dW, dW_dtype, colscale);
             }
+            ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");
         } else {
             dim3 grid(static_cast<unsigned>((in + 31) / 32), static_cast<unsigned>(row_groups));
             {
@@ -391,9 +665,9 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
                 hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
                                    scales, zeros, dW, dW_dtype, colscale);
             }
+            ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");
         }
-        ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");
     }
-    if (packed) return launch_pack(ctx, codes, out, in, dim, bits, packed);
+    if (packed && !fused_pack) return launch_pack(ctx, codes, out, in, dim, bits, packed);
     return ADADIM_OK;
 }

@@ -125,3 +125,20 @@ def test_product_does_not_import_oracle():
         if f.endswith(".py"):
             src = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2309_15531_amd" not in src and "ctypes" not in src, f
+
+
+def test_fast_division_matches_ieee(tmp_path):
+    """The quantizer's three-operation quotient (csrc/fastdiv.h) must equal the IEEE
+    division for every fp16-valued numerator; sampled here (2^12 scale significands per
+    weight significand, four exponent pairs, both signs), exhaustive with argument 23."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    exe = tmp_path / "fastdiv_check"
+    src = os.path.join(ROOT, "tests", "host", "fastdiv_check.cpp")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-mfma", "-ffp-contract=off", "-pthread", src, "-o", str(exe)],
+                   check=True)
+    res = subprocess.run([str(exe), "12", "8"], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout
+    assert " 0 mismatches" in res.stdout
