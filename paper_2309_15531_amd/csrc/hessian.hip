@@ -184,14 +184,24 @@ template <int BT>
 int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H, int accumulate) {
     const int nb = static_cast<int>((in + BT - 1) / BT);
     const int n_tiles = nb * (nb + 1) / 2;
-    // Split the tokens so that there are a few workgroups per compute unit, in
-    // whole LDS stages, but never more than 32 ways.
+    // Token split: every (tile, split) is one workgroup and one workgroup fits a compute unit, so
+    // the tile kernel runs in about ceil(workgroups / 256) rounds of stages/n_split stages each,
+    // while every split adds one partial tile per tile to write and to read back.  Take the split
+    // count with the lowest estimate (unit: the time of one 32-token stage; a 256x256 partial
+    // costs about a fifth of that per split in traffic).
     constexpr int STAGE = BT == 256 ? dma::KT : KT;
     const int64_t stages = (tokens + STAGE - 1) / STAGE;
-    int n_split = static_cast<int>((4 * 256 + n_tiles - 1) / n_tiles);
-    if (n_split > 32) n_split = 32;
-    if (n_split > stages) n_split = static_cast<int>(stages);
-    if (n_split < 1) n_split = 1;
+    int n_split = 1;
+    double best_cost = 0.0;
+    for (int n = 1; n <= 32 && n <= stages; ++n) {
+        const int64_t per = (stages + n - 1) / n;
+        const int64_t rounds = (int64_t(n_tiles) * n + 255) / 256;
+        const double cost = double(rounds) * double(per) + 0.19 * double(n) * double(n_tiles) * (BT * BT / 65536.0);
+        if (n == 1 || cost < best_cost) {
+            best_cost = cost;
+            n_split = n;
+        }
+    }
     const int64_t t_per_split = ((stages + n_split - 1) / n_split) * STAGE;
     n_split = static_cast<int>((tokens + t_per_split - 1) / t_per_split);
 
