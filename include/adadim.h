@@ -141,6 +141,14 @@ int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, i
                                 const void* Hs, const float* hmeta, float* loss_rows, float* loss);
 
 /*
+ * The same for n candidates that share H, in one pass (the Hs tiles are fetched once for
+ * all of them): dW is a HOST array of n device pointers, each [out, in] of type dW_dtype;
+ * losses is a device array of n floats, loss_rows optional device [n, out].
+ */
+int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out,
+                             int64_t in, const void* Hs, const float* hmeta, float* loss_rows, float* losses);
+
+/*
  * Eq. 1's argmin: index of the first minimum of losses[0..n) (a later
  * candidate wins only if strictly lower, as in App. B where 'oc' is visited
  * before 'ic').  NaN entries never win.

@@ -20,7 +20,7 @@ DW_F32, DW_F16, DW_F16_SCALED = 0, 1, 2
 EXPORTS = (
     "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version",
     "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
-    "adadim_layer_error", "adadim_layer_error_prepared", "adadim_select",
+    "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -64,6 +64,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_layer_error_prepared.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p,
                                                 c_void_p, c_void_p]
     lib.adadim_layer_error_prepared.restype = c_int
+    lib.adadim_layer_error_batch.argtypes = [c_void_p, c_int, POINTER(c_void_p), c_int, c_int64, c_int64, c_void_p,
+                                             c_void_p, c_void_p, c_void_p]
+    lib.adadim_layer_error_batch.restype = c_int
     lib.adadim_select.argtypes = [c_void_p, c_void_p, c_int, c_void_p, POINTER(c_int32)]
     lib.adadim_select.restype = c_int
     lib.adadim_profile.argtypes = [c_void_p, c_int]
@@ -147,6 +150,12 @@ class Context:
         out_f, in_f = dW.shape
         self._check(self._lib.adadim_layer_error_prepared(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(Hs),
                                                           _ptr(hmeta), _ptr(loss_rows), _ptr(loss)))
+
+    def adadim_layer_error_batch(self, dWs, dW_dtype: int, Hs, hmeta, losses, loss_rows=None):
+        out_f, in_f = dWs[0].shape
+        arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
+        self._check(self._lib.adadim_layer_error_batch(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
+                                                       _ptr(hmeta), _ptr(loss_rows), _ptr(losses)))
 
     def adadim_select(self, losses, n: int | None = None, best_dev=None, to_host: bool = True):
         n = losses.numel() if n is None else n

@@ -240,7 +240,7 @@ int adadim_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t ou
     if (!Hs || !hmeta) return ADADIM_EHIP;
     rc = launch_hessian_prepare(ctx, H, in, Hs, hmeta);
     if (rc != ADADIM_OK) return rc;
-    return launch_layer_error(ctx, dW, dW_dtype, out, in, Hs, hmeta, loss_rows, loss);
+    return launch_layer_error(ctx, 1, &dW, dW_dtype, out, in, Hs, hmeta, loss_rows, loss);
 }
 
 int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in,
@@ -251,8 +251,24 @@ int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, i
     if (!hmeta) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_prepared: hmeta is NULL");
     if (!aligned16(hmeta))
         return adadim_fail(ctx, ADADIM_EALIGN, "adadim_layer_error_prepared: hmeta must be 16-byte aligned");
-    return launch_layer_error(ctx, dW, dW_dtype, out, in, static_cast<const __half*>(Hs), hmeta, loss_rows,
+    return launch_layer_error(ctx, 1, &dW, dW_dtype, out, in, static_cast<const __half*>(Hs), hmeta, loss_rows,
                               loss);
+}
+
+int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
+                             const void* Hs, const float* hmeta, float* loss_rows, float* losses) {
+    if (!ctx) return ADADIM_ENULL;
+    if (n <= 0 || n > 4096) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_layer_error_batch: bad n=%d", n);
+    if (!dW) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch: dW is NULL");
+    for (int c = 0; c < n; ++c) {
+        int rc = check_error_args(ctx, "adadim_layer_error_batch", dW[c], dW_dtype, out, in, Hs, losses, true);
+        if (rc != ADADIM_OK) return rc;
+    }
+    if (!hmeta) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch: hmeta is NULL");
+    if (!aligned16(hmeta))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_layer_error_batch: hmeta must be 16-byte aligned");
+    return launch_layer_error(ctx, n, dW, dW_dtype, out, in, static_cast<const __half*>(Hs), hmeta, loss_rows,
+                              losses);
 }
 
 int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best) {

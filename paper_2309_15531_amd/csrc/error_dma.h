@@ -62,6 +62,13 @@ struct Frags {
     half8 v[TM + TN];
 };
 
+// Candidates scored by one launch: their (column-scaled fp16) dW matrices share H.
+constexpr int MAX_BATCH = 8;
+struct Batch {
+    const __half* A[MAX_BATCH];
+    int n;
+};
+
 // Column block nb contracts over k < kend(nb) = min(in, (nb+1)*256), cut into
 // chunks of kc_len (a multiple of 32).  Slots enumerate (nb, chunk) with nb
 // descending; slot_of_nb[] is not stored: the decode loop below recomputes it.
@@ -70,20 +77,23 @@ __device__ __forceinline__ int chunks_of(int nb, int64_t in, int kc_len) {
     return static_cast<int>((kend + kc_len - 1) / kc_len);
 }
 
-__global__ __launch_bounds__(256) void error_tiles_dma(const __half* __restrict__ A, const __half* __restrict__ Hs,
-                                                       int64_t out, int64_t in, int MB, int NB, int kc_len,
-                                                       int n_slots, const void* zero16,
-                                                       float* __restrict__ part) {
+__global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half* __restrict__ Hs, int64_t out,
+                                                       int64_t in, int MB, int NB, int kc_len, int n_slots,
+                                                       const void* zero16, float* __restrict__ part) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
     // Workgroups go to the eight XCDs round-robin by launch index.  Slots are sorted by
     // decreasing contraction length, so XCD x takes slots x, x+8, x+16, ... (a balanced share,
-    // longest first) and all MB row blocks of a slot run on the same XCD, sharing its Hs tile in L2.
+    // longest first) and all row blocks of all candidates of a slot run on the same XCD, sharing
+    // its Hs tile in L2.
     const int xcd = static_cast<int>(blockIdx.x % 8), seq = static_cast<int>(blockIdx.x / 8);
-    const int slot = (seq / MB) * 8 + xcd, mb = seq % MB;
+    const int per_slot = batch.n * MB;
+    const int slot = (seq / per_slot) * 8 + xcd;
     if (slot >= n_slots) return;
+    const int cand = (seq % per_slot) / MB, mb = seq % MB;
+    const __half* __restrict__ A = batch.A[cand];
     int nb = NB - 1, rem = slot;
     for (;;) {
         const int c = chunks_of(nb, in, kc_len);
@@ -274,7 +284,8 @@ __global__ __launch_bounds__(256) void error_tiles_dma(const __half* __restrict_
         for (int j = 0; j < TN; ++j) s_rows[wm][wn * WN + 32 * j + lane] = v[j];
     }
     __syncthreads();
-    if (tid < BT && row0 + tid < out) part[int64_t(slot) * out + row0 + tid] = s_rows[0][tid] + s_rows[1][tid];
+    if (tid < BT && row0 + tid < out)
+        part[(int64_t(cand) * n_slots + slot) * out + row0 + tid] = s_rows[0][tid] + s_rows[1][tid];
 }
 
 }  // namespace edma

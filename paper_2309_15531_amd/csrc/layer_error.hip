@@ -21,11 +21,19 @@ using namespace mfma;
 
 // dW (fp32 / fp16 / already scaled fp16) -> dW16 = fp16(dW * d) if needed, and
 // diag[o] = sum_j H_jj dW_oj^2 in fp32.  One block per row.
-__global__ __launch_bounds__(256) void error_prologue(const void* __restrict__ dW, int dW_dtype, int64_t in,
+struct SrcBatch {
+    const void* dW[edma::MAX_BATCH];
+};
+
+// blockIdx.y = candidate; dW16 and diag are laid out [candidate][...].
+__global__ __launch_bounds__(256) void error_prologue(SrcBatch src, int dW_dtype, int64_t out, int64_t in,
                                                       const float* __restrict__ hmeta,
-                                                      __half* __restrict__ dW16, float* __restrict__ diag) {
+                                                      __half* __restrict__ dW16_all, float* __restrict__ diag_all) {
     __shared__ float s_red[256];
     const int64_t o = blockIdx.x;
+    const void* __restrict__ dW = src.dW[blockIdx.y];
+    __half* __restrict__ dW16 = dW16_all ? dW16_all + int64_t(blockIdx.y) * out * in : nullptr;
+    float* __restrict__ diag = diag_all + int64_t(blockIdx.y) * out;
     const float* d = hmeta;
     const float* hd = hmeta + in;
     float sum = 0.0f;
@@ -78,12 +86,20 @@ __global__ __launch_bounds__(256) void error_prologue(const void* __restrict__ d
 // and, in the block that finishes last, loss = sum of the block totals in block order (so the
 // result does not depend on which block that is).  `ticket` must be zero on entry and is zero
 // again on exit.
-__global__ __launch_bounds__(256) void error_finish(const float* __restrict__ diag, const float* __restrict__ part,
-                                                    int64_t out, int n_slots, float* __restrict__ loss_rows,
-                                                    float* __restrict__ loss, double* __restrict__ block_tot,
-                                                    unsigned int* __restrict__ ticket) {
+__global__ __launch_bounds__(256) void error_finish(const float* __restrict__ diag_all,
+                                                    const float* __restrict__ part_all, int64_t out, int n_slots,
+                                                    float* __restrict__ loss_rows_all, float* __restrict__ loss_all,
+                                                    double* __restrict__ block_tot_all,
+                                                    unsigned int* __restrict__ ticket_all) {
     __shared__ double s_red[256];
     __shared__ bool s_last;
+    // blockIdx.y = candidate
+    const float* __restrict__ diag = diag_all + int64_t(blockIdx.y) * out;
+    const float* __restrict__ part = part_all + int64_t(blockIdx.y) * n_slots * out;
+    float* __restrict__ loss_rows = loss_rows_all ? loss_rows_all + int64_t(blockIdx.y) * out : nullptr;
+    float* __restrict__ loss = loss_all + blockIdx.y;
+    double* __restrict__ block_tot = block_tot_all + int64_t(blockIdx.y) * gridDim.x;
+    unsigned int* __restrict__ ticket = ticket_all + blockIdx.y;
     const int64_t o = int64_t(blockIdx.x) * 256 + threadIdx.x;
     double mine = 0.0;
     if (o < out) {
@@ -143,80 +159,94 @@ __global__ void select_first_min(const float* __restrict__ losses, int n, int32_
 
 }  // namespace
 
-int launch_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t out, int64_t in, const __half* Hs,
-                       const float* hmeta, float* loss_rows, float* loss) {
+int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
+                       const __half* Hs, const float* hmeta, float* loss_rows, float* losses) {
     constexpr int BT = edma::BT;
     const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
-    // Contraction chunk: about half of the work one compute unit gets, in 256-k blocks,
-    // so that the triangular work balances without multiplying epilogues.
-    const int64_t total_blocks = int64_t(MB) * NB * (NB + 1) / 2;
-    int kb = static_cast<int>(total_blocks / (256 * 2));
-    kb = kb < 1 ? 1 : (kb > 16 ? 16 : kb);
-    const int kc_len = kb * BT;
-    int n_slots = 0;
-    for (int nb = 0; nb < NB; ++nb) {
-        const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
-        n_slots += static_cast<int>((kend + kc_len - 1) / kc_len);
-    }
-    // scratch: [n_slots+1, out] floats: row partials per (column block, chunk), then the diagonal term
-    float* part = static_cast<float*>(
-        adadim_workspace(ctx, WS_ERR_PART, size_t(n_slots + 1) * size_t(out) * sizeof(float)));
-    if (!part) return ADADIM_EHIP;
-    float* diag = part + size_t(n_slots) * size_t(out);
-    // scratch of the final reduction: one double per 256 rows, then the (self-resetting) ticket
-    const unsigned fin_blocks = static_cast<unsigned>((out + 255) / 256);
-    const size_t fin_bytes = size_t(fin_blocks) * sizeof(double) + 256;
-    const bool fin_fresh = ctx->ws_bytes[WS_ERR_FIN] < fin_bytes;
-    double* block_tot = static_cast<double*>(adadim_workspace(ctx, WS_ERR_FIN, fin_bytes));
-    if (!block_tot) return ADADIM_EHIP;
-    unsigned int* ticket = reinterpret_cast<unsigned int*>(block_tot + (ctx->ws_bytes[WS_ERR_FIN] - 256) / sizeof(double));
-    if (fin_fresh) {
-        hipLaunchKernelGGL(fill_zero_f32, dim3(1), dim3(64), 0, ctx->stream, reinterpret_cast<float*>(ticket),
-                           int64_t(64));
-        ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
-    }
     void* zero16 = adadim_workspace(ctx, WS_ZERO, 256);
     if (!zero16) return ADADIM_EHIP;
     if (ctx->zero_ready_bytes != ctx->ws_bytes[WS_ZERO]) {
         // a fill kernel rather than a memset node, so that the call stays safe to capture in a graph
-        const int64_t n = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
-        hipLaunchKernelGGL(fill_zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
-                           static_cast<float*>(zero16), n);
+        const int64_t nz = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
+        hipLaunchKernelGGL(fill_zero_f32, dim3(static_cast<unsigned>((nz + 255) / 256)), dim3(256), 0, ctx->stream,
+                           static_cast<float*>(zero16), nz);
         ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
         ctx->zero_ready_bytes = ctx->ws_bytes[WS_ZERO];
     }
-    const __half* A = static_cast<const __half*>(dW);
-    __half* dW16 = nullptr;
-    if (dW_dtype != ADADIM_DW_F16_SCALED) {
-        dW16 = static_cast<__half*>(adadim_workspace(ctx, WS_DW16, size_t(out) * size_t(in) * sizeof(__half)));
-        if (!dW16) return ADADIM_EHIP;
-        A = dW16;
-    }
-    {
-        ProfScope prof(ctx, "error_prologue");
-        hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out)), dim3(256), 0, ctx->stream, dW, dW_dtype,
-                           in, hmeta, dW16, diag);
-    }
-    ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
     static bool attr_set = false;
     if (!attr_set) {
         ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(edma::error_tiles_dma),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, edma::SMEM_BYTES));
         attr_set = true;
     }
-    {
-        ProfScope prof(ctx, "error_tiles");
-        const unsigned grid = 8u * static_cast<unsigned>((n_slots + 7) / 8) * static_cast<unsigned>(MB);
-        hipLaunchKernelGGL(edma::error_tiles_dma, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, A, Hs, out,
-                           in, MB, NB, kc_len, n_slots, zero16, part);
+    for (int c0 = 0; c0 < n; c0 += edma::MAX_BATCH) {
+        const int nc = n - c0 < edma::MAX_BATCH ? n - c0 : edma::MAX_BATCH;
+        // Contraction chunk: about half of the work one compute unit gets, in 256-k blocks,
+        // so that the triangular work balances without multiplying epilogues.
+        const int64_t total_blocks = int64_t(nc) * MB * NB * (NB + 1) / 2;
+        int kb = static_cast<int>(total_blocks / (256 * 2));
+        kb = kb < 1 ? 1 : (kb > 16 ? 16 : kb);
+        const int kc_len = kb * BT;
+        int n_slots = 0;
+        for (int nb = 0; nb < NB; ++nb) {
+            const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
+            n_slots += static_cast<int>((kend + kc_len - 1) / kc_len);
+        }
+        // scratch: per candidate [n_slots, out] row partials; then per candidate [out] diagonal terms
+        float* part = static_cast<float*>(adadim_workspace(
+            ctx, WS_ERR_PART, size_t(nc) * size_t(n_slots + 1) * size_t(out) * sizeof(float)));
+        if (!part) return ADADIM_EHIP;
+        float* diag = part + size_t(nc) * size_t(n_slots) * size_t(out);
+        // scratch of the final reduction: per candidate one double per 256 rows; then the tickets
+        const unsigned fin_blocks = static_cast<unsigned>((out + 255) / 256);
+        const size_t fin_bytes = size_t(edma::MAX_BATCH) * fin_blocks * sizeof(double) + 256;
+        const bool fin_fresh = ctx->ws_bytes[WS_ERR_FIN] < fin_bytes;
+        double* block_tot = static_cast<double*>(adadim_workspace(ctx, WS_ERR_FIN, fin_bytes));
+        if (!block_tot) return ADADIM_EHIP;
+        unsigned int* ticket =
+            reinterpret_cast<unsigned int*>(block_tot + (ctx->ws_bytes[WS_ERR_FIN] - 256) / sizeof(double));
+        if (fin_fresh) {
+            hipLaunchKernelGGL(fill_zero_f32, dim3(1), dim3(64), 0, ctx->stream, reinterpret_cast<float*>(ticket),
+                               int64_t(64));
+            ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
+        }
+        SrcBatch src;
+        edma::Batch batch;
+        batch.n = nc;
+        __half* dW16 = nullptr;
+        if (dW_dtype != ADADIM_DW_F16_SCALED) {
+            dW16 = static_cast<__half*>(
+                adadim_workspace(ctx, WS_DW16, size_t(nc) * size_t(out) * size_t(in) * sizeof(__half)));
+            if (!dW16) return ADADIM_EHIP;
+        }
+        for (int c = 0; c < edma::MAX_BATCH; ++c) {
+            src.dW[c] = c < nc ? dW[c0 + c] : nullptr;
+            batch.A[c] = c < nc ? (dW16 ? dW16 + size_t(c) * size_t(out) * size_t(in)
+                                        : static_cast<const __half*>(dW[c0 + c]))
+                                : nullptr;
+        }
+        {
+            ProfScope prof(ctx, "error_prologue");
+            hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out), nc), dim3(256), 0, ctx->stream, src,
+                               dW_dtype, out, in, hmeta, dW16, diag);
+        }
+        ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
+        {
+            ProfScope prof(ctx, "error_tiles");
+            const unsigned grid =
+                8u * static_cast<unsigned>((n_slots + 7) / 8) * static_cast<unsigned>(MB) * static_cast<unsigned>(nc);
+            hipLaunchKernelGGL(edma::error_tiles_dma, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
+                               out, in, MB, NB, kc_len, n_slots, zero16, part);
+        }
+        ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
+        {
+            ProfScope prof(ctx, "error_finish");
+            hipLaunchKernelGGL(error_finish, dim3(fin_blocks, nc), dim3(256), 0, ctx->stream, diag, part, out, n_slots,
+                               loss_rows ? loss_rows + size_t(c0) * size_t(out) : nullptr, losses + c0, block_tot,
+                               ticket);
+        }
+        ADADIM_LAUNCH_CHECK(ctx, "error_finish");
     }
-    ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
-    {
-        ProfScope prof(ctx, "error_finish");
-        hipLaunchKernelGGL(error_finish, dim3(fin_blocks), dim3(256), 0, ctx->stream, diag, part, out, n_slots,
-                           loss_rows, loss, block_tot, ticket);
-    }
-    ADADIM_LAUNCH_CHECK(ctx, "error_finish");
     return ADADIM_OK;
 }
 

@@ -43,42 +43,61 @@ class PreparedHessian:
 
 
 class LayerSearch:
-    """Buffers for searching layers of one shape; reused across layers and candidates."""
+    """Buffers for searching layers of one shape; reused across layers and candidates.
+
+    Candidates are scored in batches of up to `batch` (one adadim_layer_error_batch call each).
+    With at most `batch` candidates and keep_winner, every candidate's packed codes, scales and
+    zeros are written while it is scored, so the winner needs no second quantization."""
 
     def __init__(self, ctx: B.Context, out_f: int, in_f: int, bits: int, group: int, clips=(1.0,),
-                 keep_winner: bool = True, device="cuda"):
+                 keep_winner: bool = True, batch: int = 8, device="cuda"):
         self.ctx, self.out_f, self.in_f, self.bits, self.group = ctx, out_f, in_f, bits, group
         self.clips = [float(np.float32(c)) for c in clips]
         self.cands = [(d, c) for d in (B.DIM_OC, B.DIM_IC) for c in self.clips]
-        self.dW = torch.empty((out_f, in_f), dtype=torch.float16, device=device)
+        self.batch = max(1, min(batch, 8, len(self.cands)))
+        self.dWs = [torch.empty((out_f, in_f), dtype=torch.float16, device=device) for _ in range(self.batch)]
         self.losses = torch.empty(len(self.cands), dtype=torch.float32, device=device)
         self.best = torch.empty(1, dtype=torch.int32, device=device)
         self.keep_winner = keep_winner
         g_oc = in_f if group == 0 else group
         g_ic = out_f if group == 0 else group
         self.meta_shape = {B.DIM_OC: (out_f, in_f // g_oc), B.DIM_IC: (out_f // g_ic, in_f)}
+        self.scales = self.zeros = self.packed = None
         if keep_winner:
             n_meta = max(out_f * (in_f // g_oc), (out_f // g_ic) * in_f)
-            self.scales = torch.empty(n_meta, dtype=torch.float32, device=device)
-            self.zeros = torch.empty(n_meta, dtype=torch.uint8, device=device)
             words = max(out_f * ((in_f * bits + 31) // 32), in_f * ((out_f * bits + 31) // 32))
-            self.packed = torch.empty(words, dtype=torch.int32, device=device)
+            # one output set per candidate when they all fit in one batch, else one set for the winner
+            self.inline = len(self.cands) <= self.batch
+            n_sets = len(self.cands) if self.inline else 1
+            self._scales = [torch.empty(n_meta, dtype=torch.float32, device=device) for _ in range(n_sets)]
+            self._zeros = [torch.empty(n_meta, dtype=torch.uint8, device=device) for _ in range(n_sets)]
+            self._packed = [torch.empty(words, dtype=torch.int32, device=device) for _ in range(n_sets)]
+        else:
+            self.inline = False
 
     def score_all(self, W, hp: PreparedHessian):
         """Quantizes and scores every candidate; losses stay on the device."""
-        for i, (dim, clip) in enumerate(self.cands):
-            self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, dW=self.dW,
-                                     dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
-            self.ctx.adadim_layer_error_prepared(self.dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta,
-                                                 self.losses[i:i + 1])
+        for c0 in range(0, len(self.cands), self.batch):
+            chunk = self.cands[c0:c0 + self.batch]
+            for k, (dim, clip) in enumerate(chunk):
+                extra = {}
+                if self.inline:
+                    extra = dict(scales=self._scales[c0 + k], zeros=self._zeros[c0 + k], packed=self._packed[c0 + k])
+                self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, dW=self.dWs[k],
+                                         dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale, **extra)
+            self.ctx.adadim_layer_error_batch(self.dWs[:len(chunk)], B.DW_F16_SCALED, hp.Hs, hp.hmeta,
+                                              self.losses[c0:c0 + len(chunk)])
 
     def run(self, W, hp: PreparedHessian):
-        """Whole search for one layer: returns (best index, dim, clip); with
-        keep_winner the winner's packed codes, scales and zeros are in self.*"""
+        """Whole search for one layer: returns (best index, dim, clip); with keep_winner the
+        winner's packed codes, scales and zeros are in self.packed / self.scales / self.zeros."""
         self.score_all(W, hp)
         best = self.ctx.adadim_select(self.losses, best_dev=self.best, to_host=True)
         dim, clip = self.cands[best]
         if self.keep_winner:
-            self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, scales=self.scales,
-                                     zeros=self.zeros, packed=self.packed)
+            k = best if self.inline else 0
+            self.scales, self.zeros, self.packed = self._scales[k], self._zeros[k], self._packed[k]
+            if not self.inline:
+                self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, scales=self.scales,
+                                         zeros=self.zeros, packed=self.packed)
         return best, dim, clip
