@@ -428,23 +428,30 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
 // per-IC fast path: group = 8*RPT rows.  A block of 8*TXW threads owns one row group x 8*TXW
 // columns; thread (tx, ty) keeps rows ty*RPT .. ty*RPT+RPT-1 of its 8 columns in registers, so W
 // is read once.  TXW = 64 makes every wavefront access one whole 1 KB row segment.
-template <int RPT, int TXW>
+template <int RPT, int TXW, int PB>
 __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restrict__ W, int64_t in, float clip,
                                                      float qmax, float rqmax, uint8_t* __restrict__ codes,
                                                      float* __restrict__ scales, uint8_t* __restrict__ zeros,
                                                      void* __restrict__ dW, int dW_dtype,
-                                                     const float* __restrict__ colscale) {
+                                                     const float* __restrict__ colscale,
+                                                     uint32_t* __restrict__ packed, int64_t n_words) {
     constexpr int G = 8 * RPT, COLS = 8 * TXW, NT = 8 * TXW;
-    __shared__ float s_mn[8][COLS];
-    __shared__ float s_mx[8][COLS];
+    // PB != 0: the bit stream is assembled here.  A thread's RPT codes of one column form a piece
+    // of RPT*PB <= 64 bits; the eight row slices OR their pieces into the column's GW words in LDS
+    // (the min/max scratch is dead by then), which are then written out 16 bytes at a time.
+    constexpr int GW = PB ? G * PB / 32 : 0;
+    static_assert(PB == 0 || (RPT * PB <= 64 && (G * PB) % 32 == 0 && GW <= 16), "fused packing limits");
+    __shared__ float s_red[16][COLS];   // [0..7] minima, [8..15] maxima of the row slices; later the packed words
     __shared__ float s_scale[COLS];
     __shared__ float s_zero[COLS];
     __shared__ float s_rcp[COLS];
+    uint32_t* s_pack = reinterpret_cast<uint32_t*>(&s_red[0][0]);   // [GW][COLS], column index permuted
 
     const int tx = threadIdx.x % TXW, ty = threadIdx.x / TXW;
     const int64_t col0 = int64_t(blockIdx.x) * COLS + tx * 8;
     const int64_t row0 = int64_t(blockIdx.y) * G + ty * RPT;
     const bool col_ok = col0 < in;
+    const bool do_pack = PB != 0 && packed != nullptr;
 
     uint4 raw[RPT];
 #pragma unroll
@@ -465,16 +472,16 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
     }
 #pragma unroll
     for (int v = 0; v < 8; ++v) {
-        s_mn[ty][tx * 8 + v] = mn[v];
-        s_mx[ty][tx * 8 + v] = mx[v];
+        s_red[ty][tx * 8 + v] = mn[v];
+        s_red[8 + ty][tx * 8 + v] = mx[v];
     }
     __syncthreads();
     for (int cidx = threadIdx.x; cidx < COLS; cidx += NT) {   // COLS == NT: one column per thread, all lanes active
-        float a = s_mn[0][cidx], b = s_mx[0][cidx];
+        float a = s_red[0][cidx], b = s_red[8][cidx];
 #pragma unroll
         for (int y = 1; y < 8; ++y) {
-            a = fminf(a, s_mn[y][cidx]);
-            b = fmaxf(b, s_mx[y][cidx]);
+            a = fminf(a, s_red[y][cidx]);
+            b = fmaxf(b, s_red[8 + y][cidx]);
         }
         const GroupParamsR gp = group_params_r(a, b, clip, qmax, rqmax);
         s_scale[cidx] = gp.scale;
@@ -488,7 +495,10 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
         }
     }
     __syncthreads();
-    if (!codes && !dW) return;
+    if (!codes && !dW && !do_pack) return;
+    if (do_pack) {
+        for (int i = threadIdx.x; i < GW * COLS; i += NT) s_pack[i] = 0u;
+    }
     float sc[8], zp[8], rc[8];
     bool all_fast = true;
 #pragma unroll
@@ -498,14 +508,20 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
         rc[v] = s_rcp[tx * 8 + v];
         all_fast = all_fast && fastdiv_ok(sc[v]);
     }
+    uint64_t piece[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v) piece[v] = 0;
 #pragma unroll
     for (int r = 0; r < RPT; ++r) {
         const int64_t elem = (row0 + r) * in + col0;
         float w[8], q[8];
         unpack8(raw[r], w);
         quant_codes8(w, sc, zp, rc, all_fast, qmax, q);   // every lane reaches the wave-wide test inside
-        if (!col_ok) continue;
-        if (codes) {
+        if constexpr (PB != 0) {
+#pragma unroll
+            for (int v = 0; v < 8; ++v) piece[v] |= static_cast<uint64_t>(static_cast<uint32_t>(q[v])) << (r * PB);
+        }
+        if (col_ok && codes) {
             uint32_t lo = 0, hi = 0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -514,11 +530,45 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
             }
             *reinterpret_cast<uint2*>(codes + elem) = make_uint2(lo, hi);
         }
-        if (dW) {
+        if (col_ok && dW) {
             float d[8];
 #pragma unroll
             for (int v = 0; v < 8; ++v) d[v] = weight_error(w[v], q[v], sc[v], zp[v]);
             store_dw8(dW, dW_dtype, colscale, elem, col0, d);
+        }
+    }
+    if constexpr (PB != 0) {
+        if (!do_pack) return;
+        __syncthreads();   // s_pack is cleared
+        const int bit0 = ty * RPT * PB, w0 = bit0 >> 5, sh = bit0 & 31;
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
+            const uint64_t lo64 = piece[v] << sh;
+            const uint32_t w2 = sh ? static_cast<uint32_t>(piece[v] >> (64 - sh)) : 0u;
+            const int pc = v * TXW + tx;   // permuted column: conflict-free across the lanes of a wave
+            atomicOr(&s_pack[w0 * COLS + pc], static_cast<uint32_t>(lo64));
+            if (w0 + 1 < GW) atomicOr(&s_pack[(w0 + 1) * COLS + pc], static_cast<uint32_t>(lo64 >> 32));
+            if (w0 + 2 < GW && w2) atomicOr(&s_pack[(w0 + 2) * COLS + pc], w2);
+        }
+        __syncthreads();
+        const int64_t colb = int64_t(blockIdx.x) * COLS;
+        const int64_t woff = int64_t(blockIdx.y) * GW;
+        if ((GW % 4) == 0 && (n_words % 4) == 0) {
+            for (int it = threadIdx.x; it < COLS * (GW / 4); it += NT) {
+                const int c = it / (GW / 4), qd = it % (GW / 4);
+                if (colb + c >= in) continue;
+                const int pc = (c & 7) * TXW + (c >> 3);
+                const uint4 o = make_uint4(s_pack[(4 * qd + 0) * COLS + pc], s_pack[(4 * qd + 1) * COLS + pc],
+                                           s_pack[(4 * qd + 2) * COLS + pc], s_pack[(4 * qd + 3) * COLS + pc]);
+                *reinterpret_cast<uint4*>(packed + (colb + c) * n_words + woff + 4 * qd) = o;
+            }
+        } else {
+            for (int it = threadIdx.x; it < COLS * GW; it += NT) {
+                const int c = it / GW, wd = it % GW;
+                if (colb + c >= in) continue;
+                const int pc = (c & 7) * TXW + (c >> 3);
+                packed[(colb + c) * n_words + woff + wd] = s_pack[wd * COLS + pc];
+            }
         }
     }
 }
@@ -573,15 +623,32 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
 #undef OC_GO
 }
 
+// fused packing is available when a thread's piece fits 64 bits and the group's words fit the LDS scratch
+constexpr bool ic_pack_ok(int rpt, int pb) {
+    return (pb == 2 || pb == 3 || pb == 4) && rpt * pb <= 64 && (8 * rpt * pb) % 32 == 0 && 8 * rpt * pb / 32 <= 16;
+}
+
 template <int RPT>
-void launch_ic_regs(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax,
+void launch_ic_regs(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
                     uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
-                    const float* colscale) {
+                    const float* colscale, uint32_t* packed, int64_t n_words) {
     constexpr int TXW = 32;
     dim3 grid(static_cast<unsigned>((in + 8 * TXW - 1) / (8 * TXW)), static_cast<unsigned>(out / (8 * RPT)));
     ProfScope prof(ctx, "quant_ic");
-    hipLaunchKernelGGL((quant_ic_regs<RPT, TXW>), grid, dim3(8 * TXW), 0, ctx->stream, W, in, clip, qmax,
-                       1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+#define IC_GO(PB)                                                                                                \
+    hipLaunchKernelGGL((quant_ic_regs<RPT, TXW, PB>), grid, dim3(8 * TXW), 0, ctx->stream, W, in, clip, qmax,     \
+                       1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
+    if constexpr (ic_pack_ok(RPT, 2)) {
+        if (pb == 2) { IC_GO(2); return; }
+    }
+    if constexpr (ic_pack_ok(RPT, 3)) {
+        if (pb == 3) { IC_GO(3); return; }
+    }
+    if constexpr (ic_pack_ok(RPT, 4)) {
+        if (pb == 4) { IC_GO(4); return; }
+    }
+    IC_GO(0);
+#undef IC_GO
 }
 
 }  // namespace
@@ -611,9 +678,11 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
     const int lpg = g / 8;
     const bool oc_lanes = dim == ADADIM_DIM_OC && vec && (g % 8) == 0 && lpg <= 64 && (lpg & (lpg - 1)) == 0 &&
                           out * in / 8 < (int64_t(1) << 31);
-    // the per-OC fast kernel assembles the bit stream itself for these widths
+    const bool ic_regs = dim == ADADIM_DIM_IC && vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
+    // the fast kernels assemble the bit stream themselves for these widths
     const bool fused_pack =
-        packed && oc_lanes && (in % 32) == 0 && (bits == 2 || bits == 3 || bits == 4 || bits == 8);
+        packed && ((oc_lanes && (in % 32) == 0 && (bits == 2 || bits == 3 || bits == 4 || bits == 8)) ||
+                   (ic_regs && ic_pack_ok(lpg, bits)));
     if (packed && !fused_pack && !codes) {
         codes = static_cast<uint8_t*>(adadim_workspace(ctx, WS_CODES, size_t(out) * size_t(in)));
         if (!codes) return ADADIM_EHIP;
@@ -642,10 +711,12 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
         const int64_t row_groups = out / g;
         if (row_groups > 65535)
             return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: more than 65535 row groups per column");
-        const bool regs = vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
-        if (regs) {
+        if (ic_regs) {
+            const int pb = fused_pack ? bits : 0;
+            uint32_t* pk = fused_pack ? packed : nullptr;
+            const int64_t n_words = (out * bits + 31) / 32;
             switch (lpg) {
-#define IC_CASE(n) case n: launch_ic_regs<n>(ctx, W, out, in, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale); break;
+#define IC_CASE(n) case n: launch_ic_regs<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk, n_words); break;
                 IC_CASE(1) IC_CASE(2) IC_CASE(4) IC_CASE(8) IC_CASE(16) IC_CASE(32)
 #undef IC_CASE
             }
