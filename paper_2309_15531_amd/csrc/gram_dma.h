@@ -105,12 +105,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
     const int item = static_cast<int>(blockIdx.x % 8) * per_xcd + static_cast<int>(blockIdx.x / 8);
     if (static_cast<int>(blockIdx.x / 8) >= per_xcd || item >= total) return;
     const int split = item / n_tiles;
-    int idx = item - split * n_tiles, I = 0;   // linear index over tiles (I <= J), row-major
-    while (idx >= nb - I) {
-        idx -= nb - I;
-        ++I;
-    }
-    const int J = I + idx;
+    int I, J;
+    decode_tile(item - split * n_tiles, nb, I, J);
     const int64_t t_begin = int64_t(split) * t_per_split;
     const int64_t t_end = min(tokens, t_begin + t_per_split);
     const int t_len = static_cast<int>(t_end - t_begin);

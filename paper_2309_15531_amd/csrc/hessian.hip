@@ -26,13 +26,8 @@ __global__ __launch_bounds__(THREADS) void gram_tiles(const __half* __restrict__
     auto sA = [&](int b) { return smem + b * (2 * TILE_BYTES); };
     auto sB = [&](int b) { return smem + b * (2 * TILE_BYTES) + TILE_BYTES; };
 
-    // linear index over tiles (I <= J), row-major over the upper triangle
-    int idx = blockIdx.x, I = 0;
-    while (idx >= nb - I) {
-        idx -= nb - I;
-        ++I;
-    }
-    const int J = I + idx;
+    int I, J;
+    decode_tile(blockIdx.x, nb, I, J);
     const int64_t t_begin = int64_t(blockIdx.y) * t_per_split;
     const int64_t t_end = min(tokens, t_begin + t_per_split);
 
@@ -93,12 +88,8 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
     constexpr int SB = BT / 32;
     __shared__ float s[32][33];
     const int tile = blockIdx.x / (SB * SB), sub = blockIdx.x % (SB * SB);
-    int idx = tile, I = 0;
-    while (idx >= nb - I) {
-        idx -= nb - I;
-        ++I;
-    }
-    const int J = I + idx;
+    int I, J;
+    decode_tile(tile, nb, I, J);
     const int sr = sub / SB, sc = sub % SB;
     const int64_t R0 = int64_t(I) * BT + sr * 32, C0 = int64_t(J) * BT + sc * 32;
     if (R0 > C0 || R0 >= in || C0 >= in) return;  // below the diagonal or outside H

@@ -116,6 +116,37 @@ struct TransposeStage {
     }
 };
 
+// Order of the upper-triangular tiles (I <= J) of an nb x nb tile grid: strips of four tile
+// rows, each strip walked column by column.  Any 32 consecutive tiles then touch about 4 row
+// panels and 8 column panels, so the workgroups that run together on one XCD share most of
+// their operand panels in its L2 (a row-major walk would touch 17 panels for 16 tiles).
+__device__ __forceinline__ void decode_tile(int idx, int nb, int& I, int& J) {
+    int s = 0;
+    for (;;) {
+        const int rows = min(4, nb - 4 * s);                      // tile rows in this strip
+        const int head = rows * (rows + 1) / 2;                   // its triangular first columns
+        const int size = head + rows * max(0, nb - 4 * s - 4);    // then full columns of `rows` tiles
+        if (idx < size) {
+            if (idx < head) {
+                int c = 0;
+                while (idx >= c + 1) {                            // column c of the head holds c + 1 tiles
+                    idx -= c + 1;
+                    ++c;
+                }
+                J = 4 * s + c;
+                I = 4 * s + idx;
+            } else {
+                const int q = idx - head;
+                J = 4 * s + 4 + q / rows;
+                I = 4 * s + q % rows;
+            }
+            return;
+        }
+        idx -= size;
+        ++s;
+    }
+}
+
 // One LDS stage of MFMAs for a wave tile of TM x TN 32x32 blocks whose first
 // rows in the A and B tiles are a_row0 and b_row0.
 template <int TM, int TN>
