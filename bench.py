@@ -162,10 +162,14 @@ def main():
         s = kern["error_tiles"]["avg_us"] * 1e-6
         bn = 256
         nbk = (in_f + bn - 1) // bn
-        issued = 2.0 * out_f * bn * bn * nbk * (nbk + 1) / 2  # k-range of column block nb is (nb+1)*BN
+        mbk = (out_f + bn - 1) // bn
+        per_launch = len(ls.cands) * args.steps / kern["error_tiles"]["launches"]   # candidates per launch
+        # MFMA flops issued: 256x256 tiles, column block nb contracts over (nb+1)*256
+        issued = per_launch * 2.0 * (mbk * bn) * bn * bn * nbk * (nbk + 1) / 2
         comps["error_tiles"] = {
-            "avg_us": s * 1e6, "tflops_issued": issued / s / 1e12, "frac_mfma": issued / s / MFMA_F16_PEAK,
-            "tflops_dense_equivalent": 2.0 * out_f * in_f * in_f / s / 1e12,
+            "avg_us": s * 1e6, "candidates_per_launch": per_launch, "tflops_issued": issued / s / 1e12,
+            "frac_mfma": issued / s / MFMA_F16_PEAK,
+            "tflops_dense_equivalent": per_launch * 2.0 * out_f * in_f * in_f / s / 1e12,
         }
     qbytes = out_f * in_f * (2 + 2) + 5.0 * out_f * in_f / group   # W read + fp16 dW written + scale/zero
     for k in ("quant_oc", "quant_ic"):

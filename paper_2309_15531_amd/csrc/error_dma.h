@@ -85,12 +85,13 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
     // Workgroups go to the eight XCDs round-robin by launch index.  Slots are sorted by
-    // decreasing contraction length, so XCD x takes slots x, x+8, x+16, ... (a balanced share,
-    // longest first) and all row blocks of all candidates of a slot run on the same XCD, sharing
-    // its Hs tile in L2.
+    // decreasing contraction length and dealt to the XCDs in serpentine order (0..7, 7..0, ...),
+    // which evens out the totals; all row blocks of all candidates of a slot run on the same XCD,
+    // longest slots first, sharing the slot's Hs tile in that XCD's L2.
     const int xcd = static_cast<int>(blockIdx.x % 8), seq = static_cast<int>(blockIdx.x / 8);
     const int per_slot = batch.n * MB;
-    const int slot = (seq / per_slot) * 8 + xcd;
+    const int round = seq / per_slot;
+    const int slot = round * 8 + ((round & 1) ? 7 - xcd : xcd);
     if (slot >= n_slots) return;
     const int cand = (seq % per_slot) / MB, mb = seq % MB;
     const __half* __restrict__ A = batch.A[cand];

@@ -181,17 +181,20 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
     }
     for (int c0 = 0; c0 < n; c0 += edma::MAX_BATCH) {
         const int nc = n - c0 < edma::MAX_BATCH ? n - c0 : edma::MAX_BATCH;
-        // Contraction chunk: about half of the work one compute unit gets, in 256-k blocks,
-        // so that the triangular work balances without multiplying epilogues.
-        const int64_t total_blocks = int64_t(nc) * MB * NB * (NB + 1) / 2;
-        int kb = static_cast<int>(total_blocks / (256 * 2));
-        kb = kb < 1 ? 1 : (kb > 16 ? 16 : kb);
-        const int kc_len = kb * BT;
-        int n_slots = 0;
-        for (int nb = 0; nb < NB; ++nb) {
-            const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
-            n_slots += static_cast<int>((kend + kc_len - 1) / kc_len);
+        // Contraction chunk, in 256-k blocks: whole contractions (one workgroup per tile, the
+        // cheapest in prologues and epilogues) unless that leaves fewer than two workgroups per
+        // compute unit; then the largest chunk that gives that many.
+        int kb = NB, n_slots = 0;
+        for (;;) {
+            n_slots = 0;
+            for (int nb = 0; nb < NB; ++nb) {
+                const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
+                n_slots += static_cast<int>((kend + int64_t(kb) * BT - 1) / (int64_t(kb) * BT));
+            }
+            if (kb == 1 || int64_t(nc) * MB * n_slots >= 512) break;
+            kb = kb > 2 ? kb / 2 : 1;
         }
+        const int kc_len = kb * BT;
         // scratch: per candidate [n_slots, out] row partials; then per candidate [out] diagonal terms
         float* part = static_cast<float*>(adadim_workspace(
             ctx, WS_ERR_PART, size_t(nc) * size_t(n_slots + 1) * size_t(out) * sizeof(float)));
