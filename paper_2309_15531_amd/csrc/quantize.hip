@@ -12,6 +12,8 @@
 #include "common.h"
 #include "fastdiv.h"
 
+#include <type_traits>
+
 namespace {
 
 struct GroupParams {
@@ -425,23 +427,24 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
     }
 }
 
-// per-IC fast path: group = 8*RPT rows.  A block of 8*TXW threads owns one row group x 8*TXW
+// per-IC fast path: group = NSL*RPT rows.  A block of 32*NSL threads owns one row group x 256
 // columns; thread (tx, ty) keeps rows ty*RPT .. ty*RPT+RPT-1 of its 8 columns in registers, so W
-// is read once.  TXW = 64 makes every wavefront access one whole 1 KB row segment.
-template <int RPT, int TXW, int PB>
-__global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restrict__ W, int64_t in, float clip,
+// is read once.  Few rows per thread keep the register count low enough for several blocks per
+// compute unit, which is what overlaps one block's arithmetic with another's memory traffic.
+template <int RPT, int NSL, int PB>
+__global__ __launch_bounds__(32 * NSL, 4) void quant_ic_regs(const __half* __restrict__ W, int64_t in, float clip,
                                                      float qmax, float rqmax, uint8_t* __restrict__ codes,
                                                      float* __restrict__ scales, uint8_t* __restrict__ zeros,
                                                      void* __restrict__ dW, int dW_dtype,
                                                      const float* __restrict__ colscale,
                                                      uint32_t* __restrict__ packed, int64_t n_words) {
-    constexpr int G = 8 * RPT, COLS = 8 * TXW, NT = 8 * TXW;
+    constexpr int TXW = 32, G = NSL * RPT, COLS = 8 * TXW, NT = NSL * TXW;
     // PB != 0: the bit stream is assembled here.  A thread's RPT codes of one column form a piece
-    // of RPT*PB <= 64 bits; the eight row slices OR their pieces into the column's GW words in LDS
+    // of RPT*PB <= 64 bits; the row slices OR their pieces into the column's GW words in LDS
     // (the min/max scratch is dead by then), which are then written out 16 bytes at a time.
     constexpr int GW = PB ? G * PB / 32 : 0;
-    static_assert(PB == 0 || (RPT * PB <= 64 && (G * PB) % 32 == 0 && GW <= 16), "fused packing limits");
-    __shared__ float s_red[16][COLS];   // [0..7] minima, [8..15] maxima of the row slices; later the packed words
+    static_assert(PB == 0 || (RPT * PB <= 64 && (G * PB) % 32 == 0 && GW <= 2 * NSL), "fused packing limits");
+    __shared__ float s_red[2 * NSL][COLS];   // minima then maxima of the row slices; later the packed words
     __shared__ float s_scale[COLS];
     __shared__ float s_zero[COLS];
     __shared__ float s_rcp[COLS];
@@ -473,15 +476,15 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
 #pragma unroll
     for (int v = 0; v < 8; ++v) {
         s_red[ty][tx * 8 + v] = mn[v];
-        s_red[8 + ty][tx * 8 + v] = mx[v];
+        s_red[NSL + ty][tx * 8 + v] = mx[v];
     }
     __syncthreads();
-    for (int cidx = threadIdx.x; cidx < COLS; cidx += NT) {   // COLS == NT: one column per thread, all lanes active
-        float a = s_red[0][cidx], b = s_red[8][cidx];
+    for (int cidx = threadIdx.x; cidx < COLS; cidx += NT) {   // whole wavefronts: COLS and NT are multiples of 64
+        float a = s_red[0][cidx], b = s_red[NSL][cidx];
 #pragma unroll
-        for (int y = 1; y < 8; ++y) {
+        for (int y = 1; y < NSL; ++y) {
             a = fminf(a, s_red[y][cidx]);
-            b = fmaxf(b, s_red[8 + y][cidx]);
+            b = fmaxf(b, s_red[NSL + y][cidx]);
         }
         const GroupParamsR gp = group_params_r(a, b, clip, qmax, rqmax);
         s_scale[cidx] = gp.scale;
@@ -508,7 +511,8 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
         rc[v] = s_rcp[tx * 8 + v];
         all_fast = all_fast && fastdiv_ok(sc[v]);
     }
-    uint64_t piece[8];
+    using piece_t = std::conditional_t<(RPT * PB <= 32), uint32_t, uint64_t>;
+    piece_t piece[8];
 #pragma unroll
     for (int v = 0; v < 8; ++v) piece[v] = 0;
 #pragma unroll
@@ -519,7 +523,7 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
         quant_codes8(w, sc, zp, rc, all_fast, qmax, q);   // every lane reaches the wave-wide test inside
         if constexpr (PB != 0) {
 #pragma unroll
-            for (int v = 0; v < 8; ++v) piece[v] |= static_cast<uint64_t>(static_cast<uint32_t>(q[v])) << (r * PB);
+            for (int v = 0; v < 8; ++v) piece[v] |= static_cast<piece_t>(static_cast<uint32_t>(q[v])) << (r * PB);
         }
         if (col_ok && codes) {
             uint32_t lo = 0, hi = 0;
@@ -543,8 +547,9 @@ __global__ __launch_bounds__(8 * TXW) void quant_ic_regs(const __half* __restric
         const int bit0 = ty * RPT * PB, w0 = bit0 >> 5, sh = bit0 & 31;
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-            const uint64_t lo64 = piece[v] << sh;
-            const uint32_t w2 = sh ? static_cast<uint32_t>(piece[v] >> (64 - sh)) : 0u;
+            const uint64_t p64 = piece[v];
+            const uint64_t lo64 = p64 << sh;
+            const uint32_t w2 = sh ? static_cast<uint32_t>(p64 >> (64 - sh)) : 0u;
             const int pc = v * TXW + tx;   // permuted column: conflict-free across the lanes of a wave
             atomicOr(&s_pack[w0 * COLS + pc], static_cast<uint32_t>(lo64));
             if (w0 + 1 < GW) atomicOr(&s_pack[(w0 + 1) * COLS + pc], static_cast<uint32_t>(lo64 >> 32));
@@ -623,28 +628,31 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
 #undef OC_GO
 }
 
+// Row slices per block for a per-IC group of g = 8*lpg rows: 16 from 64 rows up, else 8.
+constexpr int ic_slices(int lpg) { return lpg >= 8 ? 16 : 8; }
 // fused packing is available when a thread's piece fits 64 bits and the group's words fit the LDS scratch
-constexpr bool ic_pack_ok(int rpt, int pb) {
-    return (pb == 2 || pb == 3 || pb == 4) && rpt * pb <= 64 && (8 * rpt * pb) % 32 == 0 && 8 * rpt * pb / 32 <= 16;
+constexpr bool ic_pack_ok(int lpg, int pb) {
+    const int nsl = ic_slices(lpg), rpt = 8 * lpg / nsl, gbits = 8 * lpg * pb;
+    return (pb == 2 || pb == 3 || pb == 4) && rpt * pb <= 64 && gbits % 32 == 0 && gbits / 32 <= 2 * nsl;
 }
 
-template <int RPT>
+template <int LPG>
 void launch_ic_regs(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
                     uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
                     const float* colscale, uint32_t* packed, int64_t n_words) {
-    constexpr int TXW = 32;
-    dim3 grid(static_cast<unsigned>((in + 8 * TXW - 1) / (8 * TXW)), static_cast<unsigned>(out / (8 * RPT)));
+    constexpr int NSL = ic_slices(LPG), RPT = 8 * LPG / NSL;
+    dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(out / (8 * LPG)));
     ProfScope prof(ctx, "quant_ic");
 #define IC_GO(PB)                                                                                                \
-    hipLaunchKernelGGL((quant_ic_regs<RPT, TXW, PB>), grid, dim3(8 * TXW), 0, ctx->stream, W, in, clip, qmax,     \
+    hipLaunchKernelGGL((quant_ic_regs<RPT, NSL, PB>), grid, dim3(32 * NSL), 0, ctx->stream, W, in, clip, qmax,    \
                        1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
-    if constexpr (ic_pack_ok(RPT, 2)) {
+    if constexpr (ic_pack_ok(LPG, 2)) {
         if (pb == 2) { IC_GO(2); return; }
     }
-    if constexpr (ic_pack_ok(RPT, 3)) {
+    if constexpr (ic_pack_ok(LPG, 3)) {
         if (pb == 3) { IC_GO(3); return; }
     }
-    if constexpr (ic_pack_ok(RPT, 4)) {
+    if constexpr (ic_pack_ok(LPG, 4)) {
         if (pb == 4) { IC_GO(4); return; }
     }
     IC_GO(0);
