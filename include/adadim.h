@@ -45,7 +45,16 @@ extern "C" {
 
 #define ADADIM_DW_F32        0  /* dW written / read as fp32 */
 #define ADADIM_DW_F16        1  /* dW written / read as fp16 (round to nearest even) */
-#define ADADIM_DW_F16_SCALED 2  /* fp16 of dW[o,j] * colscale[j]; see adadim_hessian_prepare */
+#define ADADIM_DW_F16_SCALED 2  /* fp16 of dW[o,j] * colscale[j] in the scoring layout (see below) */
+
+/*
+ * Scoring layout.  The two fp16 operands of the error GEMM, the column-scaled dW
+ * (ADADIM_DW_F16_SCALED) and the prepared Hs, are consumed 32 contraction elements at a
+ * time from 256 consecutive rows.  When `in` is a multiple of 32 an [rows, in] operand is
+ * therefore stored blocked along its columns: element (r, c) at index
+ * ((c / 32) * rows + r) * 32 + c % 32; otherwise plain row-major (r * in + c).  The buffers
+ * hold rows * in elements either way.
+ */
 
 typedef struct adadim_ctx adadim_ctx;
 
@@ -114,7 +123,7 @@ int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in,
 /*
  * Prepares H for scoring on the matrix cores.  With the power-of-two column
  * scales d_j ~ sqrt(H_jj):
- *   Hs     fp16 [in, in]: Hs[n,k] = H[n,k]/(d_n d_k) for k < n, 0 elsewhere
+ *   Hs     fp16 [in, in] in the scoring layout: Hs[n,k] = H[n,k]/(d_n d_k) for k < n, 0 elsewhere
  *   hmeta  f32  [2, in]:  hmeta[0,j] = d_j (the colscale of adadim_quantize),
  *                         hmeta[1,j] = H_jj
  * so that tr(dW H dW^T) = sum_o ( sum_j H_jj dW_oj^2 + 2 sum_{k<n} dW'_ok Hs_nk dW'_on ),

@@ -27,6 +27,18 @@ EXPORTS = (
 _lib = None
 
 
+def from_score_layout(a, rows: int, cols: int):
+    """Row-major [rows, cols] view of a numpy array held in the library's scoring layout
+    (ADADIM_DW_F16_SCALED dW and the prepared Hs): blocked by 32 along the columns when cols
+    is a multiple of 32 (element (r, c) at ((c // 32) * rows + r) * 32 + c % 32), row-major
+    otherwise.  Index shuffling only."""
+    import numpy as np
+    a = np.asarray(a).reshape(-1)
+    if cols % 32:
+        return a.reshape(rows, cols)
+    return np.ascontiguousarray(a.reshape(cols // 32, rows, 32).transpose(1, 0, 2)).reshape(rows, cols)
+
+
 class AdaDimError(RuntimeError):
     def __init__(self, code: int, text: str):
         super().__init__(f"adadim error {code}: {text}")

@@ -76,6 +76,15 @@ void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes);
             return adadim_fail((ctx), ADADIM_EHIP, "launch %s: %s", (what), hipGetErrorString(e__)); \
     } while (0)
 
+// Scoring layout of an fp16 [rows, cols] operand of the error GEMM (the column-scaled dW and the
+// prepared H): blocked along the contraction index when cols is a multiple of 32, so that the 64
+// bytes a pipeline stage needs from each of 256 consecutive rows are contiguous in memory (whole
+// 128-byte lines per request); plain row-major otherwise.
+__host__ __device__ inline bool score_blocked(int64_t cols) { return (cols & 31) == 0; }
+__host__ __device__ inline int64_t score_index(int64_t row, int64_t col, int64_t rows, int64_t cols) {
+    return score_blocked(cols) ? ((col >> 5) * rows + row) * 32 + (col & 31) : row * cols + col;
+}
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Launchers implemented in the .hip files.  All validate nothing: the API layer does.

@@ -14,9 +14,13 @@
 // 32-wide block and four consecutive n per accumulator quad, so the epilogue's
 // dW'[o,n] factors are 8-byte loads and the sum over n stays inside the lane.
 //
-// Both operands are contraction-contiguous in memory ([row][k]), so a DMA
-// transfer (global_load_lds_dwordx4, 1 KB per wavefront instruction) brings 16
-// rows x 32 k and the MFMA fragments are plain 16-byte LDS reads.  Stage layout:
+// Both operands are contraction-contiguous per row, so a DMA transfer
+// (global_load_lds_dwordx4, 1 KB per wavefront instruction) brings 16 rows x
+// 32 k and the MFMA fragments are plain 16-byte LDS reads.  In the scoring
+// layout (common.h: blocked by 32 along k when `in` is a multiple of 32) those
+// 16 x 64 bytes are one contiguous kilobyte, i.e. eight whole 128-byte lines;
+// with row-major operands they would be sixteen half lines and the L2 request
+// rate, not the matrix cores, would set the pace.  Stage layout:
 // operand 0 (256 rows of Hs) then operand 1 (256 rows of dW'), each [256 rows][64 bytes];
 // the 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 2) & 3), which
 // makes the fragment reads (32 consecutive rows, one chunk) conflict-free.  The
@@ -29,6 +33,7 @@
 // stage through per-lane predicates.
 #pragma once
 
+#include "common.h"
 #include "mfma_tile.h"
 
 #include <type_traits>
@@ -77,6 +82,7 @@ __device__ __forceinline__ int chunks_of(int nb, int64_t in, int kc_len) {
     return static_cast<int>((kend + kc_len - 1) / kc_len);
 }
 
+template <int DBG = 0>
 __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half* __restrict__ Hs, int64_t out,
                                                        int64_t in, int MB, int NB, int kc_len, int n_slots,
                                                        const void* zero16, float* __restrict__ part) {
@@ -102,7 +108,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         rem -= c;
         --nb;
     }
-    const int64_t kend = min(in, int64_t(nb + 1) * BT);
+    const int64_t kend = (DBG & 1) ? in : min(in, int64_t(nb + 1) * BT);   // DBG 1: dense timing probe
     const int64_t k_begin = int64_t(rem) * kc_len;
     const int k_len = static_cast<int>(min(kend, k_begin + kc_len) - k_begin);   // > 0, multiple of 8
     const int n_st = (k_len + KT - 1) / KT;
@@ -118,6 +124,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     // dW' rows of row block mb); lane l takes row l >> 2, chunk slot l & 3.  Rows past the end of a
     // matrix re-read the block's first row: they only feed entries of E that the epilogue skips.
     const int lr = lane >> 2, p = lane & 3;
+    const bool blocked = score_blocked(in);
     uint32_t goff[LOADS], gdst[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
@@ -129,15 +136,19 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         int64_t grow = blk0 + row;
         if (grow >= lim) grow = blk0;
         const __half* base = op ? A : Hs;
-        goff[j] = static_cast<uint32_t>(((grow - blk0) * in + 8 * c) * 2);
+        // offset of this lane's 16 bytes from the first row of the block, within one stage
+        goff[j] = static_cast<uint32_t>(((grow - blk0) * (blocked ? 32 : in) + 8 * c) * 2);
         gdst[j] = lds0 + op * OP_BYTES + rq * 1024;
         // stage 0, predicated on the ragged length
-        const void* g = 8 * c < r0 ? static_cast<const void*>(base + grow * in + k_begin + 8 * c) : zero16;
+        const void* g = 8 * c < r0 ? static_cast<const void*>(base + score_index(grow, k_begin + 8 * c, lim, in))
+                                   : zero16;
         g2l16(g, gdst[j]);
     }
-    // scalar bases of the two operands for the next stage to issue
-    const char* baseA = reinterpret_cast<const char*>(Hs + col0 * in + k_begin + r0);   // operand 0
-    const char* baseB = reinterpret_cast<const char*>(A + row0 * in + k_begin + r0);    // operand 1
+    // scalar bases of the two operands for the next stage to issue (first row of the block, first k
+    // of the stage) and their advance per stage
+    const char* baseA = reinterpret_cast<const char*>(Hs + score_index(col0, k_begin + r0, in, in));    // operand 0
+    const char* baseB = reinterpret_cast<const char*>(A + score_index(row0, k_begin + r0, out, in));    // operand 1
+    const int64_t stepA = blocked ? in * 64 : KT * 2, stepB = blocked ? out * 64 : KT * 2;
     int issued = 1;
     const char* curA = baseA;
     const char* curB = baseB;
@@ -159,8 +170,8 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     };
     auto stage_issued = [&]() {
         ++issued;
-        baseA += KT * 2;
-        baseB += KT * 2;
+        baseA += stepA;
+        baseB += stepB;
     };
     auto issue_stage = [&](int buf) {
         stage_begin();
@@ -260,14 +271,13 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         const int64_t o = row0 + wn * WN + 32 * j + (lane & 31);
         float sum = 0.0f;
         if (o < out) {
-            const __half* arow = A + o * in;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int64_t n0 = col0 + wm * WM + 32 * i + 8 * g + 4 * (lane >> 5);
                     if (n0 < in) {   // in % 8 == 0: the four columns are inside together
-                        const uint2 raw = *reinterpret_cast<const uint2*>(arow + n0);
+                        const uint2 raw = *reinterpret_cast<const uint2*>(A + score_index(o, n0, out, in));
                         const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&raw.x));
                         const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&raw.y));
                         sum += acc[i][j][4 * g + 0] * a.x;

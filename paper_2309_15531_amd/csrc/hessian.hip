@@ -145,7 +145,7 @@ __global__ void hprep_meta(const float* __restrict__ H, int64_t in, float* __res
     hmeta[in + j] = h;
 }
 
-// Hs[n,k] = fp16(H[n,k] / (d_n d_k)) for k < n, else 0.  8 elements per thread.
+// Hs[n,k] = fp16(H[n,k] / (d_n d_k)) for k < n, else 0, stored in the scoring layout.  8 elements per thread.
 __global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, int64_t in,
                                                    const float* __restrict__ hmeta, __half* __restrict__ Hs) {
     const int64_t chunks_per_row = in / 8;
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, 
 #pragma unroll
         for (int e = 0; e < 4; ++e) h[e] = __floats2half2_rn(v[2 * e], v[2 * e + 1]);
     }
-    *reinterpret_cast<uint4*>(Hs + n * in + k0) = o;
+    *reinterpret_cast<uint4*>(Hs + score_index(n, k0, in, in)) = o;
 }
 
 template <int BT>

@@ -19,7 +19,7 @@ namespace {
 
 using namespace mfma;
 
-// dW (fp32 / fp16 / already scaled fp16) -> dW16 = fp16(dW * d) if needed, and
+// dW (fp32 / fp16 / already scaled fp16) -> dW16 = fp16(dW * d) in the scoring layout if needed, and
 // diag[o] = sum_j H_jj dW_oj^2 in fp32.  One block per row.
 struct SrcBatch {
     const void* dW[edma::MAX_BATCH];
@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void error_prologue(SrcBatch src, int dW_dtype
             const float4 b = *reinterpret_cast<const float4*>(static_cast<const float*>(dW) + o * in + j0 + 4);
             w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
         } else {
-            const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const __half*>(dW) + o * in + j0);
+            const int64_t at = dW_dtype == ADADIM_DW_F16_SCALED ? score_index(o, j0, out, in) : o * in + j0;
+            const uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const __half*>(dW) + at);
             const __half2* h = reinterpret_cast<const __half2*>(&raw);
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void error_prologue(SrcBatch src, int dW_dtype
             for (int i = 0; i < 8; ++i) sum += hh[i] * (w[i] * w[i]);
 #pragma unroll
             for (int i = 0; i < 4; ++i) h[i] = __floats2half2_rn(w[2 * i] * dd[2 * i], w[2 * i + 1] * dd[2 * i + 1]);
-            *reinterpret_cast<uint4*>(dW16 + o * in + j0) = o16;
+            *reinterpret_cast<uint4*>(dW16 + score_index(o, j0, out, in)) = o16;
         }
     }
     s_red[threadIdx.x] = sum;
@@ -175,7 +176,7 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
     }
     static bool attr_set = false;
     if (!attr_set) {
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(edma::error_tiles_dma),
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(edma::error_tiles_dma<0>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, edma::SMEM_BYTES));
         attr_set = true;
     }
@@ -238,7 +239,7 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
             ProfScope prof(ctx, "error_tiles");
             const unsigned grid =
                 8u * static_cast<unsigned>((n_slots + 7) / 8) * static_cast<unsigned>(MB) * static_cast<unsigned>(nc);
-            hipLaunchKernelGGL(edma::error_tiles_dma, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
+            hipLaunchKernelGGL(edma::error_tiles_dma<0>, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
                                out, in, MB, NB, kc_len, n_slots, zero16, part);
         }
         ADADIM_LAUNCH_CHECK(ctx, "error_tiles");

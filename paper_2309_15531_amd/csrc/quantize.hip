@@ -54,9 +54,11 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&w)[8]) {
     }
 }
 
-// Stores 8 consecutive dW values of one row starting at column `col`.
+// Stores 8 consecutive dW values of row `row` starting at column `col` (a multiple of 8);
+// elem = row*in + col.  The scaled fp16 form goes to the scoring layout.
 __device__ __forceinline__ void store_dw8(void* dW, int dW_dtype, const float* __restrict__ colscale,
-                                          int64_t elem, int64_t col, const float (&d)[8]) {
+                                          int64_t elem, int64_t row, int64_t col, int64_t out, int64_t in,
+                                          const float (&d)[8]) {
     if (dW_dtype == ADADIM_DW_F32) {
         float4* p = reinterpret_cast<float4*>(static_cast<float*>(dW) + elem);
         p[0] = make_float4(d[0], d[1], d[2], d[3]);
@@ -76,23 +78,25 @@ __device__ __forceinline__ void store_dw8(void* dW, int dW_dtype, const float* _
         __half2* h = reinterpret_cast<__half2*>(&o);
 #pragma unroll
         for (int i = 0; i < 4; ++i) h[i] = __floats2half2_rn(s[2 * i], s[2 * i + 1]);
-        *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + elem) = o;
+        const int64_t at = dW_dtype == ADADIM_DW_F16_SCALED ? score_index(row, col, out, in) : elem;
+        *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = o;
     }
 }
 
 __device__ __forceinline__ void store_dw1(void* dW, int dW_dtype, const float* __restrict__ colscale,
-                                          int64_t elem, int64_t col, float d) {
+                                          int64_t elem, int64_t row, int64_t col, int64_t out, int64_t in, float d) {
     if (dW_dtype == ADADIM_DW_F32) {
         static_cast<float*>(dW)[elem] = d;
+    } else if (dW_dtype == ADADIM_DW_F16_SCALED) {
+        static_cast<__half*>(dW)[score_index(row, col, out, in)] = __float2half_rn(d * colscale[col]);
     } else {
-        if (dW_dtype == ADADIM_DW_F16_SCALED) d = d * colscale[col];
         static_cast<__half*>(dW)[elem] = __float2half_rn(d);
     }
 }
 
 // per-OC, any group length: one wavefront per group, element-wise accesses.
 __global__ __launch_bounds__(256) void quant_oc_generic(const __half* __restrict__ W, int64_t n_groups, int g,
-                                                        int64_t in, float clip, float qmax,
+                                                        int64_t out, int64_t in, float clip, float qmax,
                                                         uint8_t* __restrict__ codes, float* __restrict__ scales,
                                                         uint8_t* __restrict__ zeros, void* __restrict__ dW,
                                                         int dW_dtype, const float* __restrict__ colscale) {
@@ -120,7 +124,9 @@ __global__ __launch_bounds__(256) void quant_oc_generic(const __half* __restrict
         const float w = __half2float(W[base + i]);
         const float q = quant_code(w, gp.scale, gp.zero, qmax);
         if (codes) codes[base + i] = static_cast<uint8_t>(q);
-        if (dW) store_dw1(dW, dW_dtype, colscale, base + i, (base + i) % in, weight_error(w, q, gp.scale, gp.zero));
+        if (dW)
+            store_dw1(dW, dW_dtype, colscale, base + i, (base + i) / in, (base + i) % in, out, in,
+                      weight_error(w, q, gp.scale, gp.zero));
     }
 }
 
@@ -252,7 +258,7 @@ __device__ __forceinline__ void pack8_store(const float (&q)[8], int64_t c, bool
 
 // per-OC fast path: LPG lanes per group, U chunks per thread.
 template <int LPG, int PB>
-__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t n_chunks,
+__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t n_chunks, int64_t out,
                                                      int chunks_per_row, float clip, float qmax, float rqmax,
                                                      uint8_t* __restrict__ codes, float* __restrict__ scales,
                                                      uint8_t* __restrict__ zeros, void* __restrict__ dW,
@@ -262,9 +268,11 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
     const int64_t base = int64_t(blockIdx.x) * (256 * U) + threadIdx.x;
     // column chunk of the first chunk (32-bit arithmetic: the launcher keeps n_chunks below 2^31);
     // later chunks follow by adding 256 and wrapping
-    uint32_t cc = dW_dtype == ADADIM_DW_F16_SCALED
-                      ? static_cast<uint32_t>(base) % static_cast<uint32_t>(chunks_per_row)
-                      : 0u;
+    uint32_t cc = 0u, crow = 0u;   // column chunk and row of the first chunk
+    if (dW_dtype == ADADIM_DW_F16_SCALED) {
+        crow = static_cast<uint32_t>(base) / static_cast<uint32_t>(chunks_per_row);
+        cc = static_cast<uint32_t>(base) - crow * static_cast<uint32_t>(chunks_per_row);
+    }
     uint4 raw[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -313,9 +321,12 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
             float d[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) d[i] = weight_error(w[i], q[i], gp.scale, gp.zero);
-            uint32_t ccu = cc + u * 256;
-            while (ccu >= static_cast<uint32_t>(chunks_per_row)) ccu -= chunks_per_row;
-            store_dw8(dW, dW_dtype, colscale, c * 8, int64_t(ccu) * 8, d);
+            uint32_t ccu = cc + u * 256, rowu = crow;
+            while (ccu >= static_cast<uint32_t>(chunks_per_row)) {
+                ccu -= chunks_per_row;
+                ++rowu;
+            }
+            store_dw8(dW, dW_dtype, colscale, c * 8, rowu, int64_t(ccu) * 8, out, int64_t(chunks_per_row) * 8, d);
         }
     }
 }
@@ -326,7 +337,7 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
 // the 8 slices are combined through LDS, the column parameters are computed
 // once, and a second sweep (served by L2) quantizes.
 template <int VEC>
-__global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ W, int64_t in, int g,
+__global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ W, int64_t out, int64_t in, int g,
                                                      float clip, float qmax, uint8_t* __restrict__ codes,
                                                      float* __restrict__ scales, uint8_t* __restrict__ zeros,
                                                      void* __restrict__ dW, int dW_dtype,
@@ -416,13 +427,13 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
                 float d[8];
 #pragma unroll
                 for (int v = 0; v < 8; ++v) d[v] = weight_error(w[v], q[v], sc[v], zp[v]);
-                store_dw8(dW, dW_dtype, colscale, elem, col0, d);
+                store_dw8(dW, dW_dtype, colscale, elem, row0 + r, col0, out, in, d);
             }
         } else {
             const float w = __half2float(W[elem]);
             const float q = quant_code(w, sc[0], zp[0], qmax);
             if (codes) codes[elem] = static_cast<uint8_t>(q);
-            if (dW) store_dw1(dW, dW_dtype, colscale, elem, col0, weight_error(w, q, sc[0], zp[0]));
+            if (dW) store_dw1(dW, dW_dtype, colscale, elem, row0 + r, col0, out, in, weight_error(w, q, sc[0], zp[0]));
         }
     }
 }
@@ -432,7 +443,7 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
 // is read once.  Few rows per thread keep the register count low enough for several blocks per
 // compute unit, which is what overlaps one block's arithmetic with another's memory traffic.
 template <int RPT, int NSL, int PB>
-__global__ __launch_bounds__(32 * NSL, 4) void quant_ic_regs(const __half* __restrict__ W, int64_t in, float clip,
+__global__ __launch_bounds__(32 * NSL, 4) void quant_ic_regs(const __half* __restrict__ W, int64_t out, int64_t in, float clip,
                                                      float qmax, float rqmax, uint8_t* __restrict__ codes,
                                                      float* __restrict__ scales, uint8_t* __restrict__ zeros,
                                                      void* __restrict__ dW, int dW_dtype,
@@ -538,7 +549,7 @@ __global__ __launch_bounds__(32 * NSL, 4) void quant_ic_regs(const __half* __res
             float d[8];
 #pragma unroll
             for (int v = 0; v < 8; ++v) d[v] = weight_error(w[v], q[v], sc[v], zp[v]);
-            store_dw8(dW, dW_dtype, colscale, elem, col0, d);
+            store_dw8(dW, dW_dtype, colscale, elem, row0 + r, col0, out, in, d);
         }
     }
     if constexpr (PB != 0) {
@@ -616,8 +627,8 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
     const int cpr = static_cast<int>(in / 8);
     ProfScope prof(ctx, "quant_oc");
 #define OC_GO(PB)                                                                                                  \
-    hipLaunchKernelGGL((quant_oc_fast<LPG, PB>), dim3(blocks), dim3(256), 0, ctx->stream, W4, n_chunks, cpr, clip, \
-                       qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed)
+    hipLaunchKernelGGL((quant_oc_fast<LPG, PB>), dim3(blocks), dim3(256), 0, ctx->stream, W4, n_chunks, out, cpr,  \
+                       clip, qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed)
     switch (pb) {
         case 2: OC_GO(2); break;
         case 3: OC_GO(3); break;
@@ -644,8 +655,8 @@ void launch_ic_regs(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, f
     dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(out / (8 * LPG)));
     ProfScope prof(ctx, "quant_ic");
 #define IC_GO(PB)                                                                                                \
-    hipLaunchKernelGGL((quant_ic_regs<RPT, NSL, PB>), grid, dim3(32 * NSL), 0, ctx->stream, W, in, clip, qmax,    \
-                       1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
+    hipLaunchKernelGGL((quant_ic_regs<RPT, NSL, PB>), grid, dim3(32 * NSL), 0, ctx->stream, W, out, in, clip,     \
+                       qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
     if constexpr (ic_pack_ok(LPG, 2)) {
         if (pb == 2) { IC_GO(2); return; }
     }
@@ -710,7 +721,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             const unsigned blocks = static_cast<unsigned>((n_groups + 3) / 4);
             {
                 ProfScope prof(ctx, "quant_oc_generic");
-                hipLaunchKernelGGL(quant_oc_generic, dim3(blocks), dim3(256), 0, ctx->stream, W, n_groups, g, in,
+                hipLaunchKernelGGL(quant_oc_generic, dim3(blocks), dim3(256), 0, ctx->stream, W, n_groups, g, out, in,
                                    clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_generic");
@@ -733,7 +744,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(row_groups));
             {
                 ProfScope prof(ctx, "quant_ic_tile");
-                hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
+                hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, out, in, g, clip, qmax, codes,
                                    scales, zeros, dW, dW_dtype, colscale);
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");
@@ -741,7 +752,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             dim3 grid(static_cast<unsigned>((in + 31) / 32), static_cast<unsigned>(row_groups));
             {
                 ProfScope prof(ctx, "quant_ic_tile");
-                hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, in, g, clip, qmax, codes,
+                hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, out, in, g, clip, qmax, codes,
                                    scales, zeros, dW, dW_dtype, colscale);
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");

@@ -110,7 +110,7 @@ def test_quantize_clip_and_fp16_outputs(ctx, dim, clip):
     # column-scaled fp16 dW: powers of two commute with the rounding
     cs = np.ldexp(np.float32(1.0), np.random.default_rng(3).integers(-2, 9, size=512)).astype(np.float32)
     got = gpu_quantize(ctx, W, dim, 3, 64, clip, dW_dtype=B.DW_F16_SCALED, colscale=dev(cs))
-    assert np.array_equal(got["dW"], (ref["dW"] * cs[None, :]).astype(np.float16))
+    assert np.array_equal(B.from_score_layout(got["dW"], 256, 512), (ref["dW"] * cs[None, :]).astype(np.float16))
     # packed stream without a caller-side code buffer
     got = gpu_quantize(ctx, W, dim, 3, 64, clip, want_codes=False)
     assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, 3))
@@ -210,8 +210,9 @@ def test_layer_error(ctx, out_f, in_f, tokens, dW_dtype):
         assert r.sum() == pytest.approx(loss.item(), rel=1e-5)
 
 
-def test_layer_error_prepared_matches_and_scaled_input(ctx):
-    out_f, in_f = 640, 520
+@pytest.mark.parametrize("in_f", [520, 544])   # row-major and k-blocked scoring layouts
+def test_layer_error_prepared_matches_and_scaled_input(ctx, in_f):
+    out_f = 640
     W = rand_w(out_f, in_f, seed=1)
     X = synth.make_activations(700, in_f, seed=2, n_outliers=3, scale_lo=60, scale_hi=60)
     hp = S.PreparedHessian(ctx, in_f).update(dev(X)).prepare()
@@ -224,8 +225,10 @@ def test_layer_error_prepared_matches_and_scaled_input(ctx):
     assert np.array_equal(hmeta[1], np.diag(Hg))
     ratio = hmeta[0] / np.sqrt(np.diag(Hg))
     assert (ratio > 0.70).all() and (ratio < 1.42).all()
-    Hs = hp.Hs.cpu().numpy().astype(np.float64)
+    Hs = B.from_score_layout(hp.Hs.cpu().numpy(), in_f, in_f).astype(np.float64)
     assert not np.triu(Hs).any() and np.abs(Hs).max() <= 2.0
+    d = hmeta[0].astype(np.float64)
+    assert np.allclose(Hs, np.tril(Hg.astype(np.float64) / d[:, None] / d[None, :], -1), rtol=2.0 ** -10, atol=1e-7)
     ref = oracle.layer_error(oracle.quantize(W, IC, 3, 64)["dW"], oracle.hessian(X))
     Wd = dev(W)
     dW = torch.empty((out_f, in_f), dtype=torch.float16, device="cuda")
