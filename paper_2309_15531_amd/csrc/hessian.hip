@@ -151,7 +151,16 @@ __global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, 
     const int64_t chunks_per_row = in / 8;
     const int64_t c = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (c >= in * chunks_per_row) return;
-    const int64_t n = c / chunks_per_row, k0 = (c % chunks_per_row) * 8;
+    // Threads walk the OUTPUT in memory order, so that stores are contiguous in either layout:
+    // blocked (in % 32 == 0): 16-byte piece c is (k block, row n, quarter) = (c / (4 in), (c / 4) % in, c % 4).
+    int64_t n, k0;
+    if (score_blocked(in)) {
+        n = (c >> 2) % in;
+        k0 = (c / (4 * in)) * 32 + (c & 3) * 8;
+    } else {
+        n = c / chunks_per_row;
+        k0 = (c % chunks_per_row) * 8;
+    }
     uint4 o = make_uint4(0, 0, 0, 0);
     if (k0 < n) {
         const float rn = 1.0f / hmeta[n];  // exact: powers of two
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, 
 #pragma unroll
         for (int e = 0; e < 4; ++e) h[e] = __floats2half2_rn(v[2 * e], v[2 * e + 1]);
     }
-    *reinterpret_cast<uint4*>(Hs + score_index(n, k0, in, in)) = o;
+    *reinterpret_cast<uint4*>(Hs + c * 8) = o;
 }
 
 template <int BT>

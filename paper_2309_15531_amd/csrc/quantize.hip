@@ -256,32 +256,43 @@ __device__ __forceinline__ void pack8_store(const float (&q)[8], int64_t c, bool
     }
 }
 
-// per-OC fast path: LPG lanes per group, U chunks per thread.
+// per-OC fast path: LPG lanes per group.  A block owns a tile of 16 rows x 64 chunks (512
+// columns); wavefront w takes rows 4w..4w+3, lane l chunk l, so every load is one contiguous
+// kilobyte and the four loads of a lane are in flight together.  The column-scaled fp16 dW goes
+// to the k-blocked scoring layout, where the 64-byte pieces of 16 consecutive rows and one
+// 32-column block are adjacent: the tile is turned through LDS so that each store instruction
+// writes such a contiguous kilobyte instead of 16 scattered pieces.
 template <int LPG, int PB>
-__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t n_chunks, int64_t out,
-                                                     int chunks_per_row, float clip, float qmax, float rqmax,
+__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t out, int chunks_per_row,
+                                                     float clip, float qmax, float rqmax,
                                                      uint8_t* __restrict__ codes, float* __restrict__ scales,
                                                      uint8_t* __restrict__ zeros, void* __restrict__ dW,
                                                      int dW_dtype, const float* __restrict__ colscale,
                                                      uint32_t* __restrict__ packed) {
-    constexpr int U = 4;
-    const int64_t base = int64_t(blockIdx.x) * (256 * U) + threadIdx.x;
-    // column chunk of the first chunk (32-bit arithmetic: the launcher keeps n_chunks below 2^31);
-    // later chunks follow by adding 256 and wrapping
-    uint32_t cc = 0u, crow = 0u;   // column chunk and row of the first chunk
-    if (dW_dtype == ADADIM_DW_F16_SCALED) {
-        crow = static_cast<uint32_t>(base) / static_cast<uint32_t>(chunks_per_row);
-        cc = static_cast<uint32_t>(base) - crow * static_cast<uint32_t>(chunks_per_row);
-    }
+    constexpr int U = 4, PITCH = 68;                        // LDS row pitch in 16-byte units (conflict-free)
+    __shared__ uint4 s_t[16 * PITCH];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cc = blockIdx.x * 64 + lane;                  // chunk within the row
+    const int64_t row0 = int64_t(blockIdx.y) * 16;
+    const bool col_ok = cc < chunks_per_row;                // whole groups: chunks_per_row % LPG == 0
+    const int64_t in = int64_t(chunks_per_row) * 8;
+    const bool turn = dW != nullptr && dW_dtype == ADADIM_DW_F16_SCALED && score_blocked(in);
     uint4 raw[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * 256;
-        raw[u] = c < n_chunks ? W[c] : make_uint4(0, 0, 0, 0);
+        const int64_t row = row0 + 4 * wave + u;
+        raw[u] = (col_ok && row < out) ? W[row * chunks_per_row + cc] : make_uint4(0, 0, 0, 0);
+    }
+    float4 csa = make_float4(1.f, 1.f, 1.f, 1.f), csb = csa;
+    if (turn && col_ok) {
+        csa = *reinterpret_cast<const float4*>(colscale + int64_t(cc) * 8);
+        csb = *reinterpret_cast<const float4*>(colscale + int64_t(cc) * 8 + 4);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t c = base + u * 256;
+        const int64_t row = row0 + 4 * wave + u;
+        const bool valid = col_ok && row < out;
+        const int64_t c = row * chunks_per_row + cc;         // flat chunk index
         float w[8];
         unpack8(raw[u], w);
         float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
@@ -300,10 +311,20 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
             quant_codes8(w, sc, zp, rc, gp.fast, qmax, q);
         }
         if constexpr (PB != 0) {
-            if (packed) pack8_store<PB>(q, c, c < n_chunks, packed);   // all lanes take part in the DPP
+            if (packed) pack8_store<PB>(q, c, valid, packed);   // all lanes take part in the DPP
         }
-        if (c >= n_chunks) continue;
-        if ((c & (LPG - 1)) == 0) {
+        if (turn) {
+            const float cs[8] = {csa.x, csa.y, csa.z, csa.w, csb.x, csb.y, csb.z, csb.w};
+            uint4 o;
+            __half2* h = reinterpret_cast<__half2*>(&o);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                h[i] = __floats2half2_rn(weight_error(w[2 * i], q[2 * i], gp.scale, gp.zero) * cs[2 * i],
+                                         weight_error(w[2 * i + 1], q[2 * i + 1], gp.scale, gp.zero) * cs[2 * i + 1]);
+            s_t[(4 * wave + u) * PITCH + lane] = o;
+        }
+        if (!valid) continue;
+        if ((cc & (LPG - 1)) == 0) {
             const int64_t grp = c / LPG;
             if (scales) scales[grp] = gp.scale;
             if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
@@ -317,16 +338,26 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
             }
             reinterpret_cast<uint2*>(codes)[c] = make_uint2(lo, hi);
         }
-        if (dW) {
+        if (dW && !turn) {
             float d[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) d[i] = weight_error(w[i], q[i], gp.scale, gp.zero);
-            uint32_t ccu = cc + u * 256, rowu = crow;
-            while (ccu >= static_cast<uint32_t>(chunks_per_row)) {
-                ccu -= chunks_per_row;
-                ++rowu;
-            }
-            store_dw8(dW, dW_dtype, colscale, c * 8, rowu, int64_t(ccu) * 8, out, int64_t(chunks_per_row) * 8, d);
+            store_dw8(dW, dW_dtype, colscale, c * 8, row, int64_t(cc) * 8, out, in, d);
+        }
+    }
+    if (!turn) return;                                       // uniform
+    __syncthreads();
+    // store phase: wavefront w writes the tile's 32-column blocks 4w..4w+3; lane l carries row l >> 2,
+    // quarter l & 3 of the block, so the 64 lanes cover 16 rows x 64 bytes = 1 KB contiguous
+    const int srow = lane >> 2, sq = lane & 3;
+    const int64_t grow = row0 + srow;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int kb = 4 * wave + u;                         // block within the tile
+        const int chunk = blockIdx.x * 64 + 4 * kb + sq;     // chunk within the row
+        if (grow < out && chunk < chunks_per_row) {
+            const int64_t at = ((int64_t(chunk >> 2) * out + grow) * 32 + sq * 8);
+            *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = s_t[srow * PITCH + 4 * kb + sq];
         }
     }
 }
@@ -621,14 +652,13 @@ template <int LPG>
 void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
                      uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
                      const float* colscale, uint32_t* packed) {
-    const int64_t n_chunks = out * in / 8;
-    const unsigned blocks = static_cast<unsigned>((n_chunks + 1023) / 1024);
     const uint4* W4 = reinterpret_cast<const uint4*>(W);
     const int cpr = static_cast<int>(in / 8);
+    const dim3 blocks(static_cast<unsigned>((cpr + 63) / 64), static_cast<unsigned>((out + 15) / 16));
     ProfScope prof(ctx, "quant_oc");
 #define OC_GO(PB)                                                                                                  \
-    hipLaunchKernelGGL((quant_oc_fast<LPG, PB>), dim3(blocks), dim3(256), 0, ctx->stream, W4, n_chunks, out, cpr,  \
-                       clip, qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed)
+    hipLaunchKernelGGL((quant_oc_fast<LPG, PB>), blocks, dim3(256), 0, ctx->stream, W4, out, cpr, clip, qmax,     \
+                       1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed)
     switch (pb) {
         case 2: OC_GO(2); break;
         case 3: OC_GO(3); break;
@@ -696,7 +726,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
     const bool vec = (in % 8) == 0;
     const int lpg = g / 8;
     const bool oc_lanes = dim == ADADIM_DIM_OC && vec && (g % 8) == 0 && lpg <= 64 && (lpg & (lpg - 1)) == 0 &&
-                          out * in / 8 < (int64_t(1) << 31);
+                          out <= 16 * 65535;
     const bool ic_regs = dim == ADADIM_DIM_IC && vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
     // the fast kernels assemble the bit stream themselves for these widths
     const bool fused_pack =
