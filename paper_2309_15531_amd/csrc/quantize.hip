@@ -621,6 +621,207 @@ __global__ __launch_bounds__(32 * NSL, 4) void quant_ic_regs(const __half* __res
 }
 
 // ---------------------------------------------------------------------------
+// Element arithmetic of the streaming kernels.  v_fma_mix_f32 reads an fp16 operand straight
+// from one half of a packed register, so the weight is never converted on its own:
+//     t   = fma(w, y, -0)            = RN(w*y)                  (y = RN(1/scale))
+//     r   = fma(-scale, t, w)        the exact residual         (fastdiv.h)
+//     quo = fma(r, y, t)             = RN(w/scale)
+//     k   = med3(rint(quo), -zero, qmax-zero)   = code - zero   (all three are small integers,
+//           so clamping before or after adding the zero point gives the same code)
+//     dW*c = fma(w, c, -(scale*c)*k) = RN((w - RN(scale*k))*c)  for a power of two c:
+//           scaling by c is exact, so RN(scale*c*k) = c*RN(scale*k) and the single rounding of
+//           the fma is the rounding of w - RN(scale*k).  c = 1 gives the plain dW.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// -0.0f the optimiser cannot see through: fma(w, y, -0) must stay an fma for the compiler to
+// pick the mixed-precision form (as a plain product it would convert the fp16 operand first).
+__device__ __forceinline__ float opaque_negzero() {
+    float z = -0.0f;
+    asm("" : "+v"(z));
+    return z;
+}
+template <int HI>
+__device__ __forceinline__ float fma_hff(uint32_t hpair, float b, float c) {   // fma(half HI of hpair, b, c)
+    return __builtin_fmaf(static_cast<float>(__builtin_bit_cast(f16x2, hpair)[HI]), b, c);
+}
+template <int HI>
+__device__ __forceinline__ float fma_ffh(float a, float b, uint32_t hpair) {   // fma(a, b, half HI of hpair)
+    return __builtin_fmaf(a, b, static_cast<float>(__builtin_bit_cast(f16x2, hpair)[HI]));
+}
+
+// Per-column (per-IC) or per-group (per-OC) constants of the element arithmetic.
+struct QConst {
+    float y;      // RN(1/scale)
+    float ns;     // -scale
+    float nz;     // -zero
+    float pz;     // qmax - zero
+    float n0;     // -0.0f, opaque
+};
+
+// RN(w/scale) for the weight in half HI of `pair` (valid when fastdiv_ok(scale))
+template <int HI>
+__device__ __forceinline__ float quant_quo(uint32_t pair, const QConst& c) {
+    const float t = fma_hff<HI>(pair, c.y, c.n0);
+    const float r = fma_ffh<HI>(c.ns, t, pair);
+    return fmaf(r, c.y, t);
+}
+
+// k = code - zero for the 8 weights of one 16-byte chunk, column constants c[0..7].  `slow`
+// (wave-uniform) takes the IEEE division for scales outside fastdiv's range.
+__device__ __forceinline__ void quant_k8(const uint32_t (&v)[4], const QConst (&c)[8], bool slow, float (&k)[8]) {
+    float quo[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        quo[2 * i] = quant_quo<0>(v[i], c[2 * i]);
+        quo[2 * i + 1] = quant_quo<1>(v[i], c[2 * i + 1]);
+    }
+    if (slow) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f16x2 w = __builtin_bit_cast(f16x2, v[i]);
+            quo[2 * i] = pinned_div(static_cast<float>(w[0]), -c[2 * i].ns);
+            quo[2 * i + 1] = pinned_div(static_cast<float>(w[1]), -c[2 * i + 1].ns);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) k[i] = __builtin_amdgcn_fmed3f(rintf(quo[i]), c[i].nz, c[i].pz);
+}
+
+__device__ __forceinline__ uint32_t pack_h2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __floats2half2_rn(lo, hi));
+}
+
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {   // v_pk_min_f16
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b)));
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {   // v_pk_max_f16
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b)));
+}
+__device__ __forceinline__ float half_of(uint32_t pair, int hi) {
+    return __half2float(__ushort_as_half(static_cast<unsigned short>(hi ? pair >> 16 : pair & 0xffffu)));
+}
+
+// per-IC streaming path: one wavefront owns a whole group of G = 8*U rows x 64 columns and
+// shares nothing with its neighbours (no LDS, no barrier), so the waves of a compute unit drift
+// apart and one wave's loads overlap another's arithmetic and stores.  Lane l takes rows
+// 8u + (l >> 3), u = 0..U-1, of the 8 columns of chunk l & 7: every load instruction fetches
+// one full 128-byte line from each of 8 rows, and all U loads of a lane are in flight together.
+// The minima and maxima are taken on the packed fp16 values (exact) and meet across the eight
+// row lanes through three exchanges; lane (row lane r, chunk c) then works out the parameters
+// of column 8c + r alone and the eight lanes of a chunk trade them.  In the scoring layout the
+// 8 rows x 64 bytes that a store instruction writes for one 32-column block are contiguous.
+template <int U, bool SCALED>
+__global__ __launch_bounds__(256) void quant_ic_wave(const __half* __restrict__ W, int64_t out, int64_t in, float clip,
+                                                     float qmax, float rqmax, uint8_t* __restrict__ codes,
+                                                     float* __restrict__ scales, uint8_t* __restrict__ zeros,
+                                                     void* __restrict__ dW, int dW_dtype,
+                                                     const float* __restrict__ colscale) {
+    constexpr int G = 8 * U;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rl = lane >> 3, cl = lane & 7;
+    const int64_t col0 = (int64_t(blockIdx.x) * 4 + wave) * 64 + cl * 8;
+    const int64_t row0 = int64_t(blockIdx.y) * G + rl;      // this lane's rows: row0 + 8u
+    const bool col_ok = col0 < in;                          // in % 8 == 0: the whole chunk is inside
+
+    uint4 raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        raw[u] = col_ok ? *reinterpret_cast<const uint4*>(W + (row0 + 8 * u) * in + col0) : make_uint4(0, 0, 0, 0);
+
+    // column minima / maxima as packed fp16 pairs; the range contains zero anyway
+    uint32_t mn2[4] = {0u, 0u, 0u, 0u}, mx2[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t v[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            mn2[i] = pk_min(mn2[i], v[i]);
+            mx2[i] = pk_max(mx2[i], v[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        mn2[i] = pk_min(mn2[i], dpp_u<0x128>(mn2[i]));     // row_ror:8 = the lane 8 away in its row of 16
+        mx2[i] = pk_max(mx2[i], dpp_u<0x128>(mx2[i]));
+        mn2[i] = pk_min(mn2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mn2[i]), 16, 64)));
+        mx2[i] = pk_max(mx2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx2[i]), 16, 64)));
+        mn2[i] = pk_min(mn2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mn2[i]), 32, 64)));
+        mx2[i] = pk_max(mx2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx2[i]), 32, 64)));
+    }
+    // this lane's column: 8*cl + rl, i.e. half rl & 1 of pair rl >> 1
+    const uint32_t mnp = (rl & 4) ? ((rl & 2) ? mn2[3] : mn2[2]) : ((rl & 2) ? mn2[1] : mn2[0]);
+    const uint32_t mxp = (rl & 4) ? ((rl & 2) ? mx2[3] : mx2[2]) : ((rl & 2) ? mx2[1] : mx2[0]);
+    const GroupParamsR gp = group_params_r(half_of(mnp, rl & 1), half_of(mxp, rl & 1), clip, qmax, rqmax);
+    const bool slow = __any(!gp.fast);
+    if (col_ok) {
+        const int64_t gi = int64_t(blockIdx.y) * in + col0 + rl;
+        if (scales) scales[gi] = gp.scale;
+        if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
+    }
+    if (!codes && !dW) return;
+    QConst qc[8];
+    float cs[8], nscs[8];
+    const float n0 = opaque_negzero();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        qc[i].n0 = n0;
+        const int src = (i << 3) | cl;                      // the lane that worked out column 8*cl + i
+        const float sc = __shfl(gp.scale, src, 64);
+        const float zp = __shfl(gp.zero, src, 64);
+        qc[i].y = __shfl(gp.rcp, src, 64);
+        qc[i].ns = -sc;
+        qc[i].nz = -zp;
+        qc[i].pz = qmax - zp;
+        cs[i] = 1.0f;
+        nscs[i] = -sc;
+    }
+    if constexpr (SCALED) {
+        if (col_ok) {
+            const float4 a = *reinterpret_cast<const float4*>(colscale + col0);
+            const float4 b = *reinterpret_cast<const float4*>(colscale + col0 + 4);
+            cs[0] = a.x; cs[1] = a.y; cs[2] = a.z; cs[3] = a.w;
+            cs[4] = b.x; cs[5] = b.y; cs[6] = b.z; cs[7] = b.w;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) nscs[i] = qc[i].ns * cs[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t row = row0 + 8 * u;
+        const int64_t elem = row * in + col0;
+        const uint32_t v[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+        float k[8];
+        quant_k8(v, qc, slow, k);
+        if (!col_ok) continue;
+        if (codes) {
+            uint32_t lo = 0, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo |= static_cast<uint32_t>(k[i] - qc[i].nz) << (8 * i);
+                hi |= static_cast<uint32_t>(k[4 + i] - qc[4 + i].nz) << (8 * i);
+            }
+            *reinterpret_cast<uint2*>(codes + elem) = make_uint2(lo, hi);
+        }
+        if (dW) {
+            float d[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                d[2 * i] = fma_hff<0>(v[i], cs[2 * i], nscs[2 * i] * k[2 * i]);
+                d[2 * i + 1] = fma_hff<1>(v[i], cs[2 * i + 1], nscs[2 * i + 1] * k[2 * i + 1]);
+            }
+            if (!SCALED && dW_dtype == ADADIM_DW_F32) {
+                float4* p = reinterpret_cast<float4*>(static_cast<float*>(dW) + elem);
+                p[0] = make_float4(d[0], d[1], d[2], d[3]);
+                p[1] = make_float4(d[4], d[5], d[6], d[7]);
+            } else {
+                const uint4 o = make_uint4(pack_h2(d[0], d[1]), pack_h2(d[2], d[3]), pack_h2(d[4], d[5]), pack_h2(d[6], d[7]));
+                const int64_t at = SCALED ? score_index(row, col0, out, in) : elem;
+                *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = o;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Bit-packing: one thread assembles one 32-bit word of a channel's stream.
 // channel stride / element stride describe where code k of channel ch lives:
 // OC: ch*in + k;  IC: k*in + ch.
@@ -675,6 +876,20 @@ constexpr int ic_slices(int lpg) { return lpg >= 8 ? 16 : 8; }
 constexpr bool ic_pack_ok(int lpg, int pb) {
     const int nsl = ic_slices(lpg), rpt = 8 * lpg / nsl, gbits = 8 * lpg * pb;
     return (pb == 2 || pb == 3 || pb == 4) && rpt * pb <= 64 && gbits % 32 == 0 && gbits / 32 <= 2 * nsl;
+}
+
+// streaming per-IC kernel for a group of 8*LPG rows (no packed output)
+template <int LPG>
+void launch_ic_wave(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax,
+                    uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale) {
+    dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(out / (8 * LPG)));
+    ProfScope prof(ctx, "quant_ic");
+    if (dW && dW_dtype == ADADIM_DW_F16_SCALED)
+        hipLaunchKernelGGL((quant_ic_wave<LPG, true>), grid, dim3(256), 0, ctx->stream, W, out, in, clip, qmax,
+                           1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+    else
+        hipLaunchKernelGGL((quant_ic_wave<LPG, false>), grid, dim3(256), 0, ctx->stream, W, out, in, clip, qmax,
+                           1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale);
 }
 
 template <int LPG>
@@ -765,7 +980,11 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             uint32_t* pk = fused_pack ? packed : nullptr;
             const int64_t n_words = (out * bits + 31) / 32;
             switch (lpg) {
-#define IC_CASE(n) case n: launch_ic_regs<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk, n_words); break;
+#define IC_CASE(n)                                                                                              \
+    case n:                                                                                                     \
+        if (pk) launch_ic_regs<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk, n_words); \
+        else launch_ic_wave<n>(ctx, W, out, in, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);     \
+        break;
                 IC_CASE(1) IC_CASE(2) IC_CASE(4) IC_CASE(8) IC_CASE(16) IC_CASE(32)
 #undef IC_CASE
             }
