@@ -188,7 +188,7 @@ def main():
     quant = {}
     n_rot = max(2, int(np.ceil(600e6 / (out_f * in_f * 2))))
     Ws = [Wd] + [Wd.clone() for _ in range(n_rot - 1)]
-    dWs = [torch.empty((out_f, in_f), dtype=torch.float16, device="cuda") for _ in range(n_rot)]
+    dWs = [ctx.alloc_score(out_f, in_f) for _ in range(n_rot)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for dim, name in ((B.DIM_OC, "quant_oc"), (B.DIM_IC, "quant_ic")):
         def sweep():

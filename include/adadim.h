@@ -51,10 +51,13 @@ extern "C" {
  * Scoring layout.  The two fp16 operands of the error GEMM, the column-scaled dW
  * (ADADIM_DW_F16_SCALED) and the prepared Hs, are consumed 32 contraction elements at a
  * time from 256 consecutive rows.  When `in` is a multiple of 32 an [rows, in] operand is
- * therefore stored blocked along its columns: element (r, c) at index
- * ((c / 32) * rows + r) * 32 + c % 32; otherwise plain row-major (r * in + c).  The buffers
- * hold rows * in elements either way.
+ * therefore stored as [row tile of 256][column block of 32][256 rows][32 columns]: element
+ * (r, c) at index (((r / 256) * (in / 32) + c / 32) * 256 + r % 256) * 32 + c % 32, the last
+ * row tile padded to 256 rows (the padding is never read or written); otherwise plain
+ * row-major (r * in + c).  adadim_score_elems gives the number of elements such a buffer
+ * must hold: round_up(rows, 256) * in, or rows * in for the row-major form.
  */
+int64_t adadim_score_elems(int64_t rows, int64_t cols);
 
 typedef struct adadim_ctx adadim_ctx;
 
@@ -106,9 +109,12 @@ int adadim_hessian(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, i
  *   scales f32 [out, in/g] (OC) or [out/g, in] (IC)
  *   zeros  u8  same shape as scales
  *   dW     [out, in] in the type named by dW_dtype.  ADADIM_DW_F16_SCALED
- *          multiplies column j by colscale[j] (fp32 [in], powers of two from
- *          adadim_hessian_prepare) before the fp16 rounding; colscale must
- *          then be non-NULL, otherwise it is ignored.
+ *          multiplies column j by colscale[j] before the fp16 rounding and
+ *          stores the result in the scoring layout (adadim_score_elems(out, in)
+ *          elements).  colscale is fp32 [in] and must hold powers of two, as
+ *          adadim_hessian_prepare writes them (the kernels fold the factor into
+ *          the scale, which is exact only then); it must be non-NULL for this
+ *          dtype and is ignored otherwise.
  *   packed u32 bitstream of the codes of each channel (row for OC, column for
  *          IC): code k of the channel at bits [k*bits, (k+1)*bits) of the
  *          channel's stream, little-endian 32-bit words, each channel padded
@@ -123,7 +129,8 @@ int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in,
 /*
  * Prepares H for scoring on the matrix cores.  With the power-of-two column
  * scales d_j ~ sqrt(H_jj):
- *   Hs     fp16 [in, in] in the scoring layout: Hs[n,k] = H[n,k]/(d_n d_k) for k < n, 0 elsewhere
+ *   Hs     fp16 [in, in] in the scoring layout (adadim_score_elems(in, in) elements):
+ *          Hs[n,k] = H[n,k]/(d_n d_k) for k < n, 0 elsewhere
  *   hmeta  f32  [2, in]:  hmeta[0,j] = d_j (the colscale of adadim_quantize),
  *                         hmeta[1,j] = H_jj
  * so that tr(dW H dW^T) = sum_o ( sum_j H_jj dW_oj^2 + 2 sum_{k<n} dW'_ok Hs_nk dW'_on ),

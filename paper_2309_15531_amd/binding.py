@@ -18,7 +18,7 @@ DIM_OC, DIM_IC = 0, 1
 DW_F32, DW_F16, DW_F16_SCALED = 0, 1, 2
 
 EXPORTS = (
-    "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version",
+    "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version", "adadim_score_elems",
     "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_profile", "adadim_profile_read",
@@ -27,16 +27,23 @@ EXPORTS = (
 _lib = None
 
 
+def score_elems(rows: int, cols: int) -> int:
+    """Elements a scoring-layout buffer for an [rows, cols] operand must hold (adadim_score_elems)."""
+    return int(load_library().adadim_score_elems(rows, cols))
+
+
 def from_score_layout(a, rows: int, cols: int):
     """Row-major [rows, cols] view of a numpy array held in the library's scoring layout
-    (ADADIM_DW_F16_SCALED dW and the prepared Hs): blocked by 32 along the columns when cols
-    is a multiple of 32 (element (r, c) at ((c // 32) * rows + r) * 32 + c % 32), row-major
+    (ADADIM_DW_F16_SCALED dW and the prepared Hs): [row tile of 256][column block of 32]
+    [256 rows][32 columns] when cols is a multiple of 32, the last row tile padded; row-major
     otherwise.  Index shuffling only."""
     import numpy as np
     a = np.asarray(a).reshape(-1)
     if cols % 32:
-        return a.reshape(rows, cols)
-    return np.ascontiguousarray(a.reshape(cols // 32, rows, 32).transpose(1, 0, 2)).reshape(rows, cols)
+        return a[:rows * cols].reshape(rows, cols)
+    tiles = (rows + 255) // 256
+    t = a[:tiles * 256 * cols].reshape(tiles, cols // 32, 256, 32).transpose(0, 2, 1, 3)
+    return np.ascontiguousarray(t).reshape(tiles * 256, cols)[:rows]
 
 
 class AdaDimError(RuntimeError):
@@ -64,6 +71,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_last_error.restype = c_char_p
     lib.adadim_version.argtypes = []
     lib.adadim_version.restype = c_char_p
+    lib.adadim_score_elems.argtypes = [c_int64, c_int64]
+    lib.adadim_score_elems.restype = c_int64
     lib.adadim_hessian.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_int]
     lib.adadim_hessian.restype = c_int
     lib.adadim_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_float,
@@ -150,6 +159,11 @@ class Context:
                                               _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(dW), dW_dtype,
                                               _ptr(colscale), _ptr(packed)))
 
+    def alloc_score(self, rows: int, cols: int, device="cuda"):
+        """Flat fp16 device buffer large enough for an [rows, cols] operand in the scoring layout."""
+        import torch
+        return torch.empty(score_elems(rows, cols), dtype=torch.float16, device=device)
+
     def adadim_hessian_prepare(self, H, Hs, hmeta):
         self._check(self._lib.adadim_hessian_prepare(self._h, _ptr(H), H.shape[0], _ptr(Hs), _ptr(hmeta)))
 
@@ -158,13 +172,14 @@ class Context:
         self._check(self._lib.adadim_layer_error(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(H),
                                                  _ptr(loss_rows), _ptr(loss)))
 
-    def adadim_layer_error_prepared(self, dW, dW_dtype: int, Hs, hmeta, loss, loss_rows=None):
-        out_f, in_f = dW.shape
+    def adadim_layer_error_prepared(self, dW, dW_dtype: int, Hs, hmeta, loss, loss_rows=None, shape=None):
+        """shape = (out, in) when dW is a flat scoring-layout buffer (see alloc_score)."""
+        out_f, in_f = dW.shape if shape is None else shape
         self._check(self._lib.adadim_layer_error_prepared(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(Hs),
                                                           _ptr(hmeta), _ptr(loss_rows), _ptr(loss)))
 
-    def adadim_layer_error_batch(self, dWs, dW_dtype: int, Hs, hmeta, losses, loss_rows=None):
-        out_f, in_f = dWs[0].shape
+    def adadim_layer_error_batch(self, dWs, dW_dtype: int, Hs, hmeta, losses, loss_rows=None, shape=None):
+        out_f, in_f = dWs[0].shape if shape is None else shape
         arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
         self._check(self._lib.adadim_layer_error_batch(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
                                                        _ptr(hmeta), _ptr(loss_rows), _ptr(losses)))

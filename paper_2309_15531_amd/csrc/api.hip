@@ -118,7 +118,12 @@ int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* t
     return ADADIM_OK;
 }
 
-const char* adadim_version(void) { return "adadim-gfx950 0.1"; }
+const char* adadim_version(void) { return "adadim-gfx950 0.2"; }
+
+int64_t adadim_score_elems(int64_t rows, int64_t cols) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return score_elems(rows, cols);
+}
 
 int adadim_create(adadim_ctx** out, void* hip_stream) {
     if (!out) return adadim_fail(nullptr, ADADIM_ENULL, "adadim_create: out is NULL");
@@ -235,7 +240,7 @@ int adadim_layer_error(adadim_ctx* ctx, const void* dW, int dW_dtype, int64_t ou
     if (!ctx) return ADADIM_ENULL;
     int rc = check_error_args(ctx, "adadim_layer_error", dW, dW_dtype, out, in, H, loss, false);
     if (rc != ADADIM_OK) return rc;
-    __half* Hs = static_cast<__half*>(adadim_workspace(ctx, WS_HS, size_t(in) * size_t(in) * sizeof(__half)));
+    __half* Hs = static_cast<__half*>(adadim_workspace(ctx, WS_HS, size_t(score_elems(in, in)) * sizeof(__half)));
     float* hmeta = static_cast<float*>(adadim_workspace(ctx, WS_HMETA, size_t(in) * 2 * sizeof(float)));
     if (!Hs || !hmeta) return ADADIM_EHIP;
     rc = launch_hessian_prepare(ctx, H, in, Hs, hmeta);

@@ -77,12 +77,22 @@ void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes);
     } while (0)
 
 // Scoring layout of an fp16 [rows, cols] operand of the error GEMM (the column-scaled dW and the
-// prepared H): blocked along the contraction index when cols is a multiple of 32, so that the 64
-// bytes a pipeline stage needs from each of 256 consecutive rows are contiguous in memory (whole
-// 128-byte lines per request); plain row-major otherwise.
+// prepared H).  The GEMM consumes 32 contraction elements (64 bytes) from each of 256 consecutive
+// rows per pipeline stage.  When cols is a multiple of 32 the operand is therefore stored as
+// [row tile of 256][column block of 32][256 rows][32 columns]: a stage is one contiguous 16 KB
+// piece (whole 128-byte lines per request), successive stages of a tile follow each other in
+// memory, and no pitch is a large power of two (a [column block][rows][32] layout had a pitch of
+// rows*64 bytes between column blocks, which for 4096 rows put every block of a producer's tile
+// on the same memory channels).  The last row tile is padded to 256 rows: a buffer holds
+// score_elems(rows, cols) elements.  Otherwise plain row-major.
 __host__ __device__ inline bool score_blocked(int64_t cols) { return (cols & 31) == 0; }
+__host__ __device__ inline int64_t score_elems(int64_t rows, int64_t cols) {
+    return score_blocked(cols) ? ((rows + 255) & ~int64_t(255)) * cols : rows * cols;
+}
 __host__ __device__ inline int64_t score_index(int64_t row, int64_t col, int64_t rows, int64_t cols) {
-    return score_blocked(cols) ? ((col >> 5) * rows + row) * 32 + (col & 31) : row * cols + col;
+    (void)rows;
+    return score_blocked(cols) ? (((row >> 8) * (cols >> 5) + (col >> 5)) * 256 + (row & 255)) * 32 + (col & 31)
+                               : row * cols + col;
 }
 
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

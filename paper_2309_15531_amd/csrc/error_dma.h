@@ -17,8 +17,9 @@
 // Both operands are contraction-contiguous per row, so a DMA transfer
 // (global_load_lds_dwordx4, 1 KB per wavefront instruction) brings 16 rows x
 // 32 k and the MFMA fragments are plain 16-byte LDS reads.  In the scoring
-// layout (common.h: blocked by 32 along k when `in` is a multiple of 32) those
-// 16 x 64 bytes are one contiguous kilobyte, i.e. eight whole 128-byte lines;
+// layout (common.h: 256-row tiles blocked by 32 along k when `in` is a multiple
+// of 32) those 16 x 64 bytes are one contiguous kilobyte, i.e. eight whole
+// 128-byte lines, and a tile's stages follow each other in memory;
 // with row-major operands they would be sixteen half lines and the L2 request
 // rate, not the matrix cores, would set the pace.  Stage layout:
 // operand 0 (256 rows of Hs) then operand 1 (256 rows of dW'), each [256 rows][64 bytes];
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     // of the stage) and their advance per stage
     const char* baseA = reinterpret_cast<const char*>(Hs + score_index(col0, k_begin + r0, in, in));    // operand 0
     const char* baseB = reinterpret_cast<const char*>(A + score_index(row0, k_begin + r0, out, in));    // operand 1
-    const int64_t stepA = blocked ? in * 64 : KT * 2, stepB = blocked ? out * 64 : KT * 2;
+    const int64_t stepA = blocked ? BT * ROWB : KT * 2, stepB = stepA;   // blocked: the next 16 KB piece
     int issued = 1;
     const char* curA = baseA;
     const char* curB = baseB;

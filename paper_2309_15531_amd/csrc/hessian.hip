@@ -150,13 +150,15 @@ __global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, 
                                                    const float* __restrict__ hmeta, __half* __restrict__ Hs) {
     const int64_t chunks_per_row = in / 8;
     const int64_t c = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (c >= in * chunks_per_row) return;
+    if (c * 8 >= score_elems(in, in)) return;
     // Threads walk the OUTPUT in memory order, so that stores are contiguous in either layout:
-    // blocked (in % 32 == 0): 16-byte piece c is (k block, row n, quarter) = (c / (4 in), (c / 4) % in, c % 4).
+    // blocked (in % 32 == 0): 16-byte piece c is (row tile, k block, row in tile, quarter).
     int64_t n, k0;
     if (score_blocked(in)) {
-        n = (c >> 2) % in;
-        k0 = (c / (4 * in)) * 32 + (c & 3) * 8;
+        const int64_t piece = c >> 10;                       // (row tile, k block): 256 rows x 4 quarters each
+        n = (piece / (in >> 5)) * 256 + ((c >> 2) & 255);
+        k0 = (piece % (in >> 5)) * 32 + (c & 3) * 8;
+        if (n >= in) return;                                 // padding rows of the last tile
     } else {
         n = c / chunks_per_row;
         k0 = (c % chunks_per_row) * 8;
@@ -287,7 +289,7 @@ int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* 
                            in, hmeta);
     }
     ADADIM_LAUNCH_CHECK(ctx, "hprep_meta");
-    const int64_t chunks = in * (in / 8);
+    const int64_t chunks = score_elems(in, in) / 8;
     {
         ProfScope prof(ctx, "hprep_scale");
         hipLaunchKernelGGL(hprep_scale, dim3(static_cast<unsigned>((chunks + 255) / 256)), dim3(256), 0, ctx->stream,

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void error_prologue(SrcBatch src, int dW_dtype
     __shared__ float s_red[256];
     const int64_t o = blockIdx.x;
     const void* __restrict__ dW = src.dW[blockIdx.y];
-    __half* __restrict__ dW16 = dW16_all ? dW16_all + int64_t(blockIdx.y) * out * in : nullptr;
+    __half* __restrict__ dW16 = dW16_all ? dW16_all + int64_t(blockIdx.y) * score_elems(out, in) : nullptr;
     float* __restrict__ diag = diag_all + int64_t(blockIdx.y) * out;
     const float* d = hmeta;
     const float* hd = hmeta + in;
@@ -220,12 +220,12 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
         __half* dW16 = nullptr;
         if (dW_dtype != ADADIM_DW_F16_SCALED) {
             dW16 = static_cast<__half*>(
-                adadim_workspace(ctx, WS_DW16, size_t(nc) * size_t(out) * size_t(in) * sizeof(__half)));
+                adadim_workspace(ctx, WS_DW16, size_t(nc) * size_t(score_elems(out, in)) * sizeof(__half)));
             if (!dW16) return ADADIM_EHIP;
         }
         for (int c = 0; c < edma::MAX_BATCH; ++c) {
             src.dW[c] = c < nc ? dW[c0 + c] : nullptr;
-            batch.A[c] = c < nc ? (dW16 ? dW16 + size_t(c) * size_t(out) * size_t(in)
+            batch.A[c] = c < nc ? (dW16 ? dW16 + size_t(c) * size_t(score_elems(out, in))
                                         : static_cast<const __half*>(dW[c0 + c]))
                                 : nullptr;
         }

@@ -12,6 +12,7 @@
 #include "common.h"
 #include "fastdiv.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace {
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
         const int kb = 4 * wave + u;                         // block within the tile
         const int chunk = blockIdx.x * 64 + 4 * kb + sq;     // chunk within the row
         if (grow < out && chunk < chunks_per_row) {
-            const int64_t at = ((int64_t(chunk >> 2) * out + grow) * 32 + sq * 8);
+            const int64_t at = score_index(grow, int64_t(chunk) * 8, out, in);
             *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = s_t[srow * PITCH + 4 * kb + sq];
         }
     }
@@ -700,27 +701,30 @@ __device__ __forceinline__ float half_of(uint32_t pair, int hi) {
     return __half2float(__ushort_as_half(static_cast<unsigned short>(hi ? pair >> 16 : pair & 0xffffu)));
 }
 
-// per-IC streaming path: one wavefront owns a whole group of G = 8*U rows x 64 columns and
-// shares nothing with its neighbours (no LDS, no barrier), so the waves of a compute unit drift
-// apart and one wave's loads overlap another's arithmetic and stores.  Lane l takes rows
-// 8u + (l >> 3), u = 0..U-1, of the 8 columns of chunk l & 7: every load instruction fetches
-// one full 128-byte line from each of 8 rows, and all U loads of a lane are in flight together.
-// The minima and maxima are taken on the packed fp16 values (exact) and meet across the eight
-// row lanes through three exchanges; lane (row lane r, chunk c) then works out the parameters
-// of column 8c + r alone and the eight lanes of a chunk trade them.  In the scoring layout the
-// 8 rows x 64 bytes that a store instruction writes for one 32-column block are contiguous.
-template <int U, bool SCALED>
-__global__ __launch_bounds__(256) void quant_ic_wave(const __half* __restrict__ W, int64_t out, int64_t in, float clip,
-                                                     float qmax, float rqmax, uint8_t* __restrict__ codes,
-                                                     float* __restrict__ scales, uint8_t* __restrict__ zeros,
-                                                     void* __restrict__ dW, int dW_dtype,
-                                                     const float* __restrict__ colscale) {
-    constexpr int G = 8 * U;
+// per-IC streaming path.  A group of G = 8*U*RW rows x 64 columns is shared by RW wavefronts, each
+// holding 8*U rows: lane l takes rows 8u + (l >> 3), u = 0..U-1, of the 8 columns of chunk l & 7,
+// so every load instruction fetches one full 128-byte line from each of 8 rows and all U loads of a
+// lane are in flight together.  Small per-wave tiles matter: a wave reads its whole tile before it
+// can write anything, and only many short waves keep reads and writes mixed on the memory fabric.
+// Minima and maxima are taken on the packed fp16 values (exact), meet across the eight row lanes
+// through three exchanges and across the RW waves through 512 bytes of LDS (the only barrier).
+// Lane (row lane r, chunk c) then works out the parameters of column 8c + r alone and the eight
+// lanes of a chunk trade them.  In the scoring layout the 8 rows x 64 bytes that a store
+// instruction writes for one 32-column block are contiguous.
+template <int U, int RW, bool SCALED>
+__global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
+    const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax,
+    uint8_t* __restrict__ codes, float* __restrict__ scales, uint8_t* __restrict__ zeros, void* __restrict__ dW,
+    int dW_dtype, const float* __restrict__ colscale) {
+    constexpr int CSW = RW <= 4 ? 4 / RW : 1;                // 64-column sets per block
+    constexpr int G = 8 * U * RW;
+    __shared__ uint32_t s_mm[CSW][RW][2][32];                // [set][row wave][min|max][chunk*4 + pair]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rw = wave % RW, cw = wave / RW;
     const int rl = lane >> 3, cl = lane & 7;
-    const int64_t col0 = (int64_t(blockIdx.x) * 4 + wave) * 64 + cl * 8;
-    const int64_t row0 = int64_t(blockIdx.y) * G + rl;      // this lane's rows: row0 + 8u
-    const bool col_ok = col0 < in;                          // in % 8 == 0: the whole chunk is inside
+    const int64_t col0 = ((int64_t(blockIdx.x) * CSW + cw) * 8 + cl) * 8;
+    const int64_t row0 = int64_t(blockIdx.y) * G + rw * (8 * U) + rl;   // this lane's rows: row0 + 8u
+    const bool col_ok = col0 < in;                           // in % 8 == 0: the whole chunk is inside
 
     uint4 raw[U];
 #pragma unroll
@@ -748,11 +752,27 @@ __global__ __launch_bounds__(256) void quant_ic_wave(const __half* __restrict__ 
         mx2[i] = pk_max(mx2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx2[i]), 32, 64)));
     }
     // this lane's column: 8*cl + rl, i.e. half rl & 1 of pair rl >> 1
-    const uint32_t mnp = (rl & 4) ? ((rl & 2) ? mn2[3] : mn2[2]) : ((rl & 2) ? mn2[1] : mn2[0]);
-    const uint32_t mxp = (rl & 4) ? ((rl & 2) ? mx2[3] : mx2[2]) : ((rl & 2) ? mx2[1] : mx2[0]);
+    uint32_t mnp, mxp;
+    if constexpr (RW > 1) {
+        if (rl == 0) {
+            *reinterpret_cast<uint4*>(&s_mm[cw][rw][0][cl * 4]) = make_uint4(mn2[0], mn2[1], mn2[2], mn2[3]);
+            *reinterpret_cast<uint4*>(&s_mm[cw][rw][1][cl * 4]) = make_uint4(mx2[0], mx2[1], mx2[2], mx2[3]);
+        }
+        __syncthreads();
+        mnp = s_mm[cw][0][0][cl * 4 + (rl >> 1)];
+        mxp = s_mm[cw][0][1][cl * 4 + (rl >> 1)];
+#pragma unroll
+        for (int w = 1; w < RW; ++w) {
+            mnp = pk_min(mnp, s_mm[cw][w][0][cl * 4 + (rl >> 1)]);
+            mxp = pk_max(mxp, s_mm[cw][w][1][cl * 4 + (rl >> 1)]);
+        }
+    } else {
+        mnp = (rl & 4) ? ((rl & 2) ? mn2[3] : mn2[2]) : ((rl & 2) ? mn2[1] : mn2[0]);
+        mxp = (rl & 4) ? ((rl & 2) ? mx2[3] : mx2[2]) : ((rl & 2) ? mx2[1] : mx2[0]);
+    }
     const GroupParamsR gp = group_params_r(half_of(mnp, rl & 1), half_of(mxp, rl & 1), clip, qmax, rqmax);
     const bool slow = __any(!gp.fast);
-    if (col_ok) {
+    if (col_ok && rw == 0) {
         const int64_t gi = int64_t(blockIdx.y) * in + col0 + rl;
         if (scales) scales[gi] = gp.scale;
         if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
@@ -882,14 +902,26 @@ constexpr bool ic_pack_ok(int lpg, int pb) {
 template <int LPG>
 void launch_ic_wave(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax,
                     uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale) {
-    dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(out / (8 * LPG)));
+    static const int force_u = getenv("ADADIM_IC_U") ? atoi(getenv("ADADIM_IC_U")) : 0;
+    const bool scaled = dW && dW_dtype == ADADIM_DW_F16_SCALED;
+    const float rq = 1.0f / qmax;
     ProfScope prof(ctx, "quant_ic");
-    if (dW && dW_dtype == ADADIM_DW_F16_SCALED)
-        hipLaunchKernelGGL((quant_ic_wave<LPG, true>), grid, dim3(256), 0, ctx->stream, W, out, in, clip, qmax,
-                           1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale);
-    else
-        hipLaunchKernelGGL((quant_ic_wave<LPG, false>), grid, dim3(256), 0, ctx->stream, W, out, in, clip, qmax,
-                           1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+#define IC_W(U, S)                                                                                              \
+    do {                                                                                                        \
+        constexpr int RW = LPG / (U), CSW = RW <= 4 ? 4 / RW : 1, TH = RW <= 4 ? 256 : 64 * RW;                  \
+        dim3 grid(static_cast<unsigned>((in + 64 * CSW - 1) / (64 * CSW)), static_cast<unsigned>(out / (8 * LPG))); \
+        hipLaunchKernelGGL((quant_ic_stream<U, RW, S>), grid, dim3(TH), 0, ctx->stream, W, out, in, clip, qmax,  \
+                           rq, codes, scales, zeros, dW, dW_dtype, colscale);                                   \
+    } while (0)
+    if constexpr (LPG >= 8) {
+        if (force_u == 8) { if (scaled) IC_W(8, true); else IC_W(8, false); return; }
+    }
+    if constexpr (LPG == 16) {
+        if (force_u == 16) { if (scaled) IC_W(16, true); else IC_W(16, false); return; }
+    }
+    constexpr int UD = LPG < 4 ? LPG : 4;
+    if (scaled) IC_W(UD, true); else IC_W(UD, false);
+#undef IC_W
 }
 
 template <int LPG>

@@ -24,7 +24,7 @@ class PreparedHessian:
         self.ctx = ctx
         self.in_f = in_f
         self.H = torch.empty((in_f, in_f), dtype=torch.float32, device=device)
-        self.Hs = torch.empty((in_f, in_f), dtype=torch.float16, device=device)
+        self.Hs = ctx.alloc_score(in_f, in_f, device)      # scoring layout, flat
         self.hmeta = torch.empty((2, in_f), dtype=torch.float32, device=device)
         self.tokens = 0
 
@@ -55,7 +55,7 @@ class LayerSearch:
         self.clips = [float(np.float32(c)) for c in clips]
         self.cands = [(d, c) for d in (B.DIM_OC, B.DIM_IC) for c in self.clips]
         self.batch = max(1, min(batch, 8, len(self.cands)))
-        self.dWs = [torch.empty((out_f, in_f), dtype=torch.float16, device=device) for _ in range(self.batch)]
+        self.dWs = [ctx.alloc_score(out_f, in_f, device) for _ in range(self.batch)]   # scoring layout, flat
         self.losses = torch.empty(len(self.cands), dtype=torch.float32, device=device)
         self.best = torch.empty(1, dtype=torch.int32, device=device)
         self.keep_winner = keep_winner
@@ -86,7 +86,7 @@ class LayerSearch:
                 self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, dW=self.dWs[k],
                                          dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale, **extra)
             self.ctx.adadim_layer_error_batch(self.dWs[:len(chunk)], B.DW_F16_SCALED, hp.Hs, hp.hmeta,
-                                              self.losses[c0:c0 + len(chunk)])
+                                              self.losses[c0:c0 + len(chunk)], shape=(self.out_f, self.in_f))
 
     def run(self, W, hp: PreparedHessian):
         """Whole search for one layer: returns (best index, dim, clip); with keep_winner the

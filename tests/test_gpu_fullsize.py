@@ -95,12 +95,13 @@ def test_down_proj_sampled(ctx):
         codes = torch.empty((out_f, in_f), dtype=torch.uint8, device="cuda")
         scales = torch.empty(meta, dtype=torch.float32, device="cuda")
         zeros = torch.empty(meta, dtype=torch.uint8, device="cuda")
-        dW = torch.empty((out_f, in_f), dtype=torch.float16, device="cuda")
+        dW = ctx.alloc_score(out_f, in_f)
         ctx.adadim_quantize(Wd, dim, bits, group, 1.0, codes=codes, scales=scales, zeros=zeros, dW=dW,
                             dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
         loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         lrows = torch.zeros(out_f, dtype=torch.float32, device="cuda")
-        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows)
+        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows,
+                                        shape=(out_f, in_f))
         torch.cuda.synchronize()
         assert np.array_equal(codes.cpu().numpy(), q["codes"])
         assert np.array_equal(scales.cpu().numpy(), q["scales"])

@@ -46,8 +46,11 @@ def gpu_quantize(ctx, W, dim, bits, group, clip=1.0, dW_dtype=B.DW_F32, colscale
     codes = torch.full((out_f, in_f), 255, dtype=torch.uint8, device="cuda") if want_codes else None
     scales = torch.full(meta, -1.0, dtype=torch.float32, device="cuda")
     zeros = torch.full(meta, 255, dtype=torch.uint8, device="cuda")
-    dW = torch.full((out_f, in_f), float("nan"), dtype=torch.float32 if dW_dtype == B.DW_F32 else torch.float16,
-                    device="cuda")
+    if dW_dtype == B.DW_F16_SCALED:
+        dW = ctx.alloc_score(out_f, in_f).fill_(float("nan"))   # flat, last row tile padded
+    else:
+        dW = torch.full((out_f, in_f), float("nan"), dtype=torch.float32 if dW_dtype == B.DW_F32 else torch.float16,
+                        device="cuda")
     n_ch, ln = (out_f, in_f) if dim == OC else (in_f, out_f)
     packed = torch.full((n_ch, (ln * bits + 31) // 32), -1, dtype=torch.int32, device="cuda") if want_packed else None
     ctx.adadim_quantize(Wd, dim, bits, group, clip, codes=codes, scales=scales, zeros=zeros, dW=dW,
@@ -111,6 +114,14 @@ def test_quantize_clip_and_fp16_outputs(ctx, dim, clip):
     cs = np.ldexp(np.float32(1.0), np.random.default_rng(3).integers(-2, 9, size=512)).astype(np.float32)
     got = gpu_quantize(ctx, W, dim, 3, 64, clip, dW_dtype=B.DW_F16_SCALED, colscale=dev(cs))
     assert np.array_equal(B.from_score_layout(got["dW"], 256, 512), (ref["dW"] * cs[None, :]).astype(np.float16))
+    # the same with row counts that leave the last 256-row tile of the scoring layout ragged
+    for (o2, i2, g2) in ((384, 640, 128), (640, 264, 8), (96, 1536, 32)):
+        W2 = rand_w(o2, i2, seed=o2 + i2)
+        cs2 = np.ldexp(np.float32(1.0), np.random.default_rng(4).integers(-2, 9, size=i2)).astype(np.float32)
+        ref2 = oracle.quantize(W2, dim, 4, g2, clip)
+        got2 = gpu_quantize(ctx, W2, dim, 4, g2, clip, dW_dtype=B.DW_F16_SCALED, colscale=dev(cs2), want_packed=False)
+        assert np.array_equal(B.from_score_layout(got2["dW"], o2, i2), (ref2["dW"] * cs2[None, :]).astype(np.float16))
+        assert np.array_equal(got2["codes"], ref2["codes"])
     # packed stream without a caller-side code buffer
     got = gpu_quantize(ctx, W, dim, 3, 64, clip, want_codes=False)
     assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, 3))
@@ -231,10 +242,10 @@ def test_layer_error_prepared_matches_and_scaled_input(ctx, in_f):
     assert np.allclose(Hs, np.tril(Hg.astype(np.float64) / d[:, None] / d[None, :], -1), rtol=2.0 ** -10, atol=1e-7)
     ref = oracle.layer_error(oracle.quantize(W, IC, 3, 64)["dW"], oracle.hessian(X))
     Wd = dev(W)
-    dW = torch.empty((out_f, in_f), dtype=torch.float16, device="cuda")
+    dW = ctx.alloc_score(out_f, in_f)   # 640 rows: the last 256-row tile of the scoring layout is half empty
     losses = torch.zeros(3, dtype=torch.float32, device="cuda")
     ctx.adadim_quantize(Wd, IC, 3, 64, dW=dW, dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
-    ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, losses[0:1])
+    ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, losses[0:1], shape=(out_f, in_f))
     dW32 = torch.empty((out_f, in_f), dtype=torch.float32, device="cuda")
     ctx.adadim_quantize(Wd, IC, 3, 64, dW=dW32, dW_dtype=B.DW_F32)
     ctx.adadim_layer_error_prepared(dW32, B.DW_F32, hp.Hs, hp.hmeta, losses[1:2])

@@ -70,9 +70,10 @@ def test_llama13b_gate_proj_131072_tokens(ctx):
         q = oracle.quantize(W, dm, 3, 128)
         lrows = torch.zeros(out_f, dtype=torch.float32, device="cuda")
         loss = torch.zeros(1, dtype=torch.float32, device="cuda")
-        dW = torch.empty((out_f, in_f), dtype=torch.float16, device="cuda")
+        dW = ctx.alloc_score(out_f, in_f)
         ctx.adadim_quantize(Wd, dm, 3, 128, dW=dW, dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
-        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows)
+        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows,
+                                        shape=(out_f, in_f))
         torch.cuda.synchronize()
         assert loss.item() == got[dm]
         g = lrows.cpu().numpy().astype(np.float64)
@@ -141,14 +142,15 @@ def test_llama70b_down_proj_widest_hessian(ctx):
         assert abs(h_ij[k] - xi @ xj) <= 2e-5 * np.sqrt((xi @ xi) * (xj @ xj))
     Wd = dev(W)
     rows = np.sort(rng.choice(out_f, 8, replace=False))
-    dW = torch.empty((out_f, in_f), dtype=torch.float16, device="cuda")
+    dW = ctx.alloc_score(out_f, in_f)
     for dm in (OC, IC):
         q = oracle.quantize(W, dm, 3, 64)
         lrows = torch.zeros(out_f, dtype=torch.float32, device="cuda")
         loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         codes = torch.empty((out_f, in_f), dtype=torch.uint8, device="cuda")
         ctx.adadim_quantize(Wd, dm, 3, 64, codes=codes, dW=dW, dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
-        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows)
+        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows,
+                                        shape=(out_f, in_f))
         torch.cuda.synchronize()
         assert np.array_equal(codes.cpu().numpy(), q["codes"])
         g = lrows.cpu().numpy().astype(np.float64)
