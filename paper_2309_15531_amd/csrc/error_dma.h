@@ -76,13 +76,8 @@ struct Batch {
 };
 
 // Column block nb contracts over k < kend(nb) = min(in, (nb+1)*256), cut into
-// chunks of kc_len (a multiple of 32).  Slots enumerate (nb, chunk) with nb
-// descending; slot_of_nb[] is not stored: the decode loop below recomputes it.
-__device__ __forceinline__ int chunks_of(int nb, int64_t in, int kc_len) {
-    const int64_t kend = min(in, int64_t(nb + 1) * BT);
-    return static_cast<int>((kend + kc_len - 1) / kc_len);
-}
-
+// chunks of kc_len (a multiple of 256).  Slots enumerate (chunk, nb): chunk
+// ascending, nb descending over the column blocks that reach the chunk.
 template <int DBG = 0>
 __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half* __restrict__ Hs, int64_t out,
                                                        int64_t in, int MB, int NB, int kc_len, int n_slots,
@@ -91,26 +86,36 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
-    // Workgroups go to the eight XCDs round-robin by launch index.  Slots are sorted by
-    // decreasing contraction length and dealt to the XCDs in serpentine order (0..7, 7..0, ...),
-    // which evens out the totals; all row blocks of all candidates of a slot run on the same XCD,
-    // longest slots first, sharing the slot's Hs tile in that XCD's L2.
+    // Workgroups go to the eight XCDs round-robin by launch index, and a compute unit holds one
+    // workgroup, so 32 consecutive workgroups of an XCD run together and share its L2.  They are
+    // made a unit of 4 slots x 8 row blocks: per pipeline stage the unit then fetches 4 Hs tiles
+    // and 8 dW' tiles instead of the 33 tiles that 32 row blocks of one slot would need (the dW'
+    // tiles, re-read for every column block, are what would otherwise saturate the memory
+    // fabric).  Slots are listed chunk by chunk, column blocks descending inside a chunk, so the
+    // slots of a unit cover the same contraction range; units are dealt to the XCDs in serpentine
+    // order (0..7, 7..0, ...), which evens out the totals, slot group by slot group, so that
+    // neighbouring XCDs work on the same Hs tiles at the same time.
     const int xcd = static_cast<int>(blockIdx.x % 8), seq = static_cast<int>(blockIdx.x / 8);
-    const int per_slot = batch.n * MB;
-    const int round = seq / per_slot;
-    const int slot = round * 8 + ((round & 1) ? 7 - xcd : xcd);
-    if (slot >= n_slots) return;
-    const int cand = (seq % per_slot) / MB, mb = seq % MB;
+    const int n_pairs = batch.n * MB;                        // (candidate, row block) pairs
+    const int n_rs = (n_pairs + 7) / 8, n_sg = (n_slots + 3) / 4;
+    const int round = seq / 32, within = seq % 32;
+    const int unit = round * 8 + ((round & 1) ? 7 - xcd : xcd);
+    if (unit >= n_sg * n_rs) return;
+    const int slot = (unit / n_rs) * 4 + (within & 3), pair = (unit % n_rs) * 8 + (within >> 2);
+    if (slot >= n_slots || pair >= n_pairs) return;
+    const int cand = pair / MB, mb = pair % MB;
     const __half* __restrict__ A = batch.A[cand];
-    int nb = NB - 1, rem = slot;
+    const int kb = kc_len / BT;
+    int chunk = 0, rem = slot;
     for (;;) {
-        const int c = chunks_of(nb, in, kc_len);
-        if (rem < c) break;
-        rem -= c;
-        --nb;
+        const int cnt = NB - chunk * kb;                     // column blocks that reach this chunk
+        if (rem < cnt) break;
+        rem -= cnt;
+        ++chunk;
     }
+    const int nb = NB - 1 - rem;
     const int64_t kend = (DBG & 1) ? in : min(in, int64_t(nb + 1) * BT);   // DBG 1: dense timing probe
-    const int64_t k_begin = int64_t(rem) * kc_len;
+    const int64_t k_begin = int64_t(chunk) * kc_len;
     const int k_len = static_cast<int>(min(kend, k_begin + kc_len) - k_begin);   // > 0, multiple of 8
     const int n_st = (k_len + KT - 1) / KT;
     const int r0 = k_len - KT * (n_st - 1);                                       // k of stage 0: 8..32

@@ -237,8 +237,9 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
         ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
         {
             ProfScope prof(ctx, "error_tiles");
-            const unsigned grid =
-                8u * static_cast<unsigned>((n_slots + 7) / 8) * static_cast<unsigned>(MB) * static_cast<unsigned>(nc);
+            // units of 4 slots x 8 (candidate, row block) pairs, 32 workgroups each, dealt to 8 XCDs
+            const int n_units = ((n_slots + 3) / 4) * ((nc * MB + 7) / 8);
+            const unsigned grid = 8u * static_cast<unsigned>((n_units + 7) / 8) * 32u;
             hipLaunchKernelGGL(edma::error_tiles_dma<0>, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
                                out, in, MB, NB, kc_len, n_slots, zero16, part);
         }

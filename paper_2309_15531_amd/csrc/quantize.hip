@@ -174,20 +174,6 @@ __device__ __forceinline__ GroupParamsR group_params_r(float mn, float mx, float
     return {scale, z, rcp, fast};
 }
 
-// 8 codes of one lane; the plain division only runs if some lane of the wave needs it
-__device__ __forceinline__ void quant_codes8(const float (&w)[8], const float (&sc)[8], const float (&zp)[8],
-                                             const float (&rc)[8], bool all_fast, float qmax, float (&q)[8]) {
-    float quo[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) quo[i] = fastdiv(w[i], sc[i], rc[i]);
-    if (__any(!all_fast)) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) quo[i] = pinned_div(w[i], sc[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[i] = __builtin_amdgcn_fmed3f(rintf(quo[i]) + zp[i], 0.0f, qmax);
-}
-
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
     return __builtin_bit_cast(
@@ -196,37 +182,6 @@ __device__ __forceinline__ float dpp_f(float v) {
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
     return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
-}
-
-// min and max over clusters of LPG adjacent lanes (LPG a power of two, aligned).
-// quad_perm [1,0,3,2] and [2,3,0,1] exchange inside a quad, row_half_mirror
-// pairs the two quads of 8 lanes, row_mirror the two halves of a 16-lane row.
-template <int LPG>
-__device__ __forceinline__ void cluster_minmax(float& mn, float& mx) {
-    if constexpr (LPG >= 2) {
-        mn = fminf(mn, dpp_f<0xB1>(mn));
-        mx = fmaxf(mx, dpp_f<0xB1>(mx));
-    }
-    if constexpr (LPG >= 4) {
-        mn = fminf(mn, dpp_f<0x4E>(mn));
-        mx = fmaxf(mx, dpp_f<0x4E>(mx));
-    }
-    if constexpr (LPG >= 8) {
-        mn = fminf(mn, dpp_f<0x141>(mn));
-        mx = fmaxf(mx, dpp_f<0x141>(mx));
-    }
-    if constexpr (LPG >= 16) {
-        mn = fminf(mn, dpp_f<0x140>(mn));
-        mx = fmaxf(mx, dpp_f<0x140>(mx));
-    }
-    if constexpr (LPG >= 32) {
-        mn = fminf(mn, __shfl_xor(mn, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    }
-    if constexpr (LPG >= 64) {
-        mn = fminf(mn, __shfl_xor(mn, 32, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    }
 }
 
 // Bit stream of 8 codes held by one lane, for chunk c of a flat [out, in] weight.
@@ -254,112 +209,6 @@ __device__ __forceinline__ void pack8_store(const float (&q)[8], int64_t c, bool
         const uint32_t next = dpp_u<0xF9>(lo);        // quad_perm [1,2,3,3]: the next lane's 24 bits
         const int j = static_cast<int>(c & 3);
         if (valid && j < 3) packed[(c >> 2) * 3 + j] = (lo >> (8 * j)) | (next << (24 - 8 * j));
-    }
-}
-
-// per-OC fast path: LPG lanes per group.  A block owns a tile of 16 rows x 64 chunks (512
-// columns); wavefront w takes rows 4w..4w+3, lane l chunk l, so every load is one contiguous
-// kilobyte and the four loads of a lane are in flight together.  The column-scaled fp16 dW goes
-// to the k-blocked scoring layout, where the 64-byte pieces of 16 consecutive rows and one
-// 32-column block are adjacent: the tile is turned through LDS so that each store instruction
-// writes such a contiguous kilobyte instead of 16 scattered pieces.
-template <int LPG, int PB>
-__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t out, int chunks_per_row,
-                                                     float clip, float qmax, float rqmax,
-                                                     uint8_t* __restrict__ codes, float* __restrict__ scales,
-                                                     uint8_t* __restrict__ zeros, void* __restrict__ dW,
-                                                     int dW_dtype, const float* __restrict__ colscale,
-                                                     uint32_t* __restrict__ packed) {
-    constexpr int U = 4, PITCH = 68;                        // LDS row pitch in 16-byte units (conflict-free)
-    __shared__ uint4 s_t[16 * PITCH];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cc = blockIdx.x * 64 + lane;                  // chunk within the row
-    const int64_t row0 = int64_t(blockIdx.y) * 16;
-    const bool col_ok = cc < chunks_per_row;                // whole groups: chunks_per_row % LPG == 0
-    const int64_t in = int64_t(chunks_per_row) * 8;
-    const bool turn = dW != nullptr && dW_dtype == ADADIM_DW_F16_SCALED && score_blocked(in);
-    uint4 raw[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t row = row0 + 4 * wave + u;
-        raw[u] = (col_ok && row < out) ? W[row * chunks_per_row + cc] : make_uint4(0, 0, 0, 0);
-    }
-    float4 csa = make_float4(1.f, 1.f, 1.f, 1.f), csb = csa;
-    if (turn && col_ok) {
-        csa = *reinterpret_cast<const float4*>(colscale + int64_t(cc) * 8);
-        csb = *reinterpret_cast<const float4*>(colscale + int64_t(cc) * 8 + 4);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int64_t row = row0 + 4 * wave + u;
-        const bool valid = col_ok && row < out;
-        const int64_t c = row * chunks_per_row + cc;         // flat chunk index
-        float w[8];
-        unpack8(raw[u], w);
-        float mn = fminf(fminf(fminf(w[0], w[1]), fminf(w[2], w[3])), fminf(fminf(w[4], w[5]), fminf(w[6], w[7])));
-        float mx = fmaxf(fmaxf(fmaxf(w[0], w[1]), fmaxf(w[2], w[3])), fmaxf(fmaxf(w[4], w[5]), fmaxf(w[6], w[7])));
-        cluster_minmax<LPG>(mn, mx);
-        const GroupParamsR gp = group_params_r(mn, mx, clip, qmax, rqmax);
-        float q[8];
-        {
-            float sc[8], zp[8], rc[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                sc[i] = gp.scale;
-                zp[i] = gp.zero;
-                rc[i] = gp.rcp;
-            }
-            quant_codes8(w, sc, zp, rc, gp.fast, qmax, q);
-        }
-        if constexpr (PB != 0) {
-            if (packed) pack8_store<PB>(q, c, valid, packed);   // all lanes take part in the DPP
-        }
-        if (turn) {
-            const float cs[8] = {csa.x, csa.y, csa.z, csa.w, csb.x, csb.y, csb.z, csb.w};
-            uint4 o;
-            __half2* h = reinterpret_cast<__half2*>(&o);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                h[i] = __floats2half2_rn(weight_error(w[2 * i], q[2 * i], gp.scale, gp.zero) * cs[2 * i],
-                                         weight_error(w[2 * i + 1], q[2 * i + 1], gp.scale, gp.zero) * cs[2 * i + 1]);
-            s_t[(4 * wave + u) * PITCH + lane] = o;
-        }
-        if (!valid) continue;
-        if ((cc & (LPG - 1)) == 0) {
-            const int64_t grp = c / LPG;
-            if (scales) scales[grp] = gp.scale;
-            if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
-        }
-        if (codes) {
-            uint32_t lo = 0, hi = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lo |= static_cast<uint32_t>(q[i]) << (8 * i);
-                hi |= static_cast<uint32_t>(q[4 + i]) << (8 * i);
-            }
-            reinterpret_cast<uint2*>(codes)[c] = make_uint2(lo, hi);
-        }
-        if (dW && !turn) {
-            float d[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) d[i] = weight_error(w[i], q[i], gp.scale, gp.zero);
-            store_dw8(dW, dW_dtype, colscale, c * 8, row, int64_t(cc) * 8, out, in, d);
-        }
-    }
-    if (!turn) return;                                       // uniform
-    __syncthreads();
-    // store phase: wavefront w writes the tile's 32-column blocks 4w..4w+3; lane l carries row l >> 2,
-    // quarter l & 3 of the block, so the 64 lanes cover 16 rows x 64 bytes = 1 KB contiguous
-    const int srow = lane >> 2, sq = lane & 3;
-    const int64_t grow = row0 + srow;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int kb = 4 * wave + u;                         // block within the tile
-        const int chunk = blockIdx.x * 64 + 4 * kb + sq;     // chunk within the row
-        if (grow < out && chunk < chunks_per_row) {
-            const int64_t at = score_index(grow, int64_t(chunk) * 8, out, in);
-            *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = s_t[srow * PITCH + 4 * kb + sq];
-        }
     }
 }
 
@@ -470,157 +319,6 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
     }
 }
 
-// per-IC fast path: group = NSL*RPT rows.  A block of 32*NSL threads owns one row group x 256
-// columns; thread (tx, ty) keeps rows ty*RPT .. ty*RPT+RPT-1 of its 8 columns in registers, so W
-// is read once.  Few rows per thread keep the register count low enough for several blocks per
-// compute unit, which is what overlaps one block's arithmetic with another's memory traffic.
-template <int RPT, int NSL, int PB>
-__global__ __launch_bounds__(32 * NSL, 4) void quant_ic_regs(const __half* __restrict__ W, int64_t out, int64_t in, float clip,
-                                                     float qmax, float rqmax, uint8_t* __restrict__ codes,
-                                                     float* __restrict__ scales, uint8_t* __restrict__ zeros,
-                                                     void* __restrict__ dW, int dW_dtype,
-                                                     const float* __restrict__ colscale,
-                                                     uint32_t* __restrict__ packed, int64_t n_words) {
-    constexpr int TXW = 32, G = NSL * RPT, COLS = 8 * TXW, NT = NSL * TXW;
-    // PB != 0: the bit stream is assembled here.  A thread's RPT codes of one column form a piece
-    // of RPT*PB <= 64 bits; the row slices OR their pieces into the column's GW words in LDS
-    // (the min/max scratch is dead by then), which are then written out 16 bytes at a time.
-    constexpr int GW = PB ? G * PB / 32 : 0;
-    static_assert(PB == 0 || (RPT * PB <= 64 && (G * PB) % 32 == 0 && GW <= 2 * NSL), "fused packing limits");
-    __shared__ float s_red[2 * NSL][COLS];   // minima then maxima of the row slices; later the packed words
-    __shared__ float s_scale[COLS];
-    __shared__ float s_zero[COLS];
-    __shared__ float s_rcp[COLS];
-    uint32_t* s_pack = reinterpret_cast<uint32_t*>(&s_red[0][0]);   // [GW][COLS], column index permuted
-
-    const int tx = threadIdx.x % TXW, ty = threadIdx.x / TXW;
-    const int64_t col0 = int64_t(blockIdx.x) * COLS + tx * 8;
-    const int64_t row0 = int64_t(blockIdx.y) * G + ty * RPT;
-    const bool col_ok = col0 < in;
-    const bool do_pack = PB != 0 && packed != nullptr;
-
-    uint4 raw[RPT];
-#pragma unroll
-    for (int r = 0; r < RPT; ++r)
-        raw[r] = col_ok ? *reinterpret_cast<const uint4*>(W + (row0 + r) * in + col0) : make_uint4(0, 0, 0, 0);
-    float mn[8], mx[8];
-#pragma unroll
-    for (int v = 0; v < 8; ++v) mn[v] = mx[v] = 0.0f;
-#pragma unroll
-    for (int r = 0; r < RPT; ++r) {
-        float w[8];
-        unpack8(raw[r], w);
-#pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            mn[v] = fminf(mn[v], w[v]);
-            mx[v] = fmaxf(mx[v], w[v]);
-        }
-    }
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        s_red[ty][tx * 8 + v] = mn[v];
-        s_red[NSL + ty][tx * 8 + v] = mx[v];
-    }
-    __syncthreads();
-    for (int cidx = threadIdx.x; cidx < COLS; cidx += NT) {   // whole wavefronts: COLS and NT are multiples of 64
-        float a = s_red[0][cidx], b = s_red[NSL][cidx];
-#pragma unroll
-        for (int y = 1; y < NSL; ++y) {
-            a = fminf(a, s_red[y][cidx]);
-            b = fmaxf(b, s_red[NSL + y][cidx]);
-        }
-        const GroupParamsR gp = group_params_r(a, b, clip, qmax, rqmax);
-        s_scale[cidx] = gp.scale;
-        s_zero[cidx] = gp.zero;
-        s_rcp[cidx] = gp.rcp;
-        const int64_t col = int64_t(blockIdx.x) * COLS + cidx;
-        if (col < in) {
-            const int64_t gi = int64_t(blockIdx.y) * in + col;
-            if (scales) scales[gi] = gp.scale;
-            if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
-        }
-    }
-    __syncthreads();
-    if (!codes && !dW && !do_pack) return;
-    if (do_pack) {
-        for (int i = threadIdx.x; i < GW * COLS; i += NT) s_pack[i] = 0u;
-    }
-    float sc[8], zp[8], rc[8];
-    bool all_fast = true;
-#pragma unroll
-    for (int v = 0; v < 8; ++v) {
-        sc[v] = s_scale[tx * 8 + v];
-        zp[v] = s_zero[tx * 8 + v];
-        rc[v] = s_rcp[tx * 8 + v];
-        all_fast = all_fast && fastdiv_ok(sc[v]);
-    }
-    using piece_t = std::conditional_t<(RPT * PB <= 32), uint32_t, uint64_t>;
-    piece_t piece[8];
-#pragma unroll
-    for (int v = 0; v < 8; ++v) piece[v] = 0;
-#pragma unroll
-    for (int r = 0; r < RPT; ++r) {
-        const int64_t elem = (row0 + r) * in + col0;
-        float w[8], q[8];
-        unpack8(raw[r], w);
-        quant_codes8(w, sc, zp, rc, all_fast, qmax, q);   // every lane reaches the wave-wide test inside
-        if constexpr (PB != 0) {
-#pragma unroll
-            for (int v = 0; v < 8; ++v) piece[v] |= static_cast<piece_t>(static_cast<uint32_t>(q[v])) << (r * PB);
-        }
-        if (col_ok && codes) {
-            uint32_t lo = 0, hi = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lo |= static_cast<uint32_t>(q[i]) << (8 * i);
-                hi |= static_cast<uint32_t>(q[4 + i]) << (8 * i);
-            }
-            *reinterpret_cast<uint2*>(codes + elem) = make_uint2(lo, hi);
-        }
-        if (col_ok && dW) {
-            float d[8];
-#pragma unroll
-            for (int v = 0; v < 8; ++v) d[v] = weight_error(w[v], q[v], sc[v], zp[v]);
-            store_dw8(dW, dW_dtype, colscale, elem, row0 + r, col0, out, in, d);
-        }
-    }
-    if constexpr (PB != 0) {
-        if (!do_pack) return;
-        __syncthreads();   // s_pack is cleared
-        const int bit0 = ty * RPT * PB, w0 = bit0 >> 5, sh = bit0 & 31;
-#pragma unroll
-        for (int v = 0; v < 8; ++v) {
-            const uint64_t p64 = piece[v];
-            const uint64_t lo64 = p64 << sh;
-            const uint32_t w2 = sh ? static_cast<uint32_t>(p64 >> (64 - sh)) : 0u;
-            const int pc = v * TXW + tx;   // permuted column: conflict-free across the lanes of a wave
-            atomicOr(&s_pack[w0 * COLS + pc], static_cast<uint32_t>(lo64));
-            if (w0 + 1 < GW) atomicOr(&s_pack[(w0 + 1) * COLS + pc], static_cast<uint32_t>(lo64 >> 32));
-            if (w0 + 2 < GW && w2) atomicOr(&s_pack[(w0 + 2) * COLS + pc], w2);
-        }
-        __syncthreads();
-        const int64_t colb = int64_t(blockIdx.x) * COLS;
-        const int64_t woff = int64_t(blockIdx.y) * GW;
-        if ((GW % 4) == 0 && (n_words % 4) == 0) {
-            for (int it = threadIdx.x; it < COLS * (GW / 4); it += NT) {
-                const int c = it / (GW / 4), qd = it % (GW / 4);
-                if (colb + c >= in) continue;
-                const int pc = (c & 7) * TXW + (c >> 3);
-                const uint4 o = make_uint4(s_pack[(4 * qd + 0) * COLS + pc], s_pack[(4 * qd + 1) * COLS + pc],
-                                           s_pack[(4 * qd + 2) * COLS + pc], s_pack[(4 * qd + 3) * COLS + pc]);
-                *reinterpret_cast<uint4*>(packed + (colb + c) * n_words + woff + 4 * qd) = o;
-            }
-        } else {
-            for (int it = threadIdx.x; it < COLS * GW; it += NT) {
-                const int c = it / GW, wd = it % GW;
-                if (colb + c >= in) continue;
-                const int pc = (c & 7) * TXW + (c >> 3);
-                packed[(colb + c) * n_words + woff + wd] = s_pack[wd * COLS + pc];
-            }
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------
 // Element arithmetic of the streaming kernels.  v_fma_mix_f32 reads an fp16 operand straight
 // from one half of a packed register, so the weight is never converted on its own:
@@ -687,6 +385,26 @@ __device__ __forceinline__ void quant_k8(const uint32_t (&v)[4], const QConst (&
     for (int i = 0; i < 8; ++i) k[i] = __builtin_amdgcn_fmed3f(rintf(quo[i]), c[i].nz, c[i].pz);
 }
 
+// the same with one group's constants for all 8 weights (per-OC)
+__device__ __forceinline__ void quant_k8(const uint32_t (&v)[4], const QConst& c, bool slow, float (&k)[8]) {
+    float quo[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        quo[2 * i] = quant_quo<0>(v[i], c);
+        quo[2 * i + 1] = quant_quo<1>(v[i], c);
+    }
+    if (slow) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const f16x2 w = __builtin_bit_cast(f16x2, v[i]);
+            quo[2 * i] = pinned_div(static_cast<float>(w[0]), -c.ns);
+            quo[2 * i + 1] = pinned_div(static_cast<float>(w[1]), -c.ns);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) k[i] = __builtin_amdgcn_fmed3f(rintf(quo[i]), c.nz, c.pz);
+}
+
 __device__ __forceinline__ uint32_t pack_h2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __floats2half2_rn(lo, hi));
 }
@@ -701,6 +419,160 @@ __device__ __forceinline__ float half_of(uint32_t pair, int hi) {
     return __half2float(__ushort_as_half(static_cast<unsigned short>(hi ? pair >> 16 : pair & 0xffffu)));
 }
 
+// (min, -max) pairs over clusters of LPG adjacent lanes (LPG a power of two, aligned): one
+// packed minimum per exchange serves both.  quad_perm [1,0,3,2] and [2,3,0,1] exchange inside
+// a quad, row_half_mirror pairs the two quads of 8 lanes, row_mirror the two halves of a row.
+template <int LPG>
+__device__ __forceinline__ uint32_t cluster_min2(uint32_t m) {
+    if constexpr (LPG >= 2) m = pk_min(m, dpp_u<0xB1>(m));
+    if constexpr (LPG >= 4) m = pk_min(m, dpp_u<0x4E>(m));
+    if constexpr (LPG >= 8) m = pk_min(m, dpp_u<0x141>(m));
+    if constexpr (LPG >= 16) m = pk_min(m, dpp_u<0x140>(m));
+    if constexpr (LPG >= 32) m = pk_min(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), 16, 64)));
+    if constexpr (LPG >= 64) m = pk_min(m, static_cast<uint32_t>(__shfl_xor(static_cast<int>(m), 32, 64)));
+    return m;
+}
+
+// per-OC fast path: LPG lanes per group.  A block owns a tile of 16 rows x 64 chunks (512
+// columns); wavefront w takes rows 4w..4w+3, lane l chunk l, so every load is one contiguous
+// kilobyte and the four loads of a lane are in flight together.  The (min, -max) of a lane's
+// chunk are taken on the packed fp16 values and meet across the group's lanes through DPP.
+// With four or more lanes per group the four lanes of a quad sit in the same group for each of
+// the wave's four rows: lane l works out the parameters of row l & 3 and the quad trades them,
+// one parameter computation per wave instead of four.  The column-scaled fp16 dW goes to the
+// scoring layout, where the 64-byte pieces of 16 consecutive rows of one 32-column block are
+// adjacent: the tile is turned through LDS so that each store instruction writes such a
+// contiguous kilobyte instead of 16 scattered pieces.
+template <int LPG, int PB, bool SCALED>
+__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t out, int chunks_per_row,
+                                                     float clip, float qmax, float rqmax,
+                                                     uint8_t* __restrict__ codes, float* __restrict__ scales,
+                                                     uint8_t* __restrict__ zeros, void* __restrict__ dW,
+                                                     int dW_dtype, const float* __restrict__ colscale,
+                                                     uint32_t* __restrict__ packed) {
+    constexpr int U = 4, PITCH = 68;                        // LDS row pitch in 16-byte units (conflict-free)
+    __shared__ uint4 s_t[SCALED ? 16 * PITCH : 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int cc = blockIdx.x * 64 + lane;                  // chunk within the row
+    const int64_t row0 = int64_t(blockIdx.y) * 16;
+    const bool col_ok = cc < chunks_per_row;                // whole groups: chunks_per_row % LPG == 0
+    const int64_t in = int64_t(chunks_per_row) * 8;
+    const bool turn = SCALED && score_blocked(in);
+    uint4 raw[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t row = row0 + 4 * wave + u;
+        raw[u] = (col_ok && row < out) ? W[row * chunks_per_row + cc] : make_uint4(0, 0, 0, 0);
+    }
+    float cs[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+    if constexpr (SCALED) {
+        if (col_ok) {
+            const float4 a = *reinterpret_cast<const float4*>(colscale + int64_t(cc) * 8);
+            const float4 b = *reinterpret_cast<const float4*>(colscale + int64_t(cc) * 8 + 4);
+            cs[0] = a.x; cs[1] = a.y; cs[2] = a.z; cs[3] = a.w;
+            cs[4] = b.x; cs[5] = b.y; cs[6] = b.z; cs[7] = b.w;
+        }
+    }
+    // per row: (min, -max) of the group, low and high half of one register
+    uint32_t m2[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t mnp = pk_min(pk_min(raw[u].x, raw[u].y), pk_min(raw[u].z, raw[u].w));
+        const uint32_t nmx = pk_max(pk_max(raw[u].x, raw[u].y), pk_max(raw[u].z, raw[u].w)) ^ 0x80008000u;
+        const uint32_t lo = __builtin_amdgcn_perm(nmx, mnp, 0x05040100u);   // (min of even, -max of even elements)
+        const uint32_t hi = __builtin_amdgcn_perm(nmx, mnp, 0x07060302u);   // the same of the odd elements
+        m2[u] = cluster_min2<LPG>(pk_min(lo, hi));
+    }
+    float sc_u[U], zp_u[U], rc_u[U];
+    bool slow;
+    if constexpr (LPG >= 4) {
+        const int mine = lane & 3;
+        const uint32_t msel = (mine & 2) ? ((mine & 1) ? m2[3] : m2[2]) : ((mine & 1) ? m2[1] : m2[0]);
+        const GroupParamsR gp = group_params_r(half_of(msel, 0), -half_of(msel, 1), clip, qmax, rqmax);
+        slow = __any(!gp.fast);
+        sc_u[0] = dpp_f<0x00>(gp.scale); zp_u[0] = dpp_f<0x00>(gp.zero); rc_u[0] = dpp_f<0x00>(gp.rcp);
+        sc_u[1] = dpp_f<0x55>(gp.scale); zp_u[1] = dpp_f<0x55>(gp.zero); rc_u[1] = dpp_f<0x55>(gp.rcp);
+        sc_u[2] = dpp_f<0xAA>(gp.scale); zp_u[2] = dpp_f<0xAA>(gp.zero); rc_u[2] = dpp_f<0xAA>(gp.rcp);
+        sc_u[3] = dpp_f<0xFF>(gp.scale); zp_u[3] = dpp_f<0xFF>(gp.zero); rc_u[3] = dpp_f<0xFF>(gp.rcp);
+    } else {
+        bool fast = true;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const GroupParamsR gp = group_params_r(half_of(m2[u], 0), -half_of(m2[u], 1), clip, qmax, rqmax);
+            sc_u[u] = gp.scale; zp_u[u] = gp.zero; rc_u[u] = gp.rcp;
+            fast = fast && gp.fast;
+        }
+        slow = __any(!fast);
+    }
+    const float n0 = opaque_negzero();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t row = row0 + 4 * wave + u;
+        const bool valid = col_ok && row < out;
+        const int64_t c = row * chunks_per_row + cc;         // flat chunk index
+        const QConst qc = {rc_u[u], -sc_u[u], -zp_u[u], qmax - zp_u[u], n0};
+        const uint32_t v[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
+        float k[8];
+        quant_k8(v, qc, slow, k);
+        if constexpr (PB != 0) {
+            if (packed) {                                    // all lanes take part in the DPP
+                float q[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) q[i] = k[i] + zp_u[u];
+                pack8_store<PB>(q, c, valid, packed);
+            }
+        }
+        if (dW != nullptr && (turn || valid)) {
+            float d[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float s0 = SCALED ? qc.ns * cs[2 * i] : qc.ns, s1 = SCALED ? qc.ns * cs[2 * i + 1] : qc.ns;
+                d[2 * i] = fma_hff<0>(v[i], cs[2 * i], s0 * k[2 * i]);
+                d[2 * i + 1] = fma_hff<1>(v[i], cs[2 * i + 1], s1 * k[2 * i + 1]);
+            }
+            if (!SCALED && dW_dtype == ADADIM_DW_F32) {
+                float4* p = reinterpret_cast<float4*>(static_cast<float*>(dW) + c * 8);
+                p[0] = make_float4(d[0], d[1], d[2], d[3]);
+                p[1] = make_float4(d[4], d[5], d[6], d[7]);
+            } else {
+                const uint4 o = make_uint4(pack_h2(d[0], d[1]), pack_h2(d[2], d[3]), pack_h2(d[4], d[5]), pack_h2(d[6], d[7]));
+                if (turn) s_t[(4 * wave + u) * PITCH + lane] = o;
+                else *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + (SCALED ? score_index(row, int64_t(cc) * 8, out, in) : c * 8)) = o;
+            }
+        }
+        if (!valid) continue;
+        if ((cc & (LPG - 1)) == 0) {
+            const int64_t grp = c / LPG;
+            if (scales) scales[grp] = sc_u[u];
+            if (zeros) zeros[grp] = static_cast<uint8_t>(zp_u[u]);
+        }
+        if (codes) {
+            uint32_t lo = 0, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo |= static_cast<uint32_t>(k[i] + zp_u[u]) << (8 * i);
+                hi |= static_cast<uint32_t>(k[4 + i] + zp_u[u]) << (8 * i);
+            }
+            reinterpret_cast<uint2*>(codes)[c] = make_uint2(lo, hi);
+        }
+    }
+    if (!turn) return;                                       // uniform
+    __syncthreads();
+    // store phase: wavefront w writes the tile's 32-column blocks 4w..4w+3; lane l carries row l >> 2,
+    // quarter l & 3 of the block, so the 64 lanes cover 16 rows x 64 bytes = 1 KB contiguous
+    const int srow = lane >> 2, sq = lane & 3;
+    const int64_t grow = row0 + srow;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int kb = 4 * wave + u;                         // block within the tile
+        const int chunk = blockIdx.x * 64 + 4 * kb + sq;     // chunk within the row
+        if (grow < out && chunk < chunks_per_row) {
+            const int64_t at = score_index(grow, int64_t(chunk) * 8, out, in);
+            *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = s_t[srow * PITCH + 4 * kb + sq];
+        }
+    }
+}
+
 // per-IC streaming path.  A group of G = 8*U*RW rows x 64 columns is shared by RW wavefronts, each
 // holding 8*U rows: lane l takes rows 8u + (l >> 3), u = 0..U-1, of the 8 columns of chunk l & 7,
 // so every load instruction fetches one full 128-byte line from each of 8 rows and all U loads of a
@@ -711,14 +583,21 @@ __device__ __forceinline__ float half_of(uint32_t pair, int hi) {
 // Lane (row lane r, chunk c) then works out the parameters of column 8c + r alone and the eight
 // lanes of a chunk trade them.  In the scoring layout the 8 rows x 64 bytes that a store
 // instruction writes for one 32-column block are contiguous.
-template <int U, int RW, bool SCALED>
+//
+// PB != 0 (2, 3 or 4 bits, U == 4): the bit stream is assembled here too.  A wave's 32 rows give
+// PB whole words per column.  Each lane collects the four codes of each of its columns as bytes
+// (byte u = row 8u + row lane), the wave turns them through a private LDS patch so that lane l
+// holds all 32 codes of column l, and that lane shifts them into place and writes the PB words.
+template <int U, int RW, bool SCALED, int PB>
 __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
     const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax,
     uint8_t* __restrict__ codes, float* __restrict__ scales, uint8_t* __restrict__ zeros, void* __restrict__ dW,
-    int dW_dtype, const float* __restrict__ colscale) {
+    int dW_dtype, const float* __restrict__ colscale, uint32_t* __restrict__ packed, int64_t n_words) {
     constexpr int CSW = RW <= 4 ? 4 / RW : 1;                // 64-column sets per block
     constexpr int G = 8 * U * RW;
+    static_assert(PB == 0 || (U == 4 && (PB == 2 || PB == 3 || PB == 4)), "fused packing: 32-row wave tiles, 2..4 bits");
     __shared__ uint32_t s_mm[CSW][RW][2][32];                // [set][row wave][min|max][chunk*4 + pair]
+    __shared__ uint32_t s_pk[PB ? CSW * RW : 1][8][65];      // [wave][row lane][column], odd pitch
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int rw = wave % RW, cw = wave / RW;
     const int rl = lane >> 3, cl = lane & 7;
@@ -777,9 +656,11 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
         if (scales) scales[gi] = gp.scale;
         if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
     }
-    if (!codes && !dW) return;
+    const bool do_pack = PB != 0 && packed != nullptr;
+    if (!codes && !dW && !do_pack) return;
     QConst qc[8];
     float cs[8], nscs[8];
+    uint32_t cbytes[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};  // codes of rows 8u + rl, byte u, per column
     const float n0 = opaque_negzero();
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -811,6 +692,12 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
         const uint32_t v[4] = {raw[u].x, raw[u].y, raw[u].z, raw[u].w};
         float k[8];
         quant_k8(v, qc, slow, k);
+        if constexpr (PB != 0) {
+            if (do_pack) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) cbytes[i] = __builtin_amdgcn_cvt_pk_u8_f32(k[i] - qc[i].nz, u, cbytes[i]);
+            }
+        }
         if (!col_ok) continue;
         if (codes) {
             uint32_t lo = 0, hi = 0;
@@ -837,6 +724,44 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
                 const int64_t at = SCALED ? score_index(row, col0, out, in) : elem;
                 *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = o;
             }
+        }
+    }
+    if constexpr (PB != 0) {
+        if (!do_pack) return;                                // uniform
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s_pk[wave][rl][cl * 8 + i] = cbytes[i];
+        // the patch is private to the wave and the LDS serves a wave's accesses in order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // lane l now takes column l of the wave: pair the row lanes (2*PB <= 8 bits per byte), then
+        // field u = the 8 codes of rows 8u..8u+7, 8*PB bits, belongs at bit 8*PB*u of the PB words
+        uint32_t pr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pr[j] = s_pk[wave][2 * j][lane] | (s_pk[wave][2 * j + 1][lane] << PB);
+        uint32_t f[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            f[u] = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f[u] |= ((pr[j] >> (8 * u)) & 0xffu) << (2 * PB * j);
+        }
+        uint32_t w[PB];
+        if constexpr (PB == 4) {
+            w[0] = f[0]; w[1] = f[1]; w[2] = f[2]; w[3] = f[3];
+        } else if constexpr (PB == 2) {
+            w[0] = f[0] | (f[1] << 16);
+            w[1] = f[2] | (f[3] << 16);
+        } else {
+            w[0] = f[0] | (f[1] << 24);
+            w[1] = (f[1] >> 8) | (f[2] << 16);
+            w[2] = (f[2] >> 16) | (f[3] << 8);
+        }
+        const int64_t col = (int64_t(blockIdx.x) * CSW + cw) * 64 + lane;
+        if (col < in) {
+            uint32_t* dst = packed + col * n_words + (int64_t(blockIdx.y) * (G / 32) + rw) * PB;
+#pragma unroll
+            for (int j = 0; j < PB; ++j) dst[j] = w[j];
         }
     }
 }
@@ -878,8 +803,14 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
     const dim3 blocks(static_cast<unsigned>((cpr + 63) / 64), static_cast<unsigned>((out + 15) / 16));
     ProfScope prof(ctx, "quant_oc");
 #define OC_GO(PB)                                                                                                  \
-    hipLaunchKernelGGL((quant_oc_fast<LPG, PB>), blocks, dim3(256), 0, ctx->stream, W4, out, cpr, clip, qmax,     \
-                       1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed)
+    do {                                                                                                           \
+        if (dW && dW_dtype == ADADIM_DW_F16_SCALED)                                                                \
+            hipLaunchKernelGGL((quant_oc_fast<LPG, PB, true>), blocks, dim3(256), 0, ctx->stream, W4, out, cpr,    \
+                               clip, qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed);     \
+        else                                                                                                       \
+            hipLaunchKernelGGL((quant_oc_fast<LPG, PB, false>), blocks, dim3(256), 0, ctx->stream, W4, out, cpr,   \
+                               clip, qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed);     \
+    } while (0)
     switch (pb) {
         case 2: OC_GO(2); break;
         case 3: OC_GO(3); break;
@@ -890,61 +821,41 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
 #undef OC_GO
 }
 
-// Row slices per block for a per-IC group of g = 8*lpg rows: 16 from 64 rows up, else 8.
-constexpr int ic_slices(int lpg) { return lpg >= 8 ? 16 : 8; }
-// fused packing is available when a thread's piece fits 64 bits and the group's words fit the LDS scratch
-constexpr bool ic_pack_ok(int lpg, int pb) {
-    const int nsl = ic_slices(lpg), rpt = 8 * lpg / nsl, gbits = 8 * lpg * pb;
-    return (pb == 2 || pb == 3 || pb == 4) && rpt * pb <= 64 && gbits % 32 == 0 && gbits / 32 <= 2 * nsl;
-}
+// fused packing in the streaming per-IC kernel: 32-row wave tiles (groups of 32 rows and up), 2..4 bits
+constexpr bool ic_stream_pack_ok(int lpg, int pb) { return lpg >= 4 && (pb == 2 || pb == 3 || pb == 4); }
 
-// streaming per-IC kernel for a group of 8*LPG rows (no packed output)
+// streaming per-IC kernel for a group of 8*LPG rows; pb != 0 also writes the packed stream
 template <int LPG>
-void launch_ic_wave(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax,
-                    uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale) {
-    static const int force_u = getenv("ADADIM_IC_U") ? atoi(getenv("ADADIM_IC_U")) : 0;
+void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
+                      uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale,
+                      uint32_t* packed, int64_t n_words) {
     const bool scaled = dW && dW_dtype == ADADIM_DW_F16_SCALED;
     const float rq = 1.0f / qmax;
+    constexpr int U = LPG < 4 ? LPG : 4, RW = LPG / U, CSW = RW <= 4 ? 4 / RW : 1, TH = RW <= 4 ? 256 : 64 * RW;
+    dim3 grid(static_cast<unsigned>((in + 64 * CSW - 1) / (64 * CSW)), static_cast<unsigned>(out / (8 * LPG)));
     ProfScope prof(ctx, "quant_ic");
-#define IC_W(U, S)                                                                                              \
-    do {                                                                                                        \
-        constexpr int RW = LPG / (U), CSW = RW <= 4 ? 4 / RW : 1, TH = RW <= 4 ? 256 : 64 * RW;                  \
-        dim3 grid(static_cast<unsigned>((in + 64 * CSW - 1) / (64 * CSW)), static_cast<unsigned>(out / (8 * LPG))); \
-        hipLaunchKernelGGL((quant_ic_stream<U, RW, S>), grid, dim3(TH), 0, ctx->stream, W, out, in, clip, qmax,  \
-                           rq, codes, scales, zeros, dW, dW_dtype, colscale);                                   \
-    } while (0)
-    if constexpr (LPG >= 8) {
-        if (force_u == 8) { if (scaled) IC_W(8, true); else IC_W(8, false); return; }
+#define IC_S(S, PB)                                                                                             \
+    hipLaunchKernelGGL((quant_ic_stream<U, RW, S, PB>), grid, dim3(TH), 0, ctx->stream, W, out, in, clip, qmax,  \
+                       rq, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
+    if constexpr (LPG >= 4) {
+        if (scaled) {
+            switch (pb) {
+                case 2: IC_S(true, 2); return;
+                case 3: IC_S(true, 3); return;
+                case 4: IC_S(true, 4); return;
+                default: break;
+            }
+        } else {
+            switch (pb) {
+                case 2: IC_S(false, 2); return;
+                case 3: IC_S(false, 3); return;
+                case 4: IC_S(false, 4); return;
+                default: break;
+            }
+        }
     }
-    if constexpr (LPG == 16) {
-        if (force_u == 16) { if (scaled) IC_W(16, true); else IC_W(16, false); return; }
-    }
-    constexpr int UD = LPG < 4 ? LPG : 4;
-    if (scaled) IC_W(UD, true); else IC_W(UD, false);
-#undef IC_W
-}
-
-template <int LPG>
-void launch_ic_regs(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
-                    uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
-                    const float* colscale, uint32_t* packed, int64_t n_words) {
-    constexpr int NSL = ic_slices(LPG), RPT = 8 * LPG / NSL;
-    dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(out / (8 * LPG)));
-    ProfScope prof(ctx, "quant_ic");
-#define IC_GO(PB)                                                                                                \
-    hipLaunchKernelGGL((quant_ic_regs<RPT, NSL, PB>), grid, dim3(32 * NSL), 0, ctx->stream, W, out, in, clip,     \
-                       qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
-    if constexpr (ic_pack_ok(LPG, 2)) {
-        if (pb == 2) { IC_GO(2); return; }
-    }
-    if constexpr (ic_pack_ok(LPG, 3)) {
-        if (pb == 3) { IC_GO(3); return; }
-    }
-    if constexpr (ic_pack_ok(LPG, 4)) {
-        if (pb == 4) { IC_GO(4); return; }
-    }
-    IC_GO(0);
-#undef IC_GO
+    if (scaled) IC_S(true, 0); else IC_S(false, 0);
+#undef IC_S
 }
 
 }  // namespace
@@ -974,11 +885,11 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
     const int lpg = g / 8;
     const bool oc_lanes = dim == ADADIM_DIM_OC && vec && (g % 8) == 0 && lpg <= 64 && (lpg & (lpg - 1)) == 0 &&
                           out <= 16 * 65535;
-    const bool ic_regs = dim == ADADIM_DIM_IC && vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
+    const bool ic_stream = dim == ADADIM_DIM_IC && vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
     // the fast kernels assemble the bit stream themselves for these widths
     const bool fused_pack =
         packed && ((oc_lanes && (in % 32) == 0 && (bits == 2 || bits == 3 || bits == 4 || bits == 8)) ||
-                   (ic_regs && ic_pack_ok(lpg, bits)));
+                   (ic_stream && ic_stream_pack_ok(lpg, bits)));
     if (packed && !fused_pack && !codes) {
         codes = static_cast<uint8_t*>(adadim_workspace(ctx, WS_CODES, size_t(out) * size_t(in)));
         if (!codes) return ADADIM_EHIP;
@@ -1007,20 +918,20 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
         const int64_t row_groups = out / g;
         if (row_groups > 65535)
             return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize: more than 65535 row groups per column");
-        if (ic_regs) {
+        if (ic_stream) {
             const int pb = fused_pack ? bits : 0;
             uint32_t* pk = fused_pack ? packed : nullptr;
             const int64_t n_words = (out * bits + 31) / 32;
             switch (lpg) {
 #define IC_CASE(n)                                                                                              \
     case n:                                                                                                     \
-        if (pk) launch_ic_regs<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk, n_words); \
-        else launch_ic_wave<n>(ctx, W, out, in, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);     \
+        launch_ic_stream<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk,  \
+                            n_words);                                                                           \
         break;
                 IC_CASE(1) IC_CASE(2) IC_CASE(4) IC_CASE(8) IC_CASE(16) IC_CASE(32)
 #undef IC_CASE
             }
-            ADADIM_LAUNCH_CHECK(ctx, "quant_ic_regs");
+            ADADIM_LAUNCH_CHECK(ctx, "quant_ic_stream");
         } else if (vec) {
             dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(row_groups));
             {
