@@ -64,6 +64,13 @@ __device__ __forceinline__ half8 lds_read8(uint32_t addr) {
     return *reinterpret_cast<lds_ptr>(uintptr_t(addr));
 }
 
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 lds_read_u2(uint32_t addr) {
+    typedef uint2v __attribute__((address_space(3))) * lds_ptr;
+    const uint2v v = *reinterpret_cast<lds_ptr>(uintptr_t(addr));
+    return make_uint2(v.x, v.y);
+}
+
 struct Frags {
     half8 v[TM + TN];
 };
@@ -81,7 +88,8 @@ struct Batch {
 template <int DBG = 0>
 __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half* __restrict__ Hs, int64_t out,
                                                        int64_t in, int MB, int NB, int kc_len, int n_slots,
-                                                       const void* zero16, float* __restrict__ part) {
+                                                       const void* zero16, const float* __restrict__ hmeta_diag,
+                                                       float* __restrict__ part) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
@@ -270,32 +278,82 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
 
     // ---- epilogue: acc[i][j][r] = E[o, n] with o = row0 + wn*WN + 32j + (lane & 31) and
     // n = col0 + wm*WM + 32i + 8*(r/4) + 4*(lane >> 5) + (r & 3).  Multiply by dW'[o, n] (four
-    // consecutive n per 8-byte load) and add up over n inside the lane.
-    float v[TN];
+    // consecutive n per 8-byte read) and add up over n inside the lane.  In the scoring layout the
+    // 256 x 256 tile of dW' is eight consecutive 16 KB pieces: it is copied into the ring (free by
+    // now) with the transfers of operand 1, one piece per operand slot, and read back with the
+    // fragment pattern; a lane's direct 8-byte loads would touch a different 64-byte row each.
+    // With hmeta_diag (column scales d then diag H, as adadim_hessian_prepare writes them) the
+    // workgroup of a column block's first chunk also adds half the diagonal term,
+    // dW'[o,n]^2 H_nn / d_n^2 / 2: the final reduction doubles the row sums.
+    if (blocked) {
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();                        // every wave is done with the ring
+        const char* ebase = reinterpret_cast<const char*>(A + score_index(row0, col0, out, in));
+        const int n_piece = static_cast<int>(min(int64_t(8), (in - col0) >> 5));
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int64_t o = row0 + wn * WN + 32 * j + (lane & 31);
-        float sum = 0.0f;
-        if (o < out) {
+        for (int blk = 0; blk < 8; ++blk) {
+            if (blk < n_piece) {                             // uniform
+                const char* sb = uniform_ptr(ebase + blk * OP_BYTES);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
+                for (int j = LOADS / 2; j < LOADS; ++j) g2l16_s(sb, goff[j], gdst[j] + (blk - 1) * OP_BYTES);
+            }
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+    }
+    const bool add_diag = hmeta_diag != nullptr && chunk == 0;
+    float sum[TN];
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int64_t n0 = col0 + wm * WM + 32 * i + 8 * g + 4 * (lane >> 5);
-                    if (n0 < in) {   // in % 8 == 0: the four columns are inside together
-                        const uint2 raw = *reinterpret_cast<const uint2*>(A + score_index(o, n0, out, in));
-                        const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&raw.x));
-                        const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&raw.y));
-                        sum += acc[i][j][4 * g + 0] * a.x;
-                        sum += acc[i][j][4 * g + 1] * a.y;
-                        sum += acc[i][j][4 * g + 2] * b.x;
-                        sum += acc[i][j][4 * g + 3] * b.y;
+    for (int j = 0; j < TN; ++j) sum[j] = 0.0f;
+    // Rows past `out` need no test on the LDS path: they hold a valid row's data and their sums
+    // are never stored.  Columns past `in` are skipped (their accumulators are not zero).
+    auto reduce = [&](auto from_lds) {
+        constexpr bool LDS = decltype(from_lds)::value;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int64_t n0 = col0 + wm * WM + 32 * i + 8 * g + 4 * (lane >> 5);
+                if (n0 >= in) continue;   // in % 8 == 0: the four columns are inside together
+                float hq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (add_diag) {
+                    const float4 d4 = *reinterpret_cast<const float4*>(hmeta_diag + n0);
+                    const float4 h4 = *reinterpret_cast<const float4*>(hmeta_diag + in + n0);
+                    // d = 2^e: the bit pattern of 1/d is 0x7F000000 minus that of d
+                    const float r0 = __uint_as_float(0x7F000000u - __float_as_uint(d4.x));
+                    const float r1 = __uint_as_float(0x7F000000u - __float_as_uint(d4.y));
+                    const float r2 = __uint_as_float(0x7F000000u - __float_as_uint(d4.z));
+                    const float r3 = __uint_as_float(0x7F000000u - __float_as_uint(d4.w));
+                    hq[0] = 0.5f * h4.x * r0 * r0;
+                    hq[1] = 0.5f * h4.y * r1 * r1;
+                    hq[2] = 0.5f * h4.z * r2 * r2;
+                    hq[3] = 0.5f * h4.w * r3 * r3;
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int ol = wn * WN + 32 * j + (lane & 31);
+                    uint2 raw = make_uint2(0u, 0u);
+                    if constexpr (LDS) {
+                        raw = lds_read_u2(lds0 + (wm * 4 + i) * OP_BYTES + ol * ROWB + ((g ^ ((ol >> 2) & 3)) << 4) +
+                                          (lane >> 5) * 8);
+                    } else {
+                        if (row0 + ol < out) raw = *reinterpret_cast<const uint2*>(A + score_index(row0 + ol, n0, out, in));
                     }
+                    const float2 a = __half22float2(*reinterpret_cast<const __half2*>(&raw.x));
+                    const float2 b = __half22float2(*reinterpret_cast<const __half2*>(&raw.y));
+                    sum[j] += (acc[i][j][4 * g + 0] + hq[0] * a.x) * a.x;
+                    sum[j] += (acc[i][j][4 * g + 1] + hq[1] * a.y) * a.y;
+                    sum[j] += (acc[i][j][4 * g + 2] + hq[2] * b.x) * b.x;
+                    sum[j] += (acc[i][j][4 * g + 3] + hq[3] * b.y) * b.y;
                 }
             }
         }
-        v[j] = sum + __shfl_xor(sum, 32, 64);
-    }
+    };
+    if (blocked) reduce(std::true_type{});
+    else reduce(std::false_type{});
+    float v[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) v[j] = sum[j] + __shfl_xor(sum[j], 32, 64);
     if (lane < 32) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) s_rows[wm][wn * WN + 32 * j + lane] = v[j];

@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void error_prologue(SrcBatch src, int dW_dtype
     if (threadIdx.x == 0) diag[o] = s_red[0];
 }
 
-// loss_rows[o] = diag[o] + 2*sum_slot part[slot,o] for 256 rows per block, a per-block total,
+// loss_rows[o] = diag[o] + 2*sum_slot part[slot,o] (no diag array: the tile kernel has put half
+// the diagonal term into its row sums) for 256 rows per block, a per-block total,
 // and, in the block that finishes last, loss = sum of the block totals in block order (so the
 // result does not depend on which block that is).  `ticket` must be zero on entry and is zero
 // again on exit.
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(256) void error_finish(const float* __restrict__ di
     if (o < out) {
         float off = 0.0f;
         for (int sl = 0; sl < n_slots; ++sl) off += part[int64_t(sl) * out + o];
-        const float l = diag[o] + 2.0f * off;
+        const float l = (diag_all ? diag[o] : 0.0f) + 2.0f * off;
         if (loss_rows) loss_rows[o] = l;
         mine = static_cast<double>(l);
     }
@@ -229,7 +230,10 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
                                         : static_cast<const __half*>(dW[c0 + c]))
                                 : nullptr;
         }
-        {
+        // Column-scaled fp16 input is consumed as it is and the tile kernel adds the diagonal term;
+        // other inputs go through the prologue, which scales them and takes that term in fp32.
+        const bool direct = dW_dtype == ADADIM_DW_F16_SCALED;
+        if (!direct) {
             ProfScope prof(ctx, "error_prologue");
             hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out), nc), dim3(256), 0, ctx->stream, src,
                                dW_dtype, out, in, hmeta, dW16, diag);
@@ -241,12 +245,13 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
             const int n_units = ((n_slots + 3) / 4) * ((nc * MB + 7) / 8);
             const unsigned grid = 8u * static_cast<unsigned>((n_units + 7) / 8) * 32u;
             hipLaunchKernelGGL(edma::error_tiles_dma<0>, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
-                               out, in, MB, NB, kc_len, n_slots, zero16, part);
+                               out, in, MB, NB, kc_len, n_slots, zero16, direct ? hmeta : nullptr, part);
         }
         ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
         {
             ProfScope prof(ctx, "error_finish");
-            hipLaunchKernelGGL(error_finish, dim3(fin_blocks, nc), dim3(256), 0, ctx->stream, diag, part, out, n_slots,
+            hipLaunchKernelGGL(error_finish, dim3(fin_blocks, nc), dim3(256), 0, ctx->stream,
+                               direct ? static_cast<const float*>(nullptr) : diag, part, out, n_slots,
                                loss_rows ? loss_rows + size_t(c0) * size_t(out) : nullptr, losses + c0, block_tot,
                                ticket);
         }
