@@ -146,10 +146,15 @@ def main():
     bt, n_tiles = gram_tiling(in_f)
     gram_flops = 2.0 * n_tiles * bt * bt * tokens
     gram_s = kern["gram_tiles"]["avg_us"] * 1e-6
+    # HBM bytes per launch of that kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+    # command (profiles/traffic.txt: "<kernel>/<workload> <bytes>" per line); null when not measured
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "traffic.txt")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"gram_tiles/{args.workload}")
+        for line in open(tpath):
+            f = line.split()
+            if len(f) >= 2 and f[0] == f"gram_tiles/{args.workload}":
+                traffic = float(f[1])
     roofline = {
         "kernel": "gram_tiles", "bound": "mfma", "achieved": gram_flops / gram_s / 1e12, "peak": MFMA_F16_PEAK / 1e12,
         "unit": "TFLOP/s", "frac": gram_flops / gram_s / MFMA_F16_PEAK, "traffic": traffic,
@@ -213,7 +218,7 @@ def main():
         "unit": "weights/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 operands, f32 accumulate (quantizer f32)", "data": "synthetic",
+        "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}/{layer} W[{out_f},{in_f}] X[{tokens},{in_f}] int{bits} g{group} "
                                "both dims + selection", "bits": bits, "group": group, "tokens": tokens},
         "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
