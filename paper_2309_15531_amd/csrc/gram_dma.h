@@ -284,21 +284,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
 
-    float* dst = part + int64_t(item) * (int64_t(BT) * BT);
+    // The partial tile is stored in register order: float4 number ((i*TN + j)*4 + q)*256 + thread
+    // holds accumulator registers 4q..4q+3 of block (i, j), so every store instruction writes one
+    // contiguous kilobyte per wave; gram_reduce reads it back in the same order.
+    static_assert(WGM == 2 && WGN == 2, "register-order partials assume 2 x 2 waves of 4 x 4 blocks");
+    float4* dst = reinterpret_cast<float4*>(part + int64_t(item) * (int64_t(BT) * BT));
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = wm * WM + 32 * i + acc_row(r, lane);
-                const int col = wn * WN + 32 * j + (lane & 31);
-                dst[row * BT + col] = acc[i][j][r];
-            }
+            for (int q = 0; q < 4; ++q)
+                dst[((i * TN + j) * 4 + q) * 256 + tid] =
+                    make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
     if constexpr (DBG & 8) {
         if (tid == 0) {
-            dst[0] = static_cast<float>(clock64() - dbg_c0);
-            dst[1] = static_cast<float>(wall_clock64() - dbg_w0);
+            dst[0].x = static_cast<float>(clock64() - dbg_c0);
+            dst[0].y = static_cast<float>(wall_clock64() - dbg_w0);
         }
     }
 }

@@ -82,7 +82,10 @@ __global__ __launch_bounds__(THREADS) void gram_tiles(const __half* __restrict__
 
 // Adds the split partials of one 32x32 sub-block, writes it to H and, off the
 // diagonal, its mirror image.  grid = tiles * (sub-blocks per tile side)^2.
-template <int BT>
+// REGMAJOR: the partial tiles are in the register order of the DMA tile kernel (float4 number
+// ((i*4 + j)*4 + q)*256 + thread holds accumulator registers 4q..4q+3 of that thread's 32x32 block
+// (i, j)), which for thread (tx, ty) here is one 16-byte load: rows 4*ty..4*ty+3 of column tx.
+template <int BT, bool REGMAJOR = false>
 __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ part, int n_tiles, int n_split,
                                                    int nb, int64_t in, float* __restrict__ H, int accumulate) {
     constexpr int SB = BT / 32;
@@ -96,12 +99,27 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const float* src = part + int64_t(tile) * (int64_t(BT) * BT);
     const int64_t split_stride = int64_t(n_tiles) * BT * BT;
+    if constexpr (REGMAJOR) {
+        static_assert(!REGMAJOR || BT == 256, "register-major partials come from the 256-wide DMA kernel");
+        const int wave = (sr >> 2) * 2 + (sc >> 2);
+        const int64_t idx = (((sr & 3) * 4 + (sc & 3)) * 4 + (ty >> 1)) * 256 + wave * 64 + (ty & 1) * 32 + tx;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        for (int sp = 0; sp < n_split; ++sp) {
+            const float4 p = *reinterpret_cast<const float4*>(src + sp * split_stride + idx * 4);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        s[ty * 4 + 0][tx] = v.x;
+        s[ty * 4 + 1][tx] = v.y;
+        s[ty * 4 + 2][tx] = v.z;
+        s[ty * 4 + 3][tx] = v.w;
+    } else {
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-        const int r = ty * 4 + rr;
-        float v = 0.0f;
-        for (int sp = 0; sp < n_split; ++sp) v += src[sp * split_stride + (sr * 32 + r) * BT + sc * 32 + tx];
-        s[r][tx] = v;
+        for (int rr = 0; rr < 4; ++rr) {
+            const int r = ty * 4 + rr;
+            float v = 0.0f;
+            for (int sp = 0; sp < n_split; ++sp) v += src[sp * split_stride + (sr * 32 + r) * BT + sc * 32 + tx];
+            s[r][tx] = v;
+        }
     }
     __syncthreads();
     const bool diag = R0 == C0;
@@ -255,8 +273,8 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
     constexpr int SB = BT / 32;
     {
         ProfScope prof(ctx, "gram_reduce");
-        hipLaunchKernelGGL(gram_reduce<BT>, dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream, part, n_tiles,
-                           n_split, nb, in, H, accumulate);
+        hipLaunchKernelGGL((gram_reduce<BT, BT == 256>), dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream, part,
+                           n_tiles, n_split, nb, in, H, accumulate);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gram_reduce");
     return ADADIM_OK;
