@@ -301,6 +301,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
         if (tid == 0) {
             dst[0].x = static_cast<float>(clock64() - dbg_c0);
             dst[0].y = static_cast<float>(wall_clock64() - dbg_w0);
+            dst[0].z = __uint_as_float(static_cast<uint32_t>(dbg_w0));            // start, 100 MHz ticks
+            dst[0].w = __uint_as_float(static_cast<uint32_t>(wall_clock64()));   // end
         }
     }
 }
