@@ -30,6 +30,8 @@ WORKLOADS = {
     "q_proj": (1, "q_proj"),           # the workload the headline metric is quoted on
     "gate_proj": (2, "gate_proj"),
     "down_proj": (2, "down_proj"),
+    # q, k and v of one decoder block: three layers that share X, one H, one scoring launch
+    "qkv": (2, ("q_proj", "k_proj", "v_proj")),
 }
 
 
@@ -76,6 +78,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=None)
+    ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference dispatch that scales "
@@ -98,9 +101,12 @@ def main():
 
     cfg_id, layer = WORKLOADS[args.workload]
     cfg = synth.CONFIGS[cfg_id]
+    layers = layer if isinstance(layer, tuple) else (layer,)
+    layer = layers[0]
     out_f, in_f = cfg["layers"][layer]
     bits = args.bits if args.bits is not None else (3 if 3 in cfg["bits"] else cfg["bits"][0])
-    group, tokens = cfg["group"], cfg["tokens"]
+    group = cfg["group"] if args.group is None else args.group
+    tokens = cfg["tokens"]
 
     W = synth.config_weight(cfg_id, layer)
     X = synth.config_activations(cfg_id, in_f)
@@ -109,12 +115,23 @@ def main():
 
     ctx = B.Context()
     hp = S.PreparedHessian(ctx, in_f)
-    ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,))
+    if len(layers) == 1:
+        ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,))
 
-    def step():
-        hp.update(Xd)
-        hp.prepare()
-        return ls.run(Wd, hp)
+        def step():
+            hp.update(Xd)
+            hp.prepare()
+            return ls.run(Wd, hp)
+    else:
+        Wds = [Wd] + [torch.from_numpy(synth.config_weight(cfg_id, l)).cuda() for l in layers[1:]]
+        ls = S.SharedSearch(ctx, len(layers), out_f, in_f, bits, group)
+        ls.cands = [(d, 1.0) for _ in layers for d in (B.DIM_OC, B.DIM_IC)]
+
+        def step():
+            hp.update(Xd)
+            hp.prepare()
+            dims = ls.run(Wds, hp)
+            return dims[0], dims[0], 1.0
 
     for _ in range(args.warmup):
         step()
@@ -176,7 +193,8 @@ def main():
             "frac_mfma": issued / s / MFMA_F16_PEAK,
             "tflops_dense_equivalent": per_launch * 2.0 * out_f * in_f * in_f / s / 1e12,
         }
-    qbytes = out_f * in_f * (2 + 2) + 5.0 * out_f * in_f / group   # W read + fp16 dW written + scale/zero
+    # W read + fp16 dW written + scale/zero (one pair per group of the larger of the two group counts)
+    qbytes = out_f * in_f * (2 + 2) + 5.0 * (out_f * in_f / group if group else max(out_f, in_f))
     for k in ("quant_oc", "quant_ic"):
         if k in kern:
             s = kern[k]["avg_us"] * 1e-6
@@ -214,13 +232,13 @@ def main():
 
     result = {
         "metric": "weight params quantized+scored (both dims)/s",
-        "value": out_f * in_f / (elapsed / args.steps),
+        "value": len(layers) * out_f * in_f / (elapsed / args.steps),
         "unit": "weights/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{cfg['name']}/{layer} W[{out_f},{in_f}] X[{tokens},{in_f}] int{bits} g{group} "
-                               "both dims + selection", "bits": bits, "group": group, "tokens": tokens},
+        "config": {"workload": f"{cfg['name']}/{'+'.join(layers)} W[{out_f},{in_f}] X[{tokens},{in_f}] int{bits} "
+                               f"g{group} both dims + selection", "bits": bits, "group": group, "tokens": tokens},
         "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
         "roofline": roofline,
         "quantizer_hbm": quant,

@@ -101,3 +101,47 @@ class LayerSearch:
                 self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, scales=self.scales,
                                          zeros=self.zeros, packed=self.packed)
         return best, dim, clip
+
+
+class SharedSearch:
+    """The same search for several layers of one shape that see the same input (q/k/v, or
+    gate/up, of a decoder block): H is formed once and every (layer, dimension) candidate is
+    scored by a single adadim_layer_error_batch launch, which fetches the prepared H once for
+    all of them.  At most four layers (eight candidates, the batch limit)."""
+
+    def __init__(self, ctx: B.Context, n_layers: int, out_f: int, in_f: int, bits: int, group: int, device="cuda"):
+        if not 1 <= n_layers <= 4:
+            raise ValueError("SharedSearch takes 1..4 layers")
+        self.ctx, self.n_layers, self.out_f, self.in_f, self.bits, self.group = ctx, n_layers, out_f, in_f, bits, group
+        n_c = 2 * n_layers
+        self.dWs = [ctx.alloc_score(out_f, in_f, device) for _ in range(n_c)]
+        self.losses = torch.empty(n_c, dtype=torch.float32, device=device)      # [layer][oc, ic]
+        self.best = torch.empty(n_layers, dtype=torch.int32, device=device)
+        g_oc = in_f if group == 0 else group
+        g_ic = out_f if group == 0 else group
+        n_meta = max(out_f * (in_f // g_oc), (out_f // g_ic) * in_f)
+        words = max(out_f * ((in_f * bits + 31) // 32), in_f * ((out_f * bits + 31) // 32))
+        self._scales = [torch.empty(n_meta, dtype=torch.float32, device=device) for _ in range(n_c)]
+        self._zeros = [torch.empty(n_meta, dtype=torch.uint8, device=device) for _ in range(n_c)]
+        self._packed = [torch.empty(words, dtype=torch.int32, device=device) for _ in range(n_c)]
+        self.scales = self.zeros = self.packed = None
+
+    def run(self, Ws, hp: PreparedHessian):
+        """Ws: the layers' weights.  Returns the list of chosen dimensions (one host sync); the
+        winners' packed codes, scales and zeros are in self.packed[l] / self.scales[l] / self.zeros[l]."""
+        assert len(Ws) == self.n_layers
+        for l, W in enumerate(Ws):
+            for dim in (B.DIM_OC, B.DIM_IC):
+                k = 2 * l + dim
+                self.ctx.adadim_quantize(W, dim, self.bits, self.group, 1.0, dW=self.dWs[k], dW_dtype=B.DW_F16_SCALED,
+                                         colscale=hp.colscale, scales=self._scales[k], zeros=self._zeros[k],
+                                         packed=self._packed[k])
+        self.ctx.adadim_layer_error_batch(self.dWs, B.DW_F16_SCALED, hp.Hs, hp.hmeta, self.losses,
+                                          shape=(self.out_f, self.in_f))
+        for l in range(self.n_layers):
+            self.ctx.adadim_select(self.losses[2 * l:2 * l + 2], best_dev=self.best[l:l + 1], to_host=False)
+        dims = self.best.cpu().tolist()          # the one synchronisation
+        self.scales = [self._scales[2 * l + d] for l, d in enumerate(dims)]
+        self.zeros = [self._zeros[2 * l + d] for l, d in enumerate(dims)]
+        self.packed = [self._packed[2 * l + d] for l, d in enumerate(dims)]
+        return dims

@@ -340,3 +340,54 @@ def test_choice_flips_under_transpose_gpu(ctx):
     _, _, dim_a, _ = run_search(ctx, W, X, 3, 32)
     _, _, dim_b, _ = run_search(ctx, np.ascontiguousarray(W.T), X, 3, 32)
     assert (dim_a, dim_b) == (IC, OC)
+
+
+def _check_winner(ls_scales, ls_zeros, ls_packed, W, dim, bits, group):
+    q = oracle.quantize(W, dim, bits, group)
+    n_meta = q["scales"].size
+    assert np.array_equal(ls_scales[:n_meta].cpu().numpy(), q["scales"].ravel())
+    assert np.array_equal(ls_zeros[:n_meta].cpu().numpy(), q["zeros"].ravel())
+    pk = oracle.pack(q["codes"], dim, bits)
+    assert np.array_equal(ls_packed[:pk.size].cpu().numpy().view(np.uint32), pk.ravel())
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+@pytest.mark.parametrize("group", [256, 128, 64, 0])
+def test_group_size_sweep(ctx, bits, group):
+    """The paper's sweep of precisions and group sizes (Sec. 4.4), plus whole-channel groups:
+    full search against the oracle, winner's stored outputs bit-exact."""
+    out_f, in_f = 768, 1024
+    W = rand_w(out_f, in_f, seed=900 + bits + group)
+    X = synth.make_activations(1100, in_f, seed=17, n_outliers=4, scale_lo=50, scale_hi=100)
+    ref = oracle.search(W, X, bits, group)
+    ls, best, dim, clip = run_search(ctx, W, X, bits, group)
+    got = ls.losses.cpu().numpy()
+    assert got == pytest.approx(ref["losses"], rel=LOSS_RTOL)
+    lo, hi = min(ref["losses"]), max(ref["losses"])
+    if (hi - lo) / lo > 0.01:
+        assert best == ref["best"]
+    _check_winner(ls.scales, ls.zeros, ls.packed, W, dim, bits, group)
+
+
+def test_shared_input_search(ctx):
+    """Three layers that see the same input (q, k, v): one H, one scoring launch for all six
+    candidates; every layer's losses equal the single-layer search's, winners bit-exact."""
+    out_f, in_f, bits, group = 512, 768, 3, 128
+    Ws = [rand_w(out_f, in_f, seed=700 + l) for l in range(3)]
+    X = synth.make_activations(900, in_f, seed=23, n_outliers=3, scale_lo=60, scale_hi=90)
+    hp = S.PreparedHessian(ctx, in_f).update(dev(X)).prepare()
+    sh = S.SharedSearch(ctx, 3, out_f, in_f, bits, group)
+    dims = sh.run([dev(W) for W in Ws], hp)
+    torch.cuda.synchronize()
+    got = sh.losses.cpu().numpy().reshape(3, 2)
+    H = oracle.hessian(X)
+    for l, W in enumerate(Ws):
+        ref = oracle.search(W, X, bits, group, H=H)
+        assert got[l] == pytest.approx(ref["losses"], rel=LOSS_RTOL)
+        if abs(ref["losses"][0] - ref["losses"][1]) / min(ref["losses"]) > 0.01:
+            assert dims[l] == ref["best"]
+        single = S.LayerSearch(ctx, out_f, in_f, bits, group)
+        single.run(dev(W), hp)
+        torch.cuda.synchronize()
+        assert single.losses.cpu().numpy() == pytest.approx(got[l], rel=1e-5)   # same kernels, other chunking
+        _check_winner(sh.scales[l], sh.zeros[l], sh.packed[l], W, dims[l], bits, group)
