@@ -21,6 +21,8 @@ enum {
     WS_SELECT,          // device int for adadim_select without a device output
     WS_ERR_FIN,         // block totals and ticket of the loss reduction
     WS_ZERO,            // zero-filled buffer: source of out-of-range token rows for LDS DMA
+    WS_QPART,           // partial (min, -max) pairs of the wide-group quantizer
+    WS_QPAR,            // its per-group scale, zero and reciprocal
     WS_COUNT
 };
 

@@ -767,6 +767,189 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
 }
 
 // ---------------------------------------------------------------------------
+// Wide groups (whole-channel quantization, groups longer than one workgroup can hold): three
+// passes with 16-byte accesses.  (1) partial (min, -max) pairs per piece of a group, (2) one
+// thread per group reduces the pieces and computes the parameters, (3) an element-wise pass
+// looks the parameters up (they sit in L2) and quantizes with the streaming arithmetic.
+// Group numbering is that of the scales array: per-OC row*(in/g) + column group, per-IC
+// (row group)*in + column.
+
+// per-OC pieces: one wavefront per (group, piece of up to 64 chunks = 512 columns)
+__global__ __launch_bounds__(256) void wide_minmax_oc(const uint4* __restrict__ W, int64_t n_groups, int cpg,
+                                                      int n_pieces, uint32_t* __restrict__ part) {
+    const int lane = threadIdx.x & 63;
+    const int64_t id = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);      // (group, piece)
+    if (id >= n_groups * n_pieces) return;                                 // whole wavefront leaves together
+    const int64_t grp = id / n_pieces;
+    const int ch = static_cast<int>(id % n_pieces) * 64 + lane;            // chunk within the group
+    uint32_t m = 0u;                                                       // (0, -0): the range contains zero
+    if (ch < cpg) {
+        const uint4 raw = W[grp * cpg + ch];                               // groups are consecutive chunks of the flat matrix
+        const uint32_t mnp = pk_min(pk_min(raw.x, raw.y), pk_min(raw.z, raw.w));
+        const uint32_t nmx = pk_max(pk_max(raw.x, raw.y), pk_max(raw.z, raw.w)) ^ 0x80008000u;
+        m = pk_min(__builtin_amdgcn_perm(nmx, mnp, 0x05040100u), __builtin_amdgcn_perm(nmx, mnp, 0x07060302u));
+        m = pk_min(m, 0x80000000u);                                        // fold in (0, -0)
+    } else {
+        m = 0x80000000u;
+    }
+    m = cluster_min2<64>(m);
+    if (lane == 0) part[id] = m;
+}
+
+// per-IC pieces: a wavefront owns 64 rows x 64 columns of one group (8 row lanes x 8 chunk lanes,
+// 8 loads per lane); partials are stored [row group][piece][column]
+__global__ __launch_bounds__(256) void wide_minmax_ic(const __half* __restrict__ W, int64_t out, int64_t in, int g,
+                                                      int n_pieces, uint32_t* __restrict__ part) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rl = lane >> 3, cl = lane & 7;
+    const int64_t col0 = (int64_t(blockIdx.x) * 4 + wave) * 64 + cl * 8;
+    const int64_t rg = blockIdx.y / n_pieces;
+    const int piece = blockIdx.y % n_pieces;
+    const int64_t r_end = min(out, (rg + 1) * int64_t(g));
+    const int64_t r_first = rg * int64_t(g) + piece * 64 + rl;
+    const bool col_ok = col0 < in;
+    uint32_t mn2[4] = {0u, 0u, 0u, 0u}, mx2[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int64_t row = r_first + 8 * u;
+        if (col_ok && row < r_end) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(W + row * in + col0);
+            const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                mn2[i] = pk_min(mn2[i], v[i]);
+                mx2[i] = pk_max(mx2[i], v[i]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        mn2[i] = pk_min(mn2[i], dpp_u<0x128>(mn2[i]));
+        mx2[i] = pk_max(mx2[i], dpp_u<0x128>(mx2[i]));
+        mn2[i] = pk_min(mn2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mn2[i]), 16, 64)));
+        mx2[i] = pk_max(mx2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx2[i]), 16, 64)));
+        mn2[i] = pk_min(mn2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mn2[i]), 32, 64)));
+        mx2[i] = pk_max(mx2[i], static_cast<uint32_t>(__shfl_xor(static_cast<int>(mx2[i]), 32, 64)));
+    }
+    if (col_ok && rl == 0) {
+        uint32_t o[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t nmx = mx2[i] ^ 0x80008000u;
+            o[2 * i] = __builtin_amdgcn_perm(nmx, mn2[i], 0x05040100u);
+            o[2 * i + 1] = __builtin_amdgcn_perm(nmx, mn2[i], 0x07060302u);
+        }
+        uint4* dst = reinterpret_cast<uint4*>(part + (rg * n_pieces + piece) * in + col0);
+        dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+        dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+    }
+}
+
+// one thread per group: pieces -> parameters.  piece p of group grp is part[grp*ps_g + p*ps_p + off(grp)]
+// (per-OC: grp*n_pieces + p; per-IC: (rg*n_pieces + p)*in + col)
+__global__ __launch_bounds__(256) void wide_params(const uint32_t* __restrict__ part, int64_t n_groups, int n_pieces,
+                                                   int64_t in, int is_ic, float clip, float qmax, float rqmax,
+                                                   float* __restrict__ par, float* __restrict__ scales,
+                                                   uint8_t* __restrict__ zeros) {
+    const int64_t grp = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const bool ok = grp < n_groups;                          // every lane reaches the wave-wide tests inside
+    uint32_t m = 0x80000000u;
+    if (ok) {
+        const int64_t base = is_ic ? (grp / in) * n_pieces * in + grp % in : grp * n_pieces;
+        const int64_t step = is_ic ? in : 1;
+        for (int p = 0; p < n_pieces; ++p) m = pk_min(m, part[base + p * step]);
+    }
+    const GroupParamsR gp = group_params_r(half_of(m, 0), -half_of(m, 1), clip, qmax, rqmax);
+    if (!ok) return;
+    par[grp] = gp.scale;
+    par[n_groups + grp] = gp.zero;
+    par[2 * n_groups + grp] = gp.rcp;
+    if (scales) scales[grp] = gp.scale;
+    if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
+}
+
+// element-wise pass: one thread per 16-byte chunk of W
+template <bool IC, bool SCALED>
+__global__ __launch_bounds__(256) void wide_apply(const uint4* __restrict__ W, int64_t out, int cpr, int g,
+                                                  int64_t n_groups, const float* __restrict__ par, float qmax,
+                                                  uint8_t* __restrict__ codes, void* __restrict__ dW, int dW_dtype,
+                                                  const float* __restrict__ colscale) {
+    const int64_t c = int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const bool valid = c < out * cpr;
+    const int64_t row = valid ? c / cpr : 0;
+    const int cc = valid ? static_cast<int>(c % cpr) : 0;
+    const int64_t in = int64_t(cpr) * 8, col0 = int64_t(cc) * 8;
+    const uint4 raw = valid ? W[c] : make_uint4(0, 0, 0, 0);
+    const float n0 = opaque_negzero();
+    QConst qc[8];
+    float sc[8];
+    bool fast = true;
+    if constexpr (IC) {
+        const int64_t p0 = (row / g) * in + col0;
+        const float4 s0 = *reinterpret_cast<const float4*>(par + p0), s1 = *reinterpret_cast<const float4*>(par + p0 + 4);
+        const float4 z0 = *reinterpret_cast<const float4*>(par + n_groups + p0);
+        const float4 z1 = *reinterpret_cast<const float4*>(par + n_groups + p0 + 4);
+        const float4 r0 = *reinterpret_cast<const float4*>(par + 2 * n_groups + p0);
+        const float4 r1 = *reinterpret_cast<const float4*>(par + 2 * n_groups + p0 + 4);
+        const float s[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+        const float z[8] = {z0.x, z0.y, z0.z, z0.w, z1.x, z1.y, z1.z, z1.w};
+        const float r[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            sc[i] = s[i];
+            qc[i] = {r[i], -s[i], -z[i], qmax - z[i], n0};
+            fast = fast && fastdiv_ok(s[i]);
+        }
+    } else {
+        const int64_t p = row * (in / g) + col0 / g;
+        const float s = par[p], z = par[n_groups + p], r = par[2 * n_groups + p];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            sc[i] = s;
+            qc[i] = {r, -s, -z, qmax - z, n0};
+        }
+        fast = fastdiv_ok(s);
+    }
+    const bool slow = __any(!fast);
+    const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
+    float k[8];
+    quant_k8(v, qc, slow, k);
+    if (!valid) return;
+    if (codes) {
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lo |= static_cast<uint32_t>(k[i] - qc[i].nz) << (8 * i);
+            hi |= static_cast<uint32_t>(k[4 + i] - qc[4 + i].nz) << (8 * i);
+        }
+        reinterpret_cast<uint2*>(codes)[c] = make_uint2(lo, hi);
+    }
+    if (dW) {
+        float cs[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+        if constexpr (SCALED) {
+            const float4 a = *reinterpret_cast<const float4*>(colscale + col0);
+            const float4 b = *reinterpret_cast<const float4*>(colscale + col0 + 4);
+            cs[0] = a.x; cs[1] = a.y; cs[2] = a.z; cs[3] = a.w;
+            cs[4] = b.x; cs[5] = b.y; cs[6] = b.z; cs[7] = b.w;
+        }
+        float d[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            d[2 * i] = fma_hff<0>(v[i], cs[2 * i], -(sc[2 * i] * cs[2 * i]) * k[2 * i]);
+            d[2 * i + 1] = fma_hff<1>(v[i], cs[2 * i + 1], -(sc[2 * i + 1] * cs[2 * i + 1]) * k[2 * i + 1]);
+        }
+        if (!SCALED && dW_dtype == ADADIM_DW_F32) {
+            float4* p = reinterpret_cast<float4*>(static_cast<float*>(dW) + c * 8);
+            p[0] = make_float4(d[0], d[1], d[2], d[3]);
+            p[1] = make_float4(d[4], d[5], d[6], d[7]);
+        } else {
+            const uint4 o = make_uint4(pack_h2(d[0], d[1]), pack_h2(d[2], d[3]), pack_h2(d[4], d[5]), pack_h2(d[6], d[7]));
+            *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + (SCALED ? score_index(row, col0, out, in) : c * 8)) = o;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Bit-packing: one thread assembles one 32-bit word of a channel's stream.
 // channel stride / element stride describe where code k of channel ch lives:
 // OC: ch*in + k;  IC: k*in + ch.
@@ -858,6 +1041,41 @@ void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in,
 #undef IC_S
 }
 
+// wide-group path (see wide_minmax_oc): in % 8 == 0; per-OC also g % 8 == 0
+int launch_wide(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int g, float clip, float qmax,
+                uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale) {
+    const bool ic = dim == ADADIM_DIM_IC;
+    const int64_t n_groups = ic ? (out / g) * in : out * (in / g);
+    const int cpr = static_cast<int>(in / 8);
+    const int n_pieces = ic ? (g + 63) / 64 : (g / 8 + 63) / 64;
+    uint32_t* part = static_cast<uint32_t*>(adadim_workspace(ctx, WS_QPART, size_t(n_groups) * n_pieces * 4));
+    float* par = static_cast<float*>(adadim_workspace(ctx, WS_QPAR, size_t(n_groups) * 3 * 4));
+    if (!part || !par) return ADADIM_EHIP;
+    ProfScope prof(ctx, ic ? "quant_ic_wide" : "quant_oc_wide");
+    if (ic) {
+        dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>((out / g) * n_pieces));
+        hipLaunchKernelGGL(wide_minmax_ic, grid, dim3(256), 0, ctx->stream, W, out, in, g, n_pieces, part);
+    } else {
+        const int64_t waves = n_groups * n_pieces;
+        hipLaunchKernelGGL(wide_minmax_oc, dim3(static_cast<unsigned>((waves + 3) / 4)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const uint4*>(W), n_groups, g / 8, n_pieces, part);
+    }
+    hipLaunchKernelGGL(wide_params, dim3(static_cast<unsigned>((n_groups + 255) / 256)), dim3(256), 0, ctx->stream, part,
+                       n_groups, n_pieces, in, ic ? 1 : 0, clip, qmax, 1.0f / qmax, par, scales, zeros);
+    if (codes || dW) {
+        const unsigned blocks = static_cast<unsigned>((out * cpr + 255) / 256);
+        const bool scaled = dW && dW_dtype == ADADIM_DW_F16_SCALED;
+        const uint4* W4 = reinterpret_cast<const uint4*>(W);
+#define WIDE_GO(IC, S)                                                                                          \
+    hipLaunchKernelGGL((wide_apply<IC, S>), dim3(blocks), dim3(256), 0, ctx->stream, W4, out, cpr, g, n_groups, \
+                       par, qmax, codes, dW, dW_dtype, colscale)
+        if (ic) { if (scaled) WIDE_GO(true, true); else WIDE_GO(true, false); }
+        else { if (scaled) WIDE_GO(false, true); else WIDE_GO(false, false); }
+#undef WIDE_GO
+    }
+    return ADADIM_OK;
+}
+
 }  // namespace
 
 int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, int dim, int bits,
@@ -904,6 +1122,10 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
 #undef OC_CASE
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_fast");
+        } else if (vec && (g % 8) == 0 && g >= 512 && out * (in / g) <= (int64_t(1) << 30)) {
+            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+            if (rc != ADADIM_OK) return rc;
+            ADADIM_LAUNCH_CHECK(ctx, "quant_oc_wide");
         } else {
             const int64_t n_groups = out * (in / g);
             const unsigned blocks = static_cast<unsigned>((n_groups + 3) / 4);
@@ -932,6 +1154,10 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
 #undef IC_CASE
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_stream");
+        } else if (vec && g >= 256 && row_groups * ((g + 63) / 64) <= 65535) {
+            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+            if (rc != ADADIM_OK) return rc;
+            ADADIM_LAUNCH_CHECK(ctx, "quant_ic_wide");
         } else if (vec) {
             dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(row_groups));
             {
