@@ -4,3 +4,4 @@ from .adadim_oracle import (  # noqa: F401
     layer_error_direct, layer_error_rows, layer_error, layer_error_rows_from_X,
     select, clip_grid, search,
 )
+from .gemv_oracle import dequantize_ic, gemv_ic, abs_terms  # noqa: F401,E402
