@@ -71,12 +71,73 @@ def cpu_baseline(W, X, bits, group, budget_tokens=4096):
     }
 
 
+def gemv_bench(args):
+    """The per-IC de-quantizing matrix-vector product on the shape of the paper's latency table
+    (App. D): weight [4m x m], m = 12288, batch 1.  One step = one adadim_gemv_ic call."""
+    import torch
+    from paper_2309_15531_amd import binding as B
+    B.load_library()
+    m = 12288
+    out_f, in_f = 4 * m, m
+    bits = 4 if args.bits is None else args.bits
+    group = 128 if args.group is None else args.group
+    g = torch.Generator(device="cuda").manual_seed(7)
+    n_words = out_f * bits // 32
+    # seeded random streams (every bit pattern is a valid code), scales and zeros
+    # two copies of the weight stream, used alternately, so that the 256 MB Infinity Cache cannot
+    # hold what the next call reads (weights of a model that does not fit the cache)
+    packs = [torch.randint(-2 ** 31, 2 ** 31 - 1, (in_f, n_words), dtype=torch.int32, device="cuda", generator=g)
+             for _ in range(2)]
+    scales = torch.empty((out_f // group, in_f), dtype=torch.float32, device="cuda").uniform_(0.004, 0.02, generator=g)
+    zeros = torch.randint(0, 2 ** bits, (out_f // group, in_f), dtype=torch.uint8, device="cuda", generator=g)
+    x = torch.randn(in_f, dtype=torch.float32, device="cuda", generator=g).half()
+    y = torch.empty(out_f, dtype=torch.float16, device="cuda")
+    packed = packs[0]
+    ctx = B.Context()
+    for i in range(args.warmup):
+        ctx.adadim_gemv_ic(packs[i & 1], scales, zeros, x, out_f, in_f, bits, group, y)
+    torch.cuda.synchronize()
+    ctx.adadim_profile(True)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ctx.adadim_gemv_ic(packs[i & 1], scales, zeros, x, out_f, in_f, bits, group, y)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.adadim_profile(False)
+    prof = ctx.adadim_profile_read()
+    kern = {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items()}
+    alg_bytes = out_f * in_f * bits / 8 + 5.0 * (out_f // group) * in_f + 2 * in_f + 2 * out_f
+    sec = kern["gemv_ic_tiles"] * 1e-6
+    result = {
+        "metric": "per-IC dequant matrix-vector product, weights/s", "value": out_f * in_f / (elapsed / args.steps),
+        "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"per-IC kernel W[{out_f},{in_f}] int{bits} g{group} x[{in_f}] batch 1 (App. D shape)",
+                   "bits": bits, "group": group},
+        "roofline": {"kernel": "gemv_ic_tiles", "bound": "hbm", "achieved": alg_bytes / sec / 1e9, "peak": HBM_PEAK / 1e9,
+                     "unit": "GB/s", "frac": alg_bytes / sec / HBM_PEAK, "traffic": None},
+        "kernels_us": kern,
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = 4
+        pk = packed[:, :max(1, rows * bits // 32 + 1)].cpu().numpy().view(np.uint32)
+        t0 = time.perf_counter()
+        oracle.gemv_ic(pk[:, :1], scales[:1].cpu().numpy(), zeros[:1].cpu().numpy(), x.cpu().numpy(), 32 // bits if bits != 3 else 10, bits, 0)
+        t = time.perf_counter() - t0
+        n_o = 32 // bits if bits != 3 else 10
+        result["cpu_baseline"] = {"value": n_o * in_f / t, "unit": "weights/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{n_o} outputs x {in_f} inputs"}
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["gemv_ic"])
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -97,6 +158,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.workload == "gemv_ic":
+        gemv_bench(args)
+        return
     B.load_library()  # fails loudly if the HIP library has not been built
 
     cfg_id, layer = WORKLOADS[args.workload]

@@ -175,6 +175,21 @@ int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int 
 int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best);
 
 /*
+ * Layer output for one activation vector from a per-IC quantized weight (Sec. 4.5 and App. D,
+ * the per-IC kernel: weight [out x in] in b bits, input [in x 1] and output [out x 1] fp16):
+ *     y[o] = sum_j scales[o/g, j] * (code[o, j] - zeros[o/g, j]) * x[j]
+ * computed as sum_j (scales*x)[o/g, j] * code[o, j] - sum_j (scales*x)[o/g, j] * zeros[o/g, j]
+ * in fp32 (the per-IC scale folded into the activation), rounded once to fp16.
+ *   packed  the stream adadim_quantize(dim = IC, bits) writes: u32 [in, out*bits/32], 16-byte aligned
+ *   scales  f32 [out/g, in] (16-byte aligned), zeros u8 [out/g, in] (4-byte aligned), as written there
+ *   x       fp16 [in], 8-byte aligned;   y  fp16 [out]
+ *   bits 2, 3 or 4; group a multiple of 32 dividing out (0 = out); in a multiple of 4.
+ * The sum is split over fixed column chunks and added up in a fixed order: same bits every run.
+ */
+int adadim_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const void* x,
+                   int64_t out, int64_t in, int bits, int group, void* y);
+
+/*
  * Measurement aid (not part of the method): per-kernel device timings.
  * adadim_profile(ctx, 1) clears the records and starts bracketing every kernel
  * the library launches on this context with a pair of HIP events on the

@@ -21,6 +21,7 @@ EXPORTS = (
     "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version", "adadim_score_elems",
     "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
+    "adadim_gemv_ic",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -95,6 +96,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_profile_read.argtypes = [c_void_p, c_int, ctypes.c_char_p, c_int, POINTER(ctypes.c_double),
                                         POINTER(c_int64)]
     lib.adadim_profile_read.restype = c_int
+    lib.adadim_gemv_ic.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
+                                   c_void_p]
+    lib.adadim_gemv_ic.restype = c_int
     if path is None:
         _lib = lib
     return lib
@@ -190,6 +194,10 @@ class Context:
         self._check(self._lib.adadim_select(self._h, _ptr(losses), n, _ptr(best_dev),
                                             byref(host) if to_host else None))
         return host.value if to_host else None
+
+    def adadim_gemv_ic(self, packed, scales, zeros, x, out_f: int, in_f: int, bits: int, group: int, y):
+        self._check(self._lib.adadim_gemv_ic(self._h, _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(x), out_f, in_f,
+                                             bits, group, _ptr(y)))
 
     def adadim_profile(self, enable: bool):
         self._check(self._lib.adadim_profile(self._h, 1 if enable else 0))

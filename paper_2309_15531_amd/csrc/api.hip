@@ -295,4 +295,26 @@ int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev
     return ADADIM_OK;
 }
 
+int adadim_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const void* x,
+                   int64_t out, int64_t in, int bits, int group, void* y) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!packed || !scales || !zeros || !x || !y) return adadim_fail(ctx, ADADIM_ENULL, "adadim_gemv_ic: NULL argument");
+    if (out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 24))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: bad shape out=%lld in=%lld", (long long)out, (long long)in);
+    if (bits < 2 || bits > 4) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: bits must be 2, 3 or 4, got %d", bits);
+    const int64_t g = group == 0 ? out : group;
+    if (group < 0 || (out % g) != 0 || (g % 32) != 0)
+        return adadim_fail(ctx, ADADIM_EINVAL,
+                           "adadim_gemv_ic: group %d must be 0 or a multiple of 32 that divides out (%lld)", group,
+                           (long long)out);
+    if ((in % 4) != 0) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: in must be a multiple of 4");
+    if (g > (int64_t(1) << 30)) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: group too long");
+    if (!aligned16(packed) || !aligned16(scales) || (reinterpret_cast<uintptr_t>(zeros) & 3u) ||
+        (reinterpret_cast<uintptr_t>(x) & 7u) || (reinterpret_cast<uintptr_t>(y) & 1u))
+        return adadim_fail(ctx, ADADIM_EALIGN,
+                           "adadim_gemv_ic: packed and scales 16-byte, x 8-byte, zeros 4-byte, y 2-byte aligned");
+    return launch_gemv_ic(ctx, packed, scales, zeros, static_cast<const __half*>(x), out, in, bits, static_cast<int>(g),
+                          static_cast<__half*>(y));
+}
+
 }  // extern "C"

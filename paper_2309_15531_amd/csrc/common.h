@@ -23,6 +23,7 @@ enum {
     WS_ZERO,            // zero-filled buffer: source of out-of-range token rows for LDS DMA
     WS_QPART,           // partial (min, -max) pairs of the wide-group quantizer
     WS_QPAR,            // its per-group scale, zero and reciprocal
+    WS_GEMV_PART,       // per-column-chunk partial outputs of the de-quantizing matrix-vector product
     WS_COUNT
 };
 
@@ -111,3 +112,5 @@ int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* 
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
                        const __half* Hs, const float* hmeta, float* loss_rows, float* losses);
 int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev);
+int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const __half* x,
+                   int64_t out, int64_t in, int bits, int g, __half* y);

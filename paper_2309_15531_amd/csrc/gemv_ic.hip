@@ -1,0 +1,229 @@
+// De-quantizing matrix-vector product for per-IC quantized weights (paper Sec. 4.5, App. D):
+//     y[o] = sum_j scale[o/g, j] * (code[o, j] - zero[o/g, j]) * x[j]
+// from the packed stream adadim_quantize(dim = IC) writes: [in, out*b/32] words, the codes of
+// one input column consecutive along the output axis.  Batch 1: every weight bit is read once
+// and used once, so the kernel is bound by HBM reads.
+//
+// The paper's kernel builds look-up tables of scale*activation products; on gfx950 a direct
+// form is simpler and reads the same bytes: with a[r, j] = scale[r, j] * x[j] (the per-IC
+// scale folded into the activation, as the paper does when it fills its tables)
+//     y[o] = sum_j a[o/g, j] * code[o, j]  -  sum_j a[o/g, j] * zero[o/g, j].
+// A lane owns 32 consecutive outputs (b words of every column, one 16-byte load for b = 4), a
+// wavefront 2048, so the codes of a column are read in contiguous kilobytes and no sum crosses
+// lanes; the second sum costs one fma per lane and column.  Columns are split over the eight
+// waves of a block and over blocks; partial outputs are added up in a fixed order (LDS inside
+// a block; across blocks by a second small kernel, chunk by chunk), so the result is
+// reproducible.  (Letting the last block of an output tile do that sum needs device-scope
+// fences, which write back and invalidate the XCD's whole L2 each time: 3x slower overall.)
+#include "common.h"
+
+namespace {
+
+constexpr int GV_WAVES = 8, GV_COLS_PER_WAVE = 64, GV_COLS_PER_BLOCK = GV_WAVES * GV_COLS_PER_WAVE, GV_OUT_PER_BLOCK = 64 * 32;
+
+template <int PB>
+struct Words {
+    uint32_t w[PB];
+};
+
+template <int PB>
+__device__ __forceinline__ Words<PB> load_words(const uint32_t* p) {
+    Words<PB> r;
+    if constexpr (PB == 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
+    } else if constexpr (PB == 2) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < PB; ++i) r.w[i] = p[i];
+    }
+    return r;
+}
+
+// float(byte n of v).  `v` must be opaque to the optimiser (see hide()), or it rewrites the
+// mask-then-byte sequence into a bit-field extract plus a conversion, one instruction more per code.
+__device__ __forceinline__ float ubyte(uint32_t v, int n) { return static_cast<float>((v >> (8 * n)) & 0xffu); }
+__device__ __forceinline__ uint32_t hide(uint32_t v) {
+    asm("" : "+v"(v));
+    return v;
+}
+#define UBYTE(v, n) ubyte(v, n)
+
+// acc[k] += a * code k of the lane's 32 codes
+template <int PB>
+__device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (&acc)[32]) {
+    if constexpr (PB == 4) {
+        const float a16 = a * 0.0625f;                      // odd nibbles are read as 16 * code
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t ev = hide(wd.w[i] & 0x0F0F0F0Fu), od = hide(wd.w[i] & 0xF0F0F0F0u);
+#pragma unroll
+            for (int n = 0; n < 4; ++n) {
+                acc[8 * i + 2 * n] = fmaf(a, UBYTE(ev, n), acc[8 * i + 2 * n]);
+                acc[8 * i + 2 * n + 1] = fmaf(a16, UBYTE(od, n), acc[8 * i + 2 * n + 1]);
+            }
+        }
+    } else if constexpr (PB == 2) {
+        const float as[4] = {a, a * 0.25f, a * 0.0625f, a * 0.015625f};   // fields read as 4^f * code
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                const uint32_t m = hide(wd.w[i] & (0x03030303u << (2 * f)));
+#pragma unroll
+                for (int n = 0; n < 4; ++n) acc[16 * i + 4 * n + f] = fmaf(as[f], UBYTE(m, n), acc[16 * i + 4 * n + f]);
+            }
+        }
+    } else {
+        static_assert(PB == 3, "2, 3 or 4 bits");
+        // 3-bit codes repeat every 3 bytes (8 codes).  In byte n = 3p + i of the 12-byte stream the
+        // codes 8p + 3i (at bit i of the byte) and 8p + 3i + 1 (at bit 3 + i) lie whole, so one mask
+        // per word isolates one code per byte and the byte conversion yields code * 2^shift, undone
+        // by a power-of-two factor on a.  The codes 8p + 2 and 8p + 5 straddle bytes; in the stream
+        // shifted right by 6 bits they sit whole in bytes 3p (bit 0) and 3p + 1 (bit 1).
+        const float as[6] = {a, a * 0.5f, a * 0.25f, a * 0.125f, a * 0.0625f, a * 0.03125f};
+        const uint32_t sh[3] = {__builtin_amdgcn_alignbit(wd.w[1], wd.w[0], 6), __builtin_amdgcn_alignbit(wd.w[2], wd.w[1], 6),
+                                wd.w[2] >> 6};
+        constexpr uint32_t MA[3] = {0x071C0E07u, 0x0E071C0Eu, 0x1C0E071Cu};
+        constexpr uint32_t MB[3] = {0x38E07038u, 0x7038E070u, 0xE07038E0u};
+        constexpr uint32_t MS[3] = {0x07000E07u, 0x0E07000Eu, 0x000E0700u};
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+            const uint32_t va = hide(wd.w[w] & MA[w]), vb = hide(wd.w[w] & MB[w]), vs = hide(sh[w] & MS[w]);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int n = 4 * w + b, p3 = n / 3, i = n % 3;
+                acc[8 * p3 + 3 * i] = fmaf(as[i], ubyte(va, b), acc[8 * p3 + 3 * i]);
+                acc[8 * p3 + 3 * i + 1] = fmaf(as[3 + i], ubyte(vb, b), acc[8 * p3 + 3 * i + 1]);
+                if (i < 2) acc[8 * p3 + 3 * i + 2] = fmaf(as[i], ubyte(vs, b), acc[8 * p3 + 3 * i + 2]);
+            }
+        }
+    }
+}
+
+template <int PB>
+__global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* __restrict__ packed,
+                                                               const float* __restrict__ scales,
+                                                               const uint8_t* __restrict__ zeros,
+                                                               const __half* __restrict__ x, int64_t out, int64_t in,
+                                                               int g, int64_t n_words, float* __restrict__ part) {
+    __shared__ float s_acc[GV_WAVES][32][65];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t o_lane = int64_t(blockIdx.x) * GV_OUT_PER_BLOCK + lane * 32;
+    const bool valid = o_lane < out;                         // out % 32 == 0: a lane's outputs are inside together
+    const int64_t r = valid ? o_lane / g : 0;
+    const int64_t j_begin = int64_t(blockIdx.y) * GV_COLS_PER_BLOCK + wave * GV_COLS_PER_WAVE;
+    const int64_t j_end = min(in, j_begin + GV_COLS_PER_WAVE);
+    const uint32_t* wp = packed + (valid ? (o_lane >> 5) * PB : 0);
+    float acc[32];
+#pragma unroll
+    for (int k = 0; k < 32; ++k) acc[k] = 0.0f;
+    float zsum = 0.0f;
+    // four columns per step, the next step's loads issued before this step's arithmetic
+    struct Step {
+        Words<PB> wd[4];
+        float4 s4;
+        uint32_t z4;
+        uint2 xr;
+    };
+    auto fetch = [&](Step& st, int64_t j0) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) st.wd[c] = load_words<PB>(wp + (j0 + c) * n_words);
+        st.s4 = *reinterpret_cast<const float4*>(scales + r * in + j0);
+        st.z4 = *reinterpret_cast<const uint32_t*>(zeros + r * in + j0);
+        st.xr = *reinterpret_cast<const uint2*>(x + j0);
+    };
+    auto consume = [&](const Step& st) {
+        const float2 x01 = __half22float2(*reinterpret_cast<const __half2*>(&st.xr.x));
+        const float2 x23 = __half22float2(*reinterpret_cast<const __half2*>(&st.xr.y));
+        const float a[4] = {st.s4.x * x01.x, st.s4.y * x01.y, st.s4.z * x23.x, st.s4.w * x23.y};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            zsum = fmaf(a[c], ubyte(st.z4, c), zsum);
+            accumulate<PB>(st.wd[c], a[c], acc);
+        }
+    };
+    if (valid && j_begin < j_end) {
+        // two buffers, no copies: A is consumed while B is in flight and the other way round.
+        // Fetches past the end re-read the chunk's last columns and are not consumed.
+        const int64_t j_last = j_end - 4;
+        Step A, B2;
+        fetch(A, j_begin);
+        for (int64_t j0 = j_begin; j0 < j_end; j0 += 8) {    // in % 4 == 0
+            fetch(B2, min(j0 + 4, j_last));
+            consume(A);
+            fetch(A, min(j0 + 8, j_last));
+            if (j0 + 4 < j_end) consume(B2);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 32; ++k) s_acc[wave][k][lane] = acc[k] - zsum;
+    __syncthreads();
+    // thread t adds up the waves for outputs 4t .. 4t+3 of the block's 2048
+    const int t = threadIdx.x;
+    const int64_t o0 = int64_t(blockIdx.x) * GV_OUT_PER_BLOCK + 4 * t;
+    const bool o_ok = o0 < out;                               // out % 4 == 0
+    if (o_ok) {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int ol = 4 * t + e, ln = ol >> 5, k = ol & 31;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < GV_WAVES; ++w) sum += s_acc[w][k][ln];
+            v[e] = sum;
+        }
+        *reinterpret_cast<float4*>(part + int64_t(blockIdx.y) * out + o0) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+}
+
+// y[o] = fp16 of the chunk sums in chunk order; one thread per four outputs
+__global__ __launch_bounds__(256) void gemv_ic_finish(const float* __restrict__ part, int n_chunks, int64_t out,
+                                                      __half* __restrict__ y) {
+    const int64_t o0 = (int64_t(blockIdx.x) * 256 + threadIdx.x) * 4;
+    if (o0 >= out) return;                                    // out % 4 == 0
+    float4 sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll 4
+    for (int c = 0; c < n_chunks; ++c) {
+        const float4 p = *reinterpret_cast<const float4*>(part + int64_t(c) * out + o0);
+        sum.x += p.x; sum.y += p.y; sum.z += p.z; sum.w += p.w;
+    }
+    uint2 o;
+    *reinterpret_cast<__half2*>(&o.x) = __floats2half2_rn(sum.x, sum.y);
+    *reinterpret_cast<__half2*>(&o.y) = __floats2half2_rn(sum.z, sum.w);
+    *reinterpret_cast<uint2*>(y + o0) = o;
+}
+
+}  // namespace
+
+int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const __half* x,
+                   int64_t out, int64_t in, int bits, int g, __half* y) {
+    const int n_chunks = static_cast<int>((in + GV_COLS_PER_BLOCK - 1) / GV_COLS_PER_BLOCK);
+    const int n_tiles = static_cast<int>((out + GV_OUT_PER_BLOCK - 1) / GV_OUT_PER_BLOCK);
+    float* part = static_cast<float*>(adadim_workspace(ctx, WS_GEMV_PART, size_t(n_chunks) * size_t(out) * sizeof(float)));
+    if (!part) return ADADIM_EHIP;
+    const int64_t n_words = out * bits / 32;
+    const dim3 grid(static_cast<unsigned>(n_tiles), static_cast<unsigned>(n_chunks));
+    {
+        ProfScope prof(ctx, "gemv_ic_tiles");
+#define GV_GO(PB)                                                                                              \
+    hipLaunchKernelGGL(gemv_ic_tiles<PB>, grid, dim3(64 * GV_WAVES), 0, ctx->stream, packed, scales, zeros, x, out, in, \
+                       g, n_words, part)
+        switch (bits) {
+            case 2: GV_GO(2); break;
+            case 3: GV_GO(3); break;
+            default: GV_GO(4); break;
+        }
+#undef GV_GO
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "gemv_ic_tiles");
+    {
+        ProfScope prof(ctx, "gemv_ic_finish");
+        hipLaunchKernelGGL(gemv_ic_finish, dim3(static_cast<unsigned>((out / 4 + 255) / 256)), dim3(256), 0, ctx->stream,
+                           part, n_chunks, out, y);
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "gemv_ic_finish");
+    return ADADIM_OK;
+}

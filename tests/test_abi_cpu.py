@@ -101,6 +101,19 @@ def test_error_and_select_validation(ctx):
     assert "adadim_select" in ctx.last_error()
 
 
+def test_gemv_validation(ctx):
+    gv = lambda *a: ctx.raw("adadim_gemv_ic", *a)
+    assert gv(None, A16, A16, A16, 64, 64, 4, 32, A16) == B.ENULL
+    assert gv(A16, A16, A16, A16, 64, 64, 4, 32, None) == B.ENULL
+    assert gv(A16, A16, A16, A16, 64, 64, 5, 32, A16) == B.EINVAL          # 2, 3 or 4 bits
+    assert gv(A16, A16, A16, A16, 64, 64, 4, 48, A16) == B.EINVAL          # group not a multiple of 32
+    assert gv(A16, A16, A16, A16, 96, 64, 4, 64, A16) == B.EINVAL          # group does not divide out
+    assert gv(A16, A16, A16, A16, 64, 62, 4, 32, A16) == B.EINVAL          # in % 4
+    assert gv(ctypes.c_void_p(A16.value + 4), A16, A16, A16, 64, 64, 4, 32, A16) == B.EALIGN
+    assert "adadim_gemv_ic" in ctx.last_error()
+    assert ctx._lib.adadim_score_elems(300, 64) == 512 * 64 and ctx._lib.adadim_score_elems(300, 40) == 300 * 40
+
+
 def test_create_destroy():
     lib = B.load_library()
     assert lib.adadim_create(None, None) == B.ENULL
