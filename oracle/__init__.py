@@ -5,3 +5,4 @@ from .adadim_oracle import (  # noqa: F401
     select, clip_grid, search,
 )
 from .gemv_oracle import dequantize_ic, gemv_ic, abs_terms  # noqa: F401,E402
+from . import gptq_oracle  # noqa: F401,E402
