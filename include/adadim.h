@@ -175,6 +175,44 @@ int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int 
 int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best);
 
 /*
+ * GPTQ in the dimension the search selected (Sec. 3.3 "Augmenting RTN and GPTQ", App. A.1, App. B
+ * `gptq_ada`; GPTQ is Frantar et al. 2022): channels are quantized one after the other and each
+ * channel's rounding error is spread over the channels not yet quantized.
+ *
+ * adadim_gptq_prepare works on H alone (shared by all layers with that input):
+ *   dead[j] = 1 where H_jj == 0 (that diagonal entry is taken as 1 and the layer's weights of the
+ *           channel as 0);  damping: percdamp * mean(diag H) is added to the diagonal;
+ *   perm    visiting order, int32 [in]: perm[i] = original index of the channel visited i-th;
+ *           act_order = 1: decreasing diag(H), equal values by index; 0: identity;
+ *   U       fp32 [in, in], upper triangular, in visiting order: inv(P (H + damp I) P^T) = U^T U.
+ *           Factorized in fp64 (device scratch: two in x in fp64 matrices), rounded once.
+ * H fp32 [in, in] as adadim_hessian writes it; in <= 46340.
+ */
+int adadim_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t in, float percdamp, int act_order, int32_t* perm,
+                        uint8_t* dead, float* U);
+
+/*
+ * The sweep.  In blocks of 128 visited channels: q_i = Q(w_i), e_i = (w_i - q_i)/U_ii,
+ * w_j -= e_i U_ij for the later channels j (inside the block at once, behind the block after it,
+ * one channel's error at a time); all in fp32, every update a rounded product followed by a
+ * rounded difference, so the result is reproducible bit for bit.  Q is the quantizer of
+ * adadim_quantize (clip 1) with
+ *   dim = OC: static groups: the parameters of (row, channel group) are static_scales /
+ *           static_zeros [out, in/g] as adadim_quantize(dim = OC) writes them for the original W,
+ *           looked up by the channel's original index (the paper's "reorder + static" setting);
+ *           scales / zeros are not written (they are the static ones);
+ *   dim = IC: the parameters of (row group, channel) are computed from the channel's current
+ *           values when it is visited and written to scales f32 / zeros u8 [out/g, in]
+ *           (the paper's "reorder" setting for per-IC); group 64 or 128.
+ * Outputs in the original channel order: codes u8 [out, in]; optional dW fp32 [out, in] = W - What
+ * (for adadim_layer_error); optional packed stream as in adadim_quantize.
+ */
+int adadim_gptq_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                         const float* U, const int32_t* perm, const uint8_t* dead, const float* static_scales,
+                         const uint8_t* static_zeros, uint8_t* codes, float* scales, uint8_t* zeros, float* dW,
+                         uint32_t* packed);
+
+/*
  * Layer output for one activation vector from a per-IC quantized weight (Sec. 4.5 and App. D,
  * the per-IC kernel: weight [out x in] in b bits, input [in x 1] and output [out x 1] fp16):
  *     y[o] = sum_j scales[o/g, j] * (code[o, j] - zeros[o/g, j]) * x[j]

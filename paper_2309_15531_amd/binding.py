@@ -21,7 +21,7 @@ EXPORTS = (
     "adadim_create", "adadim_destroy", "adadim_last_error", "adadim_version", "adadim_score_elems",
     "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
-    "adadim_gemv_ic",
+    "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -99,6 +99,11 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_gemv_ic.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
                                    c_void_p]
     lib.adadim_gemv_ic.restype = c_int
+    lib.adadim_gptq_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p, c_void_p]
+    lib.adadim_gptq_prepare.restype = c_int
+    lib.adadim_gptq_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_void_p, c_void_p,
+                                         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.adadim_gptq_quantize.restype = c_int
     if path is None:
         _lib = lib
     return lib
@@ -198,6 +203,17 @@ class Context:
     def adadim_gemv_ic(self, packed, scales, zeros, x, out_f: int, in_f: int, bits: int, group: int, y):
         self._check(self._lib.adadim_gemv_ic(self._h, _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(x), out_f, in_f,
                                              bits, group, _ptr(y)))
+
+    def adadim_gptq_prepare(self, H, perm, dead, U, percdamp: float = 0.01, act_order: bool = True):
+        self._check(self._lib.adadim_gptq_prepare(self._h, _ptr(H), H.shape[0], c_float(percdamp), 1 if act_order else 0,
+                                                  _ptr(perm), _ptr(dead), _ptr(U)))
+
+    def adadim_gptq_quantize(self, W, dim: int, bits: int, group: int, U, perm, dead, codes, static_scales=None,
+                             static_zeros=None, scales=None, zeros=None, dW=None, packed=None):
+        out_f, in_f = W.shape
+        self._check(self._lib.adadim_gptq_quantize(self._h, _ptr(W), out_f, in_f, dim, bits, group, _ptr(U), _ptr(perm),
+                                                   _ptr(dead), _ptr(static_scales), _ptr(static_zeros), _ptr(codes),
+                                                   _ptr(scales), _ptr(zeros), _ptr(dW), _ptr(packed)))
 
     def adadim_profile(self, enable: bool):
         self._check(self._lib.adadim_profile(self._h, 1 if enable else 0))

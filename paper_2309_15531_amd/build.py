@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadadim.so")
-SOURCES = ["api.hip", "quantize.hip", "hessian.hip", "layer_error.hip", "gemv_ic.hip"]
+SOURCES = ["api.hip", "quantize.hip", "hessian.hip", "layer_error.hip", "gemv_ic.hip", "gptq.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                      # one rounding per operation in the quantizer

@@ -317,4 +317,50 @@ int adadim_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales,
                           static_cast<__half*>(y));
 }
 
+int adadim_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t in, float percdamp, int act_order, int32_t* perm,
+                        uint8_t* dead, float* U) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!H || !perm || !dead || !U) return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_prepare: NULL argument");
+    if (in <= 0 || in > 46340) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_prepare: bad in=%lld", (long long)in);
+    if (!(percdamp >= 0.0f && percdamp <= 1.0f) || (act_order != 0 && act_order != 1))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_prepare: percdamp must be in [0,1], act_order 0 or 1");
+    return launch_gptq_prepare(ctx, H, in, percdamp, act_order, perm, dead, U);
+}
+
+int adadim_gptq_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                         const float* U, const int32_t* perm, const uint8_t* dead, const float* static_scales,
+                         const uint8_t* static_zeros, uint8_t* codes, float* scales, uint8_t* zeros, float* dW,
+                         uint32_t* packed) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!W || !U || !perm || !dead || !codes)
+        return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_quantize: W, U, perm, dead or codes is NULL");
+    if (out <= 0 || in <= 0 || out > 500000 || in > 46340)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: bad shape out=%lld in=%lld", (long long)out,
+                           (long long)in);
+    if (dim != ADADIM_DIM_OC && dim != ADADIM_DIM_IC)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: dim must be 0 (OC) or 1 (IC), got %d", dim);
+    if (bits < 2 || bits > 8) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: bits must be in [2,8]");
+    if (dim == ADADIM_DIM_OC) {
+        const int64_t g = group == 0 ? in : group;
+        if (group < 0 || (in % g) != 0)
+            return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: group %d must be 0 or divide in", group);
+        if (!static_scales || !static_zeros)
+            return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_quantize: per-OC needs the static scales and zeros");
+        const int rc = launch_gptq_quantize(ctx, static_cast<const __half*>(W), out, in, dim, bits, static_cast<int>(g), U,
+                                            perm, dead, static_scales, static_zeros, codes, nullptr, nullptr, dW);
+        if (rc != ADADIM_OK) return rc;
+    } else {
+        if ((group != 64 && group != 128) || (out % group) != 0)
+            return adadim_fail(ctx, ADADIM_EINVAL,
+                               "adadim_gptq_quantize: per-IC groups of 64 or 128 rows dividing out are supported, got %d",
+                               group);
+        if (!scales || !zeros) return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_quantize: per-IC needs scales and zeros");
+        const int rc = launch_gptq_quantize(ctx, static_cast<const __half*>(W), out, in, dim, bits, group, U, perm, dead,
+                                            nullptr, nullptr, codes, scales, zeros, dW);
+        if (rc != ADADIM_OK) return rc;
+    }
+    if (packed) return launch_pack(ctx, codes, out, in, dim, bits, packed);
+    return ADADIM_OK;
+}
+
 }  // extern "C"

@@ -24,6 +24,11 @@ enum {
     WS_QPART,           // partial (min, -max) pairs of the wide-group quantizer
     WS_QPAR,            // its per-group scale, zero and reciprocal
     WS_GEMV_PART,       // per-column-chunk partial outputs of the de-quantizing matrix-vector product
+    WS_GPTQ_A,          // fp64 reversed, permuted, damped Hessian and its Cholesky factor
+    WS_GPTQ_M,          // fp64 inverse of that factor
+    WS_GPTQ_D,          // fp64 diagonal and damping term
+    WS_GPTQ_W,          // fp32 working copy of the weight in visiting order
+    WS_GPTQ_E,          // fp32 propagated errors in visiting order
     WS_COUNT
 };
 
@@ -112,5 +117,10 @@ int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* 
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
                        const __half* Hs, const float* hmeta, float* loss_rows, float* losses);
 int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev);
+int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percdamp, int act_order, int32_t* perm,
+                        uint8_t* dead, float* U);
+int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
+                         const float* U, const int32_t* perm, const uint8_t* dead, const float* st_scales,
+                         const uint8_t* st_zeros, uint8_t* codes, float* scales_out, uint8_t* zeros_out, float* dW);
 int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const __half* x,
                    int64_t out, int64_t in, int bits, int g, __half* y);
