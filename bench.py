@@ -132,12 +132,60 @@ def gemv_bench(args):
     print(json.dumps(result))
 
 
+def gptq_bench(args):
+    """GPTQ-ada on the q_proj workload: H and its preparation are already there; one step = the RTN
+    search for the dimension plus GPTQ in that dimension and the scoring of its result; the factor
+    of the inverse Hessian (once per distinct input) is timed on its own."""
+    import torch
+    from paper_2309_15531_amd import binding as B
+    from paper_2309_15531_amd import search as S
+    from paper_2309_15531_amd import synth
+    B.load_library()
+    cfg = synth.CONFIGS[1]
+    out_f, in_f = cfg["layers"]["q_proj"]
+    bits = 3 if args.bits is None else args.bits
+    group = cfg["group"] if args.group is None else args.group
+    Wd = torch.from_numpy(synth.config_weight(1, "q_proj")).cuda()
+    Xd = torch.from_numpy(synth.config_activations(1, in_f)).cuda()
+    ctx = B.Context()
+    hp = S.PreparedHessian(ctx, in_f).update(Xd).prepare()
+    del Xd
+    fac = S.GptqFactor(ctx, hp)
+    ga = S.GptqAda(ctx, out_f, in_f, bits, group)
+    for _ in range(max(1, args.warmup)):
+        dim = ga.run(Wd, hp, fac)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    fac.update(hp)
+    torch.cuda.synchronize()
+    t_factor = time.perf_counter() - t0
+    ctx.adadim_profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dim = ga.run(Wd, hp, fac)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ctx.adadim_profile(False)
+    prof = ctx.adadim_profile_read()
+    kern = {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items()}
+    print(json.dumps({
+        "metric": "weight params searched + GPTQ-quantized /s", "value": out_f * in_f / (elapsed / args.steps),
+        "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"gptq-ada llama7b-q_proj W[{out_f},{in_f}] int{bits} g{group}", "bits": bits, "group": group},
+        "result": {"dim": "oc" if dim == 0 else "ic", "loss_rtn": float(ga.loss_rtn.item()),
+                   "loss_gptq": float(ga.loss_gptq.item())},
+        "factor_ms": t_factor * 1e3, "kernels_us": kern,
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["gemv_ic"])
+    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["gemv_ic", "gptq"])
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -160,6 +208,9 @@ def main():
         sys.exit(1)
     if args.workload == "gemv_ic":
         gemv_bench(args)
+        return
+    if args.workload == "gptq":
+        gptq_bench(args)
         return
     B.load_library()  # fails loudly if the HIP library has not been built
 

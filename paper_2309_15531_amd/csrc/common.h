@@ -29,6 +29,7 @@ enum {
     WS_GPTQ_D,          // fp64 diagonal and damping term
     WS_GPTQ_W,          // fp32 working copy of the weight in visiting order
     WS_GPTQ_E,          // fp32 propagated errors in visiting order
+    WS_GPTQ_Q,          // u8 codes in visiting order
     WS_COUNT
 };
 

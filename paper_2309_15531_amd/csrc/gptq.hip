@@ -124,7 +124,7 @@ __global__ __launch_bounds__(64) void chol_trsm(double* __restrict__ A, int64_t 
         if (c < w) {
             double v = x[c];
 #pragma unroll
-            for (int t2 = 0; t2 < c; ++t2) v -= x[t2] * L[c][t2];
+            for (int t2 = 0; t2 < c; ++t2) v = fma(-x[t2], L[c][t2], v);
             x[c] = v / L[c][c];
         }
     }
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+            for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(64) void trinv_diag(const double* __restrict__ A, d
         if (r < w && r >= c) {
             double v = r == c ? 1.0 : 0.0;
 #pragma unroll
-            for (int t2 = 0; t2 < r; ++t2) v -= L[r][t2] * x[t2];
+            for (int t2 = 0; t2 < r; ++t2) v = fma(-L[r][t2], x[t2], v);
             x[r] = v / L[r][r];
         }
     }
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(256) void trinv_row(const double* __restrict__ A, d
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+                for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
         }
     }
     // S (w x 64) into Tb, M_ii into Ta, then M_ij = -M_ii S
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void trinv_row(const double* __restrict__ A, d
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) o[i][j] += a[i] * b[j];
+            for (int j = 0; j < 4; ++j) o[i][j] = fma(a[i], b[j], o[i][j]);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -293,74 +293,160 @@ __global__ void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t i
     Wp[idx] = dead[j] ? 0.0f : __half2float(W[r * in + j]);
 }
 
-// One 128-channel block [i1, i2) for RT rows per workgroup, one thread per row.
-// IC: the workgroup is one row group (RT = g rows) and the parameters of (group, channel) come from
-// the channel's current values; OC: parameters looked up in the static arrays.
-template <bool IC>
-__global__ void gq_sweep(float* __restrict__ Wp, const float* __restrict__ U, const int32_t* __restrict__ perm,
-                         const uint8_t* __restrict__ dead, const __half* __restrict__ W, int64_t out, int64_t in,
-                         int64_t i1, int nbw, int g, float qmax, const float* __restrict__ st_scales,
-                         const uint8_t* __restrict__ st_zeros, float* __restrict__ scales_out,
-                         uint8_t* __restrict__ zeros_out, uint8_t* __restrict__ codes, float* __restrict__ dW,
-                         float* __restrict__ Ep) {
+// One 128-channel block [i1, i1 + nbw) for the rows of one wavefront (a workgroup is one wave, so
+// nothing is shared and there is no barrier).  Lane l holds RPL rows: per-OC rows 64*block + l
+// (RPL = 1), per-IC rows l + 64p of the block's row group (RPL = g/64), so that the group's minimum
+// and maximum are a lane-local step plus one wave reduction.  A lane's rows live in its own strip of
+// LDS; the channels are walked in sub-blocks of 16 held in registers: the sub-block's own updates
+// stay in registers, then its 16 errors are applied to the rest of the block, one LDS read and one
+// write per element for 16 updates, always in channel order.  The block of U is staged in LDS and
+// read with wave-uniform addresses.  Codes go out in visiting order (16 bytes per row and sub-block).
+template <bool IC, int RPL>
+__global__ __launch_bounds__(64) void gq_sweep(float* __restrict__ Wp, const float* __restrict__ U,
+                                               const int32_t* __restrict__ perm, int64_t out, int64_t in, int64_t i1,
+                                               int nbw, int g, float qmax, const float* __restrict__ st_scales,
+                                               const uint8_t* __restrict__ st_zeros, float* __restrict__ scales_out,
+                                               uint8_t* __restrict__ zeros_out, uint8_t* __restrict__ Qp,
+                                               float* __restrict__ Ep) {
+    constexpr int SB = 16, PITCH = GB + 1;
     extern __shared__ __align__(16) char smem[];
-    const int RT = blockDim.x;
-    float* Us = reinterpret_cast<float*>(smem);                         // [nbw][GB] rows i1.., columns i1..
-    float* Ws = Us + GB * GB;                                           // [RT][GB + 1]
-    float* red = Ws + int64_t(RT) * (GB + 1);                           // [2][waves] (IC)
-    const int tid = threadIdx.x;
-    const int64_t r = int64_t(blockIdx.x) * RT + tid;
-    const bool row_ok = r < out;
-    for (int e = tid; e < nbw * nbw; e += RT) Us[(e / nbw) * GB + e % nbw] = U[(i1 + e / nbw) * in + i1 + e % nbw];
-    if (row_ok)
-        for (int c = 0; c < nbw; ++c) Ws[tid * (GB + 1) + c] = Wp[r * in + i1 + c];
-    __syncthreads();
-    const int n_waves = RT / 64, lane = tid & 63, wave = tid >> 6;
-    const int n_cg = IC ? 0 : static_cast<int>(in / g);
-    for (int c = 0; c < nbw; ++c) {
-        const int32_t j = perm[i1 + c];                                 // original channel
-        const float w = row_ok ? Ws[tid * (GB + 1) + c] : 0.0f;
-        QP p;
-        if constexpr (IC) {
-            float mn = w, mx = w;
-#pragma unroll
-            for (int m = 1; m < 64; m <<= 1) {
-                mn = fminf(mn, __shfl_xor(mn, m, 64));
-                mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-            }
-            if (n_waves > 1) {
-                __syncthreads();                                        // red[] free again
-                if (lane == 0) {
-                    red[wave] = mn;
-                    red[n_waves + wave] = mx;
-                }
-                __syncthreads();
-                for (int k = 0; k < n_waves; ++k) {
-                    mn = fminf(mn, red[k]);
-                    mx = fmaxf(mx, red[n_waves + k]);
-                }
-            }
-            p = params_of(mn, mx, qmax);
-            if (tid == 0) {
-                scales_out[int64_t(blockIdx.x) * in + j] = p.scale;
-                zeros_out[int64_t(blockIdx.x) * in + j] = static_cast<uint8_t>(p.zero);
-            }
+    float* Us = reinterpret_cast<float*>(smem);                         // [GB][GB]: rows / columns i1.. of U
+    float* Ws = Us + GB * GB;                                           // [64 * RPL][PITCH]
+    const int lane = threadIdx.x;
+    for (int e4 = lane; e4 < nbw * (GB / 4); e4 += 64) {                // in % 4 == 0 is not required: guarded
+        const int k = e4 / (GB / 4), c4 = (e4 % (GB / 4)) * 4;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        const float* src = U + (i1 + k) * in + i1 + c4;
+        if (c4 + 3 < nbw && ((reinterpret_cast<uintptr_t>(src) & 15u) == 0)) {
+            v = *reinterpret_cast<const float4*>(src);
         } else {
-            p.scale = row_ok ? st_scales[r * n_cg + j / g] : 1.0f;
-            p.zero = row_ok ? static_cast<float>(st_zeros[r * n_cg + j / g]) : 0.0f;
+            if (c4 + 0 < nbw) v.x = src[0];
+            if (c4 + 1 < nbw) v.y = src[1];
+            if (c4 + 2 < nbw) v.z = src[2];
+            if (c4 + 3 < nbw) v.w = src[3];
         }
-        if (!row_ok) continue;                                          // no barrier below in the OC form; IC has whole groups
-        float q = rintf(w / p.scale) + p.zero;
-        q = fminf(fmaxf(q, 0.0f), qmax);
-        const float wq = p.scale * (q - p.zero);
-        codes[r * in + j] = static_cast<uint8_t>(q);
-        if (dW) dW[r * in + j] = (dead[j] ? 0.0f : __half2float(W[r * in + j])) - wq;
-        const float e = (w - wq) / Us[c * GB + c];
-        Ep[r * in + i1 + c] = e;
-        for (int cc = c + 1; cc < nbw; ++cc) {
-            const float upd = e * Us[c * GB + cc];
-            Ws[tid * (GB + 1) + cc] = Ws[tid * (GB + 1) + cc] - upd;
+        *reinterpret_cast<float4*>(Us + k * GB + c4) = v;
+    }
+    __syncthreads();
+    int64_t row[RPL];
+    bool ok[RPL];
+#pragma unroll
+    for (int p = 0; p < RPL; ++p) {
+        row[p] = IC ? int64_t(blockIdx.x) * g + lane + 64 * p : int64_t(blockIdx.x) * 64 + lane;
+        ok[p] = row[p] < out;
+        if (ok[p])
+            for (int c = 0; c < nbw; ++c) Ws[(lane * RPL + p) * PITCH + c] = Wp[row[p] * in + i1 + c];
+    }
+    const int n_cg = IC ? 0 : static_cast<int>(in / g);
+    for (int s0 = 0; s0 < nbw; s0 += SB) {
+        const int sbw = nbw - s0 < SB ? nbw - s0 : SB;
+        float w[RPL][SB], e[RPL][SB];
+        uint32_t qpk[RPL][SB / 4];
+#pragma unroll
+        for (int p = 0; p < RPL; ++p) {
+#pragma unroll
+            for (int c = 0; c < SB; ++c) w[p][c] = (ok[p] && c < sbw) ? Ws[(lane * RPL + p) * PITCH + s0 + c] : 0.0f;
+#pragma unroll
+            for (int c = 0; c < SB / 4; ++c) qpk[p][c] = 0u;
         }
+#pragma unroll
+        for (int c = 0; c < SB; ++c) {
+            if (c < sbw) {                                              // uniform
+                const int64_t ig = i1 + s0 + c;                        // visiting index
+                const int32_t j = perm[ig];                            // original channel (uniform)
+                const float d = Us[(s0 + c) * GB + s0 + c];
+                QP pr[RPL];
+                if constexpr (IC) {
+                    float mn = w[0][c], mx = w[0][c];
+#pragma unroll
+                    for (int p = 1; p < RPL; ++p) {
+                        mn = fminf(mn, w[p][c]);
+                        mx = fmaxf(mx, w[p][c]);
+                    }
+#pragma unroll
+                    for (int m = 1; m < 64; m <<= 1) {
+                        mn = fminf(mn, __shfl_xor(mn, m, 64));
+                        mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+                    }
+                    const QP q1 = params_of(mn, mx, qmax);
+#pragma unroll
+                    for (int p = 0; p < RPL; ++p) pr[p] = q1;
+                    if (lane == 0) {
+                        scales_out[int64_t(blockIdx.x) * in + j] = q1.scale;
+                        zeros_out[int64_t(blockIdx.x) * in + j] = static_cast<uint8_t>(q1.zero);
+                    }
+                } else {
+                    pr[0].scale = ok[0] ? st_scales[row[0] * n_cg + j / g] : 1.0f;
+                    pr[0].zero = ok[0] ? static_cast<float>(st_zeros[row[0] * n_cg + j / g]) : 0.0f;
+                }
+#pragma unroll
+                for (int p = 0; p < RPL; ++p) {
+                    float q = rintf(w[p][c] / pr[p].scale) + pr[p].zero;
+                    q = fminf(fmaxf(q, 0.0f), qmax);
+                    const float wq = pr[p].scale * (q - pr[p].zero);
+                    qpk[p][c / 4] |= static_cast<uint32_t>(q) << (8 * (c % 4));
+                    e[p][c] = (w[p][c] - wq) / d;
+#pragma unroll
+                    for (int cc = c + 1; cc < SB; ++cc) {
+                        if (cc < sbw) {
+                            const float upd = e[p][c] * Us[(s0 + c) * GB + s0 + cc];
+                            w[p][cc] = w[p][cc] - upd;
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int p = 0; p < RPL; ++p) e[p][c] = 0.0f;
+            }
+        }
+        // the sub-block's codes and errors, in visiting order
+#pragma unroll
+        for (int p = 0; p < RPL; ++p) {
+            if (!ok[p]) continue;
+            const int64_t at = row[p] * in + i1 + s0;
+            if (sbw == SB && ((at & 15) == 0)) {
+                *reinterpret_cast<uint4*>(Qp + at) = make_uint4(qpk[p][0], qpk[p][1], qpk[p][2], qpk[p][3]);
+            } else {
+                for (int c = 0; c < sbw; ++c) Qp[at + c] = static_cast<uint8_t>(qpk[p][c / 4] >> (8 * (c % 4)));
+            }
+            for (int c = 0; c < sbw; ++c) Ep[at + c] = e[p][c];
+        }
+        // its errors applied to the rest of the block, channel order kept per element
+        for (int cc = s0 + SB; cc < nbw; ++cc) {
+            float u[SB];
+#pragma unroll
+            for (int k = 0; k < SB; ++k) u[k] = k < sbw ? Us[(s0 + k) * GB + cc] : 0.0f;
+#pragma unroll
+            for (int p = 0; p < RPL; ++p) {
+                if (!ok[p]) continue;
+                float v = Ws[(lane * RPL + p) * PITCH + cc];
+#pragma unroll
+                for (int k = 0; k < SB; ++k) {
+                    const float upd = e[p][k] * u[k];
+                    v = v - upd;
+                }
+                Ws[(lane * RPL + p) * PITCH + cc] = v;
+            }
+        }
+    }
+}
+
+// codes back to the original channel order, and dW = W - scale*(code - zero) there
+template <bool IC>
+__global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __restrict__ perm,
+                           const uint8_t* __restrict__ dead, const __half* __restrict__ W, int64_t out, int64_t in, int g,
+                           const float* __restrict__ scales, const uint8_t* __restrict__ zeros,
+                           uint8_t* __restrict__ codes, float* __restrict__ dW) {
+    const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (idx >= out * in) return;
+    const int64_t r = idx / in, i = idx % in;
+    const int32_t j = perm[i];
+    const uint8_t q = Qp[idx];
+    codes[r * in + j] = q;
+    if (dW) {
+        const int64_t pi = IC ? (r / g) * in + j : r * (in / g) + j / g;
+        const float wq = scales[pi] * (static_cast<float>(q) - static_cast<float>(zeros[pi]));
+        dW[r * in + j] = (dead[j] ? 0.0f : __half2float(W[r * in + j])) - wq;
     }
 }
 
@@ -439,36 +525,55 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
     const size_t mat = size_t(out) * size_t(in) * sizeof(float);
     float* Wp = static_cast<float*>(adadim_workspace(ctx, WS_GPTQ_W, mat));
     float* Ep = static_cast<float*>(adadim_workspace(ctx, WS_GPTQ_E, mat));
-    if (!Wp || !Ep) return ADADIM_EHIP;
+    uint8_t* Qp = static_cast<uint8_t*>(adadim_workspace(ctx, WS_GPTQ_Q, size_t(out) * size_t(in)));
+    if (!Wp || !Ep || !Qp) return ADADIM_EHIP;
     const float qmax = static_cast<float>((1 << bits) - 1);
     const bool ic = dim == ADADIM_DIM_IC;
-    const int rt = ic ? g : 64;                                        // threads (rows) per workgroup
+    const int rpl = ic ? g / 64 : 1;                                   // rows per lane
     const unsigned blocks = static_cast<unsigned>(ic ? out / g : (out + 63) / 64);
-    const size_t smem = (size_t(GB) * GB + size_t(rt) * (GB + 1) + 2 * 16) * sizeof(float);
+    const size_t smem = (size_t(GB) * GB + size_t(64) * rpl * (GB + 1)) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<false>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 2>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 1>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<false, 1>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
         attr_set = true;
     }
-    ProfScope prof(ctx, "gptq_sweep");
-    hipLaunchKernelGGL(gq_gather_w, dim3(static_cast<unsigned>((out * in + 255) / 256)), dim3(256), 0, ctx->stream, W, out,
-                       in, perm, dead, Wp);
+    const unsigned eb = static_cast<unsigned>((out * in + 255) / 256);
+    {
+        ProfScope prof(ctx, "gptq_gather");
+        hipLaunchKernelGGL(gq_gather_w, dim3(eb), dim3(256), 0, ctx->stream, W, out, in, perm, dead, Wp);
+    }
     for (int64_t i1 = 0; i1 < in; i1 += GB) {
         const int nbw = static_cast<int>(in - i1 < GB ? in - i1 : GB);
-        if (ic)
-            hipLaunchKernelGGL(gq_sweep<true>, dim3(blocks), dim3(rt), smem, ctx->stream, Wp, U, perm, dead, W, out, in, i1,
-                               nbw, g, qmax, st_scales, st_zeros, scales_out, zeros_out, codes, dW, Ep);
-        else
-            hipLaunchKernelGGL(gq_sweep<false>, dim3(blocks), dim3(rt), smem, ctx->stream, Wp, U, perm, dead, W, out, in,
-                               i1, nbw, g, qmax, st_scales, st_zeros, scales_out, zeros_out, codes, dW, Ep);
+        {
+            ProfScope prof(ctx, "gptq_sweep");
+#define GQ_GO(IC_, RPL_)                                                                                          \
+    hipLaunchKernelGGL((gq_sweep<IC_, RPL_>), dim3(blocks), dim3(64), smem, ctx->stream, Wp, U, perm, out, in, i1, \
+                       nbw, g, qmax, st_scales, st_zeros, scales_out, zeros_out, Qp, Ep)
+            if (!ic) GQ_GO(false, 1);
+            else if (rpl == 1) GQ_GO(true, 1);
+            else GQ_GO(true, 2);
+#undef GQ_GO
+        }
         const int64_t rest = in - i1 - nbw;
         if (rest > 0) {
+            ProfScope prof(ctx, "gptq_trailing");
             dim3 grid(static_cast<unsigned>((rest + 255) / 256), static_cast<unsigned>((out + 7) / 8));
             hipLaunchKernelGGL(gq_trailing, grid, dim3(256), 0, ctx->stream, Wp, U, Ep, out, in, i1, nbw);
         }
+    }
+    {
+        ProfScope prof(ctx, "gptq_scatter");
+        if (ic)
+            hipLaunchKernelGGL(gq_scatter<true>, dim3(eb), dim3(256), 0, ctx->stream, Qp, perm, dead, W, out, in, g,
+                               scales_out, zeros_out, codes, dW);
+        else
+            hipLaunchKernelGGL(gq_scatter<false>, dim3(eb), dim3(256), 0, ctx->stream, Qp, perm, dead, W, out, in, g,
+                               st_scales, st_zeros, codes, dW);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gptq sweep");
     return ADADIM_OK;

@@ -145,3 +145,58 @@ class SharedSearch:
         self.zeros = [self._zeros[2 * l + d] for l, d in enumerate(dims)]
         self.packed = [self._packed[2 * l + d] for l, d in enumerate(dims)]
         return dims
+
+
+class GptqFactor:
+    """Visiting order, dead-channel flags and the factor U of the inverse Hessian (adadim_gptq_prepare);
+    depends on H only, so one is shared by every layer that sees that input."""
+
+    def __init__(self, ctx: B.Context, hp: PreparedHessian, percdamp: float = 0.01, act_order: bool = True,
+                 device="cuda"):
+        n = hp.in_f
+        self.ctx, self.in_f = ctx, n
+        self.perm = torch.empty(n, dtype=torch.int32, device=device)
+        self.dead = torch.empty(n, dtype=torch.uint8, device=device)
+        self.U = torch.empty((n, n), dtype=torch.float32, device=device)
+        self.percdamp, self.act_order = percdamp, act_order
+        self.update(hp)
+
+    def update(self, hp: PreparedHessian):
+        self.ctx.adadim_gptq_prepare(hp.H, self.perm, self.dead, self.U, self.percdamp, self.act_order)
+        return self
+
+
+class GptqAda:
+    """`gptq_ada` of App. B: the RTN search picks the dimension, GPTQ then quantizes in it.
+    Per-OC uses the RTN winner's parameters as static groups; per-IC (group 64 or 128) recomputes
+    them channel by channel.  Results: codes u8 [out, in], scales, zeros, packed; `loss_rtn` and
+    `loss_gptq` (device scalars) are the layer errors before and after."""
+
+    def __init__(self, ctx: B.Context, out_f: int, in_f: int, bits: int, group: int, device="cuda"):
+        self.ctx, self.out_f, self.in_f, self.bits, self.group = ctx, out_f, in_f, bits, group
+        self.search = LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,))
+        self.codes = torch.empty((out_f, in_f), dtype=torch.uint8, device=device)
+        self.dW = torch.empty((out_f, in_f), dtype=torch.float32, device=device)
+        self.loss_gptq = torch.empty(1, dtype=torch.float32, device=device)
+        g_ic = out_f if group == 0 else group
+        self.ic_scales = torch.empty((out_f // g_ic, in_f), dtype=torch.float32, device=device)
+        self.ic_zeros = torch.empty((out_f // g_ic, in_f), dtype=torch.uint8, device=device)
+        self.scales = self.zeros = None
+        self.packed = self.search._packed[0]
+
+    def run(self, W, hp: PreparedHessian, fac: GptqFactor):
+        best, dim, _ = self.search.run(W, hp)
+        self.loss_rtn = self.search.losses[best:best + 1]
+        if dim == B.DIM_OC:
+            # static groups: the search's per-OC parameters (of the weight as given; a layer with dead
+            # input channels should be passed with those columns already zero)
+            self.scales, self.zeros = self.search.scales, self.search.zeros
+            self.ctx.adadim_gptq_quantize(W, dim, self.bits, self.group, fac.U, fac.perm, fac.dead, self.codes,
+                                          static_scales=self.scales, static_zeros=self.zeros, dW=self.dW,
+                                          packed=self.packed)
+        else:
+            self.scales, self.zeros = self.ic_scales, self.ic_zeros
+            self.ctx.adadim_gptq_quantize(W, dim, self.bits, self.group, fac.U, fac.perm, fac.dead, self.codes,
+                                          scales=self.scales, zeros=self.zeros, dW=self.dW, packed=self.packed)
+        self.ctx.adadim_layer_error_prepared(self.dW, B.DW_F32, hp.Hs, hp.hmeta, self.loss_gptq)
+        return dim
