@@ -55,6 +55,9 @@ struct adadim_ctx {
     void* ws[WS_COUNT];
     size_t ws_bytes[WS_COUNT];
     size_t zero_ready_bytes;         // size of WS_ZERO when it was last cleared
+    int64_t gram_key_tokens;         // token count and tile count the cached Gram split length was chosen for
+    int gram_key_tiles;
+    int64_t gram_t_per_split;
     adadim_prof prof;
 };
 

@@ -86,7 +86,7 @@ struct Frags {
 template <int WGM, int WGN, int DBG = 0>
 __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* __restrict__ X, int64_t tokens,
                                                                  int64_t in, int64_t ldx, int nb, int n_split,
-                                                                 int64_t t_per_split, const void* zero16,
+                                                                 int n_full, int64_t t_per_split, const void* zero16,
                                                                  float* __restrict__ part) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BT / WGM, WN = BT / WGN, TM = WM / 32, TN = WN / 32;
@@ -99,11 +99,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
     // round-robin by launch index, and each XCD has its own L2: give XCD x the x-th contiguous
     // eighth of the work list, so that the workgroups resident on one XCD at a time stream the
     // same token range and share row/column panels in its L2.
+    // The first n_full splits have full length, a last one (if any) is shorter: each XCD takes
+    // its eighth of the full-length items first and then its eighth of the short ones, so the
+    // short items fill the gaps of the last round on every XCD.
     const int n_tiles = nb * (nb + 1) / 2;
-    const int total = n_tiles * n_split;
-    const int per_xcd = (total + 7) / 8;
-    const int item = static_cast<int>(blockIdx.x % 8) * per_xcd + static_cast<int>(blockIdx.x / 8);
-    if (static_cast<int>(blockIdx.x / 8) >= per_xcd || item >= total) return;
+    const int total_big = n_tiles * n_full, total_small = n_tiles * (n_split - n_full);
+    const int per_big = (total_big + 7) / 8, per_small = (total_small + 7) / 8;
+    const int xcd = static_cast<int>(blockIdx.x % 8), q = static_cast<int>(blockIdx.x / 8);
+    int item;
+    if (q < per_big) {
+        item = xcd * per_big + q;
+        if (item >= total_big) return;
+    } else {
+        const int sidx = xcd * per_small + (q - per_big);
+        if (q - per_big >= per_small || sidx >= total_small) return;
+        item = total_big + sidx;
+    }
     const int split = item / n_tiles;
     int I, J;
     decode_tile(item - split * n_tiles, nb, I, J);

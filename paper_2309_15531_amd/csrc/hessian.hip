@@ -9,6 +9,8 @@
 // partials in a fixed order, mirrors the result and stores or accumulates H.
 // No atomics: the result is bit-reproducible and exactly symmetric.
 #include "common.h"
+
+#include <cmath>
 #include "mfma_tile.h"
 #include "gram_dma.h"
 
@@ -222,9 +224,52 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
             n_split = n;
         }
     }
-    const int64_t t_per_split = ((stages + n_split - 1) / n_split) * STAGE;
+    int64_t t_per_split = ((stages + n_split - 1) / n_split) * STAGE;
+    if constexpr (BT == 256) {
+        // The 256-wide kernel runs one workgroup per compute unit, 32 per XCD, each XCD working through
+        // its own share of the items, long ones first.  Equal splits leave the last round partly
+        // empty (952 items on 256 units: 3.7 rounds), so the split length is chosen by simulating
+        // that schedule for "n full splits plus a shorter remainder", the remainder's items filling
+        // the gaps of the last round.  Unit: one 32-token stage; an item costs about 12 stages of
+        // prologue and epilogue, a partial tile about 0.1 stage of write and reduction traffic.
+        if (ctx->gram_key_tokens == tokens && ctx->gram_key_tiles == n_tiles) {
+            t_per_split = ctx->gram_t_per_split;
+        } else {
+            double best = 0.0;
+            int64_t best_per = stages;
+            for (int nf = 1; nf <= 32 && nf <= stages; ++nf) {
+                for (int f = 0; f <= 10; ++f) {
+                    const int64_t per = static_cast<int64_t>(std::ceil(double(stages) / (nf + 0.1 * f)));
+                    if (per <= 0 || stages / per != nf) continue;
+                    const int64_t rem = stages - nf * per;
+                    const int64_t big = (int64_t(n_tiles) * nf + 7) / 8, small = rem > 0 ? (int64_t(n_tiles) + 7) / 8 : 0;
+                    if (big + small > 4096) continue;
+                    double slot[32] = {};                          // finish times of one XCD's 32 units
+                    auto place = [&](double dur) {
+                        int m = 0;
+                        for (int k = 1; k < 32; ++k)
+                            if (slot[k] < slot[m]) m = k;
+                        slot[m] += dur;
+                    };
+                    for (int64_t i = 0; i < big; ++i) place(double(per) + 12.0);
+                    for (int64_t i = 0; i < small; ++i) place(double(rem) + 12.0);
+                    double span = 0.0;
+                    for (int k = 0; k < 32; ++k) span = slot[k] > span ? slot[k] : span;
+                    const double cost = span + 0.10 * double(n_tiles) * double(nf + (rem > 0 ? 1 : 0));
+                    if (best == 0.0 || cost < best) {
+                        best = cost;
+                        best_per = per;
+                    }
+                }
+            }
+            t_per_split = best_per * STAGE;
+            ctx->gram_key_tokens = tokens;
+            ctx->gram_key_tiles = n_tiles;
+            ctx->gram_t_per_split = t_per_split;
+        }
+    }
     n_split = static_cast<int>((tokens + t_per_split - 1) / t_per_split);
-
+    const int n_full = static_cast<int>(tokens / t_per_split);       // splits of full length; at most one shorter
     const size_t part_bytes = size_t(n_split) * n_tiles * BT * BT * sizeof(float);
     float* part = static_cast<float*>(adadim_workspace(ctx, WS_HESS_PART, part_bytes));
     if (!part) return ADADIM_EHIP;
@@ -250,9 +295,10 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         }
         {
             ProfScope prof(ctx, "gram_tiles");
-            const unsigned grid = 8u * static_cast<unsigned>((n_tiles * n_split + 7) / 8);
+            const int per_big = (n_tiles * n_full + 7) / 8, per_small = (n_tiles * (n_split - n_full) + 7) / 8;
+            const unsigned grid = 8u * static_cast<unsigned>(per_big + per_small);
             hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2>), dim3(grid), dim3(256), dma::SMEM_BYTES, ctx->stream, X,
-                               tokens, in, ldx, nb, n_split, t_per_split, zero16, part);
+                               tokens, in, ldx, nb, n_split, n_full, t_per_split, zero16, part);
         }
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     } else {
