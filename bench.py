@@ -41,7 +41,7 @@ def gram_tiling(in_f: int):
     return bt, nb * (nb + 1) // 2
 
 
-def cpu_baseline(W, X, bits, group, budget_tokens=32768):
+def cpu_baseline(W, X, bits, group, budget_tokens=65536):
     """Times the CPU oracle, as it stands, on a bounded sample (about 10 s of host work on the
     default workload): the Gram matrix on the first `budget_tokens` tokens (scaled linearly to all
     tokens), the two quantizations and the two fp64 scorings in full."""

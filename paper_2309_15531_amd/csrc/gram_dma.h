@@ -287,6 +287,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
     };
     // Four stages per trip so that ring slots are constants; the up to three surplus stages at
     // the end multiply zeros.
+    long long dbg_w1 = 0, dbg_w2 = 0;
+    if constexpr (DBG & 8) dbg_w1 = wall_clock64();
     for (int s = 0; s < n_st; s += 4) {
         stage_body(std::integral_constant<int, 0>{});
         stage_body(std::integral_constant<int, 1>{});
@@ -294,6 +296,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
         stage_body(std::integral_constant<int, 3>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
+    if constexpr (DBG & 8) dbg_w2 = wall_clock64();
 
     // The partial tile is stored in register order: float4 number ((i*TN + j)*4 + q)*256 + thread
     // holds accumulator registers 4q..4q+3 of block (i, j), so every store instruction writes one
@@ -314,6 +317,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
             dst[0].y = static_cast<float>(wall_clock64() - dbg_w0);
             dst[0].z = __uint_as_float(static_cast<uint32_t>(dbg_w0));            // start, 100 MHz ticks
             dst[0].w = __uint_as_float(static_cast<uint32_t>(wall_clock64()));   // end
+            dst[256].x = static_cast<float>(dbg_w1 - dbg_w0);                    // prologue ticks
+            dst[256].y = static_cast<float>(dbg_w2 - dbg_w1);                    // main loop ticks
         }
     }
 }
