@@ -6,3 +6,4 @@ from .adadim_oracle import (  # noqa: F401
 )
 from .gemv_oracle import dequantize_ic, gemv_ic, abs_terms  # noqa: F401,E402
 from . import gptq_oracle  # noqa: F401,E402
+from . import meta16_oracle  # noqa: F401,E402

@@ -55,7 +55,7 @@ def _as_f32_weight(W) -> np.ndarray:
     return W.astype(_F32)  # fp16 -> fp32 is exact
 
 
-def quantize(W, dim: int, bits: int, group: int, clip: float = 1.0) -> dict:
+def quantize(W, dim: int, bits: int, group: int, clip: float = 1.0, scale_round=None) -> dict:
     """Group-wise asymmetric RTN of W[out, in] (Sec. 2.1, 3.2, 4.1).
 
     dim=OC: group (o, k) is W[o, k*g:(k+1)*g];  dim=IC: group (r, j) is
@@ -64,6 +64,10 @@ def quantize(W, dim: int, bits: int, group: int, clip: float = 1.0) -> dict:
     Returns codes u8 [out, in]; scales f32 and zeros u8 of shape
     [out, in/g] (OC) or [out/g, in] (IC); What f32 (de-quantized weight);
     dW f32 = W - What.
+
+    scale_round, if given, maps the fp32 scales of step 3 to the values a
+    storage format can hold (see meta16_oracle); the zero-point, the codes and
+    dW are then computed from the rounded scales.
     """
     w = _as_f32_weight(W)
     out_f, in_f = w.shape
@@ -97,6 +101,8 @@ def quantize(W, dim: int, bits: int, group: int, clip: float = 1.0) -> dict:
     rng = (mx - mn).astype(_F32)
     scale = (rng / qmax).astype(_F32)
     scale = np.where(rng == zero_f, _F32(1.0), scale).astype(_F32)
+    if scale_round is not None:
+        scale = np.asarray(scale_round(scale), dtype=_F32)
     # 4. zero-point
     z = np.rint(((-mn) / scale).astype(_F32)).astype(_F32)
     z = np.minimum(np.maximum(z, zero_f), qmax).astype(_F32)
