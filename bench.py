@@ -93,27 +93,38 @@ def gemv_bench(args):
     x = torch.randn(in_f, dtype=torch.float32, device="cuda", generator=g).half()
     y = torch.empty(out_f, dtype=torch.float16, device="cuda")
     packed = packs[0]
+    # the same parameters as 16-bit group words: random patterns of scales in about [0.004, 0.02]
+    meta = ((torch.randint(0x1C19 >> (bits - 1), 0x251F >> (bits - 1), (out_f // group, in_f), dtype=torch.int32,
+                           device="cuda", generator=g) << bits) | zeros.int()).to(torch.int16)
     ctx = B.Context()
+
+    def call(i):
+        if args.meta16:
+            ctx.adadim_gemv_ic_meta16(packs[i & 1], meta, x, out_f, in_f, bits, group, y)
+        else:
+            ctx.adadim_gemv_ic(packs[i & 1], scales, zeros, x, out_f, in_f, bits, group, y)
+
     for i in range(args.warmup):
-        ctx.adadim_gemv_ic(packs[i & 1], scales, zeros, x, out_f, in_f, bits, group, y)
+        call(i)
     torch.cuda.synchronize()
     ctx.adadim_profile(True)
     t0 = time.perf_counter()
     for i in range(args.steps):
-        ctx.adadim_gemv_ic(packs[i & 1], scales, zeros, x, out_f, in_f, bits, group, y)
+        call(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ctx.adadim_profile(False)
     prof = ctx.adadim_profile_read()
     kern = {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items()}
-    alg_bytes = out_f * in_f * bits / 8 + 5.0 * (out_f // group) * in_f + 2 * in_f + 2 * out_f
+    alg_bytes = out_f * in_f * bits / 8 + (2.0 if args.meta16 else 5.0) * (out_f // group) * in_f + 2 * in_f + 2 * out_f
     sec = kern["gemv_ic_tiles"] * 1e-6
     result = {
         "metric": "per-IC dequant matrix-vector product, weights/s", "value": out_f * in_f / (elapsed / args.steps),
         "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"per-IC kernel W[{out_f},{in_f}] int{bits} g{group} x[{in_f}] batch 1 (App. D shape)",
+        "config": {"workload": f"per-IC kernel W[{out_f},{in_f}] int{bits} g{group} x[{in_f}] batch 1 (App. D shape)"
+                               + (", 16-bit group words" if args.meta16 else ""),
                    "bits": bits, "group": group},
         "roofline": {"kernel": "gemv_ic_tiles", "bound": "hbm", "achieved": alg_bytes / sec / 1e9, "peak": HBM_PEAK / 1e9,
                      "unit": "GB/s", "frac": alg_bytes / sec / HBM_PEAK, "traffic": None},
@@ -188,6 +199,8 @@ def main():
     ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["gemv_ic", "gptq"])
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
+    ap.add_argument("--meta16", action="store_true",
+                    help="quantize into / multiply from the b + 16/g storage format (one 16-bit word per group)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference dispatch that scales "
@@ -231,7 +244,7 @@ def main():
     ctx = B.Context()
     hp = S.PreparedHessian(ctx, in_f)
     if len(layers) == 1:
-        ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,))
+        ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,), meta16=args.meta16)
 
         def step():
             hp.update(Xd)
@@ -353,7 +366,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}/{'+'.join(layers)} W[{out_f},{in_f}] X[{tokens},{in_f}] int{bits} "
-                               f"g{group} both dims + selection", "bits": bits, "group": group, "tokens": tokens},
+                               f"g{group} both dims + selection" + (", 16-bit group words" if args.meta16 else ""),
+                   "bits": bits, "group": group, "tokens": tokens},
         "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
         "roofline": roofline,
         "quantizer_hbm": quant,

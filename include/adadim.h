@@ -127,6 +127,29 @@ int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in,
                     uint32_t* packed);
 
 /*
+ * The same quantizer writing the storage format of b + 16/g bits per weight, the figure the
+ * paper counts with (Sec. 4.1: INT3/INT4 with groups of 128; "Avg Bits" of App. C: 4.125 for
+ * b = 4, g = 128): the packed codes plus ONE 16-bit word per group.  The paper does not say
+ * how scale and zero-point share the sixteen bits; here
+ *     word = pattern << bits | zero
+ *     pattern = the leading 16-bits bits of the 15-bit fp16 pattern of the scale (sign 0), i.e.
+ *               an unsigned float with fp16's exponent and 11-bits fraction bits;
+ *               scale = fp16(pattern << (bits-1)).
+ * The fp32 scale of adadim_quantize is rounded to fp16 (nearest even), then to the nearest
+ * pattern (ties to the even pattern; a pattern of 0 becomes 1), and zero, code, What and dW
+ * are computed from the rounded scale with the formulas above: what is stored de-quantizes
+ * to exactly the weights that dW (and so the search) saw.
+ *   bits   2, 3 or 4.
+ *   meta   u16, shape of `scales` above: [out, in/g] (OC) or [out/g, in] (IC); optional.
+ * Everything else as in adadim_quantize.
+ */
+int adadim_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t in,
+                           int dim, int bits, int group, float clip,
+                           uint8_t* codes, uint16_t* meta,
+                           void* dW, int dW_dtype, const float* colscale,
+                           uint32_t* packed);
+
+/*
  * Prepares H for scoring on the matrix cores.  With the power-of-two column
  * scales d_j ~ sqrt(H_jj):
  *   Hs     fp16 [in, in] in the scoring layout (adadim_score_elems(in, in) elements):
@@ -226,6 +249,13 @@ int adadim_gptq_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in
  */
 int adadim_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const void* x,
                    int64_t out, int64_t in, int bits, int group, void* y);
+
+/*
+ * The same product from the b + 16/g format: `meta` u16 [out/g, in] as adadim_quantize_meta16(dim = IC)
+ * writes it (8-byte aligned) in place of scales and zeros.  Half the parameter bytes of the call above.
+ */
+int adadim_gemv_ic_meta16(adadim_ctx* ctx, const uint32_t* packed, const uint16_t* meta, const void* x,
+                          int64_t out, int64_t in, int bits, int group, void* y);
 
 /*
  * Measurement aid (not part of the method): per-kernel device timings.

@@ -22,6 +22,7 @@ EXPORTS = (
     "adadim_hessian", "adadim_quantize", "adadim_hessian_prepare",
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
+    "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -79,6 +80,12 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_float,
                                     c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p]
     lib.adadim_quantize.restype = c_int
+    lib.adadim_quantize_meta16.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_float,
+                                           c_void_p, c_void_p, c_void_p, c_int, c_void_p, c_void_p]
+    lib.adadim_quantize_meta16.restype = c_int
+    lib.adadim_gemv_ic_meta16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
+                                          c_void_p]
+    lib.adadim_gemv_ic_meta16.restype = c_int
     lib.adadim_hessian_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
     lib.adadim_hessian_prepare.restype = c_int
     lib.adadim_layer_error.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
@@ -168,6 +175,13 @@ class Context:
                                               _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(dW), dW_dtype,
                                               _ptr(colscale), _ptr(packed)))
 
+    def adadim_quantize_meta16(self, W, dim: int, bits: int, group: int, clip: float = 1.0, codes=None, meta=None,
+                               dW=None, dW_dtype: int = DW_F32, colscale=None, packed=None):
+        out_f, in_f = W.shape
+        self._check(self._lib.adadim_quantize_meta16(self._h, _ptr(W), out_f, in_f, dim, bits, group, c_float(clip),
+                                                     _ptr(codes), _ptr(meta), _ptr(dW), dW_dtype, _ptr(colscale),
+                                                     _ptr(packed)))
+
     def alloc_score(self, rows: int, cols: int, device="cuda"):
         """Flat fp16 device buffer large enough for an [rows, cols] operand in the scoring layout."""
         import torch
@@ -203,6 +217,10 @@ class Context:
     def adadim_gemv_ic(self, packed, scales, zeros, x, out_f: int, in_f: int, bits: int, group: int, y):
         self._check(self._lib.adadim_gemv_ic(self._h, _ptr(packed), _ptr(scales), _ptr(zeros), _ptr(x), out_f, in_f,
                                              bits, group, _ptr(y)))
+
+    def adadim_gemv_ic_meta16(self, packed, meta, x, out_f: int, in_f: int, bits: int, group: int, y):
+        self._check(self._lib.adadim_gemv_ic_meta16(self._h, _ptr(packed), _ptr(meta), _ptr(x), out_f, in_f, bits, group,
+                                                    _ptr(y)))
 
     def adadim_gptq_prepare(self, H, perm, dead, U, percdamp: float = 0.01, act_order: bool = True):
         self._check(self._lib.adadim_gptq_prepare(self._h, _ptr(H), H.shape[0], c_float(percdamp), 1 if act_order else 0,

@@ -177,9 +177,10 @@ int adadim_hessian(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, i
     return launch_hessian(ctx, static_cast<const __half*>(X), tokens, in, ldx, H, accumulate);
 }
 
-int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
-                    float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
-                    const float* colscale, uint32_t* packed) {
+// shared by the two quantizer entry points; mfmt = 0: fp32 scales and u8 zeros, else the 16-bit group word
+static int quantize_checked(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                            float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
+                            const float* colscale, uint32_t* packed, int mfmt) {
     if (!ctx) return ADADIM_ENULL;
     if (!W) return adadim_fail(ctx, ADADIM_ENULL, "adadim_quantize: W is NULL");
     if (out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 24))
@@ -207,7 +208,24 @@ int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int
                            "adadim_quantize: W and dW must be 16-byte, codes 8-byte aligned");
     const int g = group == 0 ? (int)axis : group;
     return launch_quantize(ctx, static_cast<const __half*>(W), out, in, dim, bits, g, clip, codes, scales,
-                           zeros, dW, dW_dtype, colscale, packed);
+                           zeros, dW, dW_dtype, colscale, packed, mfmt);
+}
+
+int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                    float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
+                    const float* colscale, uint32_t* packed) {
+    return quantize_checked(ctx, W, out, in, dim, bits, group, clip, codes, scales, zeros, dW, dW_dtype, colscale,
+                            packed, 0);
+}
+
+int adadim_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                           float clip, uint8_t* codes, uint16_t* meta, void* dW, int dW_dtype,
+                           const float* colscale, uint32_t* packed) {
+    if (!ctx) return ADADIM_ENULL;
+    if (bits < 2 || bits > 4)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize_meta16: bits must be 2, 3 or 4, got %d", bits);
+    return quantize_checked(ctx, W, out, in, dim, bits, group, clip, codes, reinterpret_cast<float*>(meta), nullptr, dW,
+                            dW_dtype, colscale, packed, bits);
 }
 
 int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs, float* hmeta) {
@@ -295,26 +313,38 @@ int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev
     return ADADIM_OK;
 }
 
-int adadim_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const void* x,
-                   int64_t out, int64_t in, int bits, int group, void* y) {
+// shared by the two matrix-vector entry points; meta16: `scales` holds the 16-bit group words and zeros is unused
+static int gemv_ic_checked(adadim_ctx* ctx, const char* who, const uint32_t* packed, const void* scales, const uint8_t* zeros,
+                           const void* x, int64_t out, int64_t in, int bits, int group, void* y, bool meta16) {
     if (!ctx) return ADADIM_ENULL;
-    if (!packed || !scales || !zeros || !x || !y) return adadim_fail(ctx, ADADIM_ENULL, "adadim_gemv_ic: NULL argument");
+    if (!packed || !scales || (!meta16 && !zeros) || !x || !y) return adadim_fail(ctx, ADADIM_ENULL, "%s: NULL argument", who);
     if (out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 24))
-        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: bad shape out=%lld in=%lld", (long long)out, (long long)in);
-    if (bits < 2 || bits > 4) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: bits must be 2, 3 or 4, got %d", bits);
+        return adadim_fail(ctx, ADADIM_EINVAL, "%s: bad shape out=%lld in=%lld", who, (long long)out, (long long)in);
+    if (bits < 2 || bits > 4) return adadim_fail(ctx, ADADIM_EINVAL, "%s: bits must be 2, 3 or 4, got %d", who, bits);
     const int64_t g = group == 0 ? out : group;
     if (group < 0 || (out % g) != 0 || (g % 32) != 0)
-        return adadim_fail(ctx, ADADIM_EINVAL,
-                           "adadim_gemv_ic: group %d must be 0 or a multiple of 32 that divides out (%lld)", group,
-                           (long long)out);
-    if ((in % 4) != 0) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: in must be a multiple of 4");
-    if (g > (int64_t(1) << 30)) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gemv_ic: group too long");
-    if (!aligned16(packed) || !aligned16(scales) || (reinterpret_cast<uintptr_t>(zeros) & 3u) ||
-        (reinterpret_cast<uintptr_t>(x) & 7u) || (reinterpret_cast<uintptr_t>(y) & 1u))
-        return adadim_fail(ctx, ADADIM_EALIGN,
-                           "adadim_gemv_ic: packed and scales 16-byte, x 8-byte, zeros 4-byte, y 2-byte aligned");
+        return adadim_fail(ctx, ADADIM_EINVAL, "%s: group %d must be 0 or a multiple of 32 that divides out (%lld)", who,
+                           group, (long long)out);
+    if ((in % 4) != 0) return adadim_fail(ctx, ADADIM_EINVAL, "%s: in must be a multiple of 4", who);
+    if (g > (int64_t(1) << 30)) return adadim_fail(ctx, ADADIM_EINVAL, "%s: group too long", who);
+    if (!aligned16(packed) || (reinterpret_cast<uintptr_t>(x) & 7u) || (reinterpret_cast<uintptr_t>(y) & 1u))
+        return adadim_fail(ctx, ADADIM_EALIGN, "%s: packed must be 16-byte, x 8-byte, y 2-byte aligned", who);
+    if (meta16 ? (reinterpret_cast<uintptr_t>(scales) & 7u) != 0
+               : (!aligned16(scales) || (reinterpret_cast<uintptr_t>(zeros) & 3u) != 0))
+        return adadim_fail(ctx, ADADIM_EALIGN, "%s: scales must be 16-byte and zeros 4-byte aligned (group words: 8-byte)",
+                           who);
     return launch_gemv_ic(ctx, packed, scales, zeros, static_cast<const __half*>(x), out, in, bits, static_cast<int>(g),
-                          static_cast<__half*>(y));
+                          static_cast<__half*>(y), meta16);
+}
+
+int adadim_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const void* x,
+                   int64_t out, int64_t in, int bits, int group, void* y) {
+    return gemv_ic_checked(ctx, "adadim_gemv_ic", packed, scales, zeros, x, out, in, bits, group, y, false);
+}
+
+int adadim_gemv_ic_meta16(adadim_ctx* ctx, const uint32_t* packed, const uint16_t* meta, const void* x, int64_t out,
+                          int64_t in, int bits, int group, void* y) {
+    return gemv_ic_checked(ctx, "adadim_gemv_ic_meta16", packed, meta, nullptr, x, out, in, bits, group, y, true);
 }
 
 int adadim_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t in, float percdamp, int act_order, int32_t* perm,

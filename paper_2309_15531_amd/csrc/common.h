@@ -112,7 +112,7 @@ static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t
 // Launchers implemented in the .hip files.  All validate nothing: the API layer does.
 int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
                     float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
-                    const float* colscale, uint32_t* packed);
+                    const float* colscale, uint32_t* packed, int mfmt);
 int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, int dim, int bits,
                 uint32_t* packed);
 int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
@@ -126,5 +126,5 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
 int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
                          const float* U, const int32_t* perm, const uint8_t* dead, const float* st_scales,
                          const uint8_t* st_zeros, uint8_t* codes, float* scales_out, uint8_t* zeros_out, float* dW);
-int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const __half* x,
-                   int64_t out, int64_t in, int bits, int g, __half* y);
+int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const void* scales, const uint8_t* zeros, const __half* x,
+                   int64_t out, int64_t in, int bits, int g, __half* y, bool meta16);

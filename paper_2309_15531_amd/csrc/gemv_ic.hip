@@ -103,9 +103,12 @@ __device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (
     }
 }
 
-template <int PB>
+// M16: the group parameters come as one 16-bit word per (group, column) in `scales` (the
+// fp16 pattern of the scale without its sign bit and its PB-1 lowest bits, above the PB-bit
+// zero-point) instead of an fp32 scale and a u8 zero-point.
+template <int PB, bool M16>
 __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* __restrict__ packed,
-                                                               const float* __restrict__ scales,
+                                                               const void* __restrict__ scales,
                                                                const uint8_t* __restrict__ zeros,
                                                                const __half* __restrict__ x, int64_t out, int64_t in,
                                                                int g, int64_t n_words, float* __restrict__ part) {
@@ -126,22 +129,42 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
         Words<PB> wd[4];
         float4 s4;
         uint32_t z4;
+        uint2 m4;
         uint2 xr;
     };
     auto fetch = [&](Step& st, int64_t j0) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) st.wd[c] = load_words<PB>(wp + (j0 + c) * n_words);
-        st.s4 = *reinterpret_cast<const float4*>(scales + r * in + j0);
-        st.z4 = *reinterpret_cast<const uint32_t*>(zeros + r * in + j0);
+        if constexpr (M16) {
+            st.m4 = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(scales) + r * in + j0);
+        } else {
+            st.s4 = *reinterpret_cast<const float4*>(static_cast<const float*>(scales) + r * in + j0);
+            st.z4 = *reinterpret_cast<const uint32_t*>(zeros + r * in + j0);
+        }
         st.xr = *reinterpret_cast<const uint2*>(x + j0);
     };
     auto consume = [&](const Step& st) {
         const float2 x01 = __half22float2(*reinterpret_cast<const __half2*>(&st.xr.x));
         const float2 x23 = __half22float2(*reinterpret_cast<const __half2*>(&st.xr.y));
-        const float a[4] = {st.s4.x * x01.x, st.s4.y * x01.y, st.s4.z * x23.x, st.s4.w * x23.y};
+        float a[4], z[4];
+        if constexpr (M16) {
+            // both words of a register at once: shifted right by one, the kept pattern bits of each
+            // word land on their fp16 positions and the mask clears what crossed over
+            constexpr uint32_t KEEP = (0x7FFFu & ~((1u << (PB - 1)) - 1u)) * 0x10001u, ZM = (1u << PB) - 1u;
+            const uint32_t h01 = (st.m4.x >> 1) & KEEP, h23 = (st.m4.y >> 1) & KEEP;
+            const float2 s01 = __half22float2(*reinterpret_cast<const __half2*>(&h01));
+            const float2 s23 = __half22float2(*reinterpret_cast<const __half2*>(&h23));
+            a[0] = s01.x * x01.x; a[1] = s01.y * x01.y; a[2] = s23.x * x23.x; a[3] = s23.y * x23.y;
+            z[0] = static_cast<float>(st.m4.x & ZM); z[1] = static_cast<float>((st.m4.x >> 16) & ZM);
+            z[2] = static_cast<float>(st.m4.y & ZM); z[3] = static_cast<float>((st.m4.y >> 16) & ZM);
+        } else {
+            a[0] = st.s4.x * x01.x; a[1] = st.s4.y * x01.y; a[2] = st.s4.z * x23.x; a[3] = st.s4.w * x23.y;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) z[c] = ubyte(st.z4, c);
+        }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            zsum = fmaf(a[c], ubyte(st.z4, c), zsum);
+            zsum = fmaf(a[c], z[c], zsum);
             accumulate<PB>(st.wd[c], a[c], acc);
         }
     };
@@ -198,8 +221,8 @@ __global__ __launch_bounds__(256) void gemv_ic_finish(const float* __restrict__ 
 
 }  // namespace
 
-int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales, const uint8_t* zeros, const __half* x,
-                   int64_t out, int64_t in, int bits, int g, __half* y) {
+int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const void* scales, const uint8_t* zeros, const __half* x,
+                   int64_t out, int64_t in, int bits, int g, __half* y, bool meta16) {
     const int n_chunks = static_cast<int>((in + GV_COLS_PER_BLOCK - 1) / GV_COLS_PER_BLOCK);
     const int n_tiles = static_cast<int>((out + GV_OUT_PER_BLOCK - 1) / GV_OUT_PER_BLOCK);
     float* part = static_cast<float*>(adadim_workspace(ctx, WS_GEMV_PART, size_t(n_chunks) * size_t(out) * sizeof(float)));
@@ -208,9 +231,15 @@ int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const float* scales,
     const dim3 grid(static_cast<unsigned>(n_tiles), static_cast<unsigned>(n_chunks));
     {
         ProfScope prof(ctx, "gemv_ic_tiles");
-#define GV_GO(PB)                                                                                              \
-    hipLaunchKernelGGL(gemv_ic_tiles<PB>, grid, dim3(64 * GV_WAVES), 0, ctx->stream, packed, scales, zeros, x, out, in, \
-                       g, n_words, part)
+#define GV_GO(PB)                                                                                                   \
+    do {                                                                                                            \
+        if (meta16)                                                                                                 \
+            hipLaunchKernelGGL((gemv_ic_tiles<PB, true>), grid, dim3(64 * GV_WAVES), 0, ctx->stream, packed, scales, \
+                               zeros, x, out, in, g, n_words, part);                                                \
+        else                                                                                                        \
+            hipLaunchKernelGGL((gemv_ic_tiles<PB, false>), grid, dim3(64 * GV_WAVES), 0, ctx->stream, packed, scales, \
+                               zeros, x, out, in, g, n_words, part);                                                \
+    } while (0)
         switch (bits) {
             case 2: GV_GO(2); break;
             case 3: GV_GO(3); break;

@@ -22,7 +22,35 @@ struct GroupParams {
     float zero;
 };
 
-__device__ __forceinline__ GroupParams group_params(float mn, float mx, float clip, float qmax) {
+// 16-bit group word (mfmt = the code width b, 0 = fp32 scale and u8 zero kept apart): the scale
+// is rounded to fp16 (nearest even) and that to the 16-b leading bits of its 15-bit pattern
+// (nearest even on the pattern: an unsigned float with fp16's exponent and 11-b fraction bits);
+// a pattern of 0 becomes 1, the format's smallest value.  Everything after it (zero-point,
+// codes, dW) is computed from the rounded scale, so what is stored de-quantizes exactly as scored.
+__device__ __forceinline__ uint32_t scale_pattern(float s, int b) {
+    const uint32_t h = __half_as_ushort(__float2half_rn(s));
+    const int d = b - 1;
+    const uint32_t q = (h + ((1u << d) >> 1) - 1u + ((h >> d) & 1u)) >> d;
+    return q ? q : 1u;
+}
+__device__ __forceinline__ float round_scale(float s, int b) {
+    return __half2float(__ushort_as_half(static_cast<unsigned short>(scale_pattern(s, b) << (b - 1))));
+}
+// writes a group's parameters: fp32 scale and u8 zero-point, or the 16-bit word (pattern << b | zero)
+// into `scales` taken as an array of u16
+__device__ __forceinline__ void store_params(float* __restrict__ scales, uint8_t* __restrict__ zeros, int64_t i, float s,
+                                             float z, int mfmt) {
+    if (mfmt) {
+        if (scales)
+            reinterpret_cast<uint16_t*>(scales)[i] =
+                static_cast<uint16_t>((scale_pattern(s, mfmt) << mfmt) | static_cast<uint32_t>(z));
+    } else {
+        if (scales) scales[i] = s;
+        if (zeros) zeros[i] = static_cast<uint8_t>(z);
+    }
+}
+
+__device__ __forceinline__ GroupParams group_params(float mn, float mx, float clip, float qmax, int mfmt) {
     mx = fmaxf(mx, 0.0f);
     mn = fminf(mn, 0.0f);
     mx = clip * mx;
@@ -30,6 +58,7 @@ __device__ __forceinline__ GroupParams group_params(float mn, float mx, float cl
     const float range = mx - mn;
     float scale = range / qmax;
     if (range == 0.0f) scale = 1.0f;
+    if (mfmt) scale = round_scale(scale, mfmt);
     float z = rintf((-mn) / scale);
     z = fminf(fmaxf(z, 0.0f), qmax);
     return {scale, z};
@@ -97,7 +126,7 @@ __device__ __forceinline__ void store_dw1(void* dW, int dW_dtype, const float* _
 
 // per-OC, any group length: one wavefront per group, element-wise accesses.
 __global__ __launch_bounds__(256) void quant_oc_generic(const __half* __restrict__ W, int64_t n_groups, int g,
-                                                        int64_t out, int64_t in, float clip, float qmax,
+                                                        int64_t out, int64_t in, float clip, float qmax, int mfmt,
                                                         uint8_t* __restrict__ codes, float* __restrict__ scales,
                                                         uint8_t* __restrict__ zeros, void* __restrict__ dW,
                                                         int dW_dtype, const float* __restrict__ colscale) {
@@ -116,10 +145,9 @@ __global__ __launch_bounds__(256) void quant_oc_generic(const __half* __restrict
         mn = fminf(mn, __shfl_xor(mn, m, 64));
         mx = fmaxf(mx, __shfl_xor(mx, m, 64));
     }
-    const GroupParams gp = group_params(mn, mx, clip, qmax);
+    const GroupParams gp = group_params(mn, mx, clip, qmax, mfmt);
     if (lane == 0) {
-        if (scales) scales[grp] = gp.scale;
-        if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
+        store_params(scales, zeros, grp, gp.scale, gp.zero, mfmt);
     }
     for (int i = lane; i < g; i += 64) {
         const float w = __half2float(W[base + i]);
@@ -157,7 +185,7 @@ __device__ __forceinline__ float pinned_div(float a, float b) {
 // range, see fastdiv_check.cpp), -mn/scale through the reciprocal of the scale when
 // mn is an fp16 value (clip == 1).  The plain divisions sit behind wave-uniform
 // branches so that they cost nothing when no lane needs them.
-__device__ __forceinline__ GroupParamsR group_params_r(float mn, float mx, float clip, float qmax, float rqmax) {
+__device__ __forceinline__ GroupParamsR group_params_r(float mn, float mx, float clip, float qmax, float rqmax, int mfmt) {
     mx = fmaxf(mx, 0.0f);
     mn = fminf(mn, 0.0f);
     mx = clip * mx;
@@ -166,6 +194,7 @@ __device__ __forceinline__ GroupParamsR group_params_r(float mn, float mx, float
     float scale = fastdiv(range, qmax, rqmax);
     if (__any(!(range >= 8.6736174e-19f) && range != 0.0f)) scale = pinned_div(range, qmax);   // below 2^-60: tiny clip
     if (range == 0.0f) scale = 1.0f;
+    if (mfmt) scale = round_scale(scale, mfmt);
     const float rcp = 1.0f / scale;
     const bool fast = fastdiv_ok(scale);
     float zq = fastdiv(-mn, scale, rcp);
@@ -219,7 +248,7 @@ __device__ __forceinline__ void pack8_store(const float (&q)[8], int64_t c, bool
 // once, and a second sweep (served by L2) quantizes.
 template <int VEC>
 __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ W, int64_t out, int64_t in, int g,
-                                                     float clip, float qmax, uint8_t* __restrict__ codes,
+                                                     float clip, float qmax, int mfmt, uint8_t* __restrict__ codes,
                                                      float* __restrict__ scales, uint8_t* __restrict__ zeros,
                                                      void* __restrict__ dW, int dW_dtype,
                                                      const float* __restrict__ colscale) {
@@ -270,14 +299,13 @@ __global__ __launch_bounds__(256) void quant_ic_tile(const __half* __restrict__ 
             a = fminf(a, s_mn[y][cidx]);
             b = fmaxf(b, s_mx[y][cidx]);
         }
-        const GroupParams gp = group_params(a, b, clip, qmax);
+        const GroupParams gp = group_params(a, b, clip, qmax, mfmt);
         s_scale[cidx] = gp.scale;
         s_zero[cidx] = gp.zero;
         const int64_t col = int64_t(blockIdx.x) * COLS + cidx;
         if (col < in) {
             const int64_t gi = int64_t(blockIdx.y) * in + col;
-            if (scales) scales[gi] = gp.scale;
-            if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
+            store_params(scales, zeros, gi, gp.scale, gp.zero, mfmt);
         }
     }
     __syncthreads();
@@ -445,7 +473,7 @@ __device__ __forceinline__ uint32_t cluster_min2(uint32_t m) {
 // contiguous kilobyte instead of 16 scattered pieces.
 template <int LPG, int PB, bool SCALED>
 __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t out, int chunks_per_row,
-                                                     float clip, float qmax, float rqmax,
+                                                     float clip, float qmax, float rqmax, int mfmt,
                                                      uint8_t* __restrict__ codes, float* __restrict__ scales,
                                                      uint8_t* __restrict__ zeros, void* __restrict__ dW,
                                                      int dW_dtype, const float* __restrict__ colscale,
@@ -488,7 +516,7 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
     if constexpr (LPG >= 4) {
         const int mine = lane & 3;
         const uint32_t msel = (mine & 2) ? ((mine & 1) ? m2[3] : m2[2]) : ((mine & 1) ? m2[1] : m2[0]);
-        const GroupParamsR gp = group_params_r(half_of(msel, 0), -half_of(msel, 1), clip, qmax, rqmax);
+        const GroupParamsR gp = group_params_r(half_of(msel, 0), -half_of(msel, 1), clip, qmax, rqmax, mfmt);
         slow = __any(!gp.fast);
         sc_u[0] = dpp_f<0x00>(gp.scale); zp_u[0] = dpp_f<0x00>(gp.zero); rc_u[0] = dpp_f<0x00>(gp.rcp);
         sc_u[1] = dpp_f<0x55>(gp.scale); zp_u[1] = dpp_f<0x55>(gp.zero); rc_u[1] = dpp_f<0x55>(gp.rcp);
@@ -498,7 +526,7 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
         bool fast = true;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const GroupParamsR gp = group_params_r(half_of(m2[u], 0), -half_of(m2[u], 1), clip, qmax, rqmax);
+            const GroupParamsR gp = group_params_r(half_of(m2[u], 0), -half_of(m2[u], 1), clip, qmax, rqmax, mfmt);
             sc_u[u] = gp.scale; zp_u[u] = gp.zero; rc_u[u] = gp.rcp;
             fast = fast && gp.fast;
         }
@@ -543,8 +571,7 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
         if (!valid) continue;
         if ((cc & (LPG - 1)) == 0) {
             const int64_t grp = c / LPG;
-            if (scales) scales[grp] = sc_u[u];
-            if (zeros) zeros[grp] = static_cast<uint8_t>(zp_u[u]);
+            store_params(scales, zeros, grp, sc_u[u], zp_u[u], mfmt);
         }
         if (codes) {
             uint32_t lo = 0, hi = 0;
@@ -590,7 +617,7 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
 // holds all 32 codes of column l, and that lane shifts them into place and writes the PB words.
 template <int U, int RW, bool SCALED, int PB>
 __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
-    const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax,
+    const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax, int mfmt,
     uint8_t* __restrict__ codes, float* __restrict__ scales, uint8_t* __restrict__ zeros, void* __restrict__ dW,
     int dW_dtype, const float* __restrict__ colscale, uint32_t* __restrict__ packed, int64_t n_words) {
     constexpr int CSW = RW <= 4 ? 4 / RW : 1;                // 64-column sets per block
@@ -649,12 +676,11 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
         mnp = (rl & 4) ? ((rl & 2) ? mn2[3] : mn2[2]) : ((rl & 2) ? mn2[1] : mn2[0]);
         mxp = (rl & 4) ? ((rl & 2) ? mx2[3] : mx2[2]) : ((rl & 2) ? mx2[1] : mx2[0]);
     }
-    const GroupParamsR gp = group_params_r(half_of(mnp, rl & 1), half_of(mxp, rl & 1), clip, qmax, rqmax);
+    const GroupParamsR gp = group_params_r(half_of(mnp, rl & 1), half_of(mxp, rl & 1), clip, qmax, rqmax, mfmt);
     const bool slow = __any(!gp.fast);
     if (col_ok && rw == 0) {
         const int64_t gi = int64_t(blockIdx.y) * in + col0 + rl;
-        if (scales) scales[gi] = gp.scale;
-        if (zeros) zeros[gi] = static_cast<uint8_t>(gp.zero);
+        store_params(scales, zeros, gi, gp.scale, gp.zero, mfmt);
     }
     const bool do_pack = PB != 0 && packed != nullptr;
     if (!codes && !dW && !do_pack) return;
@@ -848,7 +874,7 @@ __global__ __launch_bounds__(256) void wide_minmax_ic(const __half* __restrict__
 // one thread per group: pieces -> parameters.  piece p of group grp is part[grp*ps_g + p*ps_p + off(grp)]
 // (per-OC: grp*n_pieces + p; per-IC: (rg*n_pieces + p)*in + col)
 __global__ __launch_bounds__(256) void wide_params(const uint32_t* __restrict__ part, int64_t n_groups, int n_pieces,
-                                                   int64_t in, int is_ic, float clip, float qmax, float rqmax,
+                                                   int64_t in, int is_ic, float clip, float qmax, float rqmax, int mfmt,
                                                    float* __restrict__ par, float* __restrict__ scales,
                                                    uint8_t* __restrict__ zeros) {
     const int64_t grp = int64_t(blockIdx.x) * 256 + threadIdx.x;
@@ -859,13 +885,12 @@ __global__ __launch_bounds__(256) void wide_params(const uint32_t* __restrict__ 
         const int64_t step = is_ic ? in : 1;
         for (int p = 0; p < n_pieces; ++p) m = pk_min(m, part[base + p * step]);
     }
-    const GroupParamsR gp = group_params_r(half_of(m, 0), -half_of(m, 1), clip, qmax, rqmax);
+    const GroupParamsR gp = group_params_r(half_of(m, 0), -half_of(m, 1), clip, qmax, rqmax, mfmt);
     if (!ok) return;
     par[grp] = gp.scale;
     par[n_groups + grp] = gp.zero;
     par[2 * n_groups + grp] = gp.rcp;
-    if (scales) scales[grp] = gp.scale;
-    if (zeros) zeros[grp] = static_cast<uint8_t>(gp.zero);
+    store_params(scales, zeros, grp, gp.scale, gp.zero, mfmt);
 }
 
 // element-wise pass: one thread per 16-byte chunk of W
@@ -978,7 +1003,7 @@ __global__ __launch_bounds__(256) void pack_words(const uint8_t* __restrict__ co
 }
 
 template <int LPG>
-void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
+void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int mfmt, int pb,
                      uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
                      const float* colscale, uint32_t* packed) {
     const uint4* W4 = reinterpret_cast<const uint4*>(W);
@@ -989,10 +1014,10 @@ void launch_oc_lanes(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, 
     do {                                                                                                           \
         if (dW && dW_dtype == ADADIM_DW_F16_SCALED)                                                                \
             hipLaunchKernelGGL((quant_oc_fast<LPG, PB, true>), blocks, dim3(256), 0, ctx->stream, W4, out, cpr,    \
-                               clip, qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed);     \
+                               clip, qmax, 1.0f / qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale, packed);     \
         else                                                                                                       \
             hipLaunchKernelGGL((quant_oc_fast<LPG, PB, false>), blocks, dim3(256), 0, ctx->stream, W4, out, cpr,   \
-                               clip, qmax, 1.0f / qmax, codes, scales, zeros, dW, dW_dtype, colscale, packed);     \
+                               clip, qmax, 1.0f / qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale, packed);     \
     } while (0)
     switch (pb) {
         case 2: OC_GO(2); break;
@@ -1009,7 +1034,7 @@ constexpr bool ic_stream_pack_ok(int lpg, int pb) { return lpg >= 4 && (pb == 2 
 
 // streaming per-IC kernel for a group of 8*LPG rows; pb != 0 also writes the packed stream
 template <int LPG>
-void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int pb,
+void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, float clip, float qmax, int mfmt, int pb,
                       uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale,
                       uint32_t* packed, int64_t n_words) {
     const bool scaled = dW && dW_dtype == ADADIM_DW_F16_SCALED;
@@ -1019,7 +1044,7 @@ void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in,
     ProfScope prof(ctx, "quant_ic");
 #define IC_S(S, PB)                                                                                             \
     hipLaunchKernelGGL((quant_ic_stream<U, RW, S, PB>), grid, dim3(TH), 0, ctx->stream, W, out, in, clip, qmax,  \
-                       rq, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
+                       rq, mfmt, codes, scales, zeros, dW, dW_dtype, colscale, packed, n_words)
     if constexpr (LPG >= 4) {
         if (scaled) {
             switch (pb) {
@@ -1042,7 +1067,7 @@ void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in,
 }
 
 // wide-group path (see wide_minmax_oc): in % 8 == 0; per-OC also g % 8 == 0
-int launch_wide(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int g, float clip, float qmax,
+int launch_wide(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int g, float clip, float qmax, int mfmt,
                 uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale) {
     const bool ic = dim == ADADIM_DIM_IC;
     const int64_t n_groups = ic ? (out / g) * in : out * (in / g);
@@ -1061,7 +1086,7 @@ int launch_wide(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int d
                            reinterpret_cast<const uint4*>(W), n_groups, g / 8, n_pieces, part);
     }
     hipLaunchKernelGGL(wide_params, dim3(static_cast<unsigned>((n_groups + 255) / 256)), dim3(256), 0, ctx->stream, part,
-                       n_groups, n_pieces, in, ic ? 1 : 0, clip, qmax, 1.0f / qmax, par, scales, zeros);
+                       n_groups, n_pieces, in, ic ? 1 : 0, clip, qmax, 1.0f / qmax, mfmt, par, scales, zeros);
     if (codes || dW) {
         const unsigned blocks = static_cast<unsigned>((out * cpr + 255) / 256);
         const bool scaled = dW && dW_dtype == ADADIM_DW_F16_SCALED;
@@ -1097,7 +1122,7 @@ int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, 
 
 int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
                     float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
-                    const float* colscale, uint32_t* packed) {
+                    const float* colscale, uint32_t* packed, int mfmt) {
     const float qmax = static_cast<float>((1 << bits) - 1);
     const bool vec = (in % 8) == 0;
     const int lpg = g / 8;
@@ -1117,13 +1142,13 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             const int pb = fused_pack ? bits : 0;
             uint32_t* pk = fused_pack ? packed : nullptr;
             switch (lpg) {
-#define OC_CASE(n) case n: launch_oc_lanes<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk); break;
+#define OC_CASE(n) case n: launch_oc_lanes<n>(ctx, W, out, in, clip, qmax, mfmt, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk); break;
                 OC_CASE(1) OC_CASE(2) OC_CASE(4) OC_CASE(8) OC_CASE(16) OC_CASE(32) OC_CASE(64)
 #undef OC_CASE
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_fast");
         } else if (vec && (g % 8) == 0 && g >= 512 && out * (in / g) <= (int64_t(1) << 30)) {
-            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale);
             if (rc != ADADIM_OK) return rc;
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_wide");
         } else {
@@ -1132,7 +1157,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             {
                 ProfScope prof(ctx, "quant_oc_generic");
                 hipLaunchKernelGGL(quant_oc_generic, dim3(blocks), dim3(256), 0, ctx->stream, W, n_groups, g, out, in,
-                                   clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+                                   clip, qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale);
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_generic");
         }
@@ -1147,7 +1172,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             switch (lpg) {
 #define IC_CASE(n)                                                                                              \
     case n:                                                                                                     \
-        launch_ic_stream<n>(ctx, W, out, in, clip, qmax, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk,  \
+        launch_ic_stream<n>(ctx, W, out, in, clip, qmax, mfmt, pb, codes, scales, zeros, dW, dW_dtype, colscale, pk,  \
                             n_words);                                                                           \
         break;
                 IC_CASE(1) IC_CASE(2) IC_CASE(4) IC_CASE(8) IC_CASE(16) IC_CASE(32)
@@ -1155,14 +1180,14 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_stream");
         } else if (vec && g >= 256 && row_groups * ((g + 63) / 64) <= 65535) {
-            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, codes, scales, zeros, dW, dW_dtype, colscale);
+            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale);
             if (rc != ADADIM_OK) return rc;
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_wide");
         } else if (vec) {
             dim3 grid(static_cast<unsigned>((in + 255) / 256), static_cast<unsigned>(row_groups));
             {
                 ProfScope prof(ctx, "quant_ic_tile");
-                hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, out, in, g, clip, qmax, codes,
+                hipLaunchKernelGGL(quant_ic_tile<8>, grid, dim3(256), 0, ctx->stream, W, out, in, g, clip, qmax, mfmt, codes,
                                    scales, zeros, dW, dW_dtype, colscale);
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");
@@ -1170,7 +1195,7 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
             dim3 grid(static_cast<unsigned>((in + 31) / 32), static_cast<unsigned>(row_groups));
             {
                 ProfScope prof(ctx, "quant_ic_tile");
-                hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, out, in, g, clip, qmax, codes,
+                hipLaunchKernelGGL(quant_ic_tile<1>, grid, dim3(256), 0, ctx->stream, W, out, in, g, clip, qmax, mfmt, codes,
                                    scales, zeros, dW, dW_dtype, colscale);
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_ic_tile");

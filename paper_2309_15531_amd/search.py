@@ -47,11 +47,16 @@ class LayerSearch:
 
     Candidates are scored in batches of up to `batch` (one adadim_layer_error_batch call each).
     With at most `batch` candidates and keep_winner, every candidate's packed codes, scales and
-    zeros are written while it is scored, so the winner needs no second quantization."""
+    zeros are written while it is scored, so the winner needs no second quantization.
+
+    meta16: candidates are quantized into the b + 16/g storage format (adadim_quantize_meta16), so
+    the losses are those of the weights that will be stored; the winner's group words are in
+    self.meta (uint16 bits in an int16 tensor) and self.scales / self.zeros stay None."""
 
     def __init__(self, ctx: B.Context, out_f: int, in_f: int, bits: int, group: int, clips=(1.0,),
-                 keep_winner: bool = True, batch: int = 8, device="cuda"):
+                 keep_winner: bool = True, batch: int = 8, device="cuda", meta16: bool = False):
         self.ctx, self.out_f, self.in_f, self.bits, self.group = ctx, out_f, in_f, bits, group
+        self.meta16 = meta16
         self.clips = [float(np.float32(c)) for c in clips]
         self.cands = [(d, c) for d in (B.DIM_OC, B.DIM_IC) for c in self.clips]
         self.batch = max(1, min(batch, 8, len(self.cands)))
@@ -62,15 +67,18 @@ class LayerSearch:
         g_oc = in_f if group == 0 else group
         g_ic = out_f if group == 0 else group
         self.meta_shape = {B.DIM_OC: (out_f, in_f // g_oc), B.DIM_IC: (out_f // g_ic, in_f)}
-        self.scales = self.zeros = self.packed = None
+        self.scales = self.zeros = self.packed = self.meta = None
         if keep_winner:
             n_meta = max(out_f * (in_f // g_oc), (out_f // g_ic) * in_f)
             words = max(out_f * ((in_f * bits + 31) // 32), in_f * ((out_f * bits + 31) // 32))
             # one output set per candidate when they all fit in one batch, else one set for the winner
             self.inline = len(self.cands) <= self.batch
             n_sets = len(self.cands) if self.inline else 1
-            self._scales = [torch.empty(n_meta, dtype=torch.float32, device=device) for _ in range(n_sets)]
-            self._zeros = [torch.empty(n_meta, dtype=torch.uint8, device=device) for _ in range(n_sets)]
+            if meta16:
+                self._meta = [torch.empty(n_meta, dtype=torch.int16, device=device) for _ in range(n_sets)]
+            else:
+                self._scales = [torch.empty(n_meta, dtype=torch.float32, device=device) for _ in range(n_sets)]
+                self._zeros = [torch.empty(n_meta, dtype=torch.uint8, device=device) for _ in range(n_sets)]
             self._packed = [torch.empty(words, dtype=torch.int32, device=device) for _ in range(n_sets)]
         else:
             self.inline = False
@@ -80,13 +88,21 @@ class LayerSearch:
         for c0 in range(0, len(self.cands), self.batch):
             chunk = self.cands[c0:c0 + self.batch]
             for k, (dim, clip) in enumerate(chunk):
-                extra = {}
-                if self.inline:
-                    extra = dict(scales=self._scales[c0 + k], zeros=self._zeros[c0 + k], packed=self._packed[c0 + k])
-                self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, dW=self.dWs[k],
-                                         dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale, **extra)
+                self._quantize(W, dim, clip, c0 + k if self.inline else None, dW=self.dWs[k],
+                               dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
             self.ctx.adadim_layer_error_batch(self.dWs[:len(chunk)], B.DW_F16_SCALED, hp.Hs, hp.hmeta,
                                               self.losses[c0:c0 + len(chunk)], shape=(self.out_f, self.in_f))
+
+    def _quantize(self, W, dim, clip, out_set, **kw):
+        """One candidate; out_set names the output set that receives its parameters and packed codes."""
+        if self.meta16:
+            if out_set is not None:
+                kw.update(meta=self._meta[out_set], packed=self._packed[out_set])
+            self.ctx.adadim_quantize_meta16(W, dim, self.bits, self.group, clip, **kw)
+        else:
+            if out_set is not None:
+                kw.update(scales=self._scales[out_set], zeros=self._zeros[out_set], packed=self._packed[out_set])
+            self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, **kw)
 
     def run(self, W, hp: PreparedHessian):
         """Whole search for one layer: returns (best index, dim, clip); with keep_winner the
@@ -96,10 +112,13 @@ class LayerSearch:
         dim, clip = self.cands[best]
         if self.keep_winner:
             k = best if self.inline else 0
-            self.scales, self.zeros, self.packed = self._scales[k], self._zeros[k], self._packed[k]
+            self.packed = self._packed[k]
+            if self.meta16:
+                self.meta = self._meta[k]
+            else:
+                self.scales, self.zeros = self._scales[k], self._zeros[k]
             if not self.inline:
-                self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, scales=self.scales,
-                                         zeros=self.zeros, packed=self.packed)
+                self._quantize(W, dim, clip, 0)
         return best, dim, clip
 
 

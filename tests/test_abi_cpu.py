@@ -25,7 +25,7 @@ def ctx():
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "adadim.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(adadim_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(adadim_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_exported(ctx):
@@ -111,6 +111,15 @@ def test_gemv_validation(ctx):
     assert gv(A16, A16, A16, A16, 64, 62, 4, 32, A16) == B.EINVAL          # in % 4
     assert gv(ctypes.c_void_p(A16.value + 4), A16, A16, A16, 64, 64, 4, 32, A16) == B.EALIGN
     assert "adadim_gemv_ic" in ctx.last_error()
+    gm = lambda *a: ctx.raw("adadim_gemv_ic_meta16", *a)
+    assert gm(A16, None, A16, 64, 64, 4, 32, A16) == B.ENULL
+    assert gm(A16, A16, A16, 64, 64, 5, 32, A16) == B.EINVAL
+    assert gm(A16, ctypes.c_void_p(A16.value + 4), A16, 64, 64, 4, 32, A16) == B.EALIGN
+    assert "adadim_gemv_ic_meta16" in ctx.last_error()
+    qm = lambda *a: ctx.raw("adadim_quantize_meta16", *a)
+    assert qm(A16, 64, 64, 0, 5, 32, ctypes.c_float(1.0), None, A16, None, 0, None, None) == B.EINVAL   # 2, 3 or 4 bits
+    assert qm(None, 64, 64, 0, 4, 32, ctypes.c_float(1.0), None, A16, None, 0, None, None) == B.ENULL
+    assert qm(A16, 64, 64, 1, 4, 48, ctypes.c_float(1.0), None, A16, None, 0, None, None) == B.EINVAL
     assert ctx._lib.adadim_score_elems(300, 64) == 512 * 64 and ctx._lib.adadim_score_elems(300, 40) == 300 * 40
 
 
