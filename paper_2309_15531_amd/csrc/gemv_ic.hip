@@ -17,9 +17,16 @@
 // fences, which write back and invalidate the XCD's whole L2 each time: 3x slower overall.)
 #include "common.h"
 
+#include <algorithm>
+
 namespace {
 
-constexpr int GV_WAVES = 8, GV_COLS_PER_WAVE = 64, GV_COLS_PER_BLOCK = GV_WAVES * GV_COLS_PER_WAVE, GV_OUT_PER_BLOCK = 64 * 32;
+constexpr int GV_WAVES = 8, GV_OUT_PER_BLOCK = 64 * 32;
+// Two blocks fit a compute unit (registers and LDS), 512 on the chip.  The columns are dealt to
+// blocks so that one launch is a whole number of such rounds as nearly as can be: a grid a little
+// larger than that would run a second, mostly empty round (576 blocks took two rounds for the work
+// of 1.1), and the kernel is short enough for that to cost a third of its time.
+constexpr int GV_BLOCK_SLOTS = 512, GV_MIN_COLS_PER_WAVE = 32;
 
 template <int PB>
 struct Words {
@@ -117,8 +124,9 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
     const int64_t o_lane = int64_t(blockIdx.x) * GV_OUT_PER_BLOCK + lane * 32;
     const bool valid = o_lane < out;                         // out % 32 == 0: a lane's outputs are inside together
     const int64_t r = valid ? o_lane / g : 0;
-    const int64_t j_begin = int64_t(blockIdx.y) * GV_COLS_PER_BLOCK + wave * GV_COLS_PER_WAVE;
-    const int64_t j_end = min(in, j_begin + GV_COLS_PER_WAVE);
+    // the in/4 column quads split evenly over the gridDim.y * 8 waves that share this output tile
+    const int64_t n_wv = int64_t(gridDim.y) * GV_WAVES, wv = int64_t(blockIdx.y) * GV_WAVES + wave, quads = in >> 2;
+    const int64_t j_begin = (wv * quads / n_wv) << 2, j_end = ((wv + 1) * quads / n_wv) << 2;
     const uint32_t* wp = packed + (valid ? (o_lane >> 5) * PB : 0);
     float acc[32];
 #pragma unroll
@@ -223,8 +231,11 @@ __global__ __launch_bounds__(256) void gemv_ic_finish(const float* __restrict__ 
 
 int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const void* scales, const uint8_t* zeros, const __half* x,
                    int64_t out, int64_t in, int bits, int g, __half* y, bool meta16) {
-    const int n_chunks = static_cast<int>((in + GV_COLS_PER_BLOCK - 1) / GV_COLS_PER_BLOCK);
     const int n_tiles = static_cast<int>((out + GV_OUT_PER_BLOCK - 1) / GV_OUT_PER_BLOCK);
+    // whole rounds of GV_BLOCK_SLOTS blocks, each wave keeping at least GV_MIN_COLS_PER_WAVE columns
+    const int64_t max_chunks = std::max<int64_t>(1, in / (GV_WAVES * GV_MIN_COLS_PER_WAVE));
+    const int64_t rounds = (n_tiles + GV_BLOCK_SLOTS - 1) / GV_BLOCK_SLOTS;
+    const int n_chunks = static_cast<int>(std::min<int64_t>(max_chunks, std::max<int64_t>(1, rounds * GV_BLOCK_SLOTS / n_tiles)));
     float* part = static_cast<float*>(adadim_workspace(ctx, WS_GEMV_PART, size_t(n_chunks) * size_t(out) * sizeof(float)));
     if (!part) return ADADIM_EHIP;
     const int64_t n_words = out * bits / 32;
