@@ -6,7 +6,8 @@ calibration activations, its preparation, quantize + score for both grouping
 dimensions, selection, and the winner's packed codes / scales / zeros.
 Prints ONE JSON line (see README / DESIGN for the fields).
 
-    python bench.py [--steps K] [--warmup W] [--workload q_proj|down_proj|gate_proj|toy]
+    python bench.py [--steps K] [--warmup W] [--workload q_proj|down_proj|gate_proj|qkv|clip_grid|toy|gemv_ic|gptq]
+                    [--bits B] [--group G] [--meta16]
 """
 from __future__ import annotations
 
@@ -32,6 +33,8 @@ WORKLOADS = {
     "down_proj": (2, "down_proj"),
     # q, k and v of one decoder block: three layers that share X, one H, one scoring launch
     "qkv": (2, ("q_proj", "k_proj", "v_proj")),
+    # the 70B-shaped block's q_proj with the clip-ratio grid: 20 ratios x both dims = 40 candidates per layer
+    "clip_grid": (4, "q_proj"),
 }
 
 
@@ -41,10 +44,11 @@ def gram_tiling(in_f: int):
     return bt, nb * (nb + 1) // 2
 
 
-def cpu_baseline(W, X, bits, group, budget_tokens=65536):
+def cpu_baseline(W, X, bits, group, budget_tokens=65536, clips=(1.0,)):
     """Times the CPU oracle, as it stands, on a bounded sample (about 10 s of host work on the
     default workload): the Gram matrix on the first `budget_tokens` tokens (scaled linearly to all
-    tokens), the two quantizations and the two fp64 scorings in full."""
+    tokens), the two quantizations and the two fp64 scorings in full (with a clip grid: for its
+    first ratio, scaled to the number of ratios)."""
     import oracle
     t_sample = min(budget_tokens, X.shape[0])
     t0 = time.perf_counter()
@@ -57,7 +61,7 @@ def cpu_baseline(W, X, bits, group, budget_tokens=65536):
         losses.append(oracle.layer_error(q["dW"], H))
     oracle.select(losses)
     t_q = time.perf_counter() - t0
-    total = t_h * (X.shape[0] / t_sample) + t_q
+    total = t_h * (X.shape[0] / t_sample) + t_q * len(clips)
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -66,7 +70,8 @@ def cpu_baseline(W, X, bits, group, budget_tokens=65536):
     return {
         "value": W.size / total, "unit": "weights/s", "cores": int(cores), "kind": "oracle",
         "sample": f"fp64 Gram matrix on the first {t_sample} of {X.shape[0]} tokens ({t_h:.2f} s, scaled x"
-                  f"{X.shape[0] / t_sample:.0f}); both quantizations and both fp64 losses in full ({t_q:.2f} s)",
+                  f"{X.shape[0] / t_sample:.0f}); both quantizations and both fp64 losses in full ({t_q:.2f} s)"
+                  + (f", scaled x{len(clips)} for the clip ratios" if len(clips) > 1 else ""),
         "seconds_extrapolated": total,
     }
 
@@ -235,6 +240,7 @@ def main():
     bits = args.bits if args.bits is not None else (3 if 3 in cfg["bits"] else cfg["bits"][0])
     group = cfg["group"] if args.group is None else args.group
     tokens = cfg["tokens"]
+    clips = tuple(S.clip_grid(cfg["clips"])) if cfg["clips"] > 1 else (1.0,)
 
     W = synth.config_weight(cfg_id, layer)
     X = synth.config_activations(cfg_id, in_f)
@@ -244,7 +250,7 @@ def main():
     ctx = B.Context()
     hp = S.PreparedHessian(ctx, in_f)
     if len(layers) == 1:
-        ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,), meta16=args.meta16)
+        ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=clips, meta16=args.meta16)
 
         def step():
             hp.update(Xd)
@@ -306,7 +312,7 @@ def main():
         "dense_equivalent": 2.0 * tokens * in_f * in_f / gram_s / 1e12,
     }
 
-    # secondary kernels: error GEMM (MFMA) and quantizers (HBM)
+    # the error GEMM (MFMA) and the quantizers (HBM)
     comps = {}
     if "error_tiles" in kern:
         s = kern["error_tiles"]["avg_us"] * 1e-6
@@ -321,6 +327,12 @@ def main():
             "frac_mfma": issued / s / MFMA_F16_PEAK,
             "tflops_dense_equivalent": per_launch * 2.0 * out_f * in_f * in_f / s / 1e12,
         }
+    # with many candidates per layer (clip grid) the error GEMM, not the Gram matrix, is the dominant kernel
+    et = comps.get("error_tiles")
+    if et and et["avg_us"] * kern["error_tiles"]["launches"] > kern["gram_tiles"]["avg_us"] * kern["gram_tiles"]["launches"]:
+        roofline = {"kernel": "error_tiles", "bound": "mfma", "achieved": et["tflops_issued"], "peak": MFMA_F16_PEAK / 1e12,
+                    "unit": "TFLOP/s", "frac": et["frac_mfma"], "traffic": None,
+                    "dense_equivalent": et["tflops_dense_equivalent"]}
     # W read + fp16 dW written + scale/zero (one pair per group of the larger of the two group counts)
     qbytes = out_f * in_f * (2 + 2) + 5.0 * (out_f * in_f / group if group else max(out_f, in_f))
     for k in ("quant_oc", "quant_ic"):
@@ -366,7 +378,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}/{'+'.join(layers)} W[{out_f},{in_f}] X[{tokens},{in_f}] int{bits} "
-                               f"g{group} both dims + selection" + (", 16-bit group words" if args.meta16 else ""),
+                               f"g{group} both dims" + (f" x {len(clips)} clip ratios" if len(clips) > 1 else "") + " + selection"
+                               + (", 16-bit group words" if args.meta16 else ""),
                    "bits": bits, "group": group, "tokens": tokens},
         "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
         "roofline": roofline,
@@ -374,7 +387,7 @@ def main():
         "kernels": comps,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(W, X, bits, group)
+        result["cpu_baseline"] = cpu_baseline(W, X, bits, group, clips=clips)
     print(json.dumps(result))
 
 
