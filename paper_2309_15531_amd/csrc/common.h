@@ -27,6 +27,7 @@ enum {
     WS_GPTQ_A,          // fp64 reversed, permuted, damped Hessian and its Cholesky factor
     WS_GPTQ_M,          // fp64 inverse of that factor
     WS_GPTQ_D,          // fp64 diagonal and damping term
+    WS_GPTQ_T,          // fp64 products of the triangular inverse's doubling levels
     WS_GPTQ_W,          // fp32 working copy of the weight in visiting order
     WS_GPTQ_E,          // fp32 propagated errors in visiting order
     WS_GPTQ_Q,          // u8 codes in visiting order

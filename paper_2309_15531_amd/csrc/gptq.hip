@@ -23,9 +23,12 @@
 // parameters from the channel's current values when it is visited.
 #include "common.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int NB = 64;        // panel width of the factorization
+constexpr int NBO = 256;      // its outer panel: trailing updates are applied 256 columns at a time
 constexpr int GB = 128;       // channels per sweep block
 
 // ------------------------------------------------------------------ prepare: order and matrix
@@ -84,179 +87,210 @@ __global__ void gq_gather(const float* __restrict__ H, int64_t n, const int32_t*
     A[idx] = v;
 }
 
-// ------------------------------------------------------------------ Cholesky, lower, in place
-// diagonal block A[k0.., k0..] of width w <= NB
-__global__ __launch_bounds__(256) void chol_diag(double* __restrict__ A, int64_t n, int64_t k0, int w) {
-    __shared__ double t[NB][NB + 1];
-    const int tid = threadIdx.x;
-    for (int e = tid; e < w * w; e += 256) t[e / w][e % w] = A[(k0 + e / w) * n + k0 + e % w];
-    __syncthreads();
-    for (int c = 0; c < w; ++c) {
-        if (tid == 0) t[c][c] = sqrt(t[c][c]);
-        __syncthreads();
-        for (int r = c + 1 + tid; r < w; r += 256) t[r][c] /= t[c][c];
-        __syncthreads();
-        const int m = w - c - 1;                              // trailing rows/columns c+1..w-1, lower part
-        for (int e = tid; e < m * m; e += 256) {
-            const int r = c + 1 + e / m, cc = c + 1 + e % m;
-            if (cc <= r) t[r][cc] -= t[r][c] * t[cc][c];
-        }
-        __syncthreads();
-    }
-    for (int e = tid; e < w * w; e += 256) {
-        const int r = e / w, c = e % w;
-        A[(k0 + r) * n + k0 + c] = c <= r ? t[r][c] : 0.0;
-    }
-}
+// ------------------------------------------------------------------ fp64 tiles on the matrix cores
+// v_mfma_f64_16x16x4_f64: lane l supplies A[l % 16][l / 16] and B[l / 16][l % 16]; register r of its
+// result is D[4 r + l / 16][l % 16].  The vector and the matrix pipe have the same fp64 peak on this
+// chip; the matrix form needs a quarter of the LDS reads per flop and no issue slots for the products.
+typedef double double4_t __attribute__((ext_vector_type(4)));
+constexpr int GT = 64, GK = 16, GP = GT + 4;     // tile edge, contraction chunk, LDS pitch (doubles)
 
-// rows below the diagonal block: X L_kk^T = A[r, k0..k0+w), one thread per row
-__global__ __launch_bounds__(64) void chol_trsm(double* __restrict__ A, int64_t n, int64_t k0, int w) {
-    __shared__ double L[NB][NB + 1];
-    for (int e = threadIdx.x; e < w * w; e += 64) L[e / w][e % w] = A[(k0 + e / w) * n + k0 + e % w];
-    __syncthreads();
-    const int64_t r = k0 + w + int64_t(blockIdx.x) * 64 + threadIdx.x;
-    if (r >= n) return;
-    double x[NB];
-#pragma unroll
-    for (int c = 0; c < NB; ++c) x[c] = c < w ? A[r * n + k0 + c] : 0.0;
-#pragma unroll
-    for (int c = 0; c < NB; ++c) {
-        if (c < w) {
-            double v = x[c];
-#pragma unroll
-            for (int t2 = 0; t2 < c; ++t2) v = fma(-x[t2], L[c][t2], v);
-            x[c] = v / L[c][c];
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-        if (c < w) A[r * n + k0 + c] = x[c];
-}
-
-// trailing update: C[r][c] -= sum_t P[r][t] P[c][t] for the 64 x 64 tile (tr, tc), tc <= tr, of the
-// rows/columns from k1 on; P = A[.., k0..k0+w)
-__global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t n, int64_t k0, int w, int64_t k1) {
-    __shared__ double Pr[NB][NB + 1], Pc[NB][NB + 1];
-    // blockIdx.x enumerates the lower-triangular tile pairs
-    int tr = 0, rem = blockIdx.x;
-    while (rem > tr) {
-        rem -= tr + 1;
-        ++tr;
-    }
-    const int tc = rem;
-    const int64_t r0 = k1 + int64_t(tr) * NB, c0 = k1 + int64_t(tc) * NB;
-    for (int e = threadIdx.x; e < NB * NB; e += 256) {
-        const int i = e / NB, t2 = e % NB;
-        Pr[i][t2] = (r0 + i < n && t2 < w) ? A[(r0 + i) * n + k0 + t2] : 0.0;
-        Pc[i][t2] = (c0 + i < n && t2 < w) ? A[(c0 + i) * n + k0 + t2] : 0.0;
-    }
-    __syncthreads();
-    const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;   // 4 x 4 outputs each: rows 4ty.., cols 4tx..
-    double acc[4][4] = {};
-    for (int t2 = 0; t2 < NB; ++t2) {
-        double a[4], b[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[i] = Pr[4 * ty + i][t2];
-            b[i] = Pc[4 * tx + i][t2];
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int64_t r = r0 + 4 * ty + i, c = c0 + 4 * tx + j;
-            if (r < n && c <= r) A[r * n + c] -= acc[i][j];
-        }
-}
-
-// ------------------------------------------------------------------ M = inv(L), lower, block rows
-// diagonal block: column c of inv(L_ii) by forward substitution, one thread per column
-__global__ __launch_bounds__(64) void trinv_diag(const double* __restrict__ A, double* __restrict__ M, int64_t n,
-                                                 int64_t k0, int w) {
-    __shared__ double L[NB][NB + 1];
-    for (int e = threadIdx.x; e < w * w; e += 64) L[e / w][e % w] = A[(k0 + e / w) * n + k0 + e % w];
-    __syncthreads();
-    const int c = threadIdx.x;
-    if (c >= w) return;
-    double x[NB];
-#pragma unroll
-    for (int r = 0; r < NB; ++r) {
-        x[r] = 0.0;
-        if (r < w && r >= c) {
-            double v = r == c ? 1.0 : 0.0;
-#pragma unroll
-            for (int t2 = 0; t2 < r; ++t2) v = fma(-L[r][t2], x[t2], v);
-            x[r] = v / L[r][r];
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < NB; ++r)
-        if (r < w) M[(k0 + r) * n + k0 + c] = r >= c ? x[r] : 0.0;
-}
-
-// block row i0 (rows k0..k0+w): M[i][j] = -M_ii * sum_{t=j}^{i-1} L[i][t] M[t][j] for the block column
-// blockIdx.x = j (64 columns from 64j); tiles through LDS
-__global__ __launch_bounds__(256) void trinv_row(const double* __restrict__ A, double* __restrict__ M, int64_t n,
-                                                 int64_t k0, int w) {
-    __shared__ double Ta[NB][NB + 1], Tb[NB][NB + 1];
-    const int64_t c0 = int64_t(blockIdx.x) * NB;              // block column (c0 < k0)
-    const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
-    double acc[4][4] = {};
-    for (int64_t t0 = c0; t0 < k0; t0 += NB) {                // t blocks j .. i-1 (all full: they lie above row k0)
+// acc += A B for one 64 x 64 tile and k in [k_lo, k_hi), 256 threads (2 x 2 waves of 32 x 32).
+//   A(i, k) = Ap[i * lda + k], rows i < m_valid;
+//   B(k, j) = B_KC ? Bp[j * ldb + k] : Bp[k * ldb + j], columns j < n_valid;
+// everything outside the valid ranges reads as zero.  As, Bs: [GK][GP] doubles each.
+template <bool B_KC>
+__device__ __forceinline__ void dgemm_tile(const double* __restrict__ Ap, int64_t lda, int m_valid,
+                                           const double* __restrict__ Bp, int64_t ldb, int n_valid, int64_t k_lo,
+                                           int64_t k_hi, double (*As)[GP], double (*Bs)[GP], double4_t (&acc)[2][2]) {
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
+    const int li = t >> 2, lk = (t & 3) * 4;              // k-contiguous operand: row li, four consecutive k
+    const int bk = t >> 4, bj = (t & 15) * 4;             // row-major B: contraction row bk, four consecutive columns
+    for (int64_t k0 = k_lo; k0 < k_hi; k0 += GK) {
         __syncthreads();
-        for (int e = threadIdx.x; e < NB * NB; e += 256) {
-            const int i = e / NB, t2 = e % NB;
-            Ta[i][t2] = i < w ? A[(k0 + i) * n + t0 + t2] : 0.0;        // L[i][t]
-            Tb[i][t2] = M[(t0 + i) * n + c0 + t2];                      // M[t][j] (zero above its diagonal)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int64_t k = k0 + lk + e;
+            As[lk + e][li] = (li < m_valid && k < k_hi) ? Ap[li * lda + k] : 0.0;
+        }
+        if constexpr (B_KC) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t k = k0 + lk + e;
+                Bs[lk + e][li] = (li < n_valid && k < k_hi) ? Bp[li * ldb + k] : 0.0;
+            }
+        } else {
+            const int64_t k = k0 + bk;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Bs[bk][bj + e] = (k < k_hi && bj + e < n_valid) ? Bp[k * ldb + bj + e] : 0.0;
         }
         __syncthreads();
-        for (int t2 = 0; t2 < NB; ++t2) {
-            double a[4], b[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = Ta[4 * ty + i][t2];
-                b[i] = Tb[t2][4 * tx + i];
+        for (int ks = 0; ks < GK; ks += 4) {
+            double a[2], b[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                a[u] = As[ks + (lane >> 4)][wm * 32 + u * 16 + (lane & 15)];
+                b[u] = Bs[ks + (lane >> 4)][wn * 32 + u * 16 + (lane & 15)];
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fma(a[i], b[j], acc[i][j]);
+                for (int v = 0; v < 2; ++v) acc[u][v] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[v], acc[u][v], 0, 0, 0);
         }
     }
-    // S (w x 64) into Tb, M_ii into Ta, then M_ij = -M_ii S
-    __syncthreads();
+}
+
+// visits the tile's elements this lane holds: f(row in tile, column in tile, value)
+template <typename F>
+__device__ __forceinline__ void dgemm_each(const double4_t (&acc)[2][2], F f) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) Tb[4 * ty + i][4 * tx + j] = acc[i][j];
-    for (int e = threadIdx.x; e < NB * NB; e += 256) {
-        const int i = e / NB, t2 = e % NB;
-        Ta[i][t2] = (i < w && t2 < w) ? M[(k0 + i) * n + k0 + t2] : 0.0;
+        for (int v = 0; v < 2; ++v)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) f(wm * 32 + u * 16 + 4 * r + (lane >> 4), wn * 32 + v * 16 + (lane & 15), acc[u][v][r]);
+}
+
+// ------------------------------------------------------------------ Cholesky, lower, in place
+// Diagonal block A[k0.., k0..] of width w <= NB, factored and inverted by one wavefront.  Lane r
+// keeps row r in registers.  Right-looking: once column c is final (pivot broadcast by a lane
+// read, reciprocal square root plus two Newton steps), the lanes post it in LDS and every lane
+// subtracts l_rc l_jc from its later columns j: independent broadcast reads and independent
+// fmas, nothing waits on a chain.  The inverse likewise (column j of inv(L) by lane j: y_k final,
+// then a_r -= l_rk y_k for the later rows) goes to the diagonal block of M: it turns the panel's
+// triangular solve into a product and is the first level of the triangular inverse.
+__global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0,
+                                                    int w) {
+    __shared__ double t[NB][NB + 1];
+    __shared__ double col[2][NB];                             // the column just finished, two buffers in turn
+    __shared__ double rd[NB];                                 // reciprocals of the diagonal of L
+    const int lane = threadIdx.x;
+    for (int e = lane; e < NB * NB; e += 64) {
+        const int r = e / NB, c = e % NB;
+        t[r][c] = (r < w && c < w) ? A[(k0 + r) * n + k0 + c] : (r == c ? 1.0 : 0.0);   // identity padding
     }
     __syncthreads();
-    double o[4][4] = {};
-    for (int t2 = 0; t2 < NB; ++t2) {
-        double a[4], b[4];
+    {
+        double x[NB];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[i] = Ta[4 * ty + i][t2];
-            b[i] = Tb[t2][4 * tx + i];
+        for (int c = 0; c < NB; ++c) x[c] = t[lane][c];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
+            const double piv = __shfl(x[c], c, 64);
+            double inv = __builtin_amdgcn_rsq(piv);
+            inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
+            inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
+            const double l = lane == c ? piv * inv : (lane > c ? x[c] * inv : 0.0);
+            x[c] = l;
+            col[c & 1][lane] = l;
+            if (lane == c) rd[c] = inv;
+            __syncthreads();
+            // sixteen broadcast reads in flight at a time: the fences keep the scheduler from issuing
+            // them all at once, which would not leave registers for the row
+#pragma unroll
+            for (int j0 = (c + 1) & ~15; j0 < NB; j0 += 16) {
+#pragma unroll
+                for (int j = j0 > c + 1 ? j0 : c + 1; j < j0 + 16; ++j) x[j] = fma(-l, col[c & 1][j], x[j]);
+                asm volatile("" ::: "memory");
+            }
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) o[i][j] = fma(a[i], b[j], o[i][j]);
+        for (int c = 0; c < NB; ++c) t[lane][c] = x[c];
     }
+    __syncthreads();
+    for (int e = lane; e < w * w; e += 64) A[(k0 + e / w) * n + k0 + e % w] = t[e / w][e % w];
+    {
+        const double my_rd = rd[lane];
+        double a[NB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < NB; ++r) {
+            a[r] = r == lane ? 1.0 : 0.0;
+            asm volatile("" : "+v"(a[r]));                    // a register now, not a lane compare kept for later
+        }
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (4 * ty + i < w) M[(k0 + 4 * ty + i) * n + c0 + 4 * tx + j] = -o[i][j];
+        for (int k = 0; k < NB; ++k) {
+            // column k of L, with the reciprocal pivot in the diagonal's place, posted like the columns above
+            col[k & 1][lane] = lane == k ? my_rd : t[lane][k];
+            __syncthreads();
+            const double yk = a[k] * col[k & 1][k];
+            a[k] = yk;
+#pragma unroll
+            for (int r0 = (k + 1) & ~15; r0 < NB; r0 += 16) {
+#pragma unroll
+                for (int r = r0 > k + 1 ? r0 : k + 1; r < r0 + 16; ++r) a[r] = fma(-col[k & 1][r], yk, a[r]);
+                asm volatile("" ::: "memory");
+            }
+        }
+        // out through LDS (t is free now): sixty-four global stores from here would each want their
+        // address computed ahead of time, and those registers are not to be had
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < NB; ++r) t[r][lane] = r >= lane ? a[r] : 0.0;
+    }
+    __syncthreads();
+    for (int e = lane; e < w * w; e += 64) M[(k0 + e / w) * n + k0 + e % w] = t[e / w][e % w];
+}
+
+// rows below the diagonal block: L21 = A21 inv(L11)^T, 64 rows per block, in place (a block reads
+// only the rows it writes, and has read them all before the first store)
+__global__ __launch_bounds__(256) void chol_panel(double* __restrict__ A, const double* __restrict__ M, int64_t n,
+                                                  int64_t k0, int w) {
+    __shared__ double As[GK][GP], Bs[GK][GP];
+    const int64_t r0 = k0 + w + int64_t(blockIdx.x) * GT;
+    const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT);
+    double4_t acc[2][2] = {};
+    dgemm_tile<true>(A + r0 * n + k0, n, m_valid, M + k0 * n + k0, n, w, 0, w, As, Bs, acc);
+    __syncthreads();
+    dgemm_each(acc, [&](int i, int j, double v) {
+        if (i < m_valid && j < w) A[(r0 + i) * n + k0 + j] = v;
+    });
+}
+
+// trailing update: C[r][c] -= sum_t P[r][t] P[c][t] on the 64 x 64 tiles (blockIdx.y, blockIdx.x <= blockIdx.y)
+// of the rows/columns from k1 on; P = A[.., k0..k0+w).  gridDim.x limits the columns that are updated
+// (inside a 256-wide outer panel only the panel's own columns; behind it all, with w = 256).
+__global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t n, int64_t k0, int w, int64_t k1) {
+    if (blockIdx.x > blockIdx.y) return;
+    __shared__ double As[GK][GP], Bs[GK][GP];
+    const int64_t r0 = k1 + int64_t(blockIdx.y) * GT, c0 = k1 + int64_t(blockIdx.x) * GT;
+    const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT), n_valid = static_cast<int>(n - c0 < GT ? n - c0 : GT);
+    double4_t acc[2][2] = {};
+    dgemm_tile<true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
+    dgemm_each(acc, [&](int i, int j, double v) {
+        if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] -= v;
+    });
+}
+
+// ------------------------------------------------------------------ M = inv(L), lower, by doubling
+// inv [[A, 0], [C, B]] = [[inv A, 0], [-inv(B) C inv(A), inv B]].  With the diagonal blocks of
+// size s inverted, level s pairs them up: pair p = blockIdx.z covers rows a0 = 2 p s (A, s rows)
+// and b0 = a0 + s (B, sb <= s rows at the matrix end).  Two products per level, every pair and
+// every tile in parallel: T = C inv(A) (PASS 0, inv(A) lower triangular: k starts at the tile's
+// first column), then M[B rows, A columns] = -inv(B) T (PASS 1, k ends with the tile's last row).
+template <int PASS>
+__global__ __launch_bounds__(256) void trinv_level(const double* __restrict__ L, double* __restrict__ M,
+                                                   double* __restrict__ T, int64_t n, int64_t s) {
+    const int64_t a0 = 2 * int64_t(blockIdx.z) * s, b0 = a0 + s;
+    const int64_t sb = n - b0 < s ? n - b0 : s;               // > 0 for every pair in the grid
+    const int64_t m0 = int64_t(blockIdx.y) * GT, n0 = int64_t(blockIdx.x) * GT;
+    if (m0 >= sb) return;
+    __shared__ double As[GK][GP], Bs[GK][GP];
+    const int m_valid = static_cast<int>(sb - m0 < GT ? sb - m0 : GT);
+    double* Tp = T + int64_t(blockIdx.z) * s * s;
+    double4_t acc[2][2] = {};
+    if constexpr (PASS == 0) {
+        dgemm_tile<false>(L + (b0 + m0) * n + a0, n, m_valid, M + a0 * n + a0 + n0, n, GT, n0, s, As, Bs, acc);
+        dgemm_each(acc, [&](int i, int j, double v) {
+            if (i < m_valid) Tp[(m0 + i) * s + n0 + j] = v;
+        });
+    } else {
+        const int64_t k_hi = sb < m0 + GT ? sb : m0 + GT;
+        dgemm_tile<false>(M + (b0 + m0) * n + b0, n, m_valid, Tp + n0, s, GT, 0, k_hi, As, Bs, acc);
+        dgemm_each(acc, [&](int i, int j, double v) {
+            if (i < m_valid) M[(b0 + m0 + i) * n + a0 + n0 + j] = -v;
+        });
+    }
 }
 
 // U[a][b] = fp32(M[n-1-a][n-1-b]): upper triangular, visiting order
@@ -487,7 +521,11 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
     double* A = static_cast<double*>(adadim_workspace(ctx, WS_GPTQ_A, mat));
     double* M = static_cast<double*>(adadim_workspace(ctx, WS_GPTQ_M, mat));
     double* dvec = static_cast<double*>(adadim_workspace(ctx, WS_GPTQ_D, size_t(n + 1) * sizeof(double)));
-    if (!A || !M || !dvec) return ADADIM_EHIP;
+    // products C inv(A) of the inverse's doubling levels: pairs * s * s doubles at level s
+    size_t t_elems = 1;
+    for (int64_t s = NB; s < n; s *= 2) t_elems = std::max(t_elems, size_t((n - s + 2 * s - 1) / (2 * s)) * size_t(s) * size_t(s));
+    double* T = static_cast<double*>(adadim_workspace(ctx, WS_GPTQ_T, t_elems * sizeof(double)));
+    if (!A || !M || !dvec || !T) return ADADIM_EHIP;
     double* damp = dvec + n;
     const unsigned nb1 = static_cast<unsigned>((n + 255) / 256), nb2 = static_cast<unsigned>((n * n + 255) / 256);
     ProfScope prof(ctx, "gptq_prepare");
@@ -496,23 +534,34 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
     hipLaunchKernelGGL(gq_rank, dim3(nb1), dim3(256), 0, ctx->stream, dvec, n, act_order, perm);
     hipLaunchKernelGGL(gq_gather, dim3(nb2), dim3(256), 0, ctx->stream, H, n, perm, dvec, damp, A);
     ADADIM_LAUNCH_CHECK(ctx, "gptq prepare");
-    for (int64_t k0 = 0; k0 < n; k0 += NB) {
-        const int w = static_cast<int>(n - k0 < NB ? n - k0 : NB);
-        hipLaunchKernelGGL(chol_diag, dim3(1), dim3(256), 0, ctx->stream, A, n, k0, w);
-        const int64_t rest = n - k0 - w;
+    // Outer panels of 256 columns: inside a panel the 64-wide steps update the panel's own columns
+    // only; the columns behind it get the whole panel at once, a product with 256 contraction steps
+    // per pass over the trailing matrix instead of 64.
+    for (int64_t K0 = 0; K0 < n; K0 += NBO) {
+        const int64_t W = n - K0 < NBO ? n - K0 : NBO;
+        for (int64_t k0 = K0; k0 < K0 + W; k0 += NB) {
+            const int w = static_cast<int>(n - k0 < NB ? n - k0 : NB);
+            hipLaunchKernelGGL(chol_diag_inv, dim3(1), dim3(64), 0, ctx->stream, A, M, n, k0, w);
+            const int64_t rest = n - k0 - w;
+            if (rest > 0) {
+                const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
+                hipLaunchKernelGGL(chol_panel, dim3(t), dim3(256), 0, ctx->stream, A, M, n, k0, w);
+                const unsigned tc = static_cast<unsigned>((K0 + W - (k0 + w) + GT - 1) / GT);
+                if (tc > 0) hipLaunchKernelGGL(chol_syrk, dim3(tc, t), dim3(256), 0, ctx->stream, A, n, k0, w, k0 + w);
+            }
+        }
+        const int64_t rest = n - K0 - W;
         if (rest > 0) {
-            hipLaunchKernelGGL(chol_trsm, dim3(static_cast<unsigned>((rest + 63) / 64)), dim3(64), 0, ctx->stream, A, n, k0, w);
-            const int64_t t = (rest + NB - 1) / NB;
-            hipLaunchKernelGGL(chol_syrk, dim3(static_cast<unsigned>(t * (t + 1) / 2)), dim3(256), 0, ctx->stream, A, n, k0,
-                               w, k0 + w);
+            const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
+            hipLaunchKernelGGL(chol_syrk, dim3(t, t), dim3(256), 0, ctx->stream, A, n, K0, static_cast<int>(W), K0 + W);
         }
     }
     ADADIM_LAUNCH_CHECK(ctx, "gptq cholesky");
-    for (int64_t k0 = 0; k0 < n; k0 += NB) {
-        const int w = static_cast<int>(n - k0 < NB ? n - k0 : NB);
-        hipLaunchKernelGGL(trinv_diag, dim3(1), dim3(64), 0, ctx->stream, A, M, n, k0, w);
-        if (k0 > 0)
-            hipLaunchKernelGGL(trinv_row, dim3(static_cast<unsigned>(k0 / NB)), dim3(256), 0, ctx->stream, A, M, n, k0, w);
+    for (int64_t s = NB; s < n; s *= 2) {
+        const unsigned pairs = static_cast<unsigned>((n - s + 2 * s - 1) / (2 * s));   // those with rows below a0 + s
+        const dim3 grid(static_cast<unsigned>(s / GT), static_cast<unsigned>(s / GT), pairs);
+        hipLaunchKernelGGL(trinv_level<0>, grid, dim3(256), 0, ctx->stream, A, M, T, n, s);
+        hipLaunchKernelGGL(trinv_level<1>, grid, dim3(256), 0, ctx->stream, A, M, T, n, s);
     }
     hipLaunchKernelGGL(gq_flip, dim3(nb2), dim3(256), 0, ctx->stream, M, n, U);
     ADADIM_LAUNCH_CHECK(ctx, "gptq inverse");
