@@ -24,6 +24,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace {
 
@@ -317,6 +318,25 @@ __device__ __forceinline__ QP params_of(float mn, float mx, float qmax) {
     return {scale, z};
 }
 
+// minimum over the wavefront, the same value in every lane: butterflies inside the rows of 16 lanes
+// through DPP, then the four rows through lane reads (min is exact, any order gives the same bits)
+template <int CTRL>
+__device__ __forceinline__ float gq_dpp(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_min(float v) {
+    v = fminf(v, gq_dpp<0xB1>(v));                            // lane ^ 1
+    v = fminf(v, gq_dpp<0x4E>(v));                            // lane ^ 2
+    v = fminf(v, gq_dpp<0x141>(v));                           // mirror within 8
+    v = fminf(v, gq_dpp<0x140>(v));                           // mirror within 16
+    const int b = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+    return fminf(fminf(r0, r1), fminf(r2, r3));
+}
+
 // Wp[r][i] = W[r][perm[i]] as fp32, zero for dead channels
 __global__ void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t in, const int32_t* __restrict__ perm,
                             const uint8_t* __restrict__ dead, float* __restrict__ Wp) {
@@ -327,16 +347,18 @@ __global__ void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t i
     Wp[idx] = dead[j] ? 0.0f : __half2float(W[r * in + j]);
 }
 
-// One 128-channel block [i1, i1 + nbw) for the rows of one wavefront (a workgroup is one wave, so
-// nothing is shared and there is no barrier).  Lane l holds RPL rows: per-OC rows 64*block + l
-// (RPL = 1), per-IC rows l + 64p of the block's row group (RPL = g/64), so that the group's minimum
-// and maximum are a lane-local step plus one wave reduction.  A lane's rows live in its own strip of
-// LDS; the channels are walked in sub-blocks of 16 held in registers: the sub-block's own updates
-// stay in registers, then its 16 errors are applied to the rest of the block, one LDS read and one
-// write per element for 16 updates, always in channel order.  The block of U is staged in LDS and
-// read with wave-uniform addresses.  Codes go out in visiting order (16 bytes per row and sub-block).
+// One 128-channel block [i1, i1 + nbw) for 64 * RPL rows, by a workgroup of four wavefronts.  Lane l
+// of the first wave holds RPL rows: per-OC rows 64*block + l (RPL = 1), per-IC rows l + 64p of the
+// block's row group (RPL = g/64), so that the group's minimum and maximum are a lane-local step
+// plus one wave reduction.  The rows live in an LDS strip; the channels are walked in sub-blocks of
+// 16 that the first wave holds in registers: the sub-block's own updates stay in registers, then
+// its 16 errors are posted in LDS and all four waves apply them to the rest of the block, each wave
+// a quarter of the columns, one LDS read and one write per element for 16 updates, always in
+// channel order (which wave applies them does not change a bit).  The block of U is staged in LDS
+// and read with wave-uniform addresses.  Codes go out in visiting order (16 bytes per row and
+// sub-block).
 template <bool IC, int RPL>
-__global__ __launch_bounds__(64) void gq_sweep(float* __restrict__ Wp, const float* __restrict__ U,
+__global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const float* __restrict__ U,
                                                const int32_t* __restrict__ perm, int64_t out, int64_t in, int64_t i1,
                                                int nbw, int g, float qmax, const float* __restrict__ st_scales,
                                                const uint8_t* __restrict__ st_zeros, float* __restrict__ scales_out,
@@ -346,8 +368,9 @@ __global__ __launch_bounds__(64) void gq_sweep(float* __restrict__ Wp, const flo
     extern __shared__ __align__(16) char smem[];
     float* Us = reinterpret_cast<float*>(smem);                         // [GB][GB]: rows / columns i1.. of U
     float* Ws = Us + GB * GB;                                           // [64 * RPL][PITCH]
-    const int lane = threadIdx.x;
-    for (int e4 = lane; e4 < nbw * (GB / 4); e4 += 64) {                // in % 4 == 0 is not required: guarded
+    float* Es = Ws + 64 * RPL * PITCH;                                  // [64 * RPL][SB + 1]: the sub-block's errors
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int e4 = threadIdx.x; e4 < nbw * (GB / 4); e4 += 256) {        // in % 4 == 0 is not required: guarded
         const int k = e4 / (GB / 4), c4 = (e4 % (GB / 4)) * 4;
         float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         const float* src = U + (i1 + k) * in + i1 + c4;
@@ -369,99 +392,138 @@ __global__ __launch_bounds__(64) void gq_sweep(float* __restrict__ Wp, const flo
         row[p] = IC ? int64_t(blockIdx.x) * g + lane + 64 * p : int64_t(blockIdx.x) * 64 + lane;
         ok[p] = row[p] < out;
         if (ok[p])
-            for (int c = 0; c < nbw; ++c) Ws[(lane * RPL + p) * PITCH + c] = Wp[row[p] * in + i1 + c];
+            for (int c = wave; c < nbw; c += 4) Ws[(lane * RPL + p) * PITCH + c] = Wp[row[p] * in + i1 + c];
     }
+    __syncthreads();
     const int n_cg = IC ? 0 : static_cast<int>(in / g);
     for (int s0 = 0; s0 < nbw; s0 += SB) {
         const int sbw = nbw - s0 < SB ? nbw - s0 : SB;
-        float w[RPL][SB], e[RPL][SB];
-        uint32_t qpk[RPL][SB / 4];
+        // the sequential part, one wave; FULL: all 16 channels exist (every sub-block but a ragged last
+        // one), which takes the bounds tests and their branches out of the chain
+        auto sub_block = [&](auto full_tag) {
+            constexpr bool FULL = decltype(full_tag)::value;
+            float w[RPL][SB], e[RPL][SB];
+            uint32_t qpk[RPL][SB / 4];
 #pragma unroll
-        for (int p = 0; p < RPL; ++p) {
+            for (int p = 0; p < RPL; ++p) {
 #pragma unroll
-            for (int c = 0; c < SB; ++c) w[p][c] = (ok[p] && c < sbw) ? Ws[(lane * RPL + p) * PITCH + s0 + c] : 0.0f;
+                for (int c = 0; c < SB; ++c) w[p][c] = (ok[p] && (FULL || c < sbw)) ? Ws[(lane * RPL + p) * PITCH + s0 + c] : 0.0f;
 #pragma unroll
-            for (int c = 0; c < SB / 4; ++c) qpk[p][c] = 0u;
-        }
+                for (int c = 0; c < SB / 4; ++c) qpk[p][c] = 0u;
+            }
+            // the sub-block's original channel indices and, for static groups, its parameters: fetched
+            // together up front, off the channel-by-channel chain
+            int32_t jo[SB];
+            QP st[SB];
 #pragma unroll
-        for (int c = 0; c < SB; ++c) {
-            if (c < sbw) {                                              // uniform
-                const int64_t ig = i1 + s0 + c;                        // visiting index
-                const int32_t j = perm[ig];                            // original channel (uniform)
-                const float d = Us[(s0 + c) * GB + s0 + c];
-                QP pr[RPL];
-                if constexpr (IC) {
-                    float mn = w[0][c], mx = w[0][c];
+            for (int c = 0; c < SB; ++c) jo[c] = (FULL || c < sbw) ? perm[i1 + s0 + c] : 0;
+            if constexpr (!IC) {
 #pragma unroll
-                    for (int p = 1; p < RPL; ++p) {
-                        mn = fminf(mn, w[p][c]);
-                        mx = fmaxf(mx, w[p][c]);
-                    }
-#pragma unroll
-                    for (int m = 1; m < 64; m <<= 1) {
-                        mn = fminf(mn, __shfl_xor(mn, m, 64));
-                        mx = fmaxf(mx, __shfl_xor(mx, m, 64));
-                    }
-                    const QP q1 = params_of(mn, mx, qmax);
-#pragma unroll
-                    for (int p = 0; p < RPL; ++p) pr[p] = q1;
-                    if (lane == 0) {
-                        scales_out[int64_t(blockIdx.x) * in + j] = q1.scale;
-                        zeros_out[int64_t(blockIdx.x) * in + j] = static_cast<uint8_t>(q1.zero);
-                    }
-                } else {
-                    pr[0].scale = ok[0] ? st_scales[row[0] * n_cg + j / g] : 1.0f;
-                    pr[0].zero = ok[0] ? static_cast<float>(st_zeros[row[0] * n_cg + j / g]) : 0.0f;
+                for (int c = 0; c < SB; ++c) {
+                    const bool have = ok[0] && (FULL || c < sbw);
+                    st[c].scale = have ? st_scales[row[0] * n_cg + jo[c] / g] : 1.0f;
+                    st[c].zero = have ? static_cast<float>(st_zeros[row[0] * n_cg + jo[c] / g]) : 0.0f;
                 }
+            }
 #pragma unroll
-                for (int p = 0; p < RPL; ++p) {
-                    float q = rintf(w[p][c] / pr[p].scale) + pr[p].zero;
-                    q = fminf(fmaxf(q, 0.0f), qmax);
-                    const float wq = pr[p].scale * (q - pr[p].zero);
-                    qpk[p][c / 4] |= static_cast<uint32_t>(q) << (8 * (c % 4));
-                    e[p][c] = (w[p][c] - wq) / d;
+            for (int c = 0; c < SB; ++c) {
+                if (FULL || c < sbw) {                                      // uniform
+                    const int32_t j = jo[c];                               // original channel (uniform)
+                    const float d = Us[(s0 + c) * GB + s0 + c];
+                    QP pr[RPL];
+                    if constexpr (IC) {
+                        float mn = w[0][c], mx = w[0][c];
 #pragma unroll
-                    for (int cc = c + 1; cc < SB; ++cc) {
-                        if (cc < sbw) {
-                            const float upd = e[p][c] * Us[(s0 + c) * GB + s0 + cc];
-                            w[p][cc] = w[p][cc] - upd;
+                        for (int p = 1; p < RPL; ++p) {
+                            mn = fminf(mn, w[p][c]);
+                            mx = fmaxf(mx, w[p][c]);
+                        }
+                        mn = wave_min(mn);
+                        mx = -wave_min(-mx);
+                        const QP q1 = params_of(mn, mx, qmax);
+#pragma unroll
+                        for (int p = 0; p < RPL; ++p) pr[p] = q1;
+                        if (lane == 0) {
+                            scales_out[int64_t(blockIdx.x) * in + j] = q1.scale;
+                            zeros_out[int64_t(blockIdx.x) * in + j] = static_cast<uint8_t>(q1.zero);
+                        }
+                    } else {
+                        pr[0] = st[c];
+                    }
+#pragma unroll
+                    for (int p = 0; p < RPL; ++p) {
+                        float q = rintf(w[p][c] / pr[p].scale) + pr[p].zero;
+                        q = fminf(fmaxf(q, 0.0f), qmax);
+                        const float wq = pr[p].scale * (q - pr[p].zero);
+                        qpk[p][c / 4] |= static_cast<uint32_t>(q) << (8 * (c % 4));
+                        e[p][c] = (w[p][c] - wq) / d;
+#pragma unroll
+                        for (int cc = c + 1; cc < SB; ++cc) {
+                            if (FULL || cc < sbw) {
+                                const float upd = e[p][c] * Us[(s0 + c) * GB + s0 + cc];
+                                w[p][cc] = w[p][cc] - upd;
+                            }
                         }
                     }
+                } else {
+#pragma unroll
+                    for (int p = 0; p < RPL; ++p) e[p][c] = 0.0f;
                 }
-            } else {
-#pragma unroll
-                for (int p = 0; p < RPL; ++p) e[p][c] = 0.0f;
             }
-        }
-        // the sub-block's codes and errors, in visiting order
-#pragma unroll
-        for (int p = 0; p < RPL; ++p) {
-            if (!ok[p]) continue;
-            const int64_t at = row[p] * in + i1 + s0;
-            if (sbw == SB && ((at & 15) == 0)) {
-                *reinterpret_cast<uint4*>(Qp + at) = make_uint4(qpk[p][0], qpk[p][1], qpk[p][2], qpk[p][3]);
-            } else {
-                for (int c = 0; c < sbw; ++c) Qp[at + c] = static_cast<uint8_t>(qpk[p][c / 4] >> (8 * (c % 4)));
-            }
-            for (int c = 0; c < sbw; ++c) Ep[at + c] = e[p][c];
-        }
-        // its errors applied to the rest of the block, channel order kept per element
-        for (int cc = s0 + SB; cc < nbw; ++cc) {
-            float u[SB];
-#pragma unroll
-            for (int k = 0; k < SB; ++k) u[k] = k < sbw ? Us[(s0 + k) * GB + cc] : 0.0f;
+            // the sub-block's codes and errors, in visiting order
 #pragma unroll
             for (int p = 0; p < RPL; ++p) {
                 if (!ok[p]) continue;
-                float v = Ws[(lane * RPL + p) * PITCH + cc];
-#pragma unroll
-                for (int k = 0; k < SB; ++k) {
-                    const float upd = e[p][k] * u[k];
-                    v = v - upd;
+                const int64_t at = row[p] * in + i1 + s0;
+                if (FULL && ((at & 15) == 0)) {
+                    *reinterpret_cast<uint4*>(Qp + at) = make_uint4(qpk[p][0], qpk[p][1], qpk[p][2], qpk[p][3]);
+                } else {
+                    for (int c = 0; c < sbw; ++c) Qp[at + c] = static_cast<uint8_t>(qpk[p][c / 4] >> (8 * (c % 4)));
                 }
-                Ws[(lane * RPL + p) * PITCH + cc] = v;
+                if (FULL && ((at & 3) == 0)) {
+#pragma unroll
+                    for (int c = 0; c < SB; c += 4)
+                        *reinterpret_cast<float4*>(Ep + at + c) = make_float4(e[p][c], e[p][c + 1], e[p][c + 2], e[p][c + 3]);
+                } else {
+                    for (int c = 0; c < sbw; ++c) Ep[at + c] = e[p][c];
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < RPL; ++p)
+#pragma unroll
+                for (int k = 0; k < SB; ++k) Es[(lane * RPL + p) * (SB + 1) + k] = e[p][k];
+        };
+        if (wave == 0) {
+            if (sbw == SB) sub_block(std::true_type{});
+            else sub_block(std::false_type{});
+        }
+        __syncthreads();
+        // its errors applied to the rest of the block, channel order kept per element; wave v takes
+        // the columns s0 + 16 + v, + 4, ...
+        if (s0 + SB < nbw) {
+            float e[RPL][SB];
+#pragma unroll
+            for (int p = 0; p < RPL; ++p)
+#pragma unroll
+                for (int k = 0; k < SB; ++k) e[p][k] = Es[(lane * RPL + p) * (SB + 1) + k];
+            for (int cc = s0 + SB + wave; cc < nbw; cc += 4) {
+                float u[SB];
+#pragma unroll
+                for (int k = 0; k < SB; ++k) u[k] = k < sbw ? Us[(s0 + k) * GB + cc] : 0.0f;
+#pragma unroll
+                for (int p = 0; p < RPL; ++p) {
+                    if (!ok[p]) continue;
+                    float v = Ws[(lane * RPL + p) * PITCH + cc];
+#pragma unroll
+                    for (int k = 0; k < SB; ++k) {
+                        const float upd = e[p][k] * u[k];
+                        v = v - upd;
+                    }
+                    Ws[(lane * RPL + p) * PITCH + cc] = v;
+                }
             }
         }
+        __syncthreads();
     }
 }
 
@@ -580,7 +642,7 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
     const bool ic = dim == ADADIM_DIM_IC;
     const int rpl = ic ? g / 64 : 1;                                   // rows per lane
     const unsigned blocks = static_cast<unsigned>(ic ? out / g : (out + 63) / 64);
-    const size_t smem = (size_t(GB) * GB + size_t(64) * rpl * (GB + 1)) * sizeof(float);
+    const size_t smem = (size_t(GB) * GB + size_t(64) * rpl * (GB + 1) + size_t(64) * rpl * 17) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 2>),
@@ -601,7 +663,7 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
         {
             ProfScope prof(ctx, "gptq_sweep");
 #define GQ_GO(IC_, RPL_)                                                                                          \
-    hipLaunchKernelGGL((gq_sweep<IC_, RPL_>), dim3(blocks), dim3(64), smem, ctx->stream, Wp, U, perm, out, in, i1, \
+    hipLaunchKernelGGL((gq_sweep<IC_, RPL_>), dim3(blocks), dim3(256), smem, ctx->stream, Wp, U, perm, out, in, i1, \
                        nbw, g, qmax, st_scales, st_zeros, scales_out, zeros_out, Qp, Ep)
             if (!ic) GQ_GO(false, 1);
             else if (rpl == 1) GQ_GO(true, 1);
