@@ -550,23 +550,26 @@ __global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __rest
 __global__ __launch_bounds__(256) void gq_trailing(float* __restrict__ Wp, const float* __restrict__ U,
                                                    const float* __restrict__ Ep, int64_t out, int64_t in, int64_t i1,
                                                    int nbw) {
-    __shared__ float Es[8][GB];
+    __shared__ __align__(16) float Es[GB][8];                 // [channel][row]: a channel's eight errors in two 16-byte reads
     const int64_t jj = i1 + nbw + int64_t(blockIdx.x) * 256 + threadIdx.x;
     const int64_t r0 = int64_t(blockIdx.y) * 8;
     for (int e = threadIdx.x; e < 8 * nbw; e += 256) {
         const int rr = e / nbw, k = e % nbw;
-        Es[rr][k] = r0 + rr < out ? Ep[(r0 + rr) * in + i1 + k] : 0.0f;
+        Es[k][rr] = r0 + rr < out ? Ep[(r0 + rr) * in + i1 + k] : 0.0f;
     }
     __syncthreads();
     if (jj >= in) return;
     float v[8];
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) v[rr] = r0 + rr < out ? Wp[(r0 + rr) * in + jj] : 0.0f;
+#pragma unroll 4
     for (int k = 0; k < nbw; ++k) {
         const float u = U[(i1 + k) * in + jj];
+        const float4 ea = *reinterpret_cast<const float4*>(&Es[k][0]), eb = *reinterpret_cast<const float4*>(&Es[k][4]);
+        const float e8[8] = {ea.x, ea.y, ea.z, ea.w, eb.x, eb.y, eb.z, eb.w};
 #pragma unroll
         for (int rr = 0; rr < 8; ++rr) {
-            const float upd = Es[rr][k] * u;
+            const float upd = e8[rr] * u;
             v[rr] = v[rr] - upd;
         }
     }
