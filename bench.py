@@ -4,7 +4,7 @@
 A step is one pass of the whole hot path over one layer: Gram matrix of the
 calibration activations, its preparation, quantize + score for both grouping
 dimensions, selection, and the winner's packed codes / scales / zeros.
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: metric, value, unit, ms_per_step, config, and the roofline / cpu_baseline objects.
 
     python bench.py [--steps K] [--warmup W] [--workload q_proj|down_proj|gate_proj|qkv|clip_grid|toy|gemv_ic|gptq]
                     [--bits B] [--group G] [--meta16]
@@ -206,14 +206,18 @@ def main():
     ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
     ap.add_argument("--meta16", action="store_true",
                     help="quantize into / multiply from the b + 16/g storage format (one 16-bit word per group)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step as one recorded HIP graph in the timed region (single layer, at most 8 "
+                         "candidates); per-kernel durations then come from a second pass of the same steps launched "
+                         "one by one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference dispatch that scales "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (layers are independent; see DESIGN.md for how the "
-              "search would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (layers are independent, so a multi-GPU run would "
+              "deal whole layers to ranks); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -247,15 +251,29 @@ def main():
     Wd = torch.from_numpy(W).cuda()
     Xd = torch.from_numpy(X).cuda()
 
+    use_graph = args.graph and len(layers) == 1 and 2 * len(clips) <= 8
+    if use_graph:
+        # a stream of its own for everything: the default stream cannot be recorded
+        torch.cuda.set_stream(torch.cuda.Stream())
     ctx = B.Context()
     hp = S.PreparedHessian(ctx, in_f)
     if len(layers) == 1:
         ls = S.LayerSearch(ctx, out_f, in_f, bits, group, clips=clips, meta16=args.meta16)
 
+        # Steps are queued back to back and the winners read after the loop, as a model driver would queue
+        # the next layer while the last one's answer is on its way (layers do not depend on each other).
+        # With more candidates than one scoring batch the winner is quantized again once it is known, so
+        # that case waits for the answer inside every step.
         def step():
             hp.update(Xd)
             hp.prepare()
-            return ls.run(Wd, hp)
+            if ls.inline:
+                ls.launch(Wd, hp)
+            else:
+                ls.run(Wd, hp)
+
+        def finish():
+            return ls.result() if ls.inline else (int(ls.best.item()),) + ls.cands[int(ls.best.item())]
     else:
         Wds = [Wd] + [torch.from_numpy(synth.config_weight(cfg_id, l)).cuda() for l in layers[1:]]
         ls = S.SharedSearch(ctx, len(layers), out_f, in_f, bits, group)
@@ -264,11 +282,19 @@ def main():
         def step():
             hp.update(Xd)
             hp.prepare()
-            dims = ls.run(Wds, hp)
+            ls.launch(Wds, hp)
+
+        def finish():
+            dims = ls.result()
             return dims[0], dims[0], 1.0
 
+    timed_step = step
+    if use_graph:
+        torch.cuda.synchronize()
+        gs = S.GraphedSearch(ctx, ls, hp, Wd, Xd)
+        timed_step, finish = gs.launch, gs.result
     for _ in range(args.warmup):
-        step()
+        timed_step()
     torch.cuda.synchronize()
     if args.copy_calibration:
         # an elementwise kernel that reads 256 MiB and writes 256 MiB (shows up as one
@@ -279,12 +305,20 @@ def main():
         torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    ctx.adadim_profile(True)
+    if not use_graph:
+        ctx.adadim_profile(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        best, dim, clip = step()
+        timed_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    best, dim, clip = finish()
+    if use_graph:
+        # the recorded graph carries no events: time the kernels in a second pass of the same steps, launched one by one
+        ctx.adadim_profile(True)
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
     ctx.adadim_profile(False)
     prof = ctx.adadim_profile_read()
     losses = ls.losses.cpu().numpy().tolist()
@@ -383,6 +417,8 @@ def main():
                    "bits": bits, "group": group, "tokens": tokens},
         "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
         "roofline": roofline,
+        "launch": ("one recorded HIP graph per step; kernel durations from a second pass of the same steps launched "
+                   "one by one" if use_graph else "kernel by kernel; kernel durations from HIP events in the timed region"),
         "quantizer_hbm": quant,
         "kernels": comps,
     }

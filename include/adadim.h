@@ -258,6 +258,25 @@ int adadim_gemv_ic_meta16(adadim_ctx* ctx, const uint32_t* packed, const uint16_
                           int64_t out, int64_t in, int bits, int group, void* y);
 
 /*
+ * Recording a sequence of calls as one HIP graph.  A layer's search is a dozen short kernels; launched one by
+ * one the gaps between them are a tenth of the step on a 4096 x 4096 layer, replayed as a graph they close.
+ *   adadim_capture_begin  starts recording on the context's stream, which must not be the default
+ *           stream (EINVAL).  Calls made on the context until adadim_capture_end are recorded, not run.
+ *           While recording, a call that would have to grow the context's scratch fails with EINVAL (make the
+ *           same calls once beforehand), adadim_select takes no host output, adadim_profile records nothing,
+ *           and the caller must not synchronise the stream or the device.
+ *   adadim_capture_end    stops recording and returns the instantiated graph (a hipGraphExec_t as void*).  The
+ *           graph holds the pointers and sizes of the recorded calls: the buffers must stay where they are,
+ *           new contents are picked up on every launch.
+ *   adadim_graph_launch   runs the graph on the context's stream (asynchronous like every other call).
+ *   adadim_graph_destroy  frees it.  NULL is allowed.
+ */
+int adadim_capture_begin(adadim_ctx* ctx);
+int adadim_capture_end(adadim_ctx* ctx, void** graph);
+int adadim_graph_launch(adadim_ctx* ctx, void* graph);
+void adadim_graph_destroy(void* graph);
+
+/*
  * Measurement aid (not part of the method): per-kernel device timings.
  * adadim_profile(ctx, 1) clears the records and starts bracketing every kernel
  * the library launches on this context with a pair of HIP events on the

@@ -23,6 +23,7 @@ EXPORTS = (
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
+    "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -86,6 +87,14 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_gemv_ic_meta16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
                                           c_void_p]
     lib.adadim_gemv_ic_meta16.restype = c_int
+    lib.adadim_capture_begin.argtypes = [c_void_p]
+    lib.adadim_capture_begin.restype = c_int
+    lib.adadim_capture_end.argtypes = [c_void_p, POINTER(c_void_p)]
+    lib.adadim_capture_end.restype = c_int
+    lib.adadim_graph_launch.argtypes = [c_void_p, c_void_p]
+    lib.adadim_graph_launch.restype = c_int
+    lib.adadim_graph_destroy.argtypes = [c_void_p]
+    lib.adadim_graph_destroy.restype = None
     lib.adadim_hessian_prepare.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
     lib.adadim_hessian_prepare.restype = c_int
     lib.adadim_layer_error.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
@@ -221,6 +230,22 @@ class Context:
     def adadim_gemv_ic_meta16(self, packed, meta, x, out_f: int, in_f: int, bits: int, group: int, y):
         self._check(self._lib.adadim_gemv_ic_meta16(self._h, _ptr(packed), _ptr(meta), _ptr(x), out_f, in_f, bits, group,
                                                     _ptr(y)))
+
+    def adadim_capture_begin(self):
+        self._check(self._lib.adadim_capture_begin(self._h))
+
+    def adadim_capture_end(self):
+        """Returns the graph handle (an int); free it with adadim_graph_destroy."""
+        g = c_void_p()
+        self._check(self._lib.adadim_capture_end(self._h, byref(g)))
+        return g.value
+
+    def adadim_graph_launch(self, graph: int):
+        self._check(self._lib.adadim_graph_launch(self._h, c_void_p(graph)))
+
+    def adadim_graph_destroy(self, graph):
+        if graph:
+            self._lib.adadim_graph_destroy(c_void_p(graph))
 
     def adadim_gptq_prepare(self, H, perm, dead, U, percdamp: float = 0.01, act_order: bool = True):
         self._check(self._lib.adadim_gptq_prepare(self._h, _ptr(H), H.shape[0], c_float(percdamp), 1 if act_order else 0,

@@ -22,6 +22,12 @@ int adadim_fail(adadim_ctx* ctx, int code, const char* fmt, ...) {
 void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes) {
     if (bytes == 0) bytes = 256;
     if (ctx->ws_bytes[slot] >= bytes) return ctx->ws[slot];
+    if (ctx->capturing) {
+        adadim_fail(ctx, ADADIM_EINVAL,
+                    "scratch slot %d would have to grow while a graph is being recorded: make the same call once "
+                    "before adadim_capture_begin", slot);
+        return nullptr;
+    }
     if (ctx->ws[slot]) {
         // Earlier kernels on the stream may still read the old buffer.
         if (hipStreamSynchronize(ctx->stream) != hipSuccess || hipFree(ctx->ws[slot]) != hipSuccess) {
@@ -46,7 +52,7 @@ void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes) {
 
 ProfScope::ProfScope(adadim_ctx* c, const char* name) : ctx(c), pair(-1) {
     adadim_prof& p = c->prof;
-    if (!p.enabled) return;
+    if (!p.enabled || c->capturing) return;
     if (p.n_used >= p.n_events) {
         ++p.dropped;
         return;
@@ -138,6 +144,11 @@ int adadim_create(adadim_ctx** out, void* hip_stream) {
 
 void adadim_destroy(adadim_ctx* ctx) {
     if (!ctx) return;
+    if (ctx->capturing) {                                     // an unfinished recording: end and drop it
+        hipGraph_t g = nullptr;
+        if (hipStreamEndCapture(ctx->stream, &g) == hipSuccess && g) (void)hipGraphDestroy(g);
+        ctx->capturing = false;
+    }
     bool any = false;
     for (int i = 0; i < WS_COUNT; ++i) any = any || ctx->ws[i];
     if (any) {
@@ -304,6 +315,8 @@ int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev
         dst = static_cast<int32_t*>(adadim_workspace(ctx, WS_SELECT, 256));
         if (!dst) return ADADIM_EHIP;
     }
+    if (host_best && ctx->capturing)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_select: no host output while a graph is being recorded");
     int rc = launch_select(ctx, losses, n, dst);
     if (rc != ADADIM_OK) return rc;
     if (host_best) {
@@ -311,6 +324,47 @@ int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev
         ADADIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     }
     return ADADIM_OK;
+}
+
+int adadim_capture_begin(adadim_ctx* ctx) {
+    if (!ctx) return ADADIM_ENULL;
+    if (ctx->capturing) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_capture_begin: already recording");
+    if (!ctx->stream)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_capture_begin: the context's stream is the default stream, "
+                                               "which cannot be recorded; create the context on a stream of its own");
+    ADADIM_HIP_TRY(ctx, hipStreamBeginCapture(ctx->stream, hipStreamCaptureModeRelaxed));
+    ctx->capturing = true;
+    return ADADIM_OK;
+}
+
+int adadim_capture_end(adadim_ctx* ctx, void** graph) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!ctx->capturing) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_capture_end: not recording");
+    ctx->capturing = false;
+    hipGraph_t g = nullptr;
+    ADADIM_HIP_TRY(ctx, hipStreamEndCapture(ctx->stream, &g));   // also ends a recording that a failed call broke
+    if (!graph) {
+        (void)hipGraphDestroy(g);
+        return adadim_fail(ctx, ADADIM_ENULL, "adadim_capture_end: graph is NULL");
+    }
+    hipGraphExec_t exec = nullptr;
+    const hipError_t e = hipGraphInstantiate(&exec, g, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(g);
+    if (e != hipSuccess) return adadim_fail(ctx, ADADIM_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e));
+    *graph = exec;
+    return ADADIM_OK;
+}
+
+int adadim_graph_launch(adadim_ctx* ctx, void* graph) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!graph) return adadim_fail(ctx, ADADIM_ENULL, "adadim_graph_launch: graph is NULL");
+    if (ctx->capturing) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_graph_launch: still recording");
+    ADADIM_HIP_TRY(ctx, hipGraphLaunch(static_cast<hipGraphExec_t>(graph), ctx->stream));
+    return ADADIM_OK;
+}
+
+void adadim_graph_destroy(void* graph) {
+    if (graph) (void)hipGraphExecDestroy(static_cast<hipGraphExec_t>(graph));
 }
 
 // shared by the two matrix-vector entry points; meta16: `scales` holds the 16-bit group words and zeros is unused

@@ -59,6 +59,7 @@ struct adadim_ctx {
     int64_t gram_key_tokens;         // token count and tile count the cached Gram split length was chosen for
     int gram_key_tiles;
     int64_t gram_t_per_split;
+    bool capturing;                  // between adadim_capture_begin and adadim_capture_end
     adadim_prof prof;
 };
 

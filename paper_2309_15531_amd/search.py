@@ -104,11 +104,26 @@ class LayerSearch:
                 kw.update(scales=self._scales[out_set], zeros=self._zeros[out_set], packed=self._packed[out_set])
             self.ctx.adadim_quantize(W, dim, self.bits, self.group, clip, **kw)
 
+    def launch(self, W, hp: PreparedHessian):
+        """Queues the whole search for one layer and returns at once: the losses and the winning index stay on
+        the device until `result` asks for them, so a driver can queue the next layer meanwhile."""
+        self.score_all(W, hp)
+        self.ctx.adadim_select(self.losses, best_dev=self.best, to_host=False)
+        self._W = W
+
+    def result(self):
+        """Waits for the last `launch`: returns (best index, dim, clip); with keep_winner the winner's packed
+        codes, scales and zeros are in self.packed / self.scales / self.zeros."""
+        torch.cuda.synchronize()
+        return self._finish(int(self.best.item()), self._W)
+
     def run(self, W, hp: PreparedHessian):
-        """Whole search for one layer: returns (best index, dim, clip); with keep_winner the
-        winner's packed codes, scales and zeros are in self.packed / self.scales / self.zeros."""
+        """launch + result with the library's own wait (one synchronisation of the context's stream)."""
         self.score_all(W, hp)
         best = self.ctx.adadim_select(self.losses, best_dev=self.best, to_host=True)
+        return self._finish(best, W)
+
+    def _finish(self, best, W):
         dim, clip = self.cands[best]
         if self.keep_winner:
             k = best if self.inline else 0
@@ -120,6 +135,65 @@ class LayerSearch:
             if not self.inline:
                 self._quantize(W, dim, clip, 0)
         return best, dim, clip
+
+
+class GraphedSearch:
+    """One layer's whole step (Gram matrix, preparation, every candidate, selection) recorded once as a HIP graph
+    and replayed per layer: the layers of a model that share a shape reuse the graph, their weights and
+    activations are copied into (or produced in) the buffers the graph was recorded with.
+
+    The context must live on a stream of its own (not the default stream); torch work that feeds the buffers must
+    be ordered before the launch by the caller (same stream, or an event)."""
+
+    def __init__(self, ctx: B.Context, ls: LayerSearch, hp: PreparedHessian, W, X):
+        if not (ls.inline or not ls.keep_winner):
+            raise ValueError("GraphedSearch needs every candidate's outputs kept while scored (candidates <= batch)")
+        self.ctx, self.ls, self.hp, self.W, self.X = ctx, ls, hp, W, X
+        self._step()                      # sizes the context's scratch; recording may not allocate
+        torch.cuda.synchronize()
+        ctx.adadim_capture_begin()
+        try:
+            self._step()
+        finally:
+            self.graph = ctx.adadim_capture_end()
+
+    def _step(self):
+        self.hp.update(self.X)
+        self.hp.prepare()
+        self.ls.score_all(self.W, self.hp)
+        self.ctx.adadim_select(self.ls.losses, best_dev=self.ls.best, to_host=False)
+
+    def launch(self):
+        """Queues one replay on the current contents of W and X."""
+        self.ctx.adadim_graph_launch(self.graph)
+
+    def run(self):
+        """Replays the step on the current contents of W and X; returns (best index, dim, clip)."""
+        self.launch()
+        return self.result()
+
+    def result(self):
+        ls = self.ls
+        torch.cuda.synchronize()          # the one synchronisation of the step (whatever stream torch is on)
+        best = int(ls.best.item())
+        dim, clip = ls.cands[best]
+        if ls.keep_winner:
+            ls.packed = ls._packed[best]
+            if ls.meta16:
+                ls.meta = ls._meta[best]
+            else:
+                ls.scales, ls.zeros = ls._scales[best], ls._zeros[best]
+        return best, dim, clip
+
+    def close(self):
+        self.ctx.adadim_graph_destroy(getattr(self, "graph", None))
+        self.graph = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class SharedSearch:
@@ -148,6 +222,11 @@ class SharedSearch:
     def run(self, Ws, hp: PreparedHessian):
         """Ws: the layers' weights.  Returns the list of chosen dimensions (one host sync); the
         winners' packed codes, scales and zeros are in self.packed[l] / self.scales[l] / self.zeros[l]."""
+        self.launch(Ws, hp)
+        return self.result()
+
+    def launch(self, Ws, hp: PreparedHessian):
+        """Queues the search of all the layers; nothing waits."""
         assert len(Ws) == self.n_layers
         for l, W in enumerate(Ws):
             for dim in (B.DIM_OC, B.DIM_IC):
@@ -159,6 +238,9 @@ class SharedSearch:
                                           shape=(self.out_f, self.in_f))
         for l in range(self.n_layers):
             self.ctx.adadim_select(self.losses[2 * l:2 * l + 2], best_dev=self.best[l:l + 1], to_host=False)
+
+    def result(self):
+        torch.cuda.synchronize()
         dims = self.best.cpu().tolist()          # the one synchronisation
         self.scales = [self._scales[2 * l + d] for l, d in enumerate(dims)]
         self.zeros = [self._zeros[2 * l + d] for l, d in enumerate(dims)]

@@ -123,6 +123,17 @@ def test_gemv_validation(ctx):
     assert ctx._lib.adadim_score_elems(300, 64) == 512 * 64 and ctx._lib.adadim_score_elems(300, 40) == 300 * 40
 
 
+def test_capture_validation(ctx):
+    """Graph recording: argument checks that need no device (the test context sits on the default stream)."""
+    assert ctx._lib.adadim_capture_begin(None) == B.ENULL
+    assert ctx.raw("adadim_capture_begin") == B.EINVAL                    # default stream cannot be recorded
+    assert "default stream" in ctx.last_error()
+    g = ctypes.c_void_p()
+    assert ctx.raw("adadim_capture_end", ctypes.byref(g)) == B.EINVAL      # not recording
+    assert ctx.raw("adadim_graph_launch", None) == B.ENULL
+    ctx._lib.adadim_graph_destroy(None)
+
+
 def test_create_destroy():
     lib = B.load_library()
     assert lib.adadim_create(None, None) == B.ENULL
