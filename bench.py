@@ -265,8 +265,7 @@ def main():
         # With more candidates than one scoring batch the winner is quantized again once it is known, so
         # that case waits for the answer inside every step.
         def step():
-            hp.update(Xd)
-            hp.prepare()
+            hp.update_prepared(Xd)
             if ls.inline:
                 ls.launch(Wd, hp)
             else:
@@ -280,8 +279,7 @@ def main():
         ls.cands = [(d, 1.0) for _ in layers for d in (B.DIM_OC, B.DIM_IC)]
 
         def step():
-            hp.update(Xd)
-            hp.prepare()
+            hp.update_prepared(Xd)
             ls.launch(Wds, hp)
 
         def finish():

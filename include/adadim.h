@@ -163,6 +163,15 @@ int adadim_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t 
 int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs, float* hmeta);
 
 /*
+ * adadim_hessian (accumulate = 0) and adadim_hessian_prepare in one call: the pass that adds up the Gram
+ * matrix's token-split partial tiles also writes Hs and hmeta, so H is not read back.  Same outputs, bit for
+ * bit, as the two calls one after the other.  For a calibration set fed in chunks use adadim_hessian with
+ * accumulate = 1 and adadim_hessian_prepare after the last chunk.
+ */
+int adadim_hessian_prepared(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx,
+                            float* H, void* Hs, float* hmeta);
+
+/*
  * Reconstruction error of one candidate (Eq. 1, squared):
  *   loss = tr(dW H dW^T) = ||X dW^T||_F^2,   loss_rows[o] = dW_o H dW_o^T.
  *   dW        [out, in] of type dW_dtype (F32 or F16; not F16_SCALED).

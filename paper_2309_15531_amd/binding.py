@@ -23,7 +23,7 @@ EXPORTS = (
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
-    "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
+    "adadim_hessian_prepared", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -87,6 +87,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_gemv_ic_meta16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
                                           c_void_p]
     lib.adadim_gemv_ic_meta16.restype = c_int
+    lib.adadim_hessian_prepared.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
+    lib.adadim_hessian_prepared.restype = c_int
     lib.adadim_capture_begin.argtypes = [c_void_p]
     lib.adadim_capture_begin.restype = c_int
     lib.adadim_capture_end.argtypes = [c_void_p, POINTER(c_void_p)]
@@ -195,6 +197,11 @@ class Context:
         """Flat fp16 device buffer large enough for an [rows, cols] operand in the scoring layout."""
         import torch
         return torch.empty(score_elems(rows, cols), dtype=torch.float16, device=device)
+
+    def adadim_hessian_prepared(self, X, H, Hs, hmeta, tokens: int | None = None):
+        t = X.shape[0] if tokens is None else tokens
+        self._check(self._lib.adadim_hessian_prepared(self._h, _ptr(X), t, X.shape[1], X.stride(0), _ptr(H), _ptr(Hs),
+                                                      _ptr(hmeta)))
 
     def adadim_hessian_prepare(self, H, Hs, hmeta):
         self._check(self._lib.adadim_hessian_prepare(self._h, _ptr(H), H.shape[0], _ptr(Hs), _ptr(hmeta)))

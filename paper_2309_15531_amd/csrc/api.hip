@@ -250,6 +250,27 @@ int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs
     return launch_hessian_prepare(ctx, H, in, static_cast<__half*>(Hs), hmeta);
 }
 
+int adadim_hessian_prepared(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx, float* H, void* Hs,
+                            float* hmeta) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!Hs || !hmeta) return adadim_fail(ctx, ADADIM_ENULL, "adadim_hessian_prepared: Hs or hmeta is NULL");
+    if (!aligned16(Hs) || !aligned16(hmeta))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_hessian_prepared: Hs and hmeta must be 16-byte aligned");
+    // the checks of adadim_hessian, then the fused launch
+    if (!H) return adadim_fail(ctx, ADADIM_ENULL, "adadim_hessian_prepared: H is NULL");
+    if (tokens < 0 || in <= 0 || ldx < in)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_hessian_prepared: need tokens >= 0, in > 0, ldx >= in "
+                                               "(tokens=%lld in=%lld ldx=%lld)",
+                           (long long)tokens, (long long)in, (long long)ldx);
+    if (in > (int64_t(1) << 20) || tokens > (int64_t(1) << 40))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_hessian_prepared: size out of range");
+    if (tokens > 0 && !X) return adadim_fail(ctx, ADADIM_ENULL, "adadim_hessian_prepared: X is NULL");
+    if ((in % 8) != 0 || (ldx % 8) != 0 || !aligned16(X) || !aligned16(H))
+        return adadim_fail(ctx, ADADIM_EALIGN,
+                           "adadim_hessian_prepared: in and ldx must be multiples of 8, X and H 16-byte aligned");
+    return launch_hessian_prepared(ctx, static_cast<const __half*>(X), tokens, in, ldx, H, static_cast<__half*>(Hs), hmeta);
+}
+
 static int check_error_args(adadim_ctx* ctx, const char* who, const void* dW, int dW_dtype, int64_t out,
                             int64_t in, const void* Hany, const float* loss, bool allow_scaled) {
     if (!dW || !Hany || !loss) return adadim_fail(ctx, ADADIM_ENULL, "%s: dW, H or loss is NULL", who);

@@ -120,6 +120,8 @@ int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, 
 int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
                    int accumulate);
 int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* Hs, float* hmeta);
+int launch_hessian_prepared(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
+                            __half* Hs, float* hmeta);
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
                        const __half* Hs, const float* hmeta, float* loss_rows, float* losses);
 int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev);

@@ -87,11 +87,45 @@ __global__ __launch_bounds__(THREADS) void gram_tiles(const __half* __restrict__
 // REGMAJOR: the partial tiles are in the register order of the DMA tile kernel (float4 number
 // ((i*4 + j)*4 + q)*256 + thread holds accumulator registers 4q..4q+3 of that thread's 32x32 block
 // (i, j)), which for thread (tx, ty) here is one 16-byte load: rows 4*ty..4*ty+3 of column tx.
-template <int BT, bool REGMAJOR = false>
+//
+// PREP (accumulate == 0 only): the same pass also writes what adadim_hessian_prepare derives from H, so
+// that H is not read back and two launches fall away: hmeta (from the diagonal blocks) and the scaled
+// fp16 Hs in the scoring layout, Hs[n,k] = H[n,k]/(d_n d_k) for k < n and 0 elsewhere.  The block
+// needs d for its 32 rows and 32 columns: each is a function of a diagonal entry of H, which the
+// block adds up itself from the partial diagonal tiles, in the same order as the block that owns
+// that entry, hence to the same bits.
+
+// index of the diagonal tile (I, I) in decode_tile's order
+__device__ __forceinline__ int diag_tile_index(int I, int nb) {
+    const int s = I >> 2;
+    int base = 0;
+    for (int t = 0; t < s; ++t) {
+        const int rows = min(4, nb - 4 * t);
+        base += rows * (rows + 1) / 2 + rows * max(0, nb - 4 * t - 4);
+    }
+    const int c = I - 4 * s;
+    return base + c * (c + 1) / 2 + c;
+}
+
+// d = 2^round(log2(h)/2) (1 if h <= 0): any power of two near sqrt(h) serves; the exponent is clamped
+// so that d, 1/d and d*d stay normal fp32 numbers
+__device__ __forceinline__ float jacobi_scale(float h) {
+    float d = 1.0f;
+    if (h > 0.0f && h < 3.0e38f) {
+        int e = static_cast<int>(rintf(0.5f * log2f(h)));
+        e = max(-30, min(30, e));
+        d = ldexpf(1.0f, e);
+    }
+    return d;
+}
+
+template <int BT, bool REGMAJOR = false, bool PREP = false>
 __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ part, int n_tiles, int n_split,
-                                                   int nb, int64_t in, float* __restrict__ H, int accumulate) {
+                                                   int nb, int64_t in, float* __restrict__ H, int accumulate,
+                                                   __half* __restrict__ Hs, float* __restrict__ hmeta) {
     constexpr int SB = BT / 32;
     __shared__ float s[32][33];
+    __shared__ float s_rd[2][32];                             // PREP: 1/d of the block's rows and columns
     const int tile = blockIdx.x / (SB * SB), sub = blockIdx.x % (SB * SB);
     int I, J;
     decode_tile(tile, nb, I, J);
@@ -123,8 +157,56 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
             s[r][tx] = v;
         }
     }
-    __syncthreads();
     const bool diag = R0 == C0;
+    if constexpr (PREP) {
+        if (threadIdx.x < 64) {
+            const int which = threadIdx.x >> 5, a = threadIdx.x & 31;   // 0: the block's rows, 1: its columns
+            const int T = which ? J : I, sb = which ? sc : sr;
+            const int64_t j = int64_t(T) * BT + sb * 32 + a;
+            float h = 0.0f;
+            if (j < in) {
+                int64_t off;
+                if constexpr (REGMAJOR) {
+                    const int ty2 = a >> 2, w2 = 3 * (sb >> 2);
+                    off = ((((sb & 3) * 5) * 4 + (ty2 >> 1)) * 256 + w2 * 64 + (ty2 & 1) * 32 + a) * 4 + (a & 3);
+                } else {
+                    off = int64_t(sb * 32 + a) * BT + sb * 32 + a;
+                }
+                const float* dsrc = part + int64_t(diag_tile_index(T, nb)) * (int64_t(BT) * BT) + off;
+                for (int sp = 0; sp < n_split; ++sp) h += dsrc[sp * split_stride];
+            }
+            const float d = jacobi_scale(h);
+            s_rd[which][a] = 1.0f / d;                        // exact: a power of two
+            if (diag && which == 0 && j < in) {
+                hmeta[j] = d;
+                hmeta[in + j] = h;
+            }
+        }
+    }
+    __syncthreads();
+    if constexpr (PREP) {
+        // 16-byte stores: a row of the block is 32 fp16 = four pieces.  Threads 0..127 write the mirrored
+        // block Hs[n = C0 + nl][k = R0 + kq ..+7] = H[k][n] / (d_n d_k), threads 128..255 the zeros above
+        // the diagonal, Hs[n = R0 + nl][k = C0 + kq ..+7].  in % 8 == 0: a piece is inside or outside whole.
+        const int t = threadIdx.x & 127, nl = t >> 2, kq = (t & 3) * 8;
+        if (threadIdx.x < 128) {
+            const int64_t n = C0 + nl, k = R0 + kq;
+            if (n < in && k < in) {
+                uint4 o;
+                __half2* h = reinterpret_cast<__half2*>(&o);
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const float v0 = k + e < n ? s[kq + e][nl] * s_rd[1][nl] * s_rd[0][kq + e] : 0.0f;
+                    const float v1 = k + e + 1 < n ? s[kq + e + 1][nl] * s_rd[1][nl] * s_rd[0][kq + e + 1] : 0.0f;
+                    h[e / 2] = __floats2half2_rn(v0, v1);
+                }
+                *reinterpret_cast<uint4*>(Hs + score_index(n, k, in, in)) = o;
+            }
+        } else if (!diag) {
+            const int64_t n = R0 + nl, k = C0 + kq;
+            if (n < in && k < in) *reinterpret_cast<uint4*>(Hs + score_index(n, k, in, in)) = make_uint4(0, 0, 0, 0);
+        }
+    }
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int r = ty * 4 + rr;
@@ -153,14 +235,7 @@ __global__ void hprep_meta(const float* __restrict__ H, int64_t in, float* __res
     const int64_t j = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (j >= in) return;
     const float h = H[j * in + j];
-    float d = 1.0f;
-    if (h > 0.0f && h < 3.0e38f) {
-        // any power of two near sqrt(h) serves; the exponent is clamped so that
-        // d, 1/d and d*d stay normal fp32 numbers
-        int e = static_cast<int>(rintf(0.5f * log2f(h)));
-        e = max(-30, min(30, e));
-        d = ldexpf(1.0f, e);
-    }
+    const float d = jacobi_scale(h);
     hmeta[j] = d;
     hmeta[in + j] = h;
 }
@@ -203,7 +278,8 @@ __global__ __launch_bounds__(256) void hprep_scale(const float* __restrict__ H, 
 }
 
 template <int BT>
-int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H, int accumulate) {
+int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H, int accumulate,
+             __half* Hs, float* hmeta) {
     const int nb = static_cast<int>((in + BT - 1) / BT);
     const int n_tiles = nb * (nb + 1) / 2;
     // Token split: every (tile, split) is one workgroup and one workgroup fits a compute unit, so
@@ -319,8 +395,12 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
     constexpr int SB = BT / 32;
     {
         ProfScope prof(ctx, "gram_reduce");
-        hipLaunchKernelGGL((gram_reduce<BT, BT == 256>), dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream, part,
-                           n_tiles, n_split, nb, in, H, accumulate);
+        if (Hs)
+            hipLaunchKernelGGL((gram_reduce<BT, BT == 256, true>), dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream,
+                               part, n_tiles, n_split, nb, in, H, 0, Hs, hmeta);
+        else
+            hipLaunchKernelGGL((gram_reduce<BT, BT == 256, false>), dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream,
+                               part, n_tiles, n_split, nb, in, H, accumulate, Hs, hmeta);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gram_reduce");
     return ADADIM_OK;
@@ -342,8 +422,19 @@ int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in,
         }
         return ADADIM_OK;
     }
-    if (in <= 1024) return run_gram<128>(ctx, X, tokens, in, ldx, H, accumulate);
-    return run_gram<256>(ctx, X, tokens, in, ldx, H, accumulate);
+    if (in <= 1024) return run_gram<128>(ctx, X, tokens, in, ldx, H, accumulate, nullptr, nullptr);
+    return run_gram<256>(ctx, X, tokens, in, ldx, H, accumulate, nullptr, nullptr);
+}
+
+// H = X^T X together with its prepared form (see gram_reduce, PREP)
+int launch_hessian_prepared(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
+                            __half* Hs, float* hmeta) {
+    if (tokens == 0) {
+        const int rc = launch_hessian(ctx, X, tokens, in, ldx, H, 0);
+        return rc != ADADIM_OK ? rc : launch_hessian_prepare(ctx, H, in, Hs, hmeta);
+    }
+    if (in <= 1024) return run_gram<128>(ctx, X, tokens, in, ldx, H, 0, Hs, hmeta);
+    return run_gram<256>(ctx, X, tokens, in, ldx, H, 0, Hs, hmeta);
 }
 
 int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* Hs, float* hmeta) {

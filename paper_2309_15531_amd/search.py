@@ -37,6 +37,12 @@ class PreparedHessian:
         self.ctx.adadim_hessian_prepare(self.H, self.Hs, self.hmeta)
         return self
 
+    def update_prepared(self, X):
+        """update(X) and prepare() in one call (adadim_hessian_prepared): for a calibration set that comes whole."""
+        self.ctx.adadim_hessian_prepared(X, self.H, self.Hs, self.hmeta)
+        self.tokens = X.shape[0]
+        return self
+
     @property
     def colscale(self):
         return self.hmeta[0]
@@ -158,8 +164,7 @@ class GraphedSearch:
             self.graph = ctx.adadim_capture_end()
 
     def _step(self):
-        self.hp.update(self.X)
-        self.hp.prepare()
+        self.hp.update_prepared(self.X)
         self.ls.score_all(self.W, self.hp)
         self.ctx.adadim_select(self.ls.losses, best_dev=self.ls.best, to_host=False)
 

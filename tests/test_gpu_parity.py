@@ -391,3 +391,32 @@ def test_shared_input_search(ctx):
         torch.cuda.synchronize()
         assert single.losses.cpu().numpy() == pytest.approx(got[l], rel=1e-5)   # same kernels, other chunking
         _check_winner(sh.scales[l], sh.zeros[l], sh.packed[l], W, dims[l], bits, group)
+
+
+@pytest.mark.parametrize("tokens,in_f", [(300, 512), (2500, 264), (77, 1288), (5000, 2080), (9000, 4096), (1, 64),
+                                         (0, 256)])
+def test_hessian_prepared_equals_the_two_calls(ctx, tokens, in_f):
+    """adadim_hessian_prepared against adadim_hessian + adadim_hessian_prepare: H, hmeta and Hs bit for bit (both
+    tile widths, one and several token splits, both scoring layouts, ragged last tiles)."""
+    X = synth.make_activations(max(tokens, 1), in_f, seed=tokens + in_f, n_outliers=min(4, in_f), scale_lo=50,
+                               scale_hi=100)[:tokens]
+    Xd = dev(X) if tokens else torch.empty((0, in_f), dtype=torch.float16, device="cuda")
+    outs = []
+    for fused in (False, True):
+        H = torch.full((in_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+        Hs = ctx.alloc_score(in_f, in_f).fill_(float("nan"))
+        hmeta = torch.full((2, in_f), float("nan"), dtype=torch.float32, device="cuda")
+        if fused:
+            ctx.adadim_hessian_prepared(Xd, H, Hs, hmeta, tokens=tokens)
+        else:
+            ctx.adadim_hessian(Xd, H, tokens=tokens)
+            ctx.adadim_hessian_prepare(H, Hs, hmeta)
+        torch.cuda.synchronize()
+        outs.append((H.cpu().numpy(), hmeta.cpu().numpy(), B.from_score_layout(Hs.cpu().numpy(), in_f, in_f)))
+    (H0, m0, s0), (H1, m1, s1) = outs
+    assert np.array_equal(H0.view(np.uint32), H1.view(np.uint32))
+    assert np.array_equal(m0.view(np.uint32), m1.view(np.uint32))
+    assert np.array_equal(s0.view(np.uint16), s1.view(np.uint16))
+    if tokens:
+        check_hessian(H1, oracle.hessian(X))
+        assert not np.triu(s1.astype(np.float32)).any()          # zero on and above the diagonal
