@@ -197,6 +197,15 @@ int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int 
                              int64_t in, const void* Hs, const float* hmeta, float* loss_rows, float* losses);
 
 /*
+ * adadim_layer_error_batch followed by adadim_select(losses, n, best_dev) in one call: the block that writes the
+ * last loss also takes the argmin (same rule as adadim_select), one launch less per layer.  best_dev is a device
+ * int32 and is required.
+ */
+int adadim_layer_error_batch_select(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out,
+                                    int64_t in, const void* Hs, const float* hmeta, float* loss_rows, float* losses,
+                                    int32_t* best_dev);
+
+/*
  * Eq. 1's argmin: index of the first minimum of losses[0..n) (a later
  * candidate wins only if strictly lower, as in App. B where 'oc' is visited
  * before 'ic').  NaN entries never win.

@@ -23,7 +23,7 @@ EXPORTS = (
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
-    "adadim_hessian_prepared", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
+    "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -107,6 +107,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_layer_error_batch.argtypes = [c_void_p, c_int, POINTER(c_void_p), c_int, c_int64, c_int64, c_void_p,
                                              c_void_p, c_void_p, c_void_p]
     lib.adadim_layer_error_batch.restype = c_int
+    lib.adadim_layer_error_batch_select.argtypes = [c_void_p, c_int, POINTER(c_void_p), c_int, c_int64, c_int64,
+                                                    c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.adadim_layer_error_batch_select.restype = c_int
     lib.adadim_select.argtypes = [c_void_p, c_void_p, c_int, c_void_p, POINTER(c_int32)]
     lib.adadim_select.restype = c_int
     lib.adadim_profile.argtypes = [c_void_p, c_int]
@@ -222,6 +225,12 @@ class Context:
         arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
         self._check(self._lib.adadim_layer_error_batch(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
                                                        _ptr(hmeta), _ptr(loss_rows), _ptr(losses)))
+
+    def adadim_layer_error_batch_select(self, dWs, dW_dtype: int, Hs, hmeta, losses, best_dev, loss_rows=None, shape=None):
+        out_f, in_f = dWs[0].shape if shape is None else shape
+        arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
+        self._check(self._lib.adadim_layer_error_batch_select(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
+                                                              _ptr(hmeta), _ptr(loss_rows), _ptr(losses), _ptr(best_dev)))
 
     def adadim_select(self, losses, n: int | None = None, best_dev=None, to_host: bool = True):
         n = losses.numel() if n is None else n

@@ -310,8 +310,8 @@ int adadim_layer_error_prepared(adadim_ctx* ctx, const void* dW, int dW_dtype, i
                               loss);
 }
 
-int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
-                             const void* Hs, const float* hmeta, float* loss_rows, float* losses) {
+static int error_batch_checked(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
+                               const void* Hs, const float* hmeta, float* loss_rows, float* losses, int32_t* best_dev) {
     if (!ctx) return ADADIM_ENULL;
     if (n <= 0 || n > 4096) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_layer_error_batch: bad n=%d", n);
     if (!dW) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch: dW is NULL");
@@ -323,7 +323,19 @@ int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int 
     if (!aligned16(hmeta))
         return adadim_fail(ctx, ADADIM_EALIGN, "adadim_layer_error_batch: hmeta must be 16-byte aligned");
     return launch_layer_error(ctx, n, dW, dW_dtype, out, in, static_cast<const __half*>(Hs), hmeta, loss_rows,
-                              losses);
+                              losses, best_dev);
+}
+
+int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
+                             const void* Hs, const float* hmeta, float* loss_rows, float* losses) {
+    return error_batch_checked(ctx, n, dW, dW_dtype, out, in, Hs, hmeta, loss_rows, losses, nullptr);
+}
+
+int adadim_layer_error_batch_select(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out,
+                                    int64_t in, const void* Hs, const float* hmeta, float* loss_rows, float* losses,
+                                    int32_t* best_dev) {
+    if (ctx && !best_dev) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch_select: best_dev is NULL");
+    return error_batch_checked(ctx, n, dW, dW_dtype, out, in, Hs, hmeta, loss_rows, losses, best_dev);
 }
 
 int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best) {

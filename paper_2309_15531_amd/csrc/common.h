@@ -123,7 +123,8 @@ int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* 
 int launch_hessian_prepared(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,
                             __half* Hs, float* hmeta);
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
-                       const __half* Hs, const float* hmeta, float* loss_rows, float* losses);
+                       const __half* Hs, const float* hmeta, float* loss_rows, float* losses,
+                       int32_t* best_dev = nullptr);
 int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev);
 int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percdamp, int act_order, int32_t* perm,
                         uint8_t* dead, float* U);

@@ -87,12 +87,16 @@ __global__ __launch_bounds__(256) void error_prologue(SrcBatch src, int dW_dtype
 // the diagonal term into its row sums) for 256 rows per block, a per-block total,
 // and, in the block that finishes last, loss = sum of the block totals in block order (so the
 // result does not depend on which block that is).  `ticket` must be zero on entry and is zero
-// again on exit.
+// again on exit.  With `best` given, the block that writes the launch's last loss also takes the
+// argmin of sel_losses[0..n_sel) (first minimum, NaN never wins, as select_first_min): one launch
+// and one kernel boundary less than a separate selection.
 __global__ __launch_bounds__(256) void error_finish(const float* __restrict__ diag_all,
                                                     const float* __restrict__ part_all, int64_t out, int n_slots,
                                                     float* __restrict__ loss_rows_all, float* __restrict__ loss_all,
                                                     double* __restrict__ block_tot_all,
-                                                    unsigned int* __restrict__ ticket_all) {
+                                                    unsigned int* __restrict__ ticket_all,
+                                                    const float* __restrict__ sel_losses, int n_sel,
+                                                    int32_t* __restrict__ best) {
     __shared__ double s_red[256];
     __shared__ bool s_last;
     // blockIdx.y = candidate
@@ -136,6 +140,25 @@ __global__ __launch_bounds__(256) void error_finish(const float* __restrict__ di
     if (threadIdx.x == 0) {
         *loss = static_cast<float>(s_red[0]);
         *ticket = 0u;
+        if (best) {
+            unsigned int* done = ticket_all + 32;             // candidates of this launch whose loss is written
+            __threadfence();
+            if (atomicAdd(done, 1u) == gridDim.y - 1) {
+                __threadfence();
+                int b = -1;
+                float bv = 0.0f;
+                for (int i = 0; i < n_sel; ++i) {
+                    const float v = __builtin_nontemporal_load(sel_losses + i);
+                    if (v != v) continue;
+                    if (b < 0 || v < bv) {
+                        b = i;
+                        bv = v;
+                    }
+                }
+                *best = b < 0 ? 0 : b;
+                *done = 0u;
+            }
+        }
     }
 }
 
@@ -162,7 +185,7 @@ __global__ void select_first_min(const float* __restrict__ losses, int n, int32_
 }  // namespace
 
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
-                       const __half* Hs, const float* hmeta, float* loss_rows, float* losses) {
+                       const __half* Hs, const float* hmeta, float* loss_rows, float* losses, int32_t* best_dev) {
     constexpr int BT = edma::BT;
     const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
     void* zero16 = adadim_workspace(ctx, WS_ZERO, 256);
@@ -253,7 +276,7 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
             hipLaunchKernelGGL(error_finish, dim3(fin_blocks, nc), dim3(256), 0, ctx->stream,
                                direct ? static_cast<const float*>(nullptr) : diag, part, out, n_slots,
                                loss_rows ? loss_rows + size_t(c0) * size_t(out) : nullptr, losses + c0, block_tot,
-                               ticket);
+                               ticket, losses, n, c0 + nc == n ? best_dev : nullptr);
         }
         ADADIM_LAUNCH_CHECK(ctx, "error_finish");
     }

@@ -89,15 +89,22 @@ class LayerSearch:
         else:
             self.inline = False
 
-    def score_all(self, W, hp: PreparedHessian):
-        """Quantizes and scores every candidate; losses stay on the device."""
+    def score_all(self, W, hp: PreparedHessian, select: bool = False):
+        """Quantizes and scores every candidate; losses stay on the device.  select: also leave the winning
+        index in self.best (taken by the scoring call itself when the candidates fit one batch)."""
         for c0 in range(0, len(self.cands), self.batch):
             chunk = self.cands[c0:c0 + self.batch]
             for k, (dim, clip) in enumerate(chunk):
                 self._quantize(W, dim, clip, c0 + k if self.inline else None, dW=self.dWs[k],
                                dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
+            if select and len(chunk) == len(self.cands):
+                self.ctx.adadim_layer_error_batch_select(self.dWs[:len(chunk)], B.DW_F16_SCALED, hp.Hs, hp.hmeta,
+                                                         self.losses, self.best, shape=(self.out_f, self.in_f))
+                return
             self.ctx.adadim_layer_error_batch(self.dWs[:len(chunk)], B.DW_F16_SCALED, hp.Hs, hp.hmeta,
                                               self.losses[c0:c0 + len(chunk)], shape=(self.out_f, self.in_f))
+        if select:
+            self.ctx.adadim_select(self.losses, best_dev=self.best, to_host=False)
 
     def _quantize(self, W, dim, clip, out_set, **kw):
         """One candidate; out_set names the output set that receives its parameters and packed codes."""
@@ -113,8 +120,7 @@ class LayerSearch:
     def launch(self, W, hp: PreparedHessian):
         """Queues the whole search for one layer and returns at once: the losses and the winning index stay on
         the device until `result` asks for them, so a driver can queue the next layer meanwhile."""
-        self.score_all(W, hp)
-        self.ctx.adadim_select(self.losses, best_dev=self.best, to_host=False)
+        self.score_all(W, hp, select=True)
         self._W = W
 
     def result(self):
@@ -165,8 +171,7 @@ class GraphedSearch:
 
     def _step(self):
         self.hp.update_prepared(self.X)
-        self.ls.score_all(self.W, self.hp)
-        self.ctx.adadim_select(self.ls.losses, best_dev=self.ls.best, to_host=False)
+        self.ls.score_all(self.W, self.hp, select=True)
 
     def launch(self):
         """Queues one replay on the current contents of W and X."""

@@ -420,3 +420,35 @@ def test_hessian_prepared_equals_the_two_calls(ctx, tokens, in_f):
     if tokens:
         check_hessian(H1, oracle.hessian(X))
         assert not np.triu(s1.astype(np.float32)).any()          # zero on and above the diagonal
+
+
+def test_layer_error_batch_select(ctx):
+    """The scoring call that also selects: same losses as adadim_layer_error_batch, same index as adadim_select,
+    over several calls in a row (its tickets must be back at zero each time), ties and NaN included."""
+    out_f, in_f = 512, 520
+    X = synth.make_activations(300, in_f, seed=5, n_outliers=3, scale_lo=50, scale_hi=100)
+    H = dev(oracle.hessian(X).astype(np.float32))
+    Hs = ctx.alloc_score(in_f, in_f)
+    hmeta = torch.empty((2, in_f), dtype=torch.float32, device="cuda")
+    ctx.adadim_hessian_prepare(H, Hs, hmeta)
+    rng = np.random.default_rng(0)
+    for n, twin in ((2, None), (5, (1, 3)), (8, (0, 7)), (3, None)):
+        dWs = [(rng.standard_normal((out_f, in_f)) * 1e-3 * (1 + c)).astype(np.float32) for c in range(n)]
+        if twin:
+            dWs[twin[1]] = dWs[twin[0]].copy()                    # a tie: the first one wins
+        if n == 3:
+            dWs[0][7, 9] = np.nan                                 # a NaN loss never wins
+        dev_dWs = [dev(d) for d in dWs]
+        ref_losses = torch.empty(n, dtype=torch.float32, device="cuda")
+        ctx.adadim_layer_error_batch(dev_dWs, B.DW_F32, Hs, hmeta, ref_losses)
+        ref_best = ctx.adadim_select(ref_losses)
+        losses = torch.full((n,), -1.0, dtype=torch.float32, device="cuda")
+        best = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        ctx.adadim_layer_error_batch_select(dev_dWs, B.DW_F32, Hs, hmeta, losses, best)
+        torch.cuda.synchronize()
+        assert torch.equal(losses.cpu().nan_to_num(nan=-1.0), ref_losses.cpu().nan_to_num(nan=-1.0))
+        assert int(best.item()) == ref_best
+        if n != 3:                                                # the oracle's argmin is not defined for NaN
+            assert ref_best == oracle.select(ref_losses.cpu().numpy().astype(np.float64).tolist())
+        else:
+            assert ref_best == 1
