@@ -93,64 +93,92 @@ __global__ void gq_gather(const float* __restrict__ H, int64_t n, const int32_t*
 // result is D[4 r + l / 16][l % 16].  The vector and the matrix pipe have the same fp64 peak on this
 // chip; the matrix form needs a quarter of the LDS reads per flop and no issue slots for the products.
 typedef double double4_t __attribute__((ext_vector_type(4)));
-constexpr int GT = 64, GK = 16, GP = GT + 4;     // tile edge, contraction chunk, LDS pitch (doubles)
+constexpr int GT = 64, GK = 16;                  // tile edge, contraction chunk
+// (128 x 128 tiles were measured too: one workgroup per compute unit instead of four, and the
+// products ran a third slower; the matrix pipe wants the other workgroups' waves to fill its gaps.)
 
-// acc += A B for one 64 x 64 tile and k in [k_lo, k_hi), 256 threads (2 x 2 waves of 32 x 32).
+// acc += A B for one TS x TS tile (TS = 64 or 128) and k in [k_lo, k_hi), 256 threads: 2 x 2 waves,
+// each TS/2 x TS/2 = MT x MT matrix-core tiles of 16 x 16.
 //   A(i, k) = Ap[i * lda + k], rows i < m_valid;
 //   B(k, j) = B_KC ? Bp[j * ldb + k] : Bp[k * ldb + j], columns j < n_valid;
-// everything outside the valid ranges reads as zero.  As, Bs: [GK][GP] doubles each.
-template <bool B_KC>
+// everything outside the valid ranges reads as zero.  As, Bs: [GK][TS + 4] doubles each.
+template <int TS, bool B_KC>
 __device__ __forceinline__ void dgemm_tile(const double* __restrict__ Ap, int64_t lda, int m_valid,
                                            const double* __restrict__ Bp, int64_t ldb, int n_valid, int64_t k_lo,
-                                           int64_t k_hi, double (*As)[GP], double (*Bs)[GP], double4_t (&acc)[2][2]) {
+                                           int64_t k_hi, double (*As)[TS + 4], double (*Bs)[TS + 4],
+                                           double4_t (&acc)[TS / 32][TS / 32]) {
+    constexpr int MT = TS / 32, E = TS / 16;              // matrix-core tiles per wave side; elements per thread and operand
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, wm = wave >> 1, wn = wave & 1;
-    const int li = t >> 2, lk = (t & 3) * 4;              // k-contiguous operand: row li, four consecutive k
-    const int bk = t >> 4, bj = (t & 15) * 4;             // row-major B: contraction row bk, four consecutive columns
-    for (int64_t k0 = k_lo; k0 < k_hi; k0 += GK) {
-        __syncthreads();
+    // Loads: 16 consecutive lanes read 16 consecutive doubles (one 128-byte line).  For an operand
+    // that is contiguous along k they are the chunk's 16 k of one row (rows t/16 + 16 e); for the
+    // row-major B they are 16 columns of one k row (k row t/16, columns t%16 + 16 e).
+    const int l16 = t & 15, h16 = t >> 4;
+    double ra[E], rb[E];
+    // the next chunk's operands travel from memory to registers while the matrix cores work on this one
+    auto fetch = [&](int64_t k0) {
+        const int64_t k = k0 + l16;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int64_t k = k0 + lk + e;
-            As[lk + e][li] = (li < m_valid && k < k_hi) ? Ap[li * lda + k] : 0.0;
+        for (int e = 0; e < E; ++e) {
+            const int row = h16 + 16 * e;
+            ra[e] = (row < m_valid && k < k_hi) ? Ap[row * lda + k] : 0.0;
         }
         if constexpr (B_KC) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int64_t k = k0 + lk + e;
-                Bs[lk + e][li] = (li < n_valid && k < k_hi) ? Bp[li * ldb + k] : 0.0;
+            for (int e = 0; e < E; ++e) {
+                const int row = h16 + 16 * e;
+                rb[e] = (row < n_valid && k < k_hi) ? Bp[row * ldb + k] : 0.0;
             }
         } else {
-            const int64_t k = k0 + bk;
+            const int64_t kr = k0 + h16;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) Bs[bk][bj + e] = (k < k_hi && bj + e < n_valid) ? Bp[k * ldb + bj + e] : 0.0;
+            for (int e = 0; e < E; ++e) {
+                const int col = l16 + 16 * e;
+                rb[e] = (kr < k_hi && col < n_valid) ? Bp[kr * ldb + col] : 0.0;
+            }
         }
+    };
+    if (k_lo < k_hi) fetch(k_lo);
+    for (int64_t k0 = k_lo; k0 < k_hi; k0 += GK) {
         __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < GK; ks += 4) {
-            double a[2], b[2];
+        for (int e = 0; e < E; ++e) As[l16][h16 + 16 * e] = ra[e];
+        if constexpr (B_KC) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                a[u] = As[ks + (lane >> 4)][wm * 32 + u * 16 + (lane & 15)];
-                b[u] = Bs[ks + (lane >> 4)][wn * 32 + u * 16 + (lane & 15)];
+            for (int e = 0; e < E; ++e) Bs[l16][h16 + 16 * e] = rb[e];
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) Bs[h16][l16 + 16 * e] = rb[e];
+        }
+        __syncthreads();
+        if (k0 + GK < k_hi) fetch(k0 + GK);
+#pragma unroll
+        for (int ks = 0; ks < GK; ks += 4) {
+            double a[MT], b[MT];
+#pragma unroll
+            for (int u = 0; u < MT; ++u) {
+                a[u] = As[ks + (lane >> 4)][wm * (TS / 2) + u * 16 + (lane & 15)];
+                b[u] = Bs[ks + (lane >> 4)][wn * (TS / 2) + u * 16 + (lane & 15)];
             }
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < MT; ++u)
 #pragma unroll
-                for (int v = 0; v < 2; ++v) acc[u][v] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[v], acc[u][v], 0, 0, 0);
+                for (int v = 0; v < MT; ++v) acc[u][v] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[u], b[v], acc[u][v], 0, 0, 0);
         }
     }
 }
 
 // visits the tile's elements this lane holds: f(row in tile, column in tile, value)
-template <typename F>
-__device__ __forceinline__ void dgemm_each(const double4_t (&acc)[2][2], F f) {
+template <int TS, typename F>
+__device__ __forceinline__ void dgemm_each(const double4_t (&acc)[TS / 32][TS / 32], F f) {
+    constexpr int MT = TS / 32;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < MT; ++u)
 #pragma unroll
-        for (int v = 0; v < 2; ++v)
+        for (int v = 0; v < MT; ++v)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) f(wm * 32 + u * 16 + 4 * r + (lane >> 4), wn * 32 + v * 16 + (lane & 15), acc[u][v][r]);
+            for (int r = 0; r < 4; ++r)
+                f(wm * (TS / 2) + u * 16 + 4 * r + (lane >> 4), wn * (TS / 2) + v * 16 + (lane & 15), acc[u][v][r]);
 }
 
 // ------------------------------------------------------------------ Cholesky, lower, in place
@@ -237,28 +265,29 @@ __global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, doub
 // only the rows it writes, and has read them all before the first store)
 __global__ __launch_bounds__(256) void chol_panel(double* __restrict__ A, const double* __restrict__ M, int64_t n,
                                                   int64_t k0, int w) {
-    __shared__ double As[GK][GP], Bs[GK][GP];
+    __shared__ double As[GK][GT + 4], Bs[GK][GT + 4];
     const int64_t r0 = k0 + w + int64_t(blockIdx.x) * GT;
     const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT);
     double4_t acc[2][2] = {};
-    dgemm_tile<true>(A + r0 * n + k0, n, m_valid, M + k0 * n + k0, n, w, 0, w, As, Bs, acc);
+    dgemm_tile<GT, true>(A + r0 * n + k0, n, m_valid, M + k0 * n + k0, n, w, 0, w, As, Bs, acc);
     __syncthreads();
-    dgemm_each(acc, [&](int i, int j, double v) {
+    dgemm_each<GT>(acc, [&](int i, int j, double v) {
         if (i < m_valid && j < w) A[(r0 + i) * n + k0 + j] = v;
     });
 }
 
-// trailing update: C[r][c] -= sum_t P[r][t] P[c][t] on the 64 x 64 tiles (blockIdx.y, blockIdx.x <= blockIdx.y)
+// trailing update: C[r][c] -= sum_t P[r][t] P[c][t] on the TS x TS tiles (blockIdx.y, blockIdx.x <= blockIdx.y)
 // of the rows/columns from k1 on; P = A[.., k0..k0+w).  gridDim.x limits the columns that are updated
 // (inside a 256-wide outer panel only the panel's own columns; behind it all, with w = 256).
+template <int TS>
 __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t n, int64_t k0, int w, int64_t k1) {
     if (blockIdx.x > blockIdx.y) return;
-    __shared__ double As[GK][GP], Bs[GK][GP];
-    const int64_t r0 = k1 + int64_t(blockIdx.y) * GT, c0 = k1 + int64_t(blockIdx.x) * GT;
-    const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT), n_valid = static_cast<int>(n - c0 < GT ? n - c0 : GT);
-    double4_t acc[2][2] = {};
-    dgemm_tile<true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
-    dgemm_each(acc, [&](int i, int j, double v) {
+    __shared__ double As[GK][TS + 4], Bs[GK][TS + 4];
+    const int64_t r0 = k1 + int64_t(blockIdx.y) * TS, c0 = k1 + int64_t(blockIdx.x) * TS;
+    const int m_valid = static_cast<int>(n - r0 < TS ? n - r0 : TS), n_valid = static_cast<int>(n - c0 < TS ? n - c0 : TS);
+    double4_t acc[TS / 32][TS / 32] = {};
+    dgemm_tile<TS, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
+    dgemm_each<TS>(acc, [&](int i, int j, double v) {
         if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] -= v;
     });
 }
@@ -269,26 +298,27 @@ __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t
 // and b0 = a0 + s (B, sb <= s rows at the matrix end).  Two products per level, every pair and
 // every tile in parallel: T = C inv(A) (PASS 0, inv(A) lower triangular: k starts at the tile's
 // first column), then M[B rows, A columns] = -inv(B) T (PASS 1, k ends with the tile's last row).
-template <int PASS>
+// TS x TS tiles, TS dividing s.
+template <int PASS, int TS>
 __global__ __launch_bounds__(256) void trinv_level(const double* __restrict__ L, double* __restrict__ M,
                                                    double* __restrict__ T, int64_t n, int64_t s) {
     const int64_t a0 = 2 * int64_t(blockIdx.z) * s, b0 = a0 + s;
     const int64_t sb = n - b0 < s ? n - b0 : s;               // > 0 for every pair in the grid
-    const int64_t m0 = int64_t(blockIdx.y) * GT, n0 = int64_t(blockIdx.x) * GT;
+    const int64_t m0 = int64_t(blockIdx.y) * TS, n0 = int64_t(blockIdx.x) * TS;
     if (m0 >= sb) return;
-    __shared__ double As[GK][GP], Bs[GK][GP];
-    const int m_valid = static_cast<int>(sb - m0 < GT ? sb - m0 : GT);
+    __shared__ double As[GK][TS + 4], Bs[GK][TS + 4];
+    const int m_valid = static_cast<int>(sb - m0 < TS ? sb - m0 : TS);
     double* Tp = T + int64_t(blockIdx.z) * s * s;
-    double4_t acc[2][2] = {};
+    double4_t acc[TS / 32][TS / 32] = {};
     if constexpr (PASS == 0) {
-        dgemm_tile<false>(L + (b0 + m0) * n + a0, n, m_valid, M + a0 * n + a0 + n0, n, GT, n0, s, As, Bs, acc);
-        dgemm_each(acc, [&](int i, int j, double v) {
+        dgemm_tile<TS, false>(L + (b0 + m0) * n + a0, n, m_valid, M + a0 * n + a0 + n0, n, TS, n0, s, As, Bs, acc);
+        dgemm_each<TS>(acc, [&](int i, int j, double v) {
             if (i < m_valid) Tp[(m0 + i) * s + n0 + j] = v;
         });
     } else {
-        const int64_t k_hi = sb < m0 + GT ? sb : m0 + GT;
-        dgemm_tile<false>(M + (b0 + m0) * n + b0, n, m_valid, Tp + n0, s, GT, 0, k_hi, As, Bs, acc);
-        dgemm_each(acc, [&](int i, int j, double v) {
+        const int64_t k_hi = sb < m0 + TS ? sb : m0 + TS;
+        dgemm_tile<TS, false>(M + (b0 + m0) * n + b0, n, m_valid, Tp + n0, s, TS, 0, k_hi, As, Bs, acc);
+        dgemm_each<TS>(acc, [&](int i, int j, double v) {
             if (i < m_valid) M[(b0 + m0 + i) * n + a0 + n0 + j] = -v;
         });
     }
@@ -612,21 +642,21 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
                 const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
                 hipLaunchKernelGGL(chol_panel, dim3(t), dim3(256), 0, ctx->stream, A, M, n, k0, w);
                 const unsigned tc = static_cast<unsigned>((K0 + W - (k0 + w) + GT - 1) / GT);
-                if (tc > 0) hipLaunchKernelGGL(chol_syrk, dim3(tc, t), dim3(256), 0, ctx->stream, A, n, k0, w, k0 + w);
+                if (tc > 0) hipLaunchKernelGGL(chol_syrk<GT>, dim3(tc, t), dim3(256), 0, ctx->stream, A, n, k0, w, k0 + w);
             }
         }
         const int64_t rest = n - K0 - W;
         if (rest > 0) {
             const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
-            hipLaunchKernelGGL(chol_syrk, dim3(t, t), dim3(256), 0, ctx->stream, A, n, K0, static_cast<int>(W), K0 + W);
+            hipLaunchKernelGGL(chol_syrk<GT>, dim3(t, t), dim3(256), 0, ctx->stream, A, n, K0, static_cast<int>(W), K0 + W);
         }
     }
     ADADIM_LAUNCH_CHECK(ctx, "gptq cholesky");
     for (int64_t s = NB; s < n; s *= 2) {
         const unsigned pairs = static_cast<unsigned>((n - s + 2 * s - 1) / (2 * s));   // those with rows below a0 + s
         const dim3 grid(static_cast<unsigned>(s / GT), static_cast<unsigned>(s / GT), pairs);
-        hipLaunchKernelGGL(trinv_level<0>, grid, dim3(256), 0, ctx->stream, A, M, T, n, s);
-        hipLaunchKernelGGL(trinv_level<1>, grid, dim3(256), 0, ctx->stream, A, M, T, n, s);
+        hipLaunchKernelGGL((trinv_level<0, GT>), grid, dim3(256), 0, ctx->stream, A, M, T, n, s);
+        hipLaunchKernelGGL((trinv_level<1, GT>), grid, dim3(256), 0, ctx->stream, A, M, T, n, s);
     }
     hipLaunchKernelGGL(gq_flip, dim3(nb2), dim3(256), 0, ctx->stream, M, n, U);
     ADADIM_LAUNCH_CHECK(ctx, "gptq inverse");
