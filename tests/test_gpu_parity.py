@@ -432,8 +432,8 @@ def test_layer_error_batch_select(ctx):
     hmeta = torch.empty((2, in_f), dtype=torch.float32, device="cuda")
     ctx.adadim_hessian_prepare(H, Hs, hmeta)
     rng = np.random.default_rng(0)
-    for n, twin in ((2, None), (5, (1, 3)), (8, (0, 7)), (3, None)):
-        dWs = [(rng.standard_normal((out_f, in_f)) * 1e-3 * (1 + c)).astype(np.float32) for c in range(n)]
+    for n, twin in ((2, None), (5, (1, 3)), (8, (0, 7)), (3, None), (11, (9, 10)), (17, (2, 16))):   # > 8: several batches
+        dWs = [(rng.standard_normal((out_f, in_f)) * 1e-3 * (1 + (c * 7) % n)).astype(np.float32) for c in range(n)]
         if twin:
             dWs[twin[1]] = dWs[twin[0]].copy()                    # a tie: the first one wins
         if n == 3:
