@@ -31,6 +31,7 @@ enum {
     WS_GPTQ_W,          // fp32 working copy of the weight in visiting order
     WS_GPTQ_E,          // fp32 propagated errors in visiting order
     WS_GPTQ_Q,          // u8 codes in visiting order
+    WS_GPTQ_V,          // int32 position of each original channel in the visiting order
     WS_COUNT
 };
 

@@ -557,18 +557,25 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
     }
 }
 
-// codes back to the original channel order, and dW = W - scale*(code - zero) there
+// visited[perm[i]] = i: where in the visiting order an original channel sits
+__global__ void gq_invperm(const int32_t* __restrict__ perm, int64_t in, int32_t* __restrict__ visited) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < in) visited[perm[i]] = static_cast<int32_t>(i);
+}
+
+// codes back to the original channel order, and dW = W - scale*(code - zero) there.  One thread per
+// output element: the writes (and the reads of W and the parameters) are consecutive, only the
+// one-byte reads of the visiting-order codes wander, inside a row that the caches hold.
 template <bool IC>
-__global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __restrict__ perm,
+__global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __restrict__ visited,
                            const uint8_t* __restrict__ dead, const __half* __restrict__ W, int64_t out, int64_t in, int g,
                            const float* __restrict__ scales, const uint8_t* __restrict__ zeros,
                            uint8_t* __restrict__ codes, float* __restrict__ dW) {
     const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (idx >= out * in) return;
-    const int64_t r = idx / in, i = idx % in;
-    const int32_t j = perm[i];
-    const uint8_t q = Qp[idx];
-    codes[r * in + j] = q;
+    const int64_t r = idx / in, j = idx % in;
+    const uint8_t q = Qp[r * in + visited[j]];
+    codes[idx] = q;
     if (dW) {
         const int64_t pi = IC ? (r / g) * in + j : r * (in / g) + j / g;
         const float wq = scales[pi] * (static_cast<float>(q) - static_cast<float>(zeros[pi]));
@@ -670,7 +677,8 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
     float* Wp = static_cast<float*>(adadim_workspace(ctx, WS_GPTQ_W, mat));
     float* Ep = static_cast<float*>(adadim_workspace(ctx, WS_GPTQ_E, mat));
     uint8_t* Qp = static_cast<uint8_t*>(adadim_workspace(ctx, WS_GPTQ_Q, size_t(out) * size_t(in)));
-    if (!Wp || !Ep || !Qp) return ADADIM_EHIP;
+    int32_t* visited = static_cast<int32_t*>(adadim_workspace(ctx, WS_GPTQ_V, size_t(in) * sizeof(int32_t)));
+    if (!Wp || !Ep || !Qp || !visited) return ADADIM_EHIP;
     const float qmax = static_cast<float>((1 << bits) - 1);
     const bool ic = dim == ADADIM_DIM_IC;
     const int rpl = ic ? g / 64 : 1;                                   // rows per lane
@@ -712,11 +720,13 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
     }
     {
         ProfScope prof(ctx, "gptq_scatter");
+        hipLaunchKernelGGL(gq_invperm, dim3(static_cast<unsigned>((in + 255) / 256)), dim3(256), 0, ctx->stream, perm, in,
+                           visited);
         if (ic)
-            hipLaunchKernelGGL(gq_scatter<true>, dim3(eb), dim3(256), 0, ctx->stream, Qp, perm, dead, W, out, in, g,
+            hipLaunchKernelGGL(gq_scatter<true>, dim3(eb), dim3(256), 0, ctx->stream, Qp, visited, dead, W, out, in, g,
                                scales_out, zeros_out, codes, dW);
         else
-            hipLaunchKernelGGL(gq_scatter<false>, dim3(eb), dim3(256), 0, ctx->stream, Qp, perm, dead, W, out, in, g,
+            hipLaunchKernelGGL(gq_scatter<false>, dim3(eb), dim3(256), 0, ctx->stream, Qp, visited, dead, W, out, in, g,
                                st_scales, st_zeros, codes, dW);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gptq sweep");
