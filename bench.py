@@ -175,12 +175,17 @@ def gptq_bench(args):
     fac.update(hp)
     torch.cuda.synchronize()
     t_factor = time.perf_counter() - t0
-    ctx.adadim_profile(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         dim = ga.run(Wd, hp, fac)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # per-kernel durations from a second pass: with the library's events on, the sweep keeps its two streams'
+    # work on one stream (so that the events bracket single kernels), which the timed pass above does not
+    ctx.adadim_profile(True)
+    for _ in range(args.steps):
+        ga.run(Wd, hp, fac)
+    torch.cuda.synchronize()
     ctx.adadim_profile(False)
     prof = ctx.adadim_profile_read()
     kern = {k: v[0] / max(v[1], 1) * 1e3 for k, v in prof.items()}

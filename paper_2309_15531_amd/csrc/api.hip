@@ -50,6 +50,25 @@ void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes) {
     return p;
 }
 
+bool adadim_side_stream(adadim_ctx* ctx) {
+    if (ctx->side) return true;
+    hipStream_t st = nullptr;
+    hipError_t e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+    for (int i = 0; e == hipSuccess && i < 2; ++i) e = hipEventCreateWithFlags(&ctx->side_ev[i], hipEventDisableTiming);
+    if (e != hipSuccess) {
+        adadim_fail(ctx, ADADIM_EHIP, "creating the side stream: %s", hipGetErrorString(e));
+        for (int i = 0; i < 2; ++i)
+            if (ctx->side_ev[i]) {
+                (void)hipEventDestroy(ctx->side_ev[i]);
+                ctx->side_ev[i] = nullptr;
+            }
+        if (st) (void)hipStreamDestroy(st);
+        return false;
+    }
+    ctx->side = st;
+    return true;
+}
+
 ProfScope::ProfScope(adadim_ctx* c, const char* name) : ctx(c), pair(-1) {
     adadim_prof& p = c->prof;
     if (!p.enabled || c->capturing) return;
@@ -148,6 +167,11 @@ void adadim_destroy(adadim_ctx* ctx) {
         hipGraph_t g = nullptr;
         if (hipStreamEndCapture(ctx->stream, &g) == hipSuccess && g) (void)hipGraphDestroy(g);
         ctx->capturing = false;
+    }
+    if (ctx->side) {
+        (void)hipStreamSynchronize(ctx->side);
+        for (int i = 0; i < 2; ++i) (void)hipEventDestroy(ctx->side_ev[i]);
+        (void)hipStreamDestroy(ctx->side);
     }
     bool any = false;
     for (int i = 0; i < WS_COUNT; ++i) any = any || ctx->ws[i];

@@ -61,6 +61,8 @@ struct adadim_ctx {
     int gram_key_tiles;
     int64_t gram_t_per_split;
     bool capturing;                  // between adadim_capture_begin and adadim_capture_end
+    hipStream_t side;                // second stream for work that may overlap the main one (created on first use)
+    hipEvent_t side_ev[2];           // main -> side and side -> main hand-overs
     adadim_prof prof;
 };
 
@@ -73,6 +75,10 @@ struct ProfScope {
 };
 
 int adadim_fail(adadim_ctx* ctx, int code, const char* fmt, ...);
+
+// Creates the context's side stream and its two events on first use (default priority, like every
+// stream here).  Returns false with the error recorded.
+bool adadim_side_stream(adadim_ctx* ctx);
 
 // Returns a device buffer of at least `bytes` for `slot`, or nullptr (error recorded).
 void* adadim_workspace(adadim_ctx* ctx, int slot, size_t bytes);

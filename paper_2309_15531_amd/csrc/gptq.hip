@@ -524,8 +524,11 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
                 for (int k = 0; k < SB; ++k) Es[(lane * RPL + p) * (SB + 1) + k] = e[p][k];
         };
         if (wave == 0) {
+            // the chain every later launch waits for: ahead of the bulk update that shares the SIMD with it
+            __builtin_amdgcn_s_setprio(3);
             if (sbw == SB) sub_block(std::true_type{});
             else sub_block(std::false_type{});
+            __builtin_amdgcn_s_setprio(0);
         }
         __syncthreads();
         // its errors applied to the rest of the block, channel order kept per element; wave v takes
@@ -583,19 +586,20 @@ __global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __rest
     }
 }
 
-// channels behind the block: Wp[r][jj] -= E[r][k] * U[k][jj], k = i1 .. i2-1 in order (product, then difference)
+// channels behind the block, columns [col0, col1): Wp[r][jj] -= E[r][k] * U[k][jj], k = i1 .. i2-1 in order
+// (product, then difference)
 __global__ __launch_bounds__(256) void gq_trailing(float* __restrict__ Wp, const float* __restrict__ U,
                                                    const float* __restrict__ Ep, int64_t out, int64_t in, int64_t i1,
-                                                   int nbw) {
+                                                   int nbw, int64_t col0, int64_t col1) {
     __shared__ __align__(16) float Es[GB][8];                 // [channel][row]: a channel's eight errors in two 16-byte reads
-    const int64_t jj = i1 + nbw + int64_t(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t jj = col0 + int64_t(blockIdx.x) * 256 + threadIdx.x;
     const int64_t r0 = int64_t(blockIdx.y) * 8;
     for (int e = threadIdx.x; e < 8 * nbw; e += 256) {
         const int rr = e / nbw, k = e % nbw;
         Es[k][rr] = r0 + rr < out ? Ep[(r0 + rr) * in + i1 + k] : 0.0f;
     }
     __syncthreads();
-    if (jj >= in) return;
+    if (jj >= col1) return;
     float v[8];
 #pragma unroll
     for (int rr = 0; rr < 8; ++rr) v[rr] = r0 + rr < out ? Wp[(r0 + rr) * in + jj] : 0.0f;
@@ -699,6 +703,15 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
         ProfScope prof(ctx, "gptq_gather");
         hipLaunchKernelGGL(gq_gather_w, dim3(eb), dim3(256), 0, ctx->stream, W, out, in, perm, dead, Wp);
     }
+    // A block's errors reach the channels behind it in two launches: the next block's 128 channels at
+    // once, on the main stream, so that the next sweep can start; the rest on a side stream, under
+    // that sweep, which keeps only a few compute units busy.  Every element still receives the
+    // blocks' errors in block order: the side stream applies them in order, and the main stream
+    // waits for the side stream's last launch before it adds the following block's errors to the
+    // channels that launch wrote.  With per-kernel timing on, everything runs on the main stream.
+    const bool overlap = !ctx->prof.enabled && in > 2 * GB;
+    if (overlap && !adadim_side_stream(ctx)) return ADADIM_EHIP;
+    bool side_busy = false;
     for (int64_t i1 = 0; i1 < in; i1 += GB) {
         const int nbw = static_cast<int>(in - i1 < GB ? in - i1 : GB);
         {
@@ -711,13 +724,30 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
             else GQ_GO(true, 2);
 #undef GQ_GO
         }
-        const int64_t rest = in - i1 - nbw;
-        if (rest > 0) {
+        const int64_t behind = i1 + nbw;                        // first channel behind the block
+        if (behind >= in) break;
+        const int64_t next_end = behind + GB < in ? behind + GB : in;
+        const unsigned rows8 = static_cast<unsigned>((out + 7) / 8);
+        if (!overlap) {
             ProfScope prof(ctx, "gptq_trailing");
-            dim3 grid(static_cast<unsigned>((rest + 255) / 256), static_cast<unsigned>((out + 7) / 8));
-            hipLaunchKernelGGL(gq_trailing, grid, dim3(256), 0, ctx->stream, Wp, U, Ep, out, in, i1, nbw);
+            hipLaunchKernelGGL(gq_trailing, dim3(static_cast<unsigned>((in - behind + 255) / 256), rows8), dim3(256), 0,
+                               ctx->stream, Wp, U, Ep, out, in, i1, nbw, behind, in);
+            continue;
+        }
+        if (side_busy) ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->side_ev[1], 0));
+        hipLaunchKernelGGL(gq_trailing, dim3(static_cast<unsigned>((next_end - behind + 255) / 256), rows8), dim3(256), 0,
+                           ctx->stream, Wp, U, Ep, out, in, i1, nbw, behind, next_end);
+        // the side stream starts behind this short launch, not beside it: the next sweep waits for it
+        ADADIM_HIP_TRY(ctx, hipEventRecord(ctx->side_ev[0], ctx->stream));
+        if (next_end < in) {
+            ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->side, ctx->side_ev[0], 0));
+            hipLaunchKernelGGL(gq_trailing, dim3(static_cast<unsigned>((in - next_end + 255) / 256), rows8), dim3(256), 0,
+                               ctx->side, Wp, U, Ep, out, in, i1, nbw, next_end, in);
+            ADADIM_HIP_TRY(ctx, hipEventRecord(ctx->side_ev[1], ctx->side));
+            side_busy = true;
         }
     }
+    if (side_busy) ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->side_ev[1], 0));   // join
     {
         ProfScope prof(ctx, "gptq_scatter");
         hipLaunchKernelGGL(gq_invperm, dim3(static_cast<unsigned>((in + 255) / 256)), dim3(256), 0, ctx->stream, perm, in,
