@@ -405,6 +405,28 @@ def main():
         sec = e0.elapsed_time(e1) * 1e-3 / (3 * n_rot)
         quant[name] = {"us_per_launch": sec * 1e6, "GBps_algorithmic": qbytes / sec / 1e9,
                        "frac_hbm": qbytes / sec / HBM_PEAK, "rotating_buffers": n_rot}
+    # both dimensions in one call, as the search issues them (one launch where both fast kernels take the shape):
+    # W read twice, two fp16 dW written
+    if group == 0 or (out_f % group == 0 and in_f % group == 0):
+        dW2 = [ctx.alloc_score(out_f, in_f) for _ in range(n_rot)]
+
+        def sweep_both():
+            for i in range(n_rot):
+                ctx.adadim_quantize_both(Ws[i], bits, group, hp.colscale, {"dW": dWs[i]}, {"dW": dW2[i]})
+        sweep_both()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(3):
+            sweep_both()
+        e1.record()
+        torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) * 1e-3 / (3 * n_rot)
+        once = 2 * qbytes - out_f * in_f * 2          # W counted once: what one pass over W would have to move
+        quant["quant_both"] = {"us_per_launch": sec * 1e6, "GBps_algorithmic": 2 * qbytes / sec / 1e9,
+                               "frac_hbm": 2 * qbytes / sec / HBM_PEAK, "frac_hbm_w_counted_once": once / sec / HBM_PEAK,
+                               "rotating_buffers": n_rot,
+                               "note": "bytes of the two dimensions added up (W read for each), as for the single launches"}
+        del dW2
     del Ws, dWs
 
     result = {

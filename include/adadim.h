@@ -150,6 +150,20 @@ int adadim_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t 
                            uint32_t* packed);
 
 /*
+ * Both candidates of the search in one call: adadim_quantize(dim = OC) and adadim_quantize(dim = IC) of the same
+ * W with the same bits, group and clip, each with its own outputs (any of them NULL to skip it), dW always as
+ * ADADIM_DW_F16_SCALED.  meta16 = 1: the storage format of adadim_quantize_meta16 (scales_* are then u16 arrays
+ * of group words and zeros_* are not written).  Same results as the two calls.  When both fast kernels take the
+ * shape (groups of 32, 64 or 128 dividing both out and in, in a multiple of 32, both dW given, 2..4 bits if a
+ * packed stream is asked for, then for both) it is one launch, which on a 4096 x 4096 layer costs what 1.6 of
+ * the single launches cost; otherwise the two launches one after the other.
+ */
+int adadim_quantize_both(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int bits, int group, float clip,
+                         int meta16, const float* colscale,
+                         uint8_t* codes_oc, void* scales_oc, uint8_t* zeros_oc, void* dW_oc, uint32_t* packed_oc,
+                         uint8_t* codes_ic, void* scales_ic, uint8_t* zeros_ic, void* dW_ic, uint32_t* packed_ic);
+
+/*
  * Prepares H for scoring on the matrix cores.  With the power-of-two column
  * scales d_j ~ sqrt(H_jj):
  *   Hs     fp16 [in, in] in the scoring layout (adadim_score_elems(in, in) elements):

@@ -23,7 +23,7 @@ EXPORTS = (
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
-    "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
+    "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -87,6 +87,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_gemv_ic_meta16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
                                           c_void_p]
     lib.adadim_gemv_ic_meta16.restype = c_int
+    lib.adadim_quantize_both.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_float, c_int, c_void_p] + \
+        [c_void_p] * 10
+    lib.adadim_quantize_both.restype = c_int
     lib.adadim_hessian_prepared.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p]
     lib.adadim_hessian_prepared.restype = c_int
     lib.adadim_capture_begin.argtypes = [c_void_p]
@@ -195,6 +198,16 @@ class Context:
         self._check(self._lib.adadim_quantize_meta16(self._h, _ptr(W), out_f, in_f, dim, bits, group, c_float(clip),
                                                      _ptr(codes), _ptr(meta), _ptr(dW), dW_dtype, _ptr(colscale),
                                                      _ptr(packed)))
+
+    def adadim_quantize_both(self, W, bits: int, group: int, colscale, oc: dict, ic: dict, clip: float = 1.0,
+                             meta16: bool = False):
+        """oc / ic: dicts with any of codes, scales (or meta when meta16), zeros, dW, packed."""
+        out_f, in_f = W.shape
+        def five(d):
+            return [_ptr(d.get("codes")), _ptr(d.get("meta") if meta16 else d.get("scales")), _ptr(d.get("zeros")),
+                    _ptr(d.get("dW")), _ptr(d.get("packed"))]
+        self._check(self._lib.adadim_quantize_both(self._h, _ptr(W), out_f, in_f, bits, group, c_float(clip),
+                                                   1 if meta16 else 0, _ptr(colscale), *five(oc), *five(ic)))
 
     def alloc_score(self, rows: int, cols: int, device="cuda"):
         """Flat fp16 device buffer large enough for an [rows, cols] operand in the scoring layout."""

@@ -253,6 +253,34 @@ int adadim_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int
                             packed, 0);
 }
 
+int adadim_quantize_both(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int bits, int group, float clip,
+                         int meta16, const float* colscale, uint8_t* codes_oc, void* scales_oc, uint8_t* zeros_oc,
+                         void* dW_oc, uint32_t* packed_oc, uint8_t* codes_ic, void* scales_ic, uint8_t* zeros_ic,
+                         void* dW_ic, uint32_t* packed_ic) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!W || !colscale) return adadim_fail(ctx, ADADIM_ENULL, "adadim_quantize_both: W or colscale is NULL");
+    if (out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 24))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize_both: bad shape out=%lld in=%lld", (long long)out,
+                           (long long)in);
+    if (bits < 2 || bits > (meta16 ? 4 : 8) || (meta16 != 0 && meta16 != 1))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize_both: bits must be in [2,8] ([2,4] for group words), "
+                                               "meta16 0 or 1 (bits=%d meta16=%d)", bits, meta16);
+    if (!(clip > 0.0f && clip <= 1.0f))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize_both: clip must be in (0,1], got %g", (double)clip);
+    if (group < 0 || (group > 0 && ((in % group) != 0 || (out % group) != 0)))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize_both: group %d must be 0 or divide both out and in", group);
+    if ((in % 8) != 0)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_quantize_both: in must be a multiple of 8 (scoring layout)");
+    if (!aligned16(W) || !aligned16(colscale) || (dW_oc && !aligned16(dW_oc)) || (dW_ic && !aligned16(dW_ic)) ||
+        (codes_oc && (reinterpret_cast<uintptr_t>(codes_oc) & 7u)) || (codes_ic && (reinterpret_cast<uintptr_t>(codes_ic) & 7u)))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_quantize_both: W, colscale and dW must be 16-byte, codes 8-byte aligned");
+    const int g_oc = group == 0 ? (int)in : group, g_ic = group == 0 ? (int)out : group;
+    return launch_quantize_both(ctx, static_cast<const __half*>(W), out, in, bits, g_oc, g_ic, clip, meta16 ? bits : 0,
+                                colscale, codes_oc, static_cast<float*>(scales_oc), meta16 ? nullptr : zeros_oc, dW_oc,
+                                packed_oc, codes_ic, static_cast<float*>(scales_ic), meta16 ? nullptr : zeros_ic, dW_ic,
+                                packed_ic);
+}
+
 int adadim_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
                            float clip, uint8_t* codes, uint16_t* meta, void* dW, int dW_dtype,
                            const float* colscale, uint32_t* packed) {

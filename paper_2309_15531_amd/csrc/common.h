@@ -122,6 +122,10 @@ static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t
 int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
                     float clip, uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype,
                     const float* colscale, uint32_t* packed, int mfmt);
+int launch_quantize_both(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int bits, int g_oc, int g_ic, float clip,
+                         int mfmt, const float* colscale, uint8_t* codes_oc, float* scales_oc, uint8_t* zeros_oc,
+                         void* dW_oc, uint32_t* packed_oc, uint8_t* codes_ic, float* scales_ic, uint8_t* zeros_ic,
+                         void* dW_ic, uint32_t* packed_ic);
 int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, int dim, int bits,
                 uint32_t* packed);
 int launch_hessian(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64_t ldx, float* H,

@@ -471,18 +471,18 @@ __device__ __forceinline__ uint32_t cluster_min2(uint32_t m) {
 // scoring layout, where the 64-byte pieces of 16 consecutive rows of one 32-column block are
 // adjacent: the tile is turned through LDS so that each store instruction writes such a
 // contiguous kilobyte instead of 16 scattered pieces.
+// (bx, by): the block's tile, handed in so that one launch can serve both grouping dimensions.
 template <int LPG, int PB, bool SCALED>
-__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t out, int chunks_per_row,
-                                                     float clip, float qmax, float rqmax, int mfmt,
-                                                     uint8_t* __restrict__ codes, float* __restrict__ scales,
-                                                     uint8_t* __restrict__ zeros, void* __restrict__ dW,
-                                                     int dW_dtype, const float* __restrict__ colscale,
-                                                     uint32_t* __restrict__ packed) {
+__device__ __forceinline__ void quant_oc_body(unsigned bx, unsigned by, const uint4* __restrict__ W, int64_t out,
+                                              int chunks_per_row, float clip, float qmax, float rqmax, int mfmt,
+                                              uint8_t* __restrict__ codes, float* __restrict__ scales,
+                                              uint8_t* __restrict__ zeros, void* __restrict__ dW, int dW_dtype,
+                                              const float* __restrict__ colscale, uint32_t* __restrict__ packed) {
     constexpr int U = 4, PITCH = 68;                        // LDS row pitch in 16-byte units (conflict-free)
     __shared__ uint4 s_t[SCALED ? 16 * PITCH : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int cc = blockIdx.x * 64 + lane;                  // chunk within the row
-    const int64_t row0 = int64_t(blockIdx.y) * 16;
+    const int cc = bx * 64 + lane;                  // chunk within the row
+    const int64_t row0 = int64_t(by) * 16;
     const bool col_ok = cc < chunks_per_row;                // whole groups: chunks_per_row % LPG == 0
     const int64_t in = int64_t(chunks_per_row) * 8;
     const bool turn = SCALED && score_blocked(in);
@@ -592,12 +592,23 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int kb = 4 * wave + u;                         // block within the tile
-        const int chunk = blockIdx.x * 64 + 4 * kb + sq;     // chunk within the row
+        const int chunk = bx * 64 + 4 * kb + sq;     // chunk within the row
         if (grow < out && chunk < chunks_per_row) {
             const int64_t at = score_index(grow, int64_t(chunk) * 8, out, in);
             *reinterpret_cast<uint4*>(static_cast<__half*>(dW) + at) = s_t[srow * PITCH + 4 * kb + sq];
         }
     }
+}
+
+template <int LPG, int PB, bool SCALED>
+__global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W, int64_t out, int chunks_per_row,
+                                                     float clip, float qmax, float rqmax, int mfmt,
+                                                     uint8_t* __restrict__ codes, float* __restrict__ scales,
+                                                     uint8_t* __restrict__ zeros, void* __restrict__ dW,
+                                                     int dW_dtype, const float* __restrict__ colscale,
+                                                     uint32_t* __restrict__ packed) {
+    quant_oc_body<LPG, PB, SCALED>(blockIdx.x, blockIdx.y, W, out, chunks_per_row, clip, qmax, rqmax, mfmt, codes, scales,
+                                   zeros, dW, dW_dtype, colscale, packed);
 }
 
 // per-IC streaming path.  A group of G = 8*U*RW rows x 64 columns is shared by RW wavefronts, each
@@ -616,9 +627,9 @@ __global__ __launch_bounds__(256) void quant_oc_fast(const uint4* __restrict__ W
 // (byte u = row 8u + row lane), the wave turns them through a private LDS patch so that lane l
 // holds all 32 codes of column l, and that lane shifts them into place and writes the PB words.
 template <int U, int RW, bool SCALED, int PB>
-__global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
-    const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax, int mfmt,
-    uint8_t* __restrict__ codes, float* __restrict__ scales, uint8_t* __restrict__ zeros, void* __restrict__ dW,
+__device__ __forceinline__ void quant_ic_body(
+    unsigned bx, unsigned by, const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax,
+    int mfmt, uint8_t* __restrict__ codes, float* __restrict__ scales, uint8_t* __restrict__ zeros, void* __restrict__ dW,
     int dW_dtype, const float* __restrict__ colscale, uint32_t* __restrict__ packed, int64_t n_words) {
     constexpr int CSW = RW <= 4 ? 4 / RW : 1;                // 64-column sets per block
     constexpr int G = 8 * U * RW;
@@ -628,8 +639,8 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int rw = wave % RW, cw = wave / RW;
     const int rl = lane >> 3, cl = lane & 7;
-    const int64_t col0 = ((int64_t(blockIdx.x) * CSW + cw) * 8 + cl) * 8;
-    const int64_t row0 = int64_t(blockIdx.y) * G + rw * (8 * U) + rl;   // this lane's rows: row0 + 8u
+    const int64_t col0 = ((int64_t(bx) * CSW + cw) * 8 + cl) * 8;
+    const int64_t row0 = int64_t(by) * G + rw * (8 * U) + rl;   // this lane's rows: row0 + 8u
     const bool col_ok = col0 < in;                           // in % 8 == 0: the whole chunk is inside
 
     uint4 raw[U];
@@ -679,7 +690,7 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
     const GroupParamsR gp = group_params_r(half_of(mnp, rl & 1), half_of(mxp, rl & 1), clip, qmax, rqmax, mfmt);
     const bool slow = __any(!gp.fast);
     if (col_ok && rw == 0) {
-        const int64_t gi = int64_t(blockIdx.y) * in + col0 + rl;
+        const int64_t gi = int64_t(by) * in + col0 + rl;
         store_params(scales, zeros, gi, gp.scale, gp.zero, mfmt);
     }
     const bool do_pack = PB != 0 && packed != nullptr;
@@ -783,12 +794,50 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
             w[1] = (f[1] >> 8) | (f[2] << 16);
             w[2] = (f[2] >> 16) | (f[3] << 8);
         }
-        const int64_t col = (int64_t(blockIdx.x) * CSW + cw) * 64 + lane;
+        const int64_t col = (int64_t(bx) * CSW + cw) * 64 + lane;
         if (col < in) {
-            uint32_t* dst = packed + col * n_words + (int64_t(blockIdx.y) * (G / 32) + rw) * PB;
+            uint32_t* dst = packed + col * n_words + (int64_t(by) * (G / 32) + rw) * PB;
 #pragma unroll
             for (int j = 0; j < PB; ++j) dst[j] = w[j];
         }
+    }
+}
+
+template <int U, int RW, bool SCALED, int PB>
+__global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
+    const __half* __restrict__ W, int64_t out, int64_t in, float clip, float qmax, float rqmax, int mfmt,
+    uint8_t* __restrict__ codes, float* __restrict__ scales, uint8_t* __restrict__ zeros, void* __restrict__ dW,
+    int dW_dtype, const float* __restrict__ colscale, uint32_t* __restrict__ packed, int64_t n_words) {
+    quant_ic_body<U, RW, SCALED, PB>(blockIdx.x, blockIdx.y, W, out, in, clip, qmax, rqmax, mfmt, codes, scales, zeros, dW,
+                                     dW_dtype, colscale, packed, n_words);
+}
+
+// Both grouping dimensions of one weight in one launch (groups of 8*LPG in either direction, at most
+// 128): the first n_oc workgroups are per-OC tiles, the rest per-IC tiles.  Short kernels spend a
+// good part of their time filling and draining the chip; one launch does that once, and the
+// per-IC tiles start while the last per-OC ones finish.
+struct QuantOut {
+    uint8_t* codes;
+    float* scales;
+    uint8_t* zeros;
+    void* dW;
+    uint32_t* packed;
+};
+template <int LPG, int PB>
+__global__ __launch_bounds__(256) void quant_both(const __half* __restrict__ W, int64_t out, int64_t in, float clip,
+                                                  float qmax, float rqmax, int mfmt, QuantOut oc, QuantOut ic,
+                                                  const float* __restrict__ colscale, int64_t n_words_ic, unsigned gx_oc,
+                                                  unsigned n_oc, unsigned gx_ic) {
+    constexpr int U = LPG < 4 ? LPG : 4, RW = LPG / U;
+    static_assert(RW <= 4, "256 threads per workgroup in both halves");
+    if (blockIdx.x < n_oc) {
+        quant_oc_body<LPG, PB, true>(blockIdx.x % gx_oc, blockIdx.x / gx_oc, reinterpret_cast<const uint4*>(W), out,
+                                     static_cast<int>(in / 8), clip, qmax, rqmax, mfmt, oc.codes, oc.scales, oc.zeros, oc.dW,
+                                     ADADIM_DW_F16_SCALED, colscale, oc.packed);
+    } else {
+        const unsigned b = blockIdx.x - n_oc;
+        quant_ic_body<U, RW, true, PB>(b % gx_ic, b / gx_ic, W, out, in, clip, qmax, rqmax, mfmt, ic.codes, ic.scales,
+                                       ic.zeros, ic.dW, ADADIM_DW_F16_SCALED, colscale, ic.packed, n_words_ic);
     }
 }
 
@@ -1117,6 +1166,53 @@ int launch_pack(adadim_ctx* ctx, const uint8_t* codes, int64_t out, int64_t in, 
                            n_words, dim == ADADIM_DIM_IC ? 1 : 0, packed);
     }
     ADADIM_LAUNCH_CHECK(ctx, "pack_words");
+    return ADADIM_OK;
+}
+
+// Both dimensions with the same group length.  One launch when both fast kernels take the shape
+// (column-scaled dW for both, groups of 32, 64 or 128, in % 32 == 0, 2..4 bits if packed), else two.
+int launch_quantize_both(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int bits, int g_oc, int g_ic, float clip,
+                         int mfmt, const float* colscale, uint8_t* codes_oc, float* scales_oc, uint8_t* zeros_oc,
+                         void* dW_oc, uint32_t* packed_oc, uint8_t* codes_ic, float* scales_ic, uint8_t* zeros_ic,
+                         void* dW_ic, uint32_t* packed_ic) {
+    const int lpg = g_oc / 8;
+    const bool want_pack = packed_oc || packed_ic;
+    const bool fused = g_oc == g_ic && dW_oc && dW_ic && colscale && (g_oc == 32 || g_oc == 64 || g_oc == 128) &&
+                       (in % 32) == 0 && (in % g_oc) == 0 && (out % g_ic) == 0 && out <= 16 * 65535 &&
+                       (!want_pack || (packed_oc && packed_ic && bits >= 2 && bits <= 4));
+    if (!fused) {
+        int rc = launch_quantize(ctx, W, out, in, ADADIM_DIM_OC, bits, g_oc, clip, codes_oc, scales_oc, zeros_oc, dW_oc,
+                                 ADADIM_DW_F16_SCALED, colscale, packed_oc, mfmt);
+        if (rc != ADADIM_OK) return rc;
+        return launch_quantize(ctx, W, out, in, ADADIM_DIM_IC, bits, g_ic, clip, codes_ic, scales_ic, zeros_ic, dW_ic,
+                               ADADIM_DW_F16_SCALED, colscale, packed_ic, mfmt);
+    }
+    const float qmax = static_cast<float>((1 << bits) - 1);
+    const int rw = lpg / 4, csw = 4 / rw;
+    const unsigned gx_oc = static_cast<unsigned>((in / 8 + 63) / 64), gy_oc = static_cast<unsigned>((out + 15) / 16);
+    const unsigned gx_ic = static_cast<unsigned>((in + 64 * csw - 1) / (64 * csw)), gy_ic = static_cast<unsigned>(out / g_ic);
+    const unsigned n_oc = gx_oc * gy_oc, n_ic = gx_ic * gy_ic;
+    const QuantOut oc = {codes_oc, scales_oc, zeros_oc, dW_oc, packed_oc}, ic = {codes_ic, scales_ic, zeros_ic, dW_ic, packed_ic};
+    const int64_t n_words_ic = (out * bits + 31) / 32;
+    {
+        ProfScope prof(ctx, "quant_both");
+#define QB_GO(L, PB)                                                                                                  \
+    hipLaunchKernelGGL((quant_both<L, PB>), dim3(n_oc + n_ic), dim3(256), 0, ctx->stream, W, out, in, clip, qmax,     \
+                       1.0f / qmax, mfmt, oc, ic, colscale, n_words_ic, gx_oc, n_oc, gx_ic)
+#define QB_PB(L)                                                                                                      \
+    do {                                                                                                              \
+        if (!want_pack) QB_GO(L, 0);                                                                                  \
+        else if (bits == 2) QB_GO(L, 2);                                                                              \
+        else if (bits == 3) QB_GO(L, 3);                                                                              \
+        else QB_GO(L, 4);                                                                                             \
+    } while (0)
+        if (lpg == 4) QB_PB(4);
+        else if (lpg == 8) QB_PB(8);
+        else QB_PB(16);
+#undef QB_PB
+#undef QB_GO
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "quant_both");
     return ADADIM_OK;
 }
 

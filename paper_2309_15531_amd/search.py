@@ -94,9 +94,17 @@ class LayerSearch:
         index in self.best (taken by the scoring call itself when the candidates fit one batch)."""
         for c0 in range(0, len(self.cands), self.batch):
             chunk = self.cands[c0:c0 + self.batch]
-            for k, (dim, clip) in enumerate(chunk):
-                self._quantize(W, dim, clip, c0 + k if self.inline else None, dW=self.dWs[k],
-                               dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
+            if len(self.cands) == 2 and self.inline:
+                # the plain search: its two candidates in one call (one launch where the shape allows)
+                key = "meta" if self.meta16 else "scales"
+                sets = [{"dW": self.dWs[k], "packed": self._packed[k], key: (self._meta if self.meta16 else self._scales)[k],
+                         "zeros": None if self.meta16 else self._zeros[k]} for k in (0, 1)]
+                self.ctx.adadim_quantize_both(W, self.bits, self.group, hp.colscale, sets[0], sets[1], clip=chunk[0][1],
+                                              meta16=self.meta16)
+            else:
+                for k, (dim, clip) in enumerate(chunk):
+                    self._quantize(W, dim, clip, c0 + k if self.inline else None, dW=self.dWs[k],
+                                   dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
             if select and len(chunk) == len(self.cands):
                 self.ctx.adadim_layer_error_batch_select(self.dWs[:len(chunk)], B.DW_F16_SCALED, hp.Hs, hp.hmeta,
                                                          self.losses, self.best, shape=(self.out_f, self.in_f))

@@ -452,3 +452,57 @@ def test_layer_error_batch_select(ctx):
             assert ref_best == oracle.select(ref_losses.cpu().numpy().astype(np.float64).tolist())
         else:
             assert ref_best == 1
+
+
+@pytest.mark.parametrize("out_f,in_f,bits,group,meta16", [
+    (512, 512, 3, 64, False),       # one launch
+    (384, 640, 4, 128, False),      # one launch, ragged row tiles of the scoring layout
+    (256, 1024, 2, 32, True),       # one launch, group words
+    (768, 768, 4, 128, True),
+    (640, 264, 3, 8, False),        # in % 32 != 0: two launches
+    (512, 768, 5, 256, False),      # groups of 256, 5 bits: two launches
+    (256, 512, 4, 0, False),        # whole channels: two launches
+])
+def test_quantize_both_equals_the_two_calls(ctx, out_f, in_f, bits, group, meta16):
+    """adadim_quantize_both against adadim_quantize(OC) + adadim_quantize(IC) (or the _meta16 pair), every output
+    bit for bit, and against the oracle."""
+    W = rand_w(out_f, in_f, seed=out_f + 3 * in_f + bits)
+    Wd = dev(W)
+    clip = float(np.float32(0.9))
+    cs = np.ldexp(np.float32(1.0), np.random.default_rng(1).integers(-2, 9, size=in_f)).astype(np.float32)
+    csd = dev(cs)
+    def bufs(dim):
+        g = (in_f if dim == OC else out_f) if group == 0 else group
+        shape = (out_f, in_f // g) if dim == OC else (out_f // g, in_f)
+        n_ch, ln = (out_f, in_f) if dim == OC else (in_f, out_f)
+        d = {"codes": torch.full((out_f, in_f), 255, dtype=torch.uint8, device="cuda"),
+             "dW": ctx.alloc_score(out_f, in_f).fill_(float("nan")),
+             "packed": torch.full((n_ch, (ln * bits + 31) // 32), -1, dtype=torch.int32, device="cuda")}
+        if meta16:
+            d["meta"] = torch.full(shape, -1, dtype=torch.int16, device="cuda")
+        else:
+            d["scales"] = torch.full(shape, -1.0, dtype=torch.float32, device="cuda")
+            d["zeros"] = torch.full(shape, 255, dtype=torch.uint8, device="cuda")
+        return d
+    one = {OC: bufs(OC), IC: bufs(IC)}
+    two = {OC: bufs(OC), IC: bufs(IC)}
+    ctx.adadim_quantize_both(Wd, bits, group, csd, one[OC], one[IC], clip=clip, meta16=meta16)
+    for dim in (OC, IC):
+        if meta16:
+            ctx.adadim_quantize_meta16(Wd, dim, bits, group, clip, codes=two[dim]["codes"], meta=two[dim]["meta"],
+                                       dW=two[dim]["dW"], dW_dtype=B.DW_F16_SCALED, colscale=csd, packed=two[dim]["packed"])
+        else:
+            ctx.adadim_quantize(Wd, dim, bits, group, clip, codes=two[dim]["codes"], scales=two[dim]["scales"],
+                                zeros=two[dim]["zeros"], dW=two[dim]["dW"], dW_dtype=B.DW_F16_SCALED, colscale=csd,
+                                packed=two[dim]["packed"])
+    torch.cuda.synchronize()
+    for dim in (OC, IC):
+        for k in one[dim]:
+            a, b = one[dim][k].cpu().numpy(), two[dim][k].cpu().numpy()
+            if k == "dW":
+                a, b = B.from_score_layout(a, out_f, in_f).view(np.uint16), B.from_score_layout(b, out_f, in_f).view(np.uint16)
+            assert np.array_equal(a, b), (dim, k)
+        ref = (oracle.meta16_oracle.quantize if meta16 else oracle.quantize)(W, dim, bits, group, clip)
+        assert np.array_equal(one[dim]["codes"].cpu().numpy(), ref["codes"])
+        assert np.array_equal(B.from_score_layout(one[dim]["dW"].cpu().numpy(), out_f, in_f),
+                              (ref["dW"] * cs[None, :]).astype(np.float16))
