@@ -247,11 +247,9 @@ class SharedSearch:
         """Queues the search of all the layers; nothing waits."""
         assert len(Ws) == self.n_layers
         for l, W in enumerate(Ws):
-            for dim in (B.DIM_OC, B.DIM_IC):
-                k = 2 * l + dim
-                self.ctx.adadim_quantize(W, dim, self.bits, self.group, 1.0, dW=self.dWs[k], dW_dtype=B.DW_F16_SCALED,
-                                         colscale=hp.colscale, scales=self._scales[k], zeros=self._zeros[k],
-                                         packed=self._packed[k])
+            sets = [{"dW": self.dWs[k], "scales": self._scales[k], "zeros": self._zeros[k], "packed": self._packed[k]}
+                    for k in (2 * l, 2 * l + 1)]                   # k = 2 l + dim
+            self.ctx.adadim_quantize_both(W, self.bits, self.group, hp.colscale, sets[0], sets[1])
         self.ctx.adadim_layer_error_batch(self.dWs, B.DW_F16_SCALED, hp.Hs, hp.hmeta, self.losses,
                                           shape=(self.out_f, self.in_f))
         for l in range(self.n_layers):
