@@ -129,6 +129,10 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     const int r0 = k_len - KT * (n_st - 1);                                       // k of stage 0: 8..32
     const int64_t row0 = int64_t(mb) * BT, col0 = int64_t(nb) * BT;
 
+    // DBG 8: four 100 MHz timestamps per workgroup (entry, main loop begin and end, exit) behind the
+    // partial sums, for the timeline probe
+    long long dbg_t[4] = {0, 0, 0, 0};
+    if constexpr (DBG & 8) dbg_t[0] = wall_clock64();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
@@ -267,6 +271,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         }
         stage_issued();
     };
+    if constexpr (DBG & 8) dbg_t[1] = wall_clock64();
     // four stages per trip (constant ring slots); surplus stages multiply zeros
     for (int s = 0; s < n_st; s += 4) {
         stage_body(std::integral_constant<int, 0>{});
@@ -275,6 +280,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         stage_body(std::integral_constant<int, 3>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
+    if constexpr (DBG & 8) dbg_t[2] = wall_clock64();
 
     // ---- epilogue: acc[i][j][r] = E[o, n] with o = row0 + wn*WN + 32j + (lane & 31) and
     // n = col0 + wm*WM + 32i + 8*(r/4) + 4*(lane >> 5) + (r & 3).  Multiply by dW'[o, n] (four
@@ -361,6 +367,18 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     __syncthreads();
     if (tid < BT && row0 + tid < out)
         part[(int64_t(cand) * n_slots + slot) * out + row0 + tid] = s_rows[0][tid] + s_rows[1][tid];
+    if constexpr (DBG & 8) {
+        if (tid == 0) {
+            dbg_t[3] = wall_clock64();
+            uint32_t* d = reinterpret_cast<uint32_t*>(part + int64_t(batch.n) * n_slots * out) + int64_t(blockIdx.x) * 8;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) d[q] = static_cast<uint32_t>(dbg_t[q]);
+            d[4] = static_cast<uint32_t>(n_st);
+            d[5] = static_cast<uint32_t>(slot);
+            d[6] = static_cast<uint32_t>(pair);
+            d[7] = 1u;
+        }
+    }
 }
 
 }  // namespace edma
