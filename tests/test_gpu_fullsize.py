@@ -36,9 +36,12 @@ def test_q_proj_full_oracle(ctx):
     W = synth.config_weight(1, "q_proj")
     X = synth.config_activations(1, 4096)
     print("inputs ready", flush=True)
-    hp = S.PreparedHessian(ctx, 4096).update(dev(X)).prepare()
+    # the calls bench.py times: Gram matrix with its prepared form, both candidates in one quantizer call,
+    # scoring and selection in one call, the answer read afterwards
+    hp = S.PreparedHessian(ctx, 4096).update_prepared(dev(X))
     ls = S.LayerSearch(ctx, 4096, 4096, bits, group)
-    best, dim, clip = ls.run(dev(W), hp)
+    ls.launch(dev(W), hp)
+    best, dim, clip = ls.result()
     torch.cuda.synchronize()
     got = ls.losses.cpu().numpy()
     Hg = hp.H.cpu().numpy()
@@ -88,6 +91,7 @@ def test_down_proj_sampled(ctx):
     del Hg
 
     rows = np.sort(rng.choice(out_f, 24, replace=False))
+    single_losses, single_packed = [], []
     for dim in (OC, IC):
         q = oracle.quantize(W, dim, bits, group)
         g = group
@@ -114,3 +118,20 @@ def test_down_proj_sampled(ctx):
         assert got_rows[rows] == pytest.approx(ref_rows, rel=LOSS_RTOL)
         assert loss.item() == pytest.approx(got_rows.sum(), rel=1e-5)
         print("dim", dim, "loss", loss.item(), flush=True)
+        single_losses.append(loss.item())
+        single_packed.append(oracle.pack(q["codes"][rows], OC, bits) if dim == OC else None)
+
+    # the same layer through the calls bench.py times (fused Gram preparation, both candidates in one
+    # quantizer launch, scoring + selection in one call): same H and Hs bit for bit, same losses
+    hp2 = S.PreparedHessian(ctx, in_f).update_prepared(Xd)
+    assert torch.equal(hp2.H, hp.H) and torch.equal(hp2.hmeta, hp.hmeta)
+    assert np.array_equal(B.from_score_layout(hp2.Hs.cpu().numpy(), in_f, in_f).view(np.uint16),
+                          B.from_score_layout(hp.Hs.cpu().numpy(), in_f, in_f).view(np.uint16))
+    ls = S.LayerSearch(ctx, out_f, in_f, bits, group)
+    ls.launch(Wd, hp2)
+    best, dim, _ = ls.result()
+    assert ls.losses.cpu().numpy() == pytest.approx(single_losses, rel=1e-5)
+    assert best == int(np.argmin(single_losses)) and dim == best
+    words = in_f * bits // 32                                   # per-OC stream: one row = `words` words
+    oc_stream = ls._packed[0][:out_f * words].view(out_f, words)[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint32)
+    assert np.array_equal(oc_stream, single_packed[0])
