@@ -73,7 +73,7 @@ void adadim_destroy(adadim_ctx* ctx);
  * the last error of a failed adadim_create).  Owned by the library. */
 const char* adadim_last_error(const adadim_ctx* ctx);
 
-/* Library version string, e.g. "adadim-gfx950 0.1". Host pointer, static. */
+/* Library version string, e.g. "adadim-gfx950 0.3". Host pointer, static. */
 const char* adadim_version(void);
 
 /*

@@ -143,7 +143,7 @@ int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* t
     return ADADIM_OK;
 }
 
-const char* adadim_version(void) { return "adadim-gfx950 0.2"; }
+const char* adadim_version(void) { return "adadim-gfx950 0.3"; }
 
 int64_t adadim_score_elems(int64_t rows, int64_t cols) {
     if (rows <= 0 || cols <= 0) return 0;
