@@ -75,6 +75,37 @@ __global__ void gq_rank(const double* __restrict__ d, int64_t n, int act_order, 
     perm[rank] = static_cast<int32_t>(j);
 }
 
+// The same ranks in two steps that use the whole chip: block (x, y) counts, for its 256 channels j,
+// the channels of the y-th kilo-entry of the diagonal that come before j (staged in LDS) and adds the
+// count to rank[j] (integer atomics: any order gives the same sum); then perm[rank[j]] = j.
+__global__ void gq_zero_i32(int32_t* __restrict__ p, int64_t n) {
+    const int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+__global__ __launch_bounds__(256) void gq_rank_count(const double* __restrict__ d, int64_t n, int32_t* __restrict__ rank) {
+    __shared__ double s[1024];
+    const int64_t j = int64_t(blockIdx.x) * 256 + threadIdx.x, k0 = int64_t(blockIdx.y) * 1024;
+    for (int e = threadIdx.x; e < 1024; e += 256) s[e] = k0 + e < n ? d[k0 + e] : -1.0;   // diagonal entries are > 0
+    __syncthreads();
+    if (j >= n) return;
+    const double dj = d[j];
+    const int m = static_cast<int>(n - k0 < 1024 ? n - k0 : 1024);
+    int c0 = 0, c1 = 0, c2 = 0, c3 = 0;                       // four counters: the adds do not wait for each other
+    int e = 0;
+    for (; e + 4 <= m; e += 4) {
+        c0 += (s[e] > dj || (s[e] == dj && k0 + e < j)) ? 1 : 0;
+        c1 += (s[e + 1] > dj || (s[e + 1] == dj && k0 + e + 1 < j)) ? 1 : 0;
+        c2 += (s[e + 2] > dj || (s[e + 2] == dj && k0 + e + 2 < j)) ? 1 : 0;
+        c3 += (s[e + 3] > dj || (s[e + 3] == dj && k0 + e + 3 < j)) ? 1 : 0;
+    }
+    for (; e < m; ++e) c0 += (s[e] > dj || (s[e] == dj && k0 + e < j)) ? 1 : 0;
+    atomicAdd(rank + j, (c0 + c1) + (c2 + c3));
+}
+__global__ void gq_rank_place(const int32_t* __restrict__ rank, int64_t n, int32_t* __restrict__ perm) {
+    const int64_t j = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (j < n) perm[rank[j]] = static_cast<int32_t>(j);
+}
+
 // A = J (P (H' + damp I) P^T) J in fp64: A[a][b] = H'[perm[n-1-a]][perm[n-1-b]] (+ damp on the diagonal),
 // H' = H with dead channels' diagonal set to 1
 __global__ void gq_gather(const float* __restrict__ H, int64_t n, const int32_t* __restrict__ perm,
@@ -631,13 +662,20 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
     size_t t_elems = 1;
     for (int64_t s = NB; s < n; s *= 2) t_elems = std::max(t_elems, size_t((n - s + 2 * s - 1) / (2 * s)) * size_t(s) * size_t(s));
     double* T = static_cast<double*>(adadim_workspace(ctx, WS_GPTQ_T, t_elems * sizeof(double)));
-    if (!A || !M || !dvec || !T) return ADADIM_EHIP;
+    int32_t* rank = static_cast<int32_t*>(adadim_workspace(ctx, WS_GPTQ_V, size_t(n) * sizeof(int32_t)));   // free here
+    if (!A || !M || !dvec || !T || !rank) return ADADIM_EHIP;
     double* damp = dvec + n;
     const unsigned nb1 = static_cast<unsigned>((n + 255) / 256), nb2 = static_cast<unsigned>((n * n + 255) / 256);
     ProfScope prof(ctx, "gptq_prepare");
     hipLaunchKernelGGL(gq_diag, dim3(nb1), dim3(256), 0, ctx->stream, H, n, dvec, dead);
     hipLaunchKernelGGL(gq_damp, dim3(1), dim3(256), 0, ctx->stream, dvec, n, static_cast<double>(percdamp), damp);
-    hipLaunchKernelGGL(gq_rank, dim3(nb1), dim3(256), 0, ctx->stream, dvec, n, act_order, perm);
+    if (act_order) {
+        hipLaunchKernelGGL(gq_zero_i32, dim3(nb1), dim3(256), 0, ctx->stream, rank, n);
+        hipLaunchKernelGGL(gq_rank_count, dim3(nb1, static_cast<unsigned>((n + 1023) / 1024)), dim3(256), 0, ctx->stream,
+                           dvec, n, rank);
+        hipLaunchKernelGGL(gq_rank_place, dim3(nb1), dim3(256), 0, ctx->stream, rank, n, perm);
+    } else
+        hipLaunchKernelGGL(gq_rank, dim3(nb1), dim3(256), 0, ctx->stream, dvec, n, act_order, perm);
     hipLaunchKernelGGL(gq_gather, dim3(nb2), dim3(256), 0, ctx->stream, H, n, perm, dvec, damp, A);
     ADADIM_LAUNCH_CHECK(ctx, "gptq prepare");
     // Outer panels of 256 columns: inside a panel the 64-wide steps update the panel's own columns
