@@ -103,6 +103,8 @@ def test_prepare_matches_fp64_factor(ctx, in_f, act_order):
     (256, 264, IC, 3, 128),
     (192, 384, IC, 4, 64),
     (64, 96, OC, 2, 32),         # less than one block
+    (64, 1280, OC, 3, 128),      # ten blocks: the bulk of each block's trailing update runs on the side stream
+    (128, 1160, IC, 4, 128),     # the same per-IC, ragged last block
 ])
 def test_sweep_bit_exact_given_u(ctx, out_f, in_f, dim, bits, group):
     W, X = layer(out_f, in_f, 900, seed=out_f + in_f, dead=(5,))
