@@ -78,26 +78,30 @@ def factor(Hp) -> np.ndarray:
     return np.linalg.cholesky(Hinv).T
 
 
-def _params_f32(mn, mx, qmax):
-    """Scale and zero of one group from its min/max (the quantizer's steps 1, 3, 4; clip = 1), fp32."""
+def _params_f32(mn, mx, qmax, scale_round=None):
+    """Scale and zero of one group from its min/max (the quantizer's steps 1, 3, 4; clip = 1), fp32;
+    scale_round as in adadim_oracle.quantize."""
     zero = _F32(0.0)
     mx = np.maximum(mx, zero)
     mn = np.minimum(mn, zero)
     rng = (mx - mn).astype(_F32)
     scale = (rng / qmax).astype(_F32)
     scale = np.where(rng == zero, _F32(1.0), scale).astype(_F32)
+    if scale_round is not None:
+        scale = np.asarray(scale_round(scale), dtype=_F32)
     z = np.rint(((-mn) / scale).astype(_F32)).astype(_F32)
     z = np.minimum(np.maximum(z, zero), qmax).astype(_F32)
     return scale, z
 
 
-def sweep(W, U, perm, dead, dim: int, bits: int, group: int, block: int = BLOCK) -> dict:
+def sweep(W, U, perm, dead, dim: int, bits: int, group: int, block: int = BLOCK, scale_round=None) -> dict:
     """Step 5 in fp32 (see the module text for the rounding sequence).
 
     W fp16 [out, in]; U fp32 [in, in] upper, in visiting order; perm[i] = original index of
     the channel visited i-th.  Returns codes u8 [out, in], scales f32 / zeros u8 ([out, in/g]
     static for OC, [out/g, in] for IC), What f32, dW f32 = W - What (all in original order),
-    E f32 [out, in] (errors in visiting order)."""
+    E f32 [out, in] (errors in visiting order).  scale_round: every scale (the static ones and the
+    ones computed during the sweep) is rounded into a storage format first, see meta16_oracle."""
     W0 = np.asarray(W).astype(_F32)
     out_f, in_f = W0.shape
     U = np.asarray(U, dtype=_F32)
@@ -108,7 +112,7 @@ def sweep(W, U, perm, dead, dim: int, bits: int, group: int, block: int = BLOCK)
     Wp = np.ascontiguousarray(W0[:, perm])
     if dim == OC:
         g = in_f if group == 0 else group
-        st = quantize(W0, OC, bits, group)        # static parameters: plain per-OC RTN of the original weight
+        st = quantize(W0, OC, bits, group, scale_round=scale_round)   # static: plain per-OC RTN of the original weight
         s_static, z_static = st["scales"], st["zeros"].astype(_F32)
         scales, zeros = st["scales"], st["zeros"]
     else:
@@ -128,7 +132,7 @@ def sweep(W, U, perm, dead, dim: int, bits: int, group: int, block: int = BLOCK)
                 z = z_static[:, j // g]
             else:
                 wg = w.reshape(out_f // g, g)
-                sg, zg = _params_f32(wg.min(axis=1), wg.max(axis=1), qmax)
+                sg, zg = _params_f32(wg.min(axis=1), wg.max(axis=1), qmax, scale_round)
                 scales[:, j] = sg
                 zeros[:, j] = zg.astype(np.uint8)
                 s = np.repeat(sg, g)

@@ -32,6 +32,7 @@ import numpy as np
 
 from . import adadim_oracle as _q
 from . import gemv_oracle as _g
+from . import gptq_oracle as _gq
 
 
 def _check_bits(bits: int) -> int:
@@ -106,3 +107,12 @@ def gemv_ic(packed, meta, x, out_f: int, bits: int, group: int) -> np.ndarray:
 def abs_terms(packed, meta, x, out_f: int, bits: int, group: int) -> np.ndarray:
     scales, zeros = decode(meta, bits)
     return _g.abs_terms(packed, scales, zeros, x, out_f, bits, group)
+
+
+def gptq_sweep(W, U, perm, dead, dim: int, bits: int, group: int) -> dict:
+    """gptq_oracle.sweep (GPTQ in the selected dimension, paper Sec. 3.3 / App. A.1) with every scale rounded into
+    the group word before it is used; adds "meta" (uint16, the shape of scales)."""
+    _check_bits(bits)
+    r = _gq.sweep(W, U, perm, dead, dim, bits, group, scale_round=lambda s: round_scale(s, bits))
+    r["meta"] = encode(r["scales"], r["zeros"], bits)
+    return r

@@ -211,3 +211,37 @@ def test_gemv_unit_vectors_give_columns(bits, group):
     y = m16.gemv_ic(pk, r["meta"], x, 128, bits, group)
     assert y == pytest.approx(r["What"].astype(np.float64) @ x.astype(np.float64), rel=1e-12, abs=1e-12)
     assert (m16.abs_terms(pk, r["meta"], x, 128, bits, group) >= np.abs(y) - 1e-12).all()
+
+
+@pytest.mark.parametrize("dim", [OC, IC])
+def test_gptq_sweep_in_the_format(dim):
+    """GPTQ in the selected dimension with the scales rounded into the group word: with a diagonal Hessian no error
+    is propagated and the sweep must give the plain quantizer of this module; with a full one the sweep's identity
+    W - What = E U must hold and What must be exactly what the stored words and codes de-quantize to."""
+    from oracle import gptq_oracle as G
+    rng = np.random.default_rng(3 + dim)
+    out_f, in_f, bits, group = 64, 96, 4, 32
+    W = _rand_w(out_f, in_f, seed=11 + dim)
+    # diagonal H: act-order still permutes the channels, the result does not depend on it
+    d = rng.uniform(0.5, 4.0, size=in_f)
+    Hp, perm, dead = G.prepare(np.diag(d), 0.01, True)
+    U = G.factor(Hp).astype(np.float32)
+    r = m16.gptq_sweep(W, U, perm, dead, dim, bits, group)
+    q = m16.quantize(W, dim, bits, group)
+    assert np.array_equal(r["codes"], q["codes"]) and np.array_equal(r["meta"], q["meta"])
+    assert np.array_equal(r["dW"], q["dW"])
+    # full H
+    X = rng.standard_normal((300, in_f)) * (1 + 10 * (rng.random(in_f) < 0.05))
+    Hp, perm, dead = G.prepare(X.T @ X, 0.01, True)
+    U = G.factor(Hp).astype(np.float32)
+    r = m16.gptq_sweep(W, U, perm, dead, dim, bits, group)
+    s, z = m16.decode(r["meta"], bits)
+    g = group
+    rep = (lambda a: np.repeat(a, g, axis=1)) if dim == OC else (lambda a: np.repeat(a, g, axis=0))
+    assert np.array_equal(r["What"], (rep(s) * (r["codes"].astype(np.float32) - rep(z).astype(np.float32))).astype(np.float32))
+    lhs = (W.astype(np.float64) - r["What"].astype(np.float64))[:, perm]
+    rhs = r["E"].astype(np.float64) @ U.astype(np.float64)
+    assert np.abs(lhs - rhs).max() <= 1e-4 * np.abs(lhs).max() + 1e-7
+    # and it is not the fp32-scale sweep in disguise
+    r32 = G.sweep(W, U, perm, dead, dim, bits, group)
+    assert (r32["scales"] != r["scales"]).any()
