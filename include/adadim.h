@@ -268,6 +268,17 @@ int adadim_gptq_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in
                          uint32_t* packed);
 
 /*
+ * The sweep in the b + 16/g storage format (see adadim_quantize_meta16): every scale is rounded into the 16-bit
+ * group word before it is used, so the stored words de-quantize to exactly the weights whose errors were spread.
+ *   dim = OC: static_meta u16 [out, in/g] as adadim_quantize_meta16(dim = OC) writes it for the original W;
+ *   dim = IC: meta u16 [out/g, in] is written (the word of (row group, channel) when the channel is visited).
+ * bits 2, 3 or 4; everything else as adadim_gptq_quantize.
+ */
+int adadim_gptq_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                                const float* U, const int32_t* perm, const uint8_t* dead, const uint16_t* static_meta,
+                                uint8_t* codes, uint16_t* meta, float* dW, uint32_t* packed);
+
+/*
  * Layer output for one activation vector from a per-IC quantized weight (Sec. 4.5 and App. D,
  * the per-IC kernel: weight [out x in] in b bits, input [in x 1] and output [out x 1] fp16):
  *     y[o] = sum_j scales[o/g, j] * (code[o, j] - zeros[o/g, j]) * x[j]

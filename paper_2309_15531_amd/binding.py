@@ -23,7 +23,7 @@ EXPORTS = (
     "adadim_layer_error", "adadim_layer_error_prepared", "adadim_layer_error_batch", "adadim_select",
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
-    "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
+    "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_read",
 )
 
@@ -128,6 +128,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_gptq_quantize.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_void_p, c_void_p,
                                          c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.adadim_gptq_quantize.restype = c_int
+    lib.adadim_gptq_quantize_meta16.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, c_int, c_int, c_void_p, c_void_p,
+                                                c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.adadim_gptq_quantize_meta16.restype = c_int
     if path is None:
         _lib = lib
     return lib
@@ -279,6 +282,13 @@ class Context:
     def adadim_gptq_prepare(self, H, perm, dead, U, percdamp: float = 0.01, act_order: bool = True):
         self._check(self._lib.adadim_gptq_prepare(self._h, _ptr(H), H.shape[0], c_float(percdamp), 1 if act_order else 0,
                                                   _ptr(perm), _ptr(dead), _ptr(U)))
+
+    def adadim_gptq_quantize_meta16(self, W, dim: int, bits: int, group: int, U, perm, dead, codes, static_meta=None,
+                                    meta=None, dW=None, packed=None):
+        out_f, in_f = W.shape
+        self._check(self._lib.adadim_gptq_quantize_meta16(self._h, _ptr(W), out_f, in_f, dim, bits, group, _ptr(U),
+                                                          _ptr(perm), _ptr(dead), _ptr(static_meta), _ptr(codes),
+                                                          _ptr(meta), _ptr(dW), _ptr(packed)))
 
     def adadim_gptq_quantize(self, W, dim: int, bits: int, group: int, U, perm, dead, codes, static_scales=None,
                              static_zeros=None, scales=None, zeros=None, dW=None, packed=None):

@@ -496,40 +496,56 @@ int adadim_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t in, float percd
     return launch_gptq_prepare(ctx, H, in, percdamp, act_order, perm, dead, U);
 }
 
-int adadim_gptq_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
-                         const float* U, const int32_t* perm, const uint8_t* dead, const float* static_scales,
-                         const uint8_t* static_zeros, uint8_t* codes, float* scales, uint8_t* zeros, float* dW,
-                         uint32_t* packed) {
+// shared by the two sweep entry points; mfmt != 0: parameters travel as 16-bit group words (static_scales / scales are
+// then u16 arrays and the zero arrays are unused)
+static int gptq_quantize_checked(adadim_ctx* ctx, const char* who, const void* W, int64_t out, int64_t in, int dim, int bits,
+                                 int group, const float* U, const int32_t* perm, const uint8_t* dead,
+                                 const float* static_scales, const uint8_t* static_zeros, uint8_t* codes, float* scales,
+                                 uint8_t* zeros, float* dW, uint32_t* packed, int mfmt) {
     if (!ctx) return ADADIM_ENULL;
     if (!W || !U || !perm || !dead || !codes)
-        return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_quantize: W, U, perm, dead or codes is NULL");
+        return adadim_fail(ctx, ADADIM_ENULL, "%s: W, U, perm, dead or codes is NULL", who);
     if (out <= 0 || in <= 0 || out > 500000 || in > 46340)
-        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: bad shape out=%lld in=%lld", (long long)out,
-                           (long long)in);
+        return adadim_fail(ctx, ADADIM_EINVAL, "%s: bad shape out=%lld in=%lld", who, (long long)out, (long long)in);
     if (dim != ADADIM_DIM_OC && dim != ADADIM_DIM_IC)
-        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: dim must be 0 (OC) or 1 (IC), got %d", dim);
-    if (bits < 2 || bits > 8) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: bits must be in [2,8]");
+        return adadim_fail(ctx, ADADIM_EINVAL, "%s: dim must be 0 (OC) or 1 (IC), got %d", who, dim);
+    if (bits < 2 || bits > (mfmt ? 4 : 8))
+        return adadim_fail(ctx, ADADIM_EINVAL, "%s: bits must be in [2,%d]", who, mfmt ? 4 : 8);
     if (dim == ADADIM_DIM_OC) {
         const int64_t g = group == 0 ? in : group;
-        if (group < 0 || (in % g) != 0)
-            return adadim_fail(ctx, ADADIM_EINVAL, "adadim_gptq_quantize: group %d must be 0 or divide in", group);
-        if (!static_scales || !static_zeros)
-            return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_quantize: per-OC needs the static scales and zeros");
+        if (group < 0 || (in % g) != 0) return adadim_fail(ctx, ADADIM_EINVAL, "%s: group %d must be 0 or divide in", who, group);
+        if (!static_scales || (!mfmt && !static_zeros))
+            return adadim_fail(ctx, ADADIM_ENULL, "%s: per-OC needs the static parameters", who);
         const int rc = launch_gptq_quantize(ctx, static_cast<const __half*>(W), out, in, dim, bits, static_cast<int>(g), U,
-                                            perm, dead, static_scales, static_zeros, codes, nullptr, nullptr, dW);
+                                            perm, dead, static_scales, static_zeros, codes, nullptr, nullptr, dW, mfmt);
         if (rc != ADADIM_OK) return rc;
     } else {
         if ((group != 64 && group != 128) || (out % group) != 0)
-            return adadim_fail(ctx, ADADIM_EINVAL,
-                               "adadim_gptq_quantize: per-IC groups of 64 or 128 rows dividing out are supported, got %d",
+            return adadim_fail(ctx, ADADIM_EINVAL, "%s: per-IC groups of 64 or 128 rows dividing out are supported, got %d", who,
                                group);
-        if (!scales || !zeros) return adadim_fail(ctx, ADADIM_ENULL, "adadim_gptq_quantize: per-IC needs scales and zeros");
+        if (!scales || (!mfmt && !zeros)) return adadim_fail(ctx, ADADIM_ENULL, "%s: per-IC needs the parameter outputs", who);
         const int rc = launch_gptq_quantize(ctx, static_cast<const __half*>(W), out, in, dim, bits, group, U, perm, dead,
-                                            nullptr, nullptr, codes, scales, zeros, dW);
+                                            nullptr, nullptr, codes, scales, zeros, dW, mfmt);
         if (rc != ADADIM_OK) return rc;
     }
     if (packed) return launch_pack(ctx, codes, out, in, dim, bits, packed);
     return ADADIM_OK;
+}
+
+int adadim_gptq_quantize(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                         const float* U, const int32_t* perm, const uint8_t* dead, const float* static_scales,
+                         const uint8_t* static_zeros, uint8_t* codes, float* scales, uint8_t* zeros, float* dW,
+                         uint32_t* packed) {
+    return gptq_quantize_checked(ctx, "adadim_gptq_quantize", W, out, in, dim, bits, group, U, perm, dead, static_scales,
+                                 static_zeros, codes, scales, zeros, dW, packed, 0);
+}
+
+int adadim_gptq_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int64_t in, int dim, int bits, int group,
+                                const float* U, const int32_t* perm, const uint8_t* dead, const uint16_t* static_meta,
+                                uint8_t* codes, uint16_t* meta, float* dW, uint32_t* packed) {
+    return gptq_quantize_checked(ctx, "adadim_gptq_quantize_meta16", W, out, in, dim, bits, group, U, perm, dead,
+                                 reinterpret_cast<const float*>(static_meta), nullptr, codes,
+                                 reinterpret_cast<float*>(meta), nullptr, dW, packed, bits);
 }
 
 }  // extern "C"

@@ -141,6 +141,6 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
                         uint8_t* dead, float* U);
 int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
                          const float* U, const int32_t* perm, const uint8_t* dead, const float* st_scales,
-                         const uint8_t* st_zeros, uint8_t* codes, float* scales_out, uint8_t* zeros_out, float* dW);
+                         const uint8_t* st_zeros, uint8_t* codes, float* scales_out, uint8_t* zeros_out, float* dW, int mfmt);
 int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const void* scales, const uint8_t* zeros, const __half* x,
                    int64_t out, int64_t in, int bits, int g, __half* y, bool meta16);

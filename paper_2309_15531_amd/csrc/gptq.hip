@@ -22,6 +22,7 @@
 // looked up by the channel's original index); per-IC recomputes each (row group, channel)'s
 // parameters from the channel's current values when it is visited.
 #include "common.h"
+#include "scale_format.h"
 
 #include <algorithm>
 #include <type_traits>
@@ -368,12 +369,14 @@ struct QP {
     float scale, zero;
 };
 // the quantizer's parameters from a group's min and max (clip = 1): same formulas as adadim_quantize
-__device__ __forceinline__ QP params_of(float mn, float mx, float qmax) {
+// (mfmt != 0: the scale rounded into the 16-bit group word first, as adadim_quantize_meta16 does)
+__device__ __forceinline__ QP params_of(float mn, float mx, float qmax, int mfmt) {
     mx = fmaxf(mx, 0.0f);
     mn = fminf(mn, 0.0f);
     const float range = mx - mn;
     float scale = range / qmax;
     if (range == 0.0f) scale = 1.0f;
+    if (mfmt) scale = round_scale(scale, mfmt);
     float z = rintf((-mn) / scale);
     z = fminf(fmaxf(z, 0.0f), qmax);
     return {scale, z};
@@ -421,7 +424,8 @@ __global__ void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t i
 template <bool IC, int RPL>
 __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const float* __restrict__ U,
                                                const int32_t* __restrict__ perm, int64_t out, int64_t in, int64_t i1,
-                                               int nbw, int g, float qmax, const float* __restrict__ st_scales,
+                                               int nbw, int g, float qmax, int mfmt,
+                                               const float* __restrict__ st_scales,
                                                const uint8_t* __restrict__ st_zeros, float* __restrict__ scales_out,
                                                uint8_t* __restrict__ zeros_out, uint8_t* __restrict__ Qp,
                                                float* __restrict__ Ep) {
@@ -482,8 +486,15 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
 #pragma unroll
                 for (int c = 0; c < SB; ++c) {
                     const bool have = ok[0] && (FULL || c < sbw);
-                    st[c].scale = have ? st_scales[row[0] * n_cg + jo[c] / g] : 1.0f;
-                    st[c].zero = have ? static_cast<float>(st_zeros[row[0] * n_cg + jo[c] / g]) : 0.0f;
+                    if (mfmt) {                                            // static parameters as group words
+                        const uint32_t wd = have ? reinterpret_cast<const uint16_t*>(st_scales)[row[0] * n_cg + jo[c] / g]
+                                                 : (0x3C00u >> (mfmt - 1)) << mfmt;           // scale 1, zero 0
+                        st[c].scale = word_scale(wd, mfmt);
+                        st[c].zero = word_zero(wd, mfmt);
+                    } else {
+                        st[c].scale = have ? st_scales[row[0] * n_cg + jo[c] / g] : 1.0f;
+                        st[c].zero = have ? static_cast<float>(st_zeros[row[0] * n_cg + jo[c] / g]) : 0.0f;
+                    }
                 }
             }
 #pragma unroll
@@ -501,12 +512,11 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
                         }
                         mn = wave_min(mn);
                         mx = -wave_min(-mx);
-                        const QP q1 = params_of(mn, mx, qmax);
+                        const QP q1 = params_of(mn, mx, qmax, mfmt);
 #pragma unroll
                         for (int p = 0; p < RPL; ++p) pr[p] = q1;
                         if (lane == 0) {
-                            scales_out[int64_t(blockIdx.x) * in + j] = q1.scale;
-                            zeros_out[int64_t(blockIdx.x) * in + j] = static_cast<uint8_t>(q1.zero);
+                            store_params(scales_out, zeros_out, int64_t(blockIdx.x) * in + j, q1.scale, q1.zero, mfmt);
                         }
                     } else {
                         pr[0] = st[c];
@@ -603,7 +613,7 @@ __global__ void gq_invperm(const int32_t* __restrict__ perm, int64_t in, int32_t
 template <bool IC>
 __global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __restrict__ visited,
                            const uint8_t* __restrict__ dead, const __half* __restrict__ W, int64_t out, int64_t in, int g,
-                           const float* __restrict__ scales, const uint8_t* __restrict__ zeros,
+                           const float* __restrict__ scales, const uint8_t* __restrict__ zeros, int mfmt,
                            uint8_t* __restrict__ codes, float* __restrict__ dW) {
     const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
     if (idx >= out * in) return;
@@ -612,7 +622,16 @@ __global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __rest
     codes[idx] = q;
     if (dW) {
         const int64_t pi = IC ? (r / g) * in + j : r * (in / g) + j / g;
-        const float wq = scales[pi] * (static_cast<float>(q) - static_cast<float>(zeros[pi]));
+        float sc, zp;
+        if (mfmt) {
+            const uint32_t wd = reinterpret_cast<const uint16_t*>(scales)[pi];
+            sc = word_scale(wd, mfmt);
+            zp = word_zero(wd, mfmt);
+        } else {
+            sc = scales[pi];
+            zp = static_cast<float>(zeros[pi]);
+        }
+        const float wq = sc * (static_cast<float>(q) - zp);
         dW[r * in + j] = (dead[j] ? 0.0f : __half2float(W[r * in + j])) - wq;
     }
 }
@@ -714,7 +733,8 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
 
 int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int bits, int g,
                          const float* U, const int32_t* perm, const uint8_t* dead, const float* st_scales,
-                         const uint8_t* st_zeros, uint8_t* codes, float* scales_out, uint8_t* zeros_out, float* dW) {
+                         const uint8_t* st_zeros, uint8_t* codes, float* scales_out, uint8_t* zeros_out, float* dW,
+                         int mfmt) {
     const size_t mat = size_t(out) * size_t(in) * sizeof(float);
     float* Wp = static_cast<float*>(adadim_workspace(ctx, WS_GPTQ_W, mat));
     float* Ep = static_cast<float*>(adadim_workspace(ctx, WS_GPTQ_E, mat));
@@ -756,7 +776,7 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
             ProfScope prof(ctx, "gptq_sweep");
 #define GQ_GO(IC_, RPL_)                                                                                          \
     hipLaunchKernelGGL((gq_sweep<IC_, RPL_>), dim3(blocks), dim3(256), smem, ctx->stream, Wp, U, perm, out, in, i1, \
-                       nbw, g, qmax, st_scales, st_zeros, scales_out, zeros_out, Qp, Ep)
+                       nbw, g, qmax, mfmt, st_scales, st_zeros, scales_out, zeros_out, Qp, Ep)
             if (!ic) GQ_GO(false, 1);
             else if (rpl == 1) GQ_GO(true, 1);
             else GQ_GO(true, 2);
@@ -792,10 +812,10 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
                            visited);
         if (ic)
             hipLaunchKernelGGL(gq_scatter<true>, dim3(eb), dim3(256), 0, ctx->stream, Qp, visited, dead, W, out, in, g,
-                               scales_out, zeros_out, codes, dW);
+                               scales_out, zeros_out, mfmt, codes, dW);
         else
             hipLaunchKernelGGL(gq_scatter<false>, dim3(eb), dim3(256), 0, ctx->stream, Qp, visited, dead, W, out, in, g,
-                               st_scales, st_zeros, codes, dW);
+                               st_scales, st_zeros, mfmt, codes, dW);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gptq sweep");
     return ADADIM_OK;

@@ -287,24 +287,33 @@ class GptqAda:
     """`gptq_ada` of App. B: the RTN search picks the dimension, GPTQ then quantizes in it.
     Per-OC uses the RTN winner's parameters as static groups; per-IC (group 64 or 128) recomputes
     them channel by channel.  Results: codes u8 [out, in], scales, zeros, packed; `loss_rtn` and
-    `loss_gptq` (device scalars) are the layer errors before and after."""
+    `loss_gptq` (device scalars) are the layer errors before and after.  meta16: search and sweep in
+    the b + 16/g storage format; the parameters are then the group words in `meta`."""
 
-    def __init__(self, ctx: B.Context, out_f: int, in_f: int, bits: int, group: int, device="cuda"):
+    def __init__(self, ctx: B.Context, out_f: int, in_f: int, bits: int, group: int, device="cuda", meta16: bool = False):
         self.ctx, self.out_f, self.in_f, self.bits, self.group = ctx, out_f, in_f, bits, group
-        self.search = LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,))
+        self.meta16 = meta16
+        self.search = LayerSearch(ctx, out_f, in_f, bits, group, clips=(1.0,), meta16=meta16)
         self.codes = torch.empty((out_f, in_f), dtype=torch.uint8, device=device)
         self.dW = torch.empty((out_f, in_f), dtype=torch.float32, device=device)
         self.loss_gptq = torch.empty(1, dtype=torch.float32, device=device)
         g_ic = out_f if group == 0 else group
         self.ic_scales = torch.empty((out_f // g_ic, in_f), dtype=torch.float32, device=device)
         self.ic_zeros = torch.empty((out_f // g_ic, in_f), dtype=torch.uint8, device=device)
-        self.scales = self.zeros = None
+        self.ic_meta = torch.empty((out_f // g_ic, in_f), dtype=torch.int16, device=device) if meta16 else None
+        self.scales = self.zeros = self.meta = None
         self.packed = self.search._packed[0]
 
     def run(self, W, hp: PreparedHessian, fac: GptqFactor):
         best, dim, _ = self.search.run(W, hp)
         self.loss_rtn = self.search.losses[best:best + 1]
-        if dim == B.DIM_OC:
+        if self.meta16:
+            self.meta = self.search.meta if dim == B.DIM_OC else self.ic_meta
+            self.ctx.adadim_gptq_quantize_meta16(W, dim, self.bits, self.group, fac.U, fac.perm, fac.dead, self.codes,
+                                                 static_meta=self.meta if dim == B.DIM_OC else None,
+                                                 meta=None if dim == B.DIM_OC else self.meta, dW=self.dW,
+                                                 packed=self.packed)
+        elif dim == B.DIM_OC:
             # static groups: the search's per-OC parameters (of the weight as given; a layer with dead
             # input channels should be passed with those columns already zero)
             self.scales, self.zeros = self.search.scales, self.search.zeros

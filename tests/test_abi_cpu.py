@@ -123,6 +123,29 @@ def test_gemv_validation(ctx):
     assert ctx._lib.adadim_score_elems(300, 64) == 512 * 64 and ctx._lib.adadim_score_elems(300, 40) == 300 * 40
 
 
+def test_gptq_validation(ctx):
+    """GPTQ entry points: argument checks that run before any launch."""
+    f1 = ctypes.c_float(0.01)
+    pr = lambda *a: ctx.raw("adadim_gptq_prepare", *a)
+    assert pr(None, 64, f1, 1, A16, A16, A16) == B.ENULL
+    assert pr(A16, 0, f1, 1, A16, A16, A16) == B.EINVAL
+    assert "adadim_gptq_prepare" in ctx.last_error()
+    gq = lambda *a: ctx.raw("adadim_gptq_quantize", *a)
+    assert gq(A16, 64, 64, 0, 4, 32, None, A16, A16, A16, A16, A16, None, None, None, None) == B.ENULL       # U
+    assert gq(A16, 64, 64, 0, 4, 32, A16, A16, A16, None, None, A16, None, None, None, None) == B.ENULL     # static parameters
+    assert gq(A16, 64, 64, 0, 4, 48, A16, A16, A16, A16, A16, A16, None, None, None, None) == B.EINVAL      # group does not divide in
+    assert gq(A16, 128, 64, 1, 4, 32, A16, A16, A16, None, None, A16, A16, A16, None, None) == B.EINVAL     # per-IC group 64 or 128
+    assert gq(A16, 128, 64, 1, 4, 64, A16, A16, A16, None, None, A16, None, None, None, None) == B.ENULL    # per-IC outputs
+    assert gq(A16, 64, 64, 2, 4, 32, A16, A16, A16, A16, A16, A16, None, None, None, None) == B.EINVAL      # dim
+    assert "adadim_gptq_quantize" in ctx.last_error()
+    gm = lambda *a: ctx.raw("adadim_gptq_quantize_meta16", *a)
+    assert gm(A16, 64, 64, 0, 5, 32, A16, A16, A16, A16, A16, None, None, None) == B.EINVAL                 # 2, 3 or 4 bits
+    assert gm(A16, 64, 64, 0, 4, 32, A16, A16, A16, None, A16, None, None, None) == B.ENULL                 # static words
+    assert gm(A16, 128, 64, 1, 4, 64, A16, A16, A16, None, A16, None, None, None) == B.ENULL                # word output
+    assert gm(A16, 128, 64, 1, 4, 32, A16, A16, A16, None, A16, A16, None, None) == B.EINVAL
+    assert "adadim_gptq_quantize_meta16" in ctx.last_error()
+
+
 def test_capture_validation(ctx):
     """Graph recording: argument checks that need no device (the test context sits on the default stream)."""
     assert ctx._lib.adadim_capture_begin(None) == B.ENULL

@@ -15,6 +15,7 @@ import oracle
 from oracle import OC, IC
 from oracle import gptq_oracle as G
 from paper_2309_15531_amd import binding as B
+from paper_2309_15531_amd import search as S
 from paper_2309_15531_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -173,3 +174,59 @@ def test_q_proj_shape_sampled(ctx):
         assert np.array_equal(got["scales"][rg], ref["scales"][0])
         assert np.array_equal(got["zeros"][rg], ref["zeros"][0])
         assert np.array_equal(got["dW"][sl], ref["dW"])
+
+
+@pytest.mark.parametrize("out_f,in_f,dim,bits,group", [
+    (128, 320, OC, 3, 64),
+    (200, 264, OC, 4, 0),
+    (256, 264, IC, 3, 128),
+    (192, 384, IC, 4, 64),
+    (128, 1160, IC, 2, 128),
+])
+def test_sweep_in_the_storage_format_bit_exact(ctx, out_f, in_f, dim, bits, group):
+    """adadim_gptq_quantize_meta16 against the oracle's sweep with every scale rounded into the group word."""
+    from oracle import meta16_oracle as m16
+    W, X = layer(out_f, in_f, 900, seed=out_f + in_f + 1, dead=(5,))
+    H32 = oracle.hessian(X).astype(np.float32)
+    Hp, perm, dead = G.prepare(H32, 0.01, True)
+    U32 = G.factor(Hp).astype(np.float32)
+    ref = m16.gptq_sweep(W, U32, perm, dead, dim, bits, group)
+    Wd, Ud, pd, dd = dev(W), dev(U32), dev(perm.astype(np.int32)), dev(dead.astype(np.uint8))
+    codes = torch.full((out_f, in_f), 255, dtype=torch.uint8, device="cuda")
+    dW = torch.full((out_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    n_ch, ln = (out_f, in_f) if dim == OC else (in_f, out_f)
+    packed = torch.full((n_ch, (ln * bits + 31) // 32), -1, dtype=torch.int32, device="cuda")
+    if dim == OC:
+        g = in_f if group == 0 else group
+        meta = torch.full((out_f, in_f // g), -1, dtype=torch.int16, device="cuda")
+        Wz = Wd.clone()
+        Wz[:, dd.bool()] = 0
+        ctx.adadim_quantize_meta16(Wz, OC, bits, group, 1.0, meta=meta)
+        ctx.adadim_gptq_quantize_meta16(Wd, dim, bits, group, Ud, pd, dd, codes, static_meta=meta, dW=dW, packed=packed)
+    else:
+        meta = torch.full((out_f // group, in_f), -1, dtype=torch.int16, device="cuda")
+        ctx.adadim_gptq_quantize_meta16(Wd, dim, bits, group, Ud, pd, dd, codes, meta=meta, dW=dW, packed=packed)
+    torch.cuda.synchronize()
+    assert np.array_equal(meta.cpu().numpy().view(np.uint16), ref["meta"])
+    assert np.array_equal(codes.cpu().numpy(), ref["codes"])
+    assert np.array_equal(dW.cpu().numpy(), ref["dW"])
+    assert np.array_equal(packed.cpu().numpy().view(np.uint32), oracle.pack(ref["codes"], dim, bits))
+
+
+def test_gptq_ada_in_the_storage_format(ctx):
+    """GptqAda(meta16=True): search and sweep in the format; the result improves on RTN and its words and codes give
+    the dW that was scored."""
+    from oracle import meta16_oracle as m16
+    out_f, in_f, bits, group = 256, 512, 4, 128
+    W, X = layer(out_f, in_f, 2000, seed=77)
+    hp = S.PreparedHessian(ctx, in_f).update(dev(X)).prepare()
+    fac = S.GptqFactor(ctx, hp)
+    ga = S.GptqAda(ctx, out_f, in_f, bits, group, meta16=True)
+    dim = ga.run(dev(W), hp, fac)
+    torch.cuda.synchronize()
+    assert ga.loss_gptq.item() < ga.loss_rtn.item()
+    meta = ga.meta.cpu().numpy().view(np.uint16).reshape((out_f, in_f // group) if dim == OC else (out_f // group, in_f))
+    s, z = m16.decode(meta, bits)
+    rep = (lambda a: np.repeat(a, group, axis=1)) if dim == OC else (lambda a: np.repeat(a, group, axis=0))
+    what = (rep(s) * (ga.codes.cpu().numpy().astype(np.float32) - rep(z).astype(np.float32))).astype(np.float32)
+    assert np.array_equal(ga.dW.cpu().numpy(), W.astype(np.float32) - what)
