@@ -201,11 +201,19 @@ def gptq_bench(args):
     }))
 
 
+# (warm-up, timed) steps when the flags are absent.  The chip needs some tens of milliseconds of load before its
+# clocks settle (the first 20 q_proj steps of a process run 5 % slower than the 200 after them), so the defaults
+# time a few tenths of a second of sustained work; clip_grid has 50 launches per step and stays within the
+# library's 8192 timed launches.
+DEFAULT_STEPS = {"toy": (20, 200), "q_proj": (20, 200), "gate_proj": (20, 200), "down_proj": (10, 100), "qkv": (20, 200),
+                 "clip_grid": (5, 50), "gemv_ic": (100, 2000), "gptq": (3, 30)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: by workload, see DEFAULT_STEPS)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them")
     ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["gemv_ic", "gptq"])
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
@@ -220,6 +228,9 @@ def main():
                     help="also run one plain 256 MiB device copy, the reference dispatch that scales "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
+    d_warm, d_steps = DEFAULT_STEPS.get(args.workload, DEFAULT_STEPS["q_proj"])
+    args.steps = d_steps if args.steps is None else args.steps
+    args.warmup = d_warm if args.warmup is None else args.warmup
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (layers are independent, so a multi-GPU run would "
               "deal whole layers to ranks); run with --gpus 1", file=sys.stderr)

@@ -382,23 +382,35 @@ __device__ __forceinline__ QP params_of(float mn, float mx, float qmax, int mfmt
     return {scale, z};
 }
 
-// minimum over the wavefront, the same value in every lane: butterflies inside the rows of 16 lanes
-// through DPP, then the four rows through lane reads (min is exact, any order gives the same bits)
-template <int CTRL>
-__device__ __forceinline__ float gq_dpp(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float wave_min(float v) {
-    v = fminf(v, gq_dpp<0xB1>(v));                            // lane ^ 1
-    v = fminf(v, gq_dpp<0x4E>(v));                            // lane ^ 2
-    v = fminf(v, gq_dpp<0x141>(v));                           // mirror within 8
-    v = fminf(v, gq_dpp<0x140>(v));                           // mirror within 16
-    const int b = __builtin_bit_cast(int, v);
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
-    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
-    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
-    return fminf(fminf(r0, r1), fminf(r2, r3));
+// Minima of two values over the wavefront, the same in every lane (min is exact, any order gives the
+// same bits).  Butterflies inside the rows of 16 lanes, then row 0 into 1 and 2 into 3, then lane 31
+// into the upper half, all as v_min_f32 with a DPP operand; lane 63 holds the result.  The two chains
+// are interleaved and padded so that two wait states separate a write from the DPP read of it.
+// Needs every lane active.
+__device__ __forceinline__ void wave_min2(float& a, float& b) {
+    asm volatile(
+        "s_nop 1\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "v_min_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "v_min_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_mirror row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 0\n\t"
+        "v_min_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "v_min_f32_dpp %1, %1, %1 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+        "s_nop 1"
+        : "+v"(a), "+v"(b));
+    a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, a), 63));
+    b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, b), 63));
 }
 
 // Wp[r][i] = W[r][perm[i]] as fp32, zero for dead channels
@@ -478,11 +490,11 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
             }
             // the sub-block's original channel indices and, for static groups, its parameters: fetched
             // together up front, off the channel-by-channel chain
-            int32_t jo[SB];
             QP st[SB];
-#pragma unroll
-            for (int c = 0; c < SB; ++c) jo[c] = (FULL || c < sbw) ? perm[i1 + s0 + c] : 0;
             if constexpr (!IC) {
+                int32_t jo[SB];
+#pragma unroll
+                for (int c = 0; c < SB; ++c) jo[c] = (FULL || c < sbw) ? perm[i1 + s0 + c] : 0;
 #pragma unroll
                 for (int c = 0; c < SB; ++c) {
                     const bool have = ok[0] && (FULL || c < sbw);
@@ -497,26 +509,37 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
                     }
                 }
             }
+            float my_scale = 1.0f, my_zero = 0.0f;                          // lane c: channel c's parameters (per-IC)
 #pragma unroll
             for (int c = 0; c < SB; ++c) {
                 if (FULL || c < sbw) {                                      // uniform
-                    const int32_t j = jo[c];                               // original channel (uniform)
-                    const float d = Us[(s0 + c) * GB + s0 + c];
+                    // row s0 + c of the block of U, columns s0 .. s0 + 15: four 16-byte reads at a wave-uniform
+                    // address, every index below a constant
+                    float u[SB];
+#pragma unroll
+                    for (int q4 = 0; q4 < SB / 4; ++q4) {
+                        const float4 t = *reinterpret_cast<const float4*>(Us + (s0 + c) * GB + s0 + 4 * q4);
+                        u[4 * q4 + 0] = t.x;
+                        u[4 * q4 + 1] = t.y;
+                        u[4 * q4 + 2] = t.z;
+                        u[4 * q4 + 3] = t.w;
+                    }
+                    const float d = u[c];
                     QP pr[RPL];
                     if constexpr (IC) {
-                        float mn = w[0][c], mx = w[0][c];
+                        float mn = w[0][c], nmx = -w[0][c];
 #pragma unroll
                         for (int p = 1; p < RPL; ++p) {
                             mn = fminf(mn, w[p][c]);
-                            mx = fmaxf(mx, w[p][c]);
+                            nmx = fminf(nmx, -w[p][c]);
                         }
-                        mn = wave_min(mn);
-                        mx = -wave_min(-mx);
-                        const QP q1 = params_of(mn, mx, qmax, mfmt);
+                        wave_min2(mn, nmx);
+                        const QP q1 = params_of(mn, -nmx, qmax, mfmt);
 #pragma unroll
                         for (int p = 0; p < RPL; ++p) pr[p] = q1;
-                        if (lane == 0) {
-                            store_params(scales_out, zeros_out, int64_t(blockIdx.x) * in + j, q1.scale, q1.zero, mfmt);
+                        if (lane == c) {                                    // two selects; stored after the chain
+                            my_scale = q1.scale;
+                            my_zero = q1.zero;
                         }
                     } else {
                         pr[0] = st[c];
@@ -528,10 +551,12 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
                         const float wq = pr[p].scale * (q - pr[p].zero);
                         qpk[p][c / 4] |= static_cast<uint32_t>(q) << (8 * (c % 4));
                         e[p][c] = (w[p][c] - wq) / d;
+                        // (constant bounds with a test, not "cc = c + 1": a trip count that depends on c is
+                        // unrolled too late, after the loop has been vectorized with a run-time-indexed remainder)
 #pragma unroll
-                        for (int cc = c + 1; cc < SB; ++cc) {
-                            if (FULL || cc < sbw) {
-                                const float upd = e[p][c] * Us[(s0 + c) * GB + s0 + cc];
+                        for (int cc = 0; cc < SB; ++cc) {
+                            if (cc > c && (FULL || cc < sbw)) {
+                                const float upd = e[p][c] * u[cc];
                                 w[p][cc] = w[p][cc] - upd;
                             }
                         }
@@ -540,6 +565,10 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
 #pragma unroll
                     for (int p = 0; p < RPL; ++p) e[p][c] = 0.0f;
                 }
+            }
+            if constexpr (IC) {
+                if (lane < sbw)
+                    store_params(scales_out, zeros_out, int64_t(blockIdx.x) * in + perm[i1 + s0 + lane], my_scale, my_zero, mfmt);
             }
             // the sub-block's codes and errors, in visiting order
 #pragma unroll
