@@ -428,11 +428,12 @@ __global__ void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t i
 // block's row group (RPL = g/64), so that the group's minimum and maximum are a lane-local step
 // plus one wave reduction.  The rows live in an LDS strip; the channels are walked in sub-blocks of
 // 16 that the first wave holds in registers: the sub-block's own updates stay in registers, then
-// its 16 errors are posted in LDS and all four waves apply them to the rest of the block, each wave
-// a quarter of the columns, one LDS read and one write per element for 16 updates, always in
-// channel order (which wave applies them does not change a bit).  The block of U is staged in LDS
-// and read with wave-uniform addresses.  Codes go out in visiting order (16 bytes per row and
-// sub-block).
+// its 16 errors are posted in LDS.  All four waves apply them to the next sub-block's 16 columns at
+// once, so that the chain can go on; the columns behind those receive them from the other three
+// waves while the first one walks the next sub-block (two error buffers, taken in turn).  One LDS
+// read and one write per element for 16 updates, always in channel order (which wave applies them
+// does not change a bit).  The block of U is staged in LDS and read with wave-uniform addresses.
+// Codes go out in visiting order (16 bytes per row and sub-block).
 template <bool IC, int RPL>
 __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const float* __restrict__ U,
                                                const int32_t* __restrict__ perm, int64_t out, int64_t in, int64_t i1,
@@ -445,7 +446,7 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
     extern __shared__ __align__(16) char smem[];
     float* Us = reinterpret_cast<float*>(smem);                         // [GB][GB]: rows / columns i1.. of U
     float* Ws = Us + GB * GB;                                           // [64 * RPL][PITCH]
-    float* Es = Ws + 64 * RPL * PITCH;                                  // [64 * RPL][SB + 1]: the sub-block's errors
+    float* Es0 = Ws + 64 * RPL * PITCH;                                 // [2][64 * RPL][SB + 1]: the errors of this sub-block and the last
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int e4 = threadIdx.x; e4 < nbw * (GB / 4); e4 += 256) {        // in % 4 == 0 is not required: guarded
         const int k = e4 / (GB / 4), c4 = (e4 % (GB / 4)) * 4;
@@ -473,8 +474,35 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
     }
     __syncthreads();
     const int n_cg = IC ? 0 : static_cast<int>(in / g);
+    // errors of a sub-block applied to columns [c_lo, c_hi), every `step`-th from c_lo + first; channel order kept
+    // per element (which wave applies them does not change a bit)
+    auto apply = [&](const float* Esrc, int k0, int kw, int c_lo, int c_hi, int first, int step) {
+        float e[RPL][SB];
+#pragma unroll
+        for (int p = 0; p < RPL; ++p)
+#pragma unroll
+            for (int k = 0; k < SB; ++k) e[p][k] = Esrc[(lane * RPL + p) * (SB + 1) + k];
+        for (int cc = c_lo + first; cc < c_hi; cc += step) {
+            float u[SB];
+#pragma unroll
+            for (int k = 0; k < SB; ++k) u[k] = k < kw ? Us[(k0 + k) * GB + cc] : 0.0f;
+#pragma unroll
+            for (int p = 0; p < RPL; ++p) {
+                if (!ok[p]) continue;
+                float v = Ws[(lane * RPL + p) * PITCH + cc];
+#pragma unroll
+                for (int k = 0; k < SB; ++k) {
+                    const float upd = e[p][k] * u[k];
+                    v = v - upd;
+                }
+                Ws[(lane * RPL + p) * PITCH + cc] = v;
+            }
+        }
+    };
     for (int s0 = 0; s0 < nbw; s0 += SB) {
         const int sbw = nbw - s0 < SB ? nbw - s0 : SB;
+        float* Es = Es0 + ((s0 / SB) & 1) * (64 * RPL * (SB + 1));
+        const float* Es_last = Es0 + (((s0 / SB) & 1) ^ 1) * (64 * RPL * (SB + 1));
         // the sequential part, one wave; FULL: all 16 channels exist (every sub-block but a ragged last
         // one), which takes the bounds tests and their branches out of the chain
         auto sub_block = [&](auto full_tag) {
@@ -599,33 +627,14 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
             if (sbw == SB) sub_block(std::true_type{});
             else sub_block(std::false_type{});
             __builtin_amdgcn_s_setprio(0);
+        } else if (s0 > 0 && s0 + SB < nbw) {
+            // meanwhile the other three waves bring the columns behind this sub-block up to date with the
+            // errors of the sub-block before it (this sub-block's own columns got them ahead of the chain)
+            apply(Es_last, s0 - SB, SB, s0 + SB, nbw, wave - 1, 3);
         }
         __syncthreads();
-        // its errors applied to the rest of the block, channel order kept per element; wave v takes
-        // the columns s0 + 16 + v, + 4, ...
-        if (s0 + SB < nbw) {
-            float e[RPL][SB];
-#pragma unroll
-            for (int p = 0; p < RPL; ++p)
-#pragma unroll
-                for (int k = 0; k < SB; ++k) e[p][k] = Es[(lane * RPL + p) * (SB + 1) + k];
-            for (int cc = s0 + SB + wave; cc < nbw; cc += 4) {
-                float u[SB];
-#pragma unroll
-                for (int k = 0; k < SB; ++k) u[k] = k < sbw ? Us[(s0 + k) * GB + cc] : 0.0f;
-#pragma unroll
-                for (int p = 0; p < RPL; ++p) {
-                    if (!ok[p]) continue;
-                    float v = Ws[(lane * RPL + p) * PITCH + cc];
-#pragma unroll
-                    for (int k = 0; k < SB; ++k) {
-                        const float upd = e[p][k] * u[k];
-                        v = v - upd;
-                    }
-                    Ws[(lane * RPL + p) * PITCH + cc] = v;
-                }
-            }
-        }
+        // the new errors go to the next sub-block's columns at once, all four waves, so that the chain can go on
+        if (s0 + SB < nbw) apply(Es, s0, sbw, s0 + SB, s0 + 2 * SB < nbw ? s0 + 2 * SB : nbw, wave, 4);
         __syncthreads();
     }
 }
@@ -774,15 +783,15 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
     const bool ic = dim == ADADIM_DIM_IC;
     const int rpl = ic ? g / 64 : 1;                                   // rows per lane
     const unsigned blocks = static_cast<unsigned>(ic ? out / g : (out + 63) / 64);
-    const size_t smem = (size_t(GB) * GB + size_t(64) * rpl * (GB + 1) + size_t(64) * rpl * 17) * sizeof(float);
+    const size_t smem = (size_t(GB) * GB + size_t(64) * rpl * (GB + 1) + size_t(2) * 64 * rpl * 17) * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
         ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 2>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 1>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<false, 1>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         attr_set = true;
     }
     const unsigned eb = static_cast<unsigned>((out * in + 255) / 256);
