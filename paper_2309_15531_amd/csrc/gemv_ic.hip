@@ -57,19 +57,34 @@ __device__ __forceinline__ uint32_t hide(uint32_t v) {
     return v;
 }
 #define UBYTE(v, n) ubyte(v, n)
+// (v & mask) | orc in one instruction: the encoding takes one scalar operand, so the mask travels in a scalar
+// register and the or-constant in a vector register (see hide()); left alone the compiler emits an and and an or,
+// each with a literal
+__device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t orc) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(v), "s"(mask), "v"(orc));
+    return r;
+}
 
 // acc[k] += a * code k of the lane's 32 codes
 template <int PB>
 __device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (&acc)[32]) {
     if constexpr (PB == 4) {
-        const float a16 = a * 0.0625f;                      // odd nibbles are read as 16 * code
+        // A nibble placed in the low fraction bits of an fp16 pattern is that code plus a constant: bits 0..3
+        // under the exponent of [1024, 2048) read 1024 + code, bits 4..7 under that of [64, 128) read 64 + code.
+        // One and-or builds two such halves, and v_fma_mix_f32 takes either half as an operand, so a code costs
+        // 5/8 + 1 instructions and no conversion.  The constants leave with the zero-point sum (see OFFSET).
+        const uint32_t c1024 = hide(0x64006400u), c64 = hide(0x54005400u);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t ev = hide(wd.w[i] & 0x0F0F0F0Fu), od = hide(wd.w[i] & 0xF0F0F0F0u);
+            const uint32_t w0 = wd.w[i], w8 = w0 >> 8;
+            const uint32_t p[4] = {and_or(w0, 0x000F000Fu, c1024), and_or(w0, 0x00F000F0u, c64),
+                                   and_or(w8, 0x000F000Fu, c1024), and_or(w8, 0x00F000F0u, c64)};
 #pragma unroll
             for (int n = 0; n < 4; ++n) {
-                acc[8 * i + 2 * n] = fmaf(a, UBYTE(ev, n), acc[8 * i + 2 * n]);
-                acc[8 * i + 2 * n + 1] = fmaf(a16, UBYTE(od, n), acc[8 * i + 2 * n + 1]);
+                const __half2 h = *reinterpret_cast<const __half2*>(&p[n]);
+                acc[8 * i + n] = fmaf(__low2float(h), a, acc[8 * i + n]);           // nibble n
+                acc[8 * i + n + 4] = fmaf(__high2float(h), a, acc[8 * i + n + 4]);   // nibble n + 4
             }
         }
     } else if constexpr (PB == 2) {
@@ -131,7 +146,7 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
     float acc[32];
 #pragma unroll
     for (int k = 0; k < 32; ++k) acc[k] = 0.0f;
-    float zsum = 0.0f;
+    float zsum = 0.0f, asum = 0.0f;                           // sums of a * zero and (4 bits) of a
     // four columns per step, the next step's loads issued before this step's arithmetic
     struct Step {
         Words<PB> wd[4];
@@ -173,6 +188,7 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             zsum = fmaf(a[c], z[c], zsum);
+            if constexpr (PB == 4) asum += a[c];
             accumulate<PB>(st.wd[c], a[c], acc);
         }
     };
@@ -189,8 +205,12 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
             if (j0 + 4 < j_end) consume(B2);
         }
     }
+    // OFFSET: 4-bit codes were read as code + 1024 (even positions) or code + 64 (odd ones)
 #pragma unroll
-    for (int k = 0; k < 32; ++k) s_acc[wave][k][lane] = acc[k] - zsum;
+    for (int k = 0; k < 32; ++k) {
+        const float off = PB == 4 ? ((k & 1) ? 64.0f : 1024.0f) : 0.0f;
+        s_acc[wave][k][lane] = (acc[k] - off * asum) - zsum;
+    }
     __syncthreads();
     // thread t adds up the waves for outputs 4t .. 4t+3 of the block's 2048
     const int t = threadIdx.x;
