@@ -56,7 +56,6 @@ __device__ __forceinline__ uint32_t hide(uint32_t v) {
     asm("" : "+v"(v));
     return v;
 }
-#define UBYTE(v, n) ubyte(v, n)
 // (v & mask) | orc in one instruction: the encoding takes one scalar operand, so the mask travels in a scalar
 // register and the or-constant in a vector register (see hide()); left alone the compiler emits an and and an or,
 // each with a literal
@@ -66,7 +65,56 @@ __device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t o
     return r;
 }
 
-// acc[k] += a * code k of the lane's 32 codes
+__device__ __forceinline__ __half2 as_half2(uint32_t v) { return *reinterpret_cast<const __half2*>(&v); }
+// bit pattern of the fp16 value 2^e
+__host__ __device__ constexpr uint32_t f16_exp2(int e) { return static_cast<uint32_t>(e + 15) << 10; }
+
+// 3-bit extraction plan.  Stream t (0: as stored, 1: shifted right by 8), word w, step q takes the field that starts
+// at bit f3_s(c, q, 0) of the low half and the one at f3_s(c, q, 1) of the high half (-1: none), c = f3_class(t, w);
+// the code's index follows from its bit position.
+__host__ __device__ constexpr int f3_s(int c, int q, int h) {
+    constexpr int S[3][3][2] = {{{0, 2}, {3, 5}, {6, -1}}, {{1, 0}, {4, 3}, {7, 6}}, {{2, 1}, {5, 4}, {-1, 7}}};
+    return S[c][q][h];
+}
+__host__ __device__ constexpr int f3_class(int t, int w) { return (w + t) % 3; }
+__host__ __device__ constexpr uint32_t f3_mask(int c, int q) {
+    return (f3_s(c, q, 0) >= 0 ? 7u << f3_s(c, q, 0) : 0u) | (f3_s(c, q, 1) >= 0 ? 7u << (16 + f3_s(c, q, 1)) : 0u);
+}
+__host__ __device__ constexpr uint32_t f3_orc(int c, int q) {
+    return (f3_s(c, q, 0) >= 0 ? f16_exp2(10 - f3_s(c, q, 0)) : 0u) |
+           (f3_s(c, q, 1) >= 0 ? f16_exp2(10 - f3_s(c, q, 1)) << 16 : 0u);
+}
+// index of the code whose field starts at bit s of half h of word w of stream t
+__host__ __device__ constexpr int f3_code(int t, int w, int h, int s) { return (32 * w + 16 * h + s + 8 * t) / 3; }
+
+// what a code was read as, minus the code: the constant that leaves with the zero-point sum
+template <int PB>
+__host__ __device__ constexpr float code_offset(int k) {
+    if (PB == 4) return (k & 1) ? 64.0f : 1024.0f;
+    if (PB == 2) {
+        const int f = k & 7;                                  // field within its half: 0..4 direct, 5..7 shifted by 10
+        return static_cast<float>(1024 >> (2 * (f < 5 ? f : f - 5)));
+    }
+    const int b = 3 * k, t = (b & 15) <= 7 ? 0 : 1;           // PB == 3
+    return static_cast<float>(1024 >> ((b - 8 * t) & 15));
+}
+
+// one step of the plan; t, w, q are constants where this is called (fully unrolled loops)
+__device__ __forceinline__ void f3_step(int t, int w, int q, uint32_t word, const uint32_t (&orc)[9], float a,
+                                        float (&acc)[32]) {
+    const int c = f3_class(t, w);
+    const __half2 h = as_half2(and_or(word, f3_mask(c, q), orc[3 * c + q]));
+    if (f3_s(c, q, 0) >= 0) {
+        const int k = f3_code(t, w, 0, f3_s(c, q, 0));
+        acc[k] = fmaf(__low2float(h), a, acc[k]);
+    }
+    if (f3_s(c, q, 1) >= 0) {
+        const int k = f3_code(t, w, 1, f3_s(c, q, 1));
+        acc[k] = fmaf(__high2float(h), a, acc[k]);
+    }
+}
+
+// acc[k] += a * (code k of the lane's 32 codes + code_offset(k))
 template <int PB>
 __device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (&acc)[32]) {
     if constexpr (PB == 4) {
@@ -88,40 +136,45 @@ __device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (
             }
         }
     } else if constexpr (PB == 2) {
-        const float as[4] = {a, a * 0.25f, a * 0.0625f, a * 0.015625f};   // fields read as 4^f * code
+        // same scheme: a field at bits s..s+1 of a 16-bit half, s = 0, 2, .. 8, reads code + 2^(10-s); the fields
+        // at 10, 12, 14 are taken from the word shifted right by 10
+        uint32_t orc[5];
+#pragma unroll
+        for (int q = 0; q < 5; ++q) orc[q] = hide(f16_exp2(10 - 2 * q) * 0x10001u);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
+            const uint32_t w0 = wd.w[i], w10 = w0 >> 10;
 #pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                const uint32_t m = hide(wd.w[i] & (0x03030303u << (2 * f)));
+            for (int q = 0; q < 5; ++q) {                    // fields 0..4 of either half
+                const __half2 h = as_half2(and_or(w0, 0x00030003u << (2 * q), orc[q]));
+                acc[16 * i + q] = fmaf(__low2float(h), a, acc[16 * i + q]);
+                acc[16 * i + 8 + q] = fmaf(__high2float(h), a, acc[16 * i + 8 + q]);
+            }
 #pragma unroll
-                for (int n = 0; n < 4; ++n) acc[16 * i + 4 * n + f] = fmaf(as[f], UBYTE(m, n), acc[16 * i + 4 * n + f]);
+            for (int q = 0; q < 3; ++q) {                    // fields 5..7
+                const __half2 h = as_half2(and_or(w10, 0x00030003u << (2 * q), orc[q]));
+                acc[16 * i + 5 + q] = fmaf(__low2float(h), a, acc[16 * i + 5 + q]);
+                acc[16 * i + 13 + q] = fmaf(__high2float(h), a, acc[16 * i + 13 + q]);
             }
         }
     } else {
         static_assert(PB == 3, "2, 3 or 4 bits");
-        // 3-bit codes repeat every 3 bytes (8 codes).  In byte n = 3p + i of the 12-byte stream the
-        // codes 8p + 3i (at bit i of the byte) and 8p + 3i + 1 (at bit 3 + i) lie whole, so one mask
-        // per word isolates one code per byte and the byte conversion yields code * 2^shift, undone
-        // by a power-of-two factor on a.  The codes 8p + 2 and 8p + 5 straddle bytes; in the stream
-        // shifted right by 6 bits they sit whole in bytes 3p (bit 0) and 3p + 1 (bit 1).
-        const float as[6] = {a, a * 0.5f, a * 0.25f, a * 0.125f, a * 0.0625f, a * 0.03125f};
-        const uint32_t sh[3] = {__builtin_amdgcn_alignbit(wd.w[1], wd.w[0], 6), __builtin_amdgcn_alignbit(wd.w[2], wd.w[1], 6),
-                                wd.w[2] >> 6};
-        constexpr uint32_t MA[3] = {0x071C0E07u, 0x0E071C0Eu, 0x1C0E071Cu};
-        constexpr uint32_t MB[3] = {0x38E07038u, 0x7038E070u, 0xE07038E0u};
-        constexpr uint32_t MS[3] = {0x07000E07u, 0x0E07000Eu, 0x000E0700u};
+        // 3-bit codes: code k sits at bit 3k of the 96-bit stream.  A field can be read as an fp16 pattern when it
+        // starts at bit 0..7 of a 16-bit half (code + 2^(10-s)); every code does so either in the stream as it is
+        // (3k mod 16 < 8) or in the stream shifted right by 8 bits.  One and-or takes a field from each half of a
+        // word, so the 32 codes cost 18 of them and three funnel shifts.
+        const uint32_t st[2][3] = {{wd.w[0], wd.w[1], wd.w[2]},
+                                   {__builtin_amdgcn_alignbit(wd.w[1], wd.w[0], 8), __builtin_amdgcn_alignbit(wd.w[2], wd.w[1], 8),
+                                    wd.w[2] >> 8}};
+        uint32_t orc[9];
 #pragma unroll
-        for (int w = 0; w < 3; ++w) {
-            const uint32_t va = hide(wd.w[w] & MA[w]), vb = hide(wd.w[w] & MB[w]), vs = hide(sh[w] & MS[w]);
+        for (int q = 0; q < 9; ++q) orc[q] = hide(f3_orc(q / 3, q % 3));
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int n = 4 * w + b, p3 = n / 3, i = n % 3;
-                acc[8 * p3 + 3 * i] = fmaf(as[i], ubyte(va, b), acc[8 * p3 + 3 * i]);
-                acc[8 * p3 + 3 * i + 1] = fmaf(as[3 + i], ubyte(vb, b), acc[8 * p3 + 3 * i + 1]);
-                if (i < 2) acc[8 * p3 + 3 * i + 2] = fmaf(as[i], ubyte(vs, b), acc[8 * p3 + 3 * i + 2]);
-            }
-        }
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int w = 0; w < 3; ++w)
+#pragma unroll
+                for (int q = 0; q < 3; ++q) f3_step(t, w, q, st[t][w], orc, a, acc);
     }
 }
 
@@ -138,15 +191,19 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t o_lane = int64_t(blockIdx.x) * GV_OUT_PER_BLOCK + lane * 32;
     const bool valid = o_lane < out;                         // out % 32 == 0: a lane's outputs are inside together
-    const int64_t r = valid ? o_lane / g : 0;
-    // the in/4 column quads split evenly over the gridDim.y * 8 waves that share this output tile
-    const int64_t n_wv = int64_t(gridDim.y) * GV_WAVES, wv = int64_t(blockIdx.y) * GV_WAVES + wave, quads = in >> 2;
-    const int64_t j_begin = (wv * quads / n_wv) << 2, j_end = ((wv + 1) * quads / n_wv) << 2;
+    // (32-bit divisions: out and in are below 2^24)
+    const int64_t r = valid ? static_cast<uint32_t>(o_lane) / static_cast<uint32_t>(g) : 0;
+    // the in/4 column quads split evenly over the gridDim.y * 8 waves that share this output tile: the first
+    // `quads % waves` waves take one quad more
+    const uint32_t n_wv = gridDim.y * GV_WAVES, wv = blockIdx.y * GV_WAVES + wave, quads = static_cast<uint32_t>(in >> 2);
+    const uint32_t q_each = quads / n_wv, q_more = quads - q_each * n_wv;
+    const int64_t j_begin = int64_t(wv * q_each + min(wv, q_more)) << 2;
+    const int64_t j_end = int64_t((wv + 1) * q_each + min(wv + 1, q_more)) << 2;
     const uint32_t* wp = packed + (valid ? (o_lane >> 5) * PB : 0);
     float acc[32];
 #pragma unroll
     for (int k = 0; k < 32; ++k) acc[k] = 0.0f;
-    float zsum = 0.0f, asum = 0.0f;                           // sums of a * zero and (4 bits) of a
+    float zsum = 0.0f, asum = 0.0f;                           // sums of a * zero and of a
     // four columns per step, the next step's loads issued before this step's arithmetic
     struct Step {
         Words<PB> wd[4];
@@ -188,28 +245,31 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* _
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             zsum = fmaf(a[c], z[c], zsum);
-            if constexpr (PB == 4) asum += a[c];
+            asum += a[c];
             accumulate<PB>(st.wd[c], a[c], acc);
         }
     };
     if (valid && j_begin < j_end) {
-        // two buffers, no copies: A is consumed while B is in flight and the other way round.
-        // Fetches past the end re-read the chunk's last columns and are not consumed.
+        // three buffers, no copies: one is consumed while the other two are in flight (two steps of 2 to 4 KB per
+        // wave are too little to keep the memory system busy with 2- and 3-bit codes).  Fetches past the end
+        // re-read the chunk's last columns and are not consumed.
         const int64_t j_last = j_end - 4;
-        Step A, B2;
+        Step A, B2, C;
         fetch(A, j_begin);
-        for (int64_t j0 = j_begin; j0 < j_end; j0 += 8) {    // in % 4 == 0
-            fetch(B2, min(j0 + 4, j_last));
+        fetch(B2, min(j_begin + 4, j_last));
+        for (int64_t j0 = j_begin; j0 < j_end; j0 += 12) {   // in % 4 == 0
+            fetch(C, min(j0 + 8, j_last));
             consume(A);
-            fetch(A, min(j0 + 8, j_last));
+            fetch(A, min(j0 + 12, j_last));
             if (j0 + 4 < j_end) consume(B2);
+            fetch(B2, min(j0 + 16, j_last));
+            if (j0 + 8 < j_end) consume(C);
         }
     }
-    // OFFSET: 4-bit codes were read as code + 1024 (even positions) or code + 64 (odd ones)
+    // OFFSET: the codes were read as code + code_offset(k)
 #pragma unroll
     for (int k = 0; k < 32; ++k) {
-        const float off = PB == 4 ? ((k & 1) ? 64.0f : 1024.0f) : 0.0f;
-        s_acc[wave][k][lane] = (acc[k] - off * asum) - zsum;
+        s_acc[wave][k][lane] = (acc[k] - code_offset<PB>(k) * asum) - zsum;
     }
     __syncthreads();
     // thread t adds up the waves for outputs 4t .. 4t+3 of the block's 2048
