@@ -227,6 +227,8 @@ __global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, doub
     __shared__ double col[2][NB];                             // the column just finished, two buffers in turn
     __shared__ double rd[NB];                                 // reciprocals of the diagonal of L
     const int lane = threadIdx.x;
+    // one wave that the whole factorization waits for: ahead of the trailing update that may share its SIMD
+    __builtin_amdgcn_s_setprio(3);
     for (int e = lane; e < NB * NB; e += 64) {
         const int r = e / NB, c = e % NB;
         t[r][c] = (r < w && c < w) ? A[(k0 + r) * n + k0 + c] : (r == c ? 1.0 : 0.0);   // identity padding
@@ -311,11 +313,13 @@ __global__ __launch_bounds__(256) void chol_panel(double* __restrict__ A, const 
 // trailing update: C[r][c] -= sum_t P[r][t] P[c][t] on the TS x TS tiles (blockIdx.y, blockIdx.x <= blockIdx.y)
 // of the rows/columns from k1 on; P = A[.., k0..k0+w).  gridDim.x limits the columns that are updated
 // (inside a 256-wide outer panel only the panel's own columns; behind it all, with w = 256).
+// ct0: first tile column of this launch (the update behind an outer panel goes out in two launches).
 template <int TS>
-__global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t n, int64_t k0, int w, int64_t k1) {
-    if (blockIdx.x > blockIdx.y) return;
+__global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t n, int64_t k0, int w, int64_t k1, int ct0) {
+    const int ct = static_cast<int>(blockIdx.x) + ct0;
+    if (ct > static_cast<int>(blockIdx.y)) return;
     __shared__ double As[GK][TS + 4], Bs[GK][TS + 4];
-    const int64_t r0 = k1 + int64_t(blockIdx.y) * TS, c0 = k1 + int64_t(blockIdx.x) * TS;
+    const int64_t r0 = k1 + int64_t(blockIdx.y) * TS, c0 = k1 + int64_t(ct) * TS;
     const int m_valid = static_cast<int>(n - r0 < TS ? n - r0 : TS), n_valid = static_cast<int>(n - c0 < TS ? n - c0 : TS);
     double4_t acc[TS / 32][TS / 32] = {};
     dgemm_tile<TS, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
@@ -738,6 +742,9 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
     // Outer panels of 256 columns: inside a panel the 64-wide steps update the panel's own columns
     // only; the columns behind it get the whole panel at once, a product with 256 contraction steps
     // per pass over the trailing matrix instead of 64.
+    const bool overlap = n > 2 * NBO;
+    if (overlap && !adadim_side_stream(ctx)) return ADADIM_EHIP;
+    bool side_busy = false;
     for (int64_t K0 = 0; K0 < n; K0 += NBO) {
         const int64_t W = n - K0 < NBO ? n - K0 : NBO;
         for (int64_t k0 = K0; k0 < K0 + W; k0 += NB) {
@@ -748,15 +755,35 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
                 const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
                 hipLaunchKernelGGL(chol_panel, dim3(t), dim3(256), 0, ctx->stream, A, M, n, k0, w);
                 const unsigned tc = static_cast<unsigned>((K0 + W - (k0 + w) + GT - 1) / GT);
-                if (tc > 0) hipLaunchKernelGGL(chol_syrk<GT>, dim3(tc, t), dim3(256), 0, ctx->stream, A, n, k0, w, k0 + w);
+                if (tc > 0) hipLaunchKernelGGL(chol_syrk<GT>, dim3(tc, t), dim3(256), 0, ctx->stream, A, n, k0, w, k0 + w, 0);
             }
         }
         const int64_t rest = n - K0 - W;
         if (rest > 0) {
+            // The panel's update of everything behind it.  The next panel's own columns first, on the main
+            // stream: its 64-wide steps need nothing else.  The columns behind those on the side stream, under
+            // those steps (which are chains of small launches that leave the chip idle).  Every element still
+            // receives the panels' updates in panel order: the side stream applies them in order, and the main
+            // stream waits for the side stream's last launch before it updates columns that launch wrote.
+            // (The overlap is partial: chol_diag_inv needs 400 registers per lane, so its one wave starts only on
+            // a SIMD that holds nothing else, and waits for the side launch to drain when it finds none.)
             const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
-            hipLaunchKernelGGL(chol_syrk<GT>, dim3(t, t), dim3(256), 0, ctx->stream, A, n, K0, static_cast<int>(W), K0 + W);
+            const unsigned tn = static_cast<unsigned>(((rest < NBO ? rest : NBO) + GT - 1) / GT);
+            if (side_busy) ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->side_ev[1], 0));
+            side_busy = false;
+            hipLaunchKernelGGL(chol_syrk<GT>, dim3(overlap ? tn : t, t), dim3(256), 0, ctx->stream, A, n, K0, static_cast<int>(W),
+                               K0 + W, 0);
+            if (overlap && t > tn) {
+                ADADIM_HIP_TRY(ctx, hipEventRecord(ctx->side_ev[0], ctx->stream));
+                ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->side, ctx->side_ev[0], 0));
+                hipLaunchKernelGGL(chol_syrk<GT>, dim3(t - tn, t), dim3(256), 0, ctx->side, A, n, K0, static_cast<int>(W),
+                                   K0 + W, static_cast<int>(tn));
+                ADADIM_HIP_TRY(ctx, hipEventRecord(ctx->side_ev[1], ctx->side));
+                side_busy = true;
+            }
         }
     }
+    if (side_busy) ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->side_ev[1], 0));   // join
     ADADIM_LAUNCH_CHECK(ctx, "gptq cholesky");
     for (int64_t s = NB; s < n; s *= 2) {
         const unsigned pairs = static_cast<unsigned>((n - s + 2 * s - 1) / (2 * s));   // those with rows below a0 + s
