@@ -400,20 +400,26 @@ def main():
     n_rot = max(2, int(np.ceil(600e6 / (out_f * in_f * 2))))
     Ws = [Wd] + [Wd.clone() for _ in range(n_rot - 1)]
     dWs = [ctx.alloc_score(out_f, in_f) for _ in range(n_rot)]
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    def kernel_seconds(sweep):
+        """Average duration of the launches of three sweeps, from the library's event pair around each launch (as
+        for every other kernel here; an interval over back-to-back launches would add the launch gaps, which for
+        these short kernels are a quarter of the kernel)."""
+        sweep()
+        torch.cuda.synchronize()
+        ctx.adadim_profile(True)
+        for _ in range(3):
+            sweep()
+        torch.cuda.synchronize()
+        ctx.adadim_profile(False)
+        tot = [v for k, v in ctx.adadim_profile_read().items() if k.startswith("quant")]
+        return sum(v[0] for v in tot) * 1e-3 / (3 * n_rot)
+
     for dim, name in ((B.DIM_OC, "quant_oc"), (B.DIM_IC, "quant_ic")):
         def sweep():
             for i in range(n_rot):
                 ctx.adadim_quantize(Ws[i], dim, bits, group, 1.0, dW=dWs[i], dW_dtype=B.DW_F16_SCALED,
                                     colscale=hp.colscale)
-        sweep()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(3):
-            sweep()
-        e1.record()
-        torch.cuda.synchronize()
-        sec = e0.elapsed_time(e1) * 1e-3 / (3 * n_rot)
+        sec = kernel_seconds(sweep)
         quant[name] = {"us_per_launch": sec * 1e6, "GBps_algorithmic": qbytes / sec / 1e9,
                        "frac_hbm": qbytes / sec / HBM_PEAK, "rotating_buffers": n_rot}
     # both dimensions in one call, as the search issues them (one launch where both fast kernels take the shape):
@@ -424,14 +430,7 @@ def main():
         def sweep_both():
             for i in range(n_rot):
                 ctx.adadim_quantize_both(Ws[i], bits, group, hp.colscale, {"dW": dWs[i]}, {"dW": dW2[i]})
-        sweep_both()
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(3):
-            sweep_both()
-        e1.record()
-        torch.cuda.synchronize()
-        sec = e0.elapsed_time(e1) * 1e-3 / (3 * n_rot)
+        sec = kernel_seconds(sweep_both)
         once = 2 * qbytes - out_f * in_f * 2          # W counted once: what one pass over W would have to move
         quant["quant_both"] = {"us_per_launch": sec * 1e6, "GBps_algorithmic": 2 * qbytes / sec / 1e9,
                                "frac_hbm": 2 * qbytes / sec / HBM_PEAK, "frac_hbm_w_counted_once": once / sec / HBM_PEAK,
