@@ -221,6 +221,13 @@ __device__ __forceinline__ void dgemm_each(const double4_t (&acc)[TS / 32][TS / 
 // fmas, nothing waits on a chain.  The inverse likewise (column j of inv(L) by lane j: y_k final,
 // then a_r -= l_rk y_k for the later rows) goes to the diagonal block of M: it turns the panel's
 // triangular solve into a product and is the first level of the triangular inverse.
+// the value `v` has in lane `src_lane` (a constant), in every lane
+__device__ __forceinline__ double lane_read(double v, int src_lane) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+    return __hiloint2double(hi, lo);
+}
+
 __global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0,
                                                     int w) {
     __shared__ double t[NB][NB + 1];
@@ -238,23 +245,33 @@ __global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, doub
         double x[NB];
 #pragma unroll
         for (int c = 0; c < NB; ++c) x[c] = t[lane][c];
-#pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            const double piv = __shfl(x[c], c, 64);
+        // the pivot's reciprocal square root: the same in every lane
+        auto rsqrt_of = [](double piv) {
             double inv = __builtin_amdgcn_rsq(piv);
             inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
-            inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
+            return inv * fma(-0.5 * piv * inv, inv, 1.5);
+        };
+        double piv = lane_read(x[0], 0), inv = rsqrt_of(piv);
+#pragma unroll
+        for (int c = 0; c < NB; ++c) {
             const double l = lane == c ? piv * inv : (lane > c ? x[c] * inv : 0.0);
             x[c] = l;
             col[c & 1][lane] = l;
             if (lane == c) rd[c] = inv;
+            // The next pivot first, by lane reads, so that its chain (update, read, reciprocal square root, two
+            // Newton steps) runs under this column's broadcast reads and updates instead of behind them.
+            if (c + 1 < NB) {
+                x[c + 1] = fma(-l, lane_read(l, c + 1), x[c + 1]);
+                piv = lane_read(x[c + 1], c + 1);
+                inv = rsqrt_of(piv);
+            }
             __syncthreads();
             // sixteen broadcast reads in flight at a time: the fences keep the scheduler from issuing
             // them all at once, which would not leave registers for the row
 #pragma unroll
-            for (int j0 = (c + 1) & ~15; j0 < NB; j0 += 16) {
+            for (int j0 = (c + 2) & ~15; j0 < NB; j0 += 16) {
 #pragma unroll
-                for (int j = j0 > c + 1 ? j0 : c + 1; j < j0 + 16; ++j) x[j] = fma(-l, col[c & 1][j], x[j]);
+                for (int j = j0 > c + 2 ? j0 : c + 2; j < j0 + 16; ++j) x[j] = fma(-l, col[c & 1][j], x[j]);
                 asm volatile("" ::: "memory");
             }
         }
@@ -274,6 +291,7 @@ __global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, doub
 #pragma unroll
         for (int k = 0; k < NB; ++k) {
             // column k of L, with the reciprocal pivot in the diagonal's place, posted like the columns above
+            // (reading it where it lies, t[r][k], one address for the whole wave, was a third slower)
             col[k & 1][lane] = lane == k ? my_rd : t[lane][k];
             __syncthreads();
             const double yk = a[k] * col[k & 1][k];
