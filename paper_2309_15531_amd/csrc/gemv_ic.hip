@@ -16,6 +16,7 @@
 // reproducible.  (Letting the last block of an output tile do that sum needs device-scope
 // fences, which write back and invalidate the XCD's whole L2 each time: 3x slower overall.)
 #include "common.h"
+#include "code_fields.h"
 
 #include <algorithm>
 
@@ -49,9 +50,9 @@ __device__ __forceinline__ Words<PB> load_words(const uint32_t* p) {
     return r;
 }
 
-// float(byte n of v).  `v` must be opaque to the optimiser (see hide()), or it rewrites the
-// mask-then-byte sequence into a bit-field extract plus a conversion, one instruction more per code.
+// float(byte n of v)
 __device__ __forceinline__ float ubyte(uint32_t v, int n) { return static_cast<float>((v >> (8 * n)) & 0xffu); }
+// the value in a vector register, opaque to the optimiser (a constant stays a register operand)
 __device__ __forceinline__ uint32_t hide(uint32_t v) {
     asm("" : "+v"(v));
     return v;
@@ -66,115 +67,29 @@ __device__ __forceinline__ uint32_t and_or(uint32_t v, uint32_t mask, uint32_t o
 }
 
 __device__ __forceinline__ __half2 as_half2(uint32_t v) { return *reinterpret_cast<const __half2*>(&v); }
-// bit pattern of the fp16 value 2^e
-__host__ __device__ constexpr uint32_t f16_exp2(int e) { return static_cast<uint32_t>(e + 15) << 10; }
-
-// 3-bit extraction plan.  Stream t (0: as stored, 1: shifted right by 8), word w, step q takes the field that starts
-// at bit f3_s(c, q, 0) of the low half and the one at f3_s(c, q, 1) of the high half (-1: none), c = f3_class(t, w);
-// the code's index follows from its bit position.
-__host__ __device__ constexpr int f3_s(int c, int q, int h) {
-    constexpr int S[3][3][2] = {{{0, 2}, {3, 5}, {6, -1}}, {{1, 0}, {4, 3}, {7, 6}}, {{2, 1}, {5, 4}, {-1, 7}}};
-    return S[c][q][h];
-}
-__host__ __device__ constexpr int f3_class(int t, int w) { return (w + t) % 3; }
-__host__ __device__ constexpr uint32_t f3_mask(int c, int q) {
-    return (f3_s(c, q, 0) >= 0 ? 7u << f3_s(c, q, 0) : 0u) | (f3_s(c, q, 1) >= 0 ? 7u << (16 + f3_s(c, q, 1)) : 0u);
-}
-__host__ __device__ constexpr uint32_t f3_orc(int c, int q) {
-    return (f3_s(c, q, 0) >= 0 ? f16_exp2(10 - f3_s(c, q, 0)) : 0u) |
-           (f3_s(c, q, 1) >= 0 ? f16_exp2(10 - f3_s(c, q, 1)) << 16 : 0u);
-}
-// index of the code whose field starts at bit s of half h of word w of stream t
-__host__ __device__ constexpr int f3_code(int t, int w, int h, int s) { return (32 * w + 16 * h + s + 8 * t) / 3; }
-
-// what a code was read as, minus the code: the constant that leaves with the zero-point sum
-template <int PB>
-__host__ __device__ constexpr float code_offset(int k) {
-    if (PB == 4) return (k & 1) ? 64.0f : 1024.0f;
-    if (PB == 2) {
-        const int f = k & 7;                                  // field within its half: 0..4 direct, 5..7 shifted by 10
-        return static_cast<float>(1024 >> (2 * (f < 5 ? f : f - 5)));
-    }
-    const int b = 3 * k, t = (b & 15) <= 7 ? 0 : 1;           // PB == 3
-    return static_cast<float>(1024 >> ((b - 8 * t) & 15));
-}
-
-// one step of the plan; t, w, q are constants where this is called (fully unrolled loops)
-__device__ __forceinline__ void f3_step(int t, int w, int q, uint32_t word, const uint32_t (&orc)[9], float a,
-                                        float (&acc)[32]) {
-    const int c = f3_class(t, w);
-    const __half2 h = as_half2(and_or(word, f3_mask(c, q), orc[3 * c + q]));
-    if (f3_s(c, q, 0) >= 0) {
-        const int k = f3_code(t, w, 0, f3_s(c, q, 0));
-        acc[k] = fmaf(__low2float(h), a, acc[k]);
-    }
-    if (f3_s(c, q, 1) >= 0) {
-        const int k = f3_code(t, w, 1, f3_s(c, q, 1));
-        acc[k] = fmaf(__high2float(h), a, acc[k]);
-    }
-}
-
-// acc[k] += a * (code k of the lane's 32 codes + code_offset(k))
+// acc[k] += a * (code k of the lane's 32 codes + code_offset(k)): the plan of code_fields.h, unrolled.  The
+// exponent constants sit in vector registers, the masks become scalar operands (see and_or).
 template <int PB>
 __device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (&acc)[32]) {
-    if constexpr (PB == 4) {
-        // A nibble placed in the low fraction bits of an fp16 pattern is that code plus a constant: bits 0..3
-        // under the exponent of [1024, 2048) read 1024 + code, bits 4..7 under that of [64, 128) read 64 + code.
-        // One and-or builds two such halves, and v_fma_mix_f32 takes either half as an operand, so a code costs
-        // 5/8 + 1 instructions and no conversion.  The constants leave with the zero-point sum (see OFFSET).
-        const uint32_t c1024 = hide(0x64006400u), c64 = hide(0x54005400u);
+    static_assert(PB >= 2 && PB <= 4, "2, 3 or 4 bits");
+    constexpr int NS = field_steps<PB>(), NO = field_orcs<PB>();
+    uint32_t orc[NO];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t w0 = wd.w[i], w8 = w0 >> 8;
-            const uint32_t p[4] = {and_or(w0, 0x000F000Fu, c1024), and_or(w0, 0x00F000F0u, c64),
-                                   and_or(w8, 0x000F000Fu, c1024), and_or(w8, 0x00F000F0u, c64)};
+    for (int q = 0; q < NO; ++q) orc[q] = hide(field_orc<PB>(q));
+    // the words as stored and shifted: per word for 4 and 2 bits (by 8, by 10), across words for 3 bits (by 8)
+    uint32_t src[PB][2];
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {
-                const __half2 h = *reinterpret_cast<const __half2*>(&p[n]);
-                acc[8 * i + n] = fmaf(__low2float(h), a, acc[8 * i + n]);           // nibble n
-                acc[8 * i + n + 4] = fmaf(__high2float(h), a, acc[8 * i + n + 4]);   // nibble n + 4
-            }
-        }
-    } else if constexpr (PB == 2) {
-        // same scheme: a field at bits s..s+1 of a 16-bit half, s = 0, 2, .. 8, reads code + 2^(10-s); the fields
-        // at 10, 12, 14 are taken from the word shifted right by 10
-        uint32_t orc[5];
+    for (int w = 0; w < PB; ++w) {
+        src[w][0] = wd.w[w];
+        if constexpr (PB == 3) src[w][1] = w + 1 < PB ? __builtin_amdgcn_alignbit(wd.w[w + 1 < PB ? w + 1 : w], wd.w[w], 8) : wd.w[w] >> 8;
+        else src[w][1] = wd.w[w] >> (PB == 4 ? 8 : 10);
+    }
 #pragma unroll
-        for (int q = 0; q < 5; ++q) orc[q] = hide(f16_exp2(10 - 2 * q) * 0x10001u);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t w0 = wd.w[i], w10 = w0 >> 10;
-#pragma unroll
-            for (int q = 0; q < 5; ++q) {                    // fields 0..4 of either half
-                const __half2 h = as_half2(and_or(w0, 0x00030003u << (2 * q), orc[q]));
-                acc[16 * i + q] = fmaf(__low2float(h), a, acc[16 * i + q]);
-                acc[16 * i + 8 + q] = fmaf(__high2float(h), a, acc[16 * i + 8 + q]);
-            }
-#pragma unroll
-            for (int q = 0; q < 3; ++q) {                    // fields 5..7
-                const __half2 h = as_half2(and_or(w10, 0x00030003u << (2 * q), orc[q]));
-                acc[16 * i + 5 + q] = fmaf(__low2float(h), a, acc[16 * i + 5 + q]);
-                acc[16 * i + 13 + q] = fmaf(__high2float(h), a, acc[16 * i + 13 + q]);
-            }
-        }
-    } else {
-        static_assert(PB == 3, "2, 3 or 4 bits");
-        // 3-bit codes: code k sits at bit 3k of the 96-bit stream.  A field can be read as an fp16 pattern when it
-        // starts at bit 0..7 of a 16-bit half (code + 2^(10-s)); every code does so either in the stream as it is
-        // (3k mod 16 < 8) or in the stream shifted right by 8 bits.  One and-or takes a field from each half of a
-        // word, so the 32 codes cost 18 of them and three funnel shifts.
-        const uint32_t st[2][3] = {{wd.w[0], wd.w[1], wd.w[2]},
-                                   {__builtin_amdgcn_alignbit(wd.w[1], wd.w[0], 8), __builtin_amdgcn_alignbit(wd.w[2], wd.w[1], 8),
-                                    wd.w[2] >> 8}};
-        uint32_t orc[9];
-#pragma unroll
-        for (int q = 0; q < 9; ++q) orc[q] = hide(f3_orc(q / 3, q % 3));
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int w = 0; w < 3; ++w)
-#pragma unroll
-                for (int q = 0; q < 3; ++q) f3_step(t, w, q, st[t][w], orc, a, acc);
+    for (int s = 0; s < NS; ++s) {
+        const FieldStep f = field_step<PB>(s);
+        const __half2 h = as_half2(and_or(src[f.word][f.shift != 0], f.mask, orc[f.orc_id]));
+        if (f.k_lo >= 0) acc[f.k_lo] = fmaf(__low2float(h), a, acc[f.k_lo]);
+        if (f.k_hi >= 0) acc[f.k_hi] = fmaf(__high2float(h), a, acc[f.k_hi]);
     }
 }
 
@@ -182,7 +97,7 @@ __device__ __forceinline__ void accumulate(const Words<PB>& wd, float a, float (
 // fp16 pattern of the scale without its sign bit and its PB-1 lowest bits, above the PB-bit
 // zero-point) instead of an fp32 scale and a u8 zero-point.
 template <int PB, bool M16>
-__global__ __launch_bounds__(64 * GV_WAVES) void gemv_ic_tiles(const uint32_t* __restrict__ packed,
+__global__ __launch_bounds__(64 * GV_WAVES, 4) void gemv_ic_tiles(const uint32_t* __restrict__ packed,
                                                                const void* __restrict__ scales,
                                                                const uint8_t* __restrict__ zeros,
                                                                const __half* __restrict__ x, int64_t out, int64_t in,

@@ -168,6 +168,21 @@ def test_create_destroy():
     c.close()
 
 
+def test_code_field_plan_on_the_host(tmp_path):
+    """csrc/code_fields.h (how the matrix-vector kernel reads 2-, 3- and 4-bit codes as fp16 patterns): the plan run
+    on the CPU returns every code of random and extreme streams exactly, each once."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    exe = tmp_path / "code_fields_check"
+    src = os.path.join(ROOT, "tests", "host", "code_fields_check.cpp")
+    subprocess.run(["g++", "-O2", "-std=c++17", src, "-o", str(exe)], check=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout
+    assert "2 bits: 0, 3 bits: 0, 4 bits: 0 mismatches" in res.stdout
+
+
 def test_product_does_not_import_oracle():
     """The product package must never reach into the oracle (and vice versa)."""
     pkg = os.path.join(ROOT, "paper_2309_15531_amd")
