@@ -435,14 +435,22 @@ __device__ __forceinline__ void wave_min2(float& a, float& b) {
     b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, b), 63));
 }
 
-// Wp[r][i] = W[r][perm[i]] as fp32, zero for dead channels
-__global__ void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t in, const int32_t* __restrict__ perm,
-                            const uint8_t* __restrict__ dead, float* __restrict__ Wp) {
-    const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (idx >= out * in) return;
-    const int64_t r = idx / in, i = idx % in;
-    const int32_t j = perm[i];
-    Wp[idx] = dead[j] ? 0.0f : __half2float(W[r * in + j]);
+// Wp[r][i] = W[r][perm[i]] as fp32, zero for dead channels.  One row per workgroup: the row is read once, in
+// order, into LDS and permuted from there (a thread per element reading W[r][perm[i]] from memory fetched a
+// separate 64-byte piece for every two bytes it used).  Dynamic LDS: in halves.
+__global__ __launch_bounds__(256) void gq_gather_w(const __half* __restrict__ W, int64_t out, int64_t in,
+                                                   const int32_t* __restrict__ perm, const uint8_t* __restrict__ dead,
+                                                   float* __restrict__ Wp) {
+    extern __shared__ __align__(16) char gw_smem[];
+    __half* row = reinterpret_cast<__half*>(gw_smem);
+    const int64_t r = blockIdx.x;
+    const __half* src = W + r * in;
+    for (int64_t j = threadIdx.x; j < in; j += 256) row[j] = src[j];
+    __syncthreads();
+    for (int64_t i = threadIdx.x; i < in; i += 256) {
+        const int32_t j = perm[i];
+        Wp[r * in + i] = dead[j] ? 0.0f : __half2float(row[j]);
+    }
 }
 
 // One 128-channel block [i1, i1 + nbw) for 64 * RPL rows, by a workgroup of four wavefronts.  Lane l
@@ -667,32 +675,38 @@ __global__ void gq_invperm(const int32_t* __restrict__ perm, int64_t in, int32_t
     if (i < in) visited[perm[i]] = static_cast<int32_t>(i);
 }
 
-// codes back to the original channel order, and dW = W - scale*(code - zero) there.  One thread per
-// output element: the writes (and the reads of W and the parameters) are consecutive, only the
-// one-byte reads of the visiting-order codes wander, inside a row that the caches hold.
+// codes back to the original channel order, and dW = W - scale*(code - zero) there.  One row per workgroup:
+// its codes in visiting order are read once into LDS and looked up there; the writes (and the reads of W and the
+// parameters) are consecutive.  Dynamic LDS: in bytes.
 template <bool IC>
-__global__ void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __restrict__ visited,
-                           const uint8_t* __restrict__ dead, const __half* __restrict__ W, int64_t out, int64_t in, int g,
-                           const float* __restrict__ scales, const uint8_t* __restrict__ zeros, int mfmt,
-                           uint8_t* __restrict__ codes, float* __restrict__ dW) {
-    const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (idx >= out * in) return;
-    const int64_t r = idx / in, j = idx % in;
-    const uint8_t q = Qp[r * in + visited[j]];
-    codes[idx] = q;
-    if (dW) {
-        const int64_t pi = IC ? (r / g) * in + j : r * (in / g) + j / g;
-        float sc, zp;
-        if (mfmt) {
-            const uint32_t wd = reinterpret_cast<const uint16_t*>(scales)[pi];
-            sc = word_scale(wd, mfmt);
-            zp = word_zero(wd, mfmt);
-        } else {
-            sc = scales[pi];
-            zp = static_cast<float>(zeros[pi]);
+__global__ __launch_bounds__(256) void gq_scatter(const uint8_t* __restrict__ Qp, const int32_t* __restrict__ visited,
+                                                  const uint8_t* __restrict__ dead, const __half* __restrict__ W, int64_t out,
+                                                  int64_t in, int g, const float* __restrict__ scales,
+                                                  const uint8_t* __restrict__ zeros, int mfmt, uint8_t* __restrict__ codes,
+                                                  float* __restrict__ dW) {
+    extern __shared__ __align__(16) char gs_smem[];
+    uint8_t* qrow = reinterpret_cast<uint8_t*>(gs_smem);
+    const int64_t r = blockIdx.x;
+    for (int64_t i = threadIdx.x; i < in; i += 256) qrow[i] = Qp[r * in + i];
+    __syncthreads();
+    for (int64_t j = threadIdx.x; j < in; j += 256) {
+        const int64_t idx = r * in + j;
+        const uint8_t q = qrow[visited[j]];
+        codes[idx] = q;
+        if (dW) {
+            const int64_t pi = IC ? (r / g) * in + j : r * (in / g) + j / g;
+            float sc, zp;
+            if (mfmt) {
+                const uint32_t wd = reinterpret_cast<const uint16_t*>(scales)[pi];
+                sc = word_scale(wd, mfmt);
+                zp = word_zero(wd, mfmt);
+            } else {
+                sc = scales[pi];
+                zp = static_cast<float>(zeros[pi]);
+            }
+            const float wq = sc * (static_cast<float>(q) - zp);
+            dW[idx] = (dead[j] ? 0.0f : __half2float(W[idx])) - wq;
         }
-        const float wq = sc * (static_cast<float>(q) - zp);
-        dW[r * in + j] = (dead[j] ? 0.0f : __half2float(W[r * in + j])) - wq;
     }
 }
 
@@ -837,12 +851,15 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
         ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<false, 1>),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
+        // a row of W in LDS: up to 46340 halves
+        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_gather_w),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
         attr_set = true;
     }
-    const unsigned eb = static_cast<unsigned>((out * in + 255) / 256);
     {
         ProfScope prof(ctx, "gptq_gather");
-        hipLaunchKernelGGL(gq_gather_w, dim3(eb), dim3(256), 0, ctx->stream, W, out, in, perm, dead, Wp);
+        hipLaunchKernelGGL(gq_gather_w, dim3(static_cast<unsigned>(out)), dim3(256), static_cast<size_t>(in) * 2, ctx->stream, W, out,
+                           in, perm, dead, Wp);
     }
     // A block's errors reach the channels behind it in two launches: the next block's 128 channels at
     // once, on the main stream, so that the next sweep can start; the rest on a side stream, under
@@ -894,10 +911,10 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
         hipLaunchKernelGGL(gq_invperm, dim3(static_cast<unsigned>((in + 255) / 256)), dim3(256), 0, ctx->stream, perm, in,
                            visited);
         if (ic)
-            hipLaunchKernelGGL(gq_scatter<true>, dim3(eb), dim3(256), 0, ctx->stream, Qp, visited, dead, W, out, in, g,
+            hipLaunchKernelGGL(gq_scatter<true>, dim3(static_cast<unsigned>(out)), dim3(256), static_cast<size_t>(in), ctx->stream, Qp, visited, dead, W, out, in, g,
                                scales_out, zeros_out, mfmt, codes, dW);
         else
-            hipLaunchKernelGGL(gq_scatter<false>, dim3(eb), dim3(256), 0, ctx->stream, Qp, visited, dead, W, out, in, g,
+            hipLaunchKernelGGL(gq_scatter<false>, dim3(static_cast<unsigned>(out)), dim3(256), static_cast<size_t>(in), ctx->stream, Qp, visited, dead, W, out, in, g,
                                st_scales, st_zeros, mfmt, codes, dW);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gptq sweep");
