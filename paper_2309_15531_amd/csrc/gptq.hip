@@ -125,7 +125,7 @@ __global__ void gq_gather(const float* __restrict__ H, int64_t n, const int32_t*
 // result is D[4 r + l / 16][l % 16].  The vector and the matrix pipe have the same fp64 peak on this
 // chip; the matrix form needs a quarter of the LDS reads per flop and no issue slots for the products.
 typedef double double4_t __attribute__((ext_vector_type(4)));
-constexpr int GT = 64, GK = 16;                  // tile edge, contraction chunk
+constexpr int GT = 64, GK = 32;                  // tile edge, contraction chunk
 // (128 x 128 tiles were measured too: one workgroup per compute unit instead of four, and the
 // products ran a third slower; the matrix pipe wants the other workgroups' waves to fill its gaps.)
 
@@ -145,27 +145,31 @@ __device__ __forceinline__ void dgemm_tile(const double* __restrict__ Ap, int64_
     // that is contiguous along k they are the chunk's 16 k of one row (rows t/16 + 16 e); for the
     // row-major B they are 16 columns of one k row (k row t/16, columns t%16 + 16 e).
     const int l16 = t & 15, h16 = t >> 4;
-    double ra[E], rb[E];
+    constexpr int KK = GK / 16;                           // 16-wide pieces of a chunk
+    double ra[KK][E], rb[KK][E];
     // the next chunk's operands travel from memory to registers while the matrix cores work on this one
     auto fetch = [&](int64_t k0) {
-        const int64_t k = k0 + l16;
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-            const int row = h16 + 16 * e;
-            ra[e] = (row < m_valid && k < k_hi) ? Ap[row * lda + k] : 0.0;
-        }
-        if constexpr (B_KC) {
+        for (int kk = 0; kk < KK; ++kk) {
+            const int64_t k = k0 + 16 * kk + l16;
 #pragma unroll
             for (int e = 0; e < E; ++e) {
                 const int row = h16 + 16 * e;
-                rb[e] = (row < n_valid && k < k_hi) ? Bp[row * ldb + k] : 0.0;
+                ra[kk][e] = (row < m_valid && k < k_hi) ? Ap[row * lda + k] : 0.0;
             }
-        } else {
-            const int64_t kr = k0 + h16;
+            if constexpr (B_KC) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) {
-                const int col = l16 + 16 * e;
-                rb[e] = (kr < k_hi && col < n_valid) ? Bp[kr * ldb + col] : 0.0;
+                for (int e = 0; e < E; ++e) {
+                    const int row = h16 + 16 * e;
+                    rb[kk][e] = (row < n_valid && k < k_hi) ? Bp[row * ldb + k] : 0.0;
+                }
+            } else {
+                const int64_t kr = k0 + 16 * kk + h16;
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    const int col = l16 + 16 * e;
+                    rb[kk][e] = (kr < k_hi && col < n_valid) ? Bp[kr * ldb + col] : 0.0;
+                }
             }
         }
     };
@@ -173,13 +177,16 @@ __device__ __forceinline__ void dgemm_tile(const double* __restrict__ Ap, int64_
     for (int64_t k0 = k_lo; k0 < k_hi; k0 += GK) {
         __syncthreads();
 #pragma unroll
-        for (int e = 0; e < E; ++e) As[l16][h16 + 16 * e] = ra[e];
-        if constexpr (B_KC) {
+        for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) Bs[l16][h16 + 16 * e] = rb[e];
-        } else {
+            for (int e = 0; e < E; ++e) As[16 * kk + l16][h16 + 16 * e] = ra[kk][e];
+            if constexpr (B_KC) {
 #pragma unroll
-            for (int e = 0; e < E; ++e) Bs[h16][l16 + 16 * e] = rb[e];
+                for (int e = 0; e < E; ++e) Bs[16 * kk + l16][h16 + 16 * e] = rb[kk][e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < E; ++e) Bs[16 * kk + h16][l16 + 16 * e] = rb[kk][e];
+            }
         }
         __syncthreads();
         if (k0 + GK < k_hi) fetch(k0 + GK);
