@@ -575,20 +575,25 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
                 }
             }
             float my_scale = 1.0f, my_zero = 0.0f;                          // lane c: channel c's parameters (per-IC)
+            // The sub-block's 16 x 16 corner of U, all of it in registers before the chain starts (16-byte reads at
+            // wave-uniform addresses, every index below a constant): read row by row where it is used, each
+            // channel's chain began by waiting for its row.  The fence keeps the reads up here.
+            float ub[SB][SB];
+#pragma unroll
+            for (int c = 0; c < SB; ++c)
+#pragma unroll
+                for (int q4 = 0; q4 < SB / 4; ++q4) {
+                    const float4 t = *reinterpret_cast<const float4*>(Us + (s0 + c) * GB + s0 + 4 * q4);
+                    ub[c][4 * q4 + 0] = t.x;
+                    ub[c][4 * q4 + 1] = t.y;
+                    ub[c][4 * q4 + 2] = t.z;
+                    ub[c][4 * q4 + 3] = t.w;
+                }
+            asm volatile("" ::: "memory");
 #pragma unroll
             for (int c = 0; c < SB; ++c) {
                 if (FULL || c < sbw) {                                      // uniform
-                    // row s0 + c of the block of U, columns s0 .. s0 + 15: four 16-byte reads at a wave-uniform
-                    // address, every index below a constant
-                    float u[SB];
-#pragma unroll
-                    for (int q4 = 0; q4 < SB / 4; ++q4) {
-                        const float4 t = *reinterpret_cast<const float4*>(Us + (s0 + c) * GB + s0 + 4 * q4);
-                        u[4 * q4 + 0] = t.x;
-                        u[4 * q4 + 1] = t.y;
-                        u[4 * q4 + 2] = t.z;
-                        u[4 * q4 + 3] = t.w;
-                    }
+                    const float (&u)[SB] = ub[c];
                     const float d = u[c];
                     QP pr[RPL];
                     if constexpr (IC) {
