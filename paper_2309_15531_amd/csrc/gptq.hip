@@ -485,29 +485,60 @@ __global__ __launch_bounds__(256) void gq_sweep(float* __restrict__ Wp, const fl
     float* Ws = Us + GB * GB;                                           // [64 * RPL][PITCH]
     float* Es0 = Ws + 64 * RPL * PITCH;                                 // [2][64 * RPL][SB + 1]: the errors of this sub-block and the last
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int e4 = threadIdx.x; e4 < nbw * (GB / 4); e4 += 256) {        // in % 4 == 0 is not required: guarded
-        const int k = e4 / (GB / 4), c4 = (e4 % (GB / 4)) * 4;
-        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        const float* src = U + (i1 + k) * in + i1 + c4;
-        if (c4 + 3 < nbw && ((reinterpret_cast<uintptr_t>(src) & 15u) == 0)) {
-            v = *reinterpret_cast<const float4*>(src);
-        } else {
-            if (c4 + 0 < nbw) v.x = src[0];
-            if (c4 + 1 < nbw) v.y = src[1];
-            if (c4 + 2 < nbw) v.z = src[2];
-            if (c4 + 3 < nbw) v.w = src[3];
+    // The block of U and the strip of W: every thread's loads are issued before the first of them is stored, so the
+    // block pays one trip to memory each, not one per loop iteration (16 and 32 of them: a fifth of the kernel).
+    {
+        constexpr int NU = GB * (GB / 4) / 256;                         // 16-byte pieces of the block of U per thread
+        float4 uv[NU];
+#pragma unroll
+        for (int q = 0; q < NU; ++q) {
+            const int e4 = threadIdx.x + 256 * q, k = e4 / (GB / 4), c4 = (e4 % (GB / 4)) * 4;
+            float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (k < nbw) {                                              // in % 4 == 0 is not required: guarded
+                const float* src = U + (i1 + k) * in + i1 + c4;
+                if (c4 + 3 < nbw && ((reinterpret_cast<uintptr_t>(src) & 15u) == 0)) {
+                    v = *reinterpret_cast<const float4*>(src);
+                } else {
+                    if (c4 + 0 < nbw) v.x = src[0];
+                    if (c4 + 1 < nbw) v.y = src[1];
+                    if (c4 + 2 < nbw) v.z = src[2];
+                    if (c4 + 3 < nbw) v.w = src[3];
+                }
+            }
+            uv[q] = v;
         }
-        *reinterpret_cast<float4*>(Us + k * GB + c4) = v;
+#pragma unroll
+        for (int q = 0; q < NU; ++q) {
+            const int e4 = threadIdx.x + 256 * q, k = e4 / (GB / 4), c4 = (e4 % (GB / 4)) * 4;
+            if (k < nbw) *reinterpret_cast<float4*>(Us + k * GB + c4) = uv[q];
+        }
     }
-    __syncthreads();
     int64_t row[RPL];
     bool ok[RPL];
 #pragma unroll
     for (int p = 0; p < RPL; ++p) {
         row[p] = IC ? int64_t(blockIdx.x) * g + lane + 64 * p : int64_t(blockIdx.x) * 64 + lane;
         ok[p] = row[p] < out;
-        if (ok[p])
-            for (int c = wave; c < nbw; c += 4) Ws[(lane * RPL + p) * PITCH + c] = Wp[row[p] * in + i1 + c];
+    }
+    {
+        // strip element (r, c): thread t takes columns t % 128 of rows t / 128 + 2 j, consecutive lanes consecutive
+        // columns
+        constexpr int NR = 64 * RPL / 2;
+        const int c = threadIdx.x & (GB - 1), r_first = threadIdx.x >> 7;
+        const int64_t strip_row0 = IC ? int64_t(blockIdx.x) * g : int64_t(blockIdx.x) * 64;
+        float wv[NR];
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int r = r_first + 2 * j;                              // strip row; per-IC rows l + 64 p sit at (l * RPL + p)
+            const int64_t grow = strip_row0 + r;
+            wv[j] = (c < nbw && grow < out) ? Wp[grow * in + i1 + c] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int r = r_first + 2 * j;
+            const int slot = IC ? (r & 63) * RPL + (r >> 6) : r;        // row l + 64 p of a group -> strip slot l * RPL + p
+            if (c < nbw) Ws[slot * PITCH + c] = wv[j];
+        }
     }
     __syncthreads();
     const int n_cg = IC ? 0 : static_cast<int>(in / g);
