@@ -230,3 +230,35 @@ def test_gptq_ada_in_the_storage_format(ctx):
     rep = (lambda a: np.repeat(a, group, axis=1)) if dim == OC else (lambda a: np.repeat(a, group, axis=0))
     what = (rep(s) * (ga.codes.cpu().numpy().astype(np.float32) - rep(z).astype(np.float32))).astype(np.float32)
     assert np.array_equal(ga.dW.cpu().numpy(), W.astype(np.float32) - what)
+
+
+@pytest.mark.parametrize("dim,group", [(OC, 128), (IC, 64)])
+def test_wide_layer_with_a_diagonal_factor(ctx, dim, group):
+    """in = 33280 (a row of W no longer fits the default 64 KB of LDS in the permuting copy; 260 blocks): with a
+    diagonal factor nothing propagates, so the sweep in a scrambled visiting order must give the plain quantizer's
+    codes, parameters and dW (Sec. 3.3 with a diagonal H; the oracle's quantize is the reference)."""
+    out_f, in_f, bits = 64, 33280, 3
+    rng = np.random.default_rng(5)
+    W = (rng.standard_normal((out_f, in_f)) * 0.02).astype(np.float16)
+    ref = oracle.quantize(W, dim, bits, group)
+    Wd = dev(W)
+    U = torch.zeros((in_f, in_f), dtype=torch.float32, device="cuda")
+    U.diagonal().copy_(torch.linspace(0.5, 2.0, in_f, device="cuda"))       # any positive diagonal
+    perm = torch.from_numpy(rng.permutation(in_f).astype(np.int32)).cuda()
+    dead = torch.zeros(in_f, dtype=torch.uint8, device="cuda")
+    codes = torch.full((out_f, in_f), 255, dtype=torch.uint8, device="cuda")
+    dW = torch.full((out_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    if dim == OC:
+        sc = torch.empty((out_f, in_f // group), dtype=torch.float32, device="cuda")
+        zp = torch.empty((out_f, in_f // group), dtype=torch.uint8, device="cuda")
+        ctx.adadim_quantize(Wd, OC, bits, group, 1.0, scales=sc, zeros=zp)
+        ctx.adadim_gptq_quantize(Wd, dim, bits, group, U, perm, dead, codes, static_scales=sc, static_zeros=zp, dW=dW)
+    else:
+        sc = torch.full((out_f // group, in_f), float("nan"), dtype=torch.float32, device="cuda")
+        zp = torch.full((out_f // group, in_f), 255, dtype=torch.uint8, device="cuda")
+        ctx.adadim_gptq_quantize(Wd, dim, bits, group, U, perm, dead, codes, scales=sc, zeros=zp, dW=dW)
+    torch.cuda.synchronize()
+    assert np.array_equal(sc.cpu().numpy(), ref["scales"])
+    assert np.array_equal(zp.cpu().numpy(), ref["zeros"])
+    assert np.array_equal(codes.cpu().numpy(), ref["codes"])
+    assert np.array_equal(dW.cpu().numpy(), ref["dW"])
