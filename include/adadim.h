@@ -283,7 +283,9 @@ int adadim_gptq_quantize_meta16(adadim_ctx* ctx, const void* W, int64_t out, int
  * the per-IC kernel: weight [out x in] in b bits, input [in x 1] and output [out x 1] fp16):
  *     y[o] = sum_j scales[o/g, j] * (code[o, j] - zeros[o/g, j]) * x[j]
  * computed as sum_j (scales*x)[o/g, j] * code[o, j] - sum_j (scales*x)[o/g, j] * zeros[o/g, j]
- * in fp32 (the per-IC scale folded into the activation), rounded once to fp16.
+ * in fp32 (the per-IC scale folded into the activation), rounded once to fp16.  (The kernel reads a code as
+ * code + c with c a power of two fixed by the code's bit position, 4 .. 1024, and takes c * sum_j (scales*x)[o/g, j]
+ * off again: a few more fp32 roundings of sums of that size, far below the fp16 rounding of y.)
  *   packed  the stream adadim_quantize(dim = IC, bits) writes: u32 [in, out*bits/32], 16-byte aligned
  *   scales  f32 [out/g, in] (16-byte aligned), zeros u8 [out/g, in] (4-byte aligned), as written there
  *   x       fp16 [in], 8-byte aligned;   y  fp16 [out]
