@@ -466,7 +466,8 @@ def main():
         "roofline": roofline,
         "launch": ("one recorded HIP graph per step; kernel durations from a second pass of the same steps launched "
                    "one by one" if use_graph else "kernel by kernel; kernel durations from HIP events in the timed region"),
-        "quantizer_hbm": quant,
+        "quantizer_hbm": dict(quant, note=("each launch moves %.0f MB: below some 150 MB a launch is mostly ramp and tail, the "
+                                           "HBM-bound rate shows on the gate_proj / down_proj / clip_grid workloads" % (qbytes / 1e6))),
         "kernels": comps,
     }
     if not args.no_cpu_baseline:
