@@ -262,3 +262,41 @@ def test_wide_layer_with_a_diagonal_factor(ctx, dim, group):
     assert np.array_equal(zp.cpu().numpy(), ref["zeros"])
     assert np.array_equal(codes.cpu().numpy(), ref["codes"])
     assert np.array_equal(dW.cpu().numpy(), ref["dW"])
+
+
+def _random_sweep_cases(n, seed):
+    """Seeded shapes for the sweep: odd row counts per-OC (ragged row tiles), every residue of the last block and
+    of its last 16-channel sub-block, groups that do and do not line up with the 128-channel blocks."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        bits = int(rng.choice([2, 3, 4, 8]))
+        if i % 2 == 0:
+            group = int(rng.choice([0, 8, 24, 40, 64, 128]))
+            g = group if group else 1
+            in_f = g * int(rng.integers(max(1, 40 // g), max(2, 420 // g) + 1))
+            out_f = int(rng.integers(1, 150))
+            cases.append((out_f, in_f, OC, bits, group))
+        else:
+            group = int(rng.choice([64, 128]))
+            out_f = group * int(rng.integers(1, 4))
+            in_f = 4 * int(rng.integers(8, 110))
+            cases.append((out_f, in_f, IC, min(bits, 8), group))
+    return cases
+
+
+@pytest.mark.parametrize("out_f,in_f,dim,bits,group", _random_sweep_cases(24, 11))
+def test_sweep_bit_exact_random_shapes(ctx, out_f, in_f, dim, bits, group):
+    W, X = layer(out_f, in_f, max(2 * in_f, 300), seed=3 * out_f + in_f, dead=(1,) if in_f > 60 else ())
+    H32 = oracle.hessian(X).astype(np.float32)
+    Hp, perm, dead = G.prepare(H32, 0.01, True)
+    U32 = G.factor(Hp).astype(np.float32)
+    ref = G.sweep(W, U32, perm, dead, dim, bits, group)
+    got = gpu_sweep(ctx, W, dim, bits, group, dev(U32), dev(perm.astype(np.int32)), dev(dead.astype(np.uint8)),
+                    want_packed=bits <= 8 and (dim == OC or out_f * bits % 32 == 0))
+    assert np.array_equal(got["codes"], ref["codes"])
+    assert np.array_equal(got["scales"].view(np.uint32), ref["scales"].view(np.uint32))
+    assert np.array_equal(got["zeros"], ref["zeros"])
+    assert np.array_equal(got["dW"], ref["dW"])
+    if "packed" in got:
+        assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, bits))
