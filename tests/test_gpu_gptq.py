@@ -300,3 +300,32 @@ def test_sweep_bit_exact_random_shapes(ctx, out_f, in_f, dim, bits, group):
     assert np.array_equal(got["dW"], ref["dW"])
     if "packed" in got:
         assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, bits))
+
+
+@pytest.mark.parametrize("out_f,in_f,dim,bits,group",
+                         [c for c in _random_sweep_cases(40, 23) if c[3] <= 4 and not (c[2] == OC and c[4] == 0 and c[1] % 2)][:14])
+def test_sweep_in_the_storage_format_random_shapes(ctx, out_f, in_f, dim, bits, group):
+    """The same in the b + 16/g format (bits 2..4), against the oracle's sweep with rounded scales."""
+    from oracle import meta16_oracle as m16
+    W, X = layer(out_f, in_f, max(2 * in_f, 300), seed=5 * out_f + in_f, dead=(2,) if in_f > 60 else ())
+    H32 = oracle.hessian(X).astype(np.float32)
+    Hp, perm, dead = G.prepare(H32, 0.01, True)
+    U32 = G.factor(Hp).astype(np.float32)
+    ref = m16.gptq_sweep(W, U32, perm, dead, dim, bits, group)
+    Wd, Ud, pd, dd = dev(W), dev(U32), dev(perm.astype(np.int32)), dev(dead.astype(np.uint8))
+    codes = torch.full((out_f, in_f), 255, dtype=torch.uint8, device="cuda")
+    dW = torch.full((out_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    if dim == OC:
+        g = in_f if group == 0 else group
+        meta = torch.full((out_f, in_f // g), -1, dtype=torch.int16, device="cuda")
+        Wz = Wd.clone()
+        Wz[:, dd.bool()] = 0
+        ctx.adadim_quantize_meta16(Wz, OC, bits, group, 1.0, meta=meta)
+        ctx.adadim_gptq_quantize_meta16(Wd, dim, bits, group, Ud, pd, dd, codes, static_meta=meta, dW=dW)
+    else:
+        meta = torch.full((out_f // group, in_f), -1, dtype=torch.int16, device="cuda")
+        ctx.adadim_gptq_quantize_meta16(Wd, dim, bits, group, Ud, pd, dd, codes, meta=meta, dW=dW)
+    torch.cuda.synchronize()
+    assert np.array_equal(meta.cpu().numpy().view(np.uint16), ref["meta"])
+    assert np.array_equal(codes.cpu().numpy(), ref["codes"])
+    assert np.array_equal(dW.cpu().numpy(), ref["dW"])
