@@ -99,7 +99,7 @@ def test_gemv_reproducible_and_zero_input(ctx):
     assert not run_gemv(ctx, packed, scales, zeros, np.zeros(in_f, np.float16), out_f, in_f, bits, g).any()
 
 
-@pytest.mark.parametrize("bits,group", [(4, 128), (3, 128), (3, 2048)])
+@pytest.mark.parametrize("bits,group", [(4, 128), (3, 128), (3, 2048), (2, 128)])
 def test_gemv_appendix_shape_sampled(ctx, bits, group):
     """The shape of the paper's latency table (App. D): weight [4m x m], m = 12288, batch 1.
     Inputs are seeded random streams (every bit pattern is a valid code for 2, 3 and 4 bits),
