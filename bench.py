@@ -331,26 +331,42 @@ def main():
         torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
-    if not use_graph:
+    # Per-kernel durations come from the library's event pair around each launch, and a pair costs the stream about
+    # 7 us: bracketing all five kernels of a q_proj step takes 3 % off the figure being measured.  So the timed
+    # region brackets one kernel, the dominant one (found in one untimed step with every kernel bracketed), which
+    # is the one the roofline object describes; the other kernels are timed in a second, untimed pass of the same
+    # steps.
+    def profiled(n, fn, only=None):
+        ctx.adadim_profile_only(only)
         ctx.adadim_profile(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        timed_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    best, dim, clip = finish()
-    if use_graph:
-        # the recorded graph carries no events: time the kernels in a second pass of the same steps, launched one by one
-        ctx.adadim_profile(True)
-        for _ in range(args.steps):
-            step()
+        t_begin = time.perf_counter()
+        for _ in range(n):
+            fn()
         torch.cuda.synchronize()
-    ctx.adadim_profile(False)
-    prof = ctx.adadim_profile_read()
+        dt = time.perf_counter() - t_begin
+        ctx.adadim_profile(False)
+        ctx.adadim_profile_only(None)
+        return dt, {k: {"avg_us": v[0] / max(v[1], 1) * 1e3, "launches": v[1], "steps": n}
+                    for k, v in ctx.adadim_profile_read().items()}
+
+    _, probe = profiled(1, step)
+    dominant = max(probe, key=lambda k: probe[k]["avg_us"] * probe[k]["launches"])
+    if use_graph:
+        # the recorded graph carries no events at all
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            timed_step()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        live = {}
+    else:
+        elapsed, live = profiled(args.steps, timed_step, only=dominant)
+    best, dim, clip = finish()
+    _, kern = profiled(min(args.steps, 50), step)
+    kern.update(live)                                         # the dominant kernel: as measured in the timed region
     losses = ls.losses.cpu().numpy().tolist()
 
     ms_per_step = elapsed / args.steps * 1e3
-    kern = {k: {"avg_us": v[0] / max(v[1], 1) * 1e3, "launches": v[1]} for k, v in prof.items()}
 
     # roofline of the dominant kernel: the Gram-matrix tiles.  MFMA flops
     # actually issued = upper-triangular tiles x 2*BT*BT*tokens.
@@ -379,7 +395,7 @@ def main():
         bn = 256
         nbk = (in_f + bn - 1) // bn
         mbk = (out_f + bn - 1) // bn
-        per_launch = len(ls.cands) * args.steps / kern["error_tiles"]["launches"]   # candidates per launch
+        per_launch = len(ls.cands) * kern["error_tiles"]["steps"] / kern["error_tiles"]["launches"]   # candidates per launch
         # MFMA flops issued: 256x256 tiles, column block nb contracts over (nb+1)*256
         issued = per_launch * 2.0 * (mbk * bn) * bn * bn * nbk * (nbk + 1) / 2
         comps["error_tiles"] = {
@@ -389,7 +405,7 @@ def main():
         }
     # with many candidates per layer (clip grid) the error GEMM, not the Gram matrix, is the dominant kernel
     et = comps.get("error_tiles")
-    if et and et["avg_us"] * kern["error_tiles"]["launches"] > kern["gram_tiles"]["avg_us"] * kern["gram_tiles"]["launches"]:
+    if et and dominant == "error_tiles":
         roofline = {"kernel": "error_tiles", "bound": "mfma", "achieved": et["tflops_issued"], "peak": MFMA_F16_PEAK / 1e12,
                     "unit": "TFLOP/s", "frac": et["frac_mfma"], "traffic": None,
                     "dense_equivalent": et["tflops_dense_equivalent"]}
@@ -403,7 +419,7 @@ def main():
                                 "each short kernel); see quantizer_hbm for the HBM-resident rate"}
     for k, v in kern.items():
         comps.setdefault(k, {"avg_us": v["avg_us"]})
-        comps[k]["launches_per_step"] = v["launches"] / args.steps
+        comps[k]["launches_per_step"] = v["launches"] / v["steps"]
 
     # The quantizer on its own, with HBM-resident inputs: back-to-back launches between two events
     # while rotating over enough weight / dW buffers (> 512 MB) that the 256 MB Infinity Cache
@@ -465,7 +481,9 @@ def main():
         "result": {"losses": losses, "best": int(best), "dim": "oc" if dim == 0 else "ic"},
         "roofline": roofline,
         "launch": ("one recorded HIP graph per step; kernel durations from a second pass of the same steps launched "
-                   "one by one" if use_graph else "kernel by kernel; kernel durations from HIP events in the timed region"),
+                   "one by one" if use_graph else
+                   "kernel by kernel; the duration of %s (the dominant kernel, which roofline describes) from HIP events in "
+                   "the timed region, the other kernels' from a second pass of the same steps" % dominant),
         "quantizer_hbm": dict(quant, note=("each launch moves %.0f MB: below some 150 MB a launch is mostly ramp and tail, the "
                                            "HBM-bound rate shows on the gate_proj / down_proj / clip_grid workloads" % (qbytes / 1e6))),
         "kernels": comps,

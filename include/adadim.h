@@ -331,8 +331,13 @@ void adadim_graph_destroy(void* graph);
  * record: name (host buffer of `cap` bytes), total milliseconds and number of
  * recorded launches.  Returns ADADIM_OK, or ADADIM_EINVAL when idx is past the
  * last record (use this to stop iterating).
+ * An event pair costs a few microseconds of the stream's time (about 7 us per launch on an MI355X: 3 % of a
+ * five-kernel step of 1.1 ms).  adadim_profile_only(ctx, name) restricts the bracketing to the kernel of that
+ * name (as adadim_profile_read reports it, at most 31 characters) until it is called with NULL or "";
+ * it changes no records and may be called while timing is on or off.
  */
 int adadim_profile(adadim_ctx* ctx, int enable);
+int adadim_profile_only(adadim_ctx* ctx, const char* name);
 int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus

@@ -24,7 +24,7 @@ EXPORTS = (
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
-    "adadim_profile", "adadim_profile_read",
+    "adadim_profile", "adadim_profile_only", "adadim_profile_read",
 )
 
 _lib = None
@@ -117,6 +117,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_select.restype = c_int
     lib.adadim_profile.argtypes = [c_void_p, c_int]
     lib.adadim_profile.restype = c_int
+    lib.adadim_profile_only.argtypes = [c_void_p, ctypes.c_char_p]
+    lib.adadim_profile_only.restype = c_int
     lib.adadim_profile_read.argtypes = [c_void_p, c_int, ctypes.c_char_p, c_int, POINTER(ctypes.c_double),
                                         POINTER(c_int64)]
     lib.adadim_profile_read.restype = c_int
@@ -299,6 +301,10 @@ class Context:
 
     def adadim_profile(self, enable: bool):
         self._check(self._lib.adadim_profile(self._h, 1 if enable else 0))
+
+    def adadim_profile_only(self, name: str | None):
+        """Bracket only the kernel of that name with events (None: every kernel again)."""
+        self._check(self._lib.adadim_profile_only(self._h, name.encode() if name else None))
 
     def adadim_profile_read(self) -> dict:
         """All per-kernel records: {kernel name: (total ms, launches)}."""

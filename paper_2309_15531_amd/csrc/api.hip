@@ -72,6 +72,7 @@ bool adadim_side_stream(adadim_ctx* ctx) {
 ProfScope::ProfScope(adadim_ctx* c, const char* name) : ctx(c), pair(-1) {
     adadim_prof& p = c->prof;
     if (!p.enabled || c->capturing) return;
+    if (p.only[0] && std::strcmp(p.only, name) != 0) return;
     if (p.n_used >= p.n_events) {
         ++p.dropped;
         return;
@@ -117,6 +118,16 @@ int adadim_profile(adadim_ctx* ctx, int enable) {
         p.n_kernels = 0;
     }
     p.enabled = enable != 0;
+    return ADADIM_OK;
+}
+
+int adadim_profile_only(adadim_ctx* ctx, const char* name) {
+    if (!ctx) return ADADIM_ENULL;
+    const size_t len = name ? std::strlen(name) : 0;
+    if (len >= sizeof(ctx->prof.only))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_profile_only: a kernel name has at most %d characters", int(sizeof(ctx->prof.only)) - 1);
+    std::memcpy(ctx->prof.only, name ? name : "", len);
+    ctx->prof.only[len] = 0;
     return ADADIM_OK;
 }
 

@@ -49,6 +49,7 @@ struct adadim_prof {
     int* kernel_of;                  // pair -> kernel slot
     int n_kernels;
     const char* names[PROF_MAX_KERNELS];
+    char only[32];                   // when not empty: the one kernel that is bracketed
 };
 
 struct adadim_ctx {

@@ -157,6 +157,14 @@ def test_capture_validation(ctx):
     ctx._lib.adadim_graph_destroy(None)
 
 
+def test_profile_only_validation(ctx):
+    assert ctx._lib.adadim_profile_only(None, b"gram_tiles") == B.ENULL
+    assert ctx.raw("adadim_profile_only", b"gram_tiles") == B.OK
+    assert ctx.raw("adadim_profile_only", b"x" * 32) == B.EINVAL          # at most 31 characters
+    assert "adadim_profile_only" in ctx.last_error()
+    assert ctx.raw("adadim_profile_only", None) == B.OK
+
+
 def test_create_destroy():
     lib = B.load_library()
     assert lib.adadim_create(None, None) == B.ENULL

@@ -506,3 +506,30 @@ def test_quantize_both_equals_the_two_calls(ctx, out_f, in_f, bits, group, meta1
         assert np.array_equal(one[dim]["codes"].cpu().numpy(), ref["codes"])
         assert np.array_equal(B.from_score_layout(one[dim]["dW"].cpu().numpy(), out_f, in_f),
                               (ref["dW"] * cs[None, :]).astype(np.float16))
+
+
+def test_profile_only_one_kernel(ctx):
+    """adadim_profile_only: with a name set only that kernel is bracketed; cleared, every kernel again."""
+    out_f, in_f = 256, 512
+    W = synth.make_weight(out_f, in_f, 3, heavy_cols=4, heavy_scale=5.0)
+    X = synth.make_activations(1024, in_f, 4, n_outliers=2, scale_lo=30, scale_hi=60)
+    hp = S.PreparedHessian(ctx, in_f)
+    ls = S.LayerSearch(ctx, out_f, in_f, 3, 64)
+    Wd, Xd = dev(W), dev(X)
+
+    def step():
+        hp.update_prepared(Xd)
+        ls.run(Wd, hp)
+
+    ctx.adadim_profile_only("gram_tiles")
+    ctx.adadim_profile(True)
+    step(); step()
+    ctx.adadim_profile(False)
+    rec = ctx.adadim_profile_read()
+    assert list(rec) == ["gram_tiles"] and rec["gram_tiles"][1] == 2 and rec["gram_tiles"][0] > 0
+    ctx.adadim_profile_only(None)
+    ctx.adadim_profile(True)
+    step()
+    ctx.adadim_profile(False)
+    rec = ctx.adadim_profile_read()
+    assert "gram_tiles" in rec and "error_tiles" in rec and len(rec) >= 4
