@@ -6,8 +6,14 @@ calibration activations, its preparation, quantize + score for both grouping
 dimensions, selection, and the winner's packed codes / scales / zeros.
 Prints ONE JSON line: metric, value, unit, ms_per_step, config, and the roofline / cpu_baseline objects.
 
-    python bench.py [--steps K] [--warmup W] [--workload q_proj|down_proj|gate_proj|qkv|clip_grid|toy|gemv_ic|gptq]
+    python bench.py [--steps K] [--warmup W]
+                    [--workload down_proj|gate_proj|q_proj|qkv|clip_grid|toy|block7b|stream13b|block70b|gemv_ic|gptq]
                     [--bits B] [--group G] [--meta16]
+
+The default workload is the layer the targets are stated on: W[4096, 11008] (the FFN down projection of the
+LLaMA-7B-shaped block) with 65536 calibration tokens.  block7b / block70b run a whole decoder block (every layer,
+every precision of the workload, one Gram matrix per input width); stream13b streams blocks of the 40-block
+13B-shaped model, weights regenerated per block, results appended to a JSON-lines file.
 """
 from __future__ import annotations
 
@@ -28,9 +34,9 @@ MFMA_F16_PEAK = 2.5e15     # flop/s, dense fp16 with fp32 accumulate
 WORKLOADS = {
     # name: (config id in synth.CONFIGS, layer name)
     "toy": (0, "fc"),
-    "q_proj": (1, "q_proj"),           # the workload the headline metric is quoted on
+    "q_proj": (1, "q_proj"),
     "gate_proj": (2, "gate_proj"),
-    "down_proj": (2, "down_proj"),
+    "down_proj": (2, "down_proj"),     # the workload the targets are stated on: W[4096, 11008], 65536 tokens
     # q, k and v of one decoder block: three layers that share X, one H, one scoring launch
     "qkv": (2, ("q_proj", "k_proj", "v_proj")),
     # the 70B-shaped block's q_proj with the clip-ratio grid: 20 ratios x both dims = 40 candidates per layer
@@ -44,35 +50,100 @@ def gram_tiling(in_f: int):
     return bt, nb * (nb + 1) // 2
 
 
-def cpu_baseline(W, X, bits, group, budget_tokens=65536, clips=(1.0,)):
-    """Times the CPU oracle, as it stands, on a bounded sample (about 10 s of host work on the
-    default workload): the Gram matrix on the first `budget_tokens` tokens (scaled linearly to all
-    tokens), the two quantizations and the two fp64 scorings in full (with a clip grid: for its
-    first ratio, scaled to the number of ratios)."""
-    import oracle
-    t_sample = min(budget_tokens, X.shape[0])
-    t0 = time.perf_counter()
-    H = oracle.hessian(X[:t_sample])
-    t_h = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    losses = []
-    for dim in (oracle.OC, oracle.IC):
-        q = oracle.quantize(W, dim, bits, group)
-        losses.append(oracle.layer_error(q["dW"], H))
-    oracle.select(losses)
-    t_q = time.perf_counter() - t0
-    total = t_h * (X.shape[0] / t_sample) + t_q * len(clips)
+def gram_issued_flops(in_f: int, tokens: int) -> float:
+    """MFMA flops the Gram kernel issues: upper-triangular tiles (full diagonal tiles) x 2*BT*BT*tokens."""
+    bt, n_tiles = gram_tiling(in_f)
+    return 2.0 * n_tiles * bt * bt * tokens
+
+
+def error_issued_flops(out_f: int, in_f: int) -> float:
+    """MFMA flops the error GEMM issues per candidate: 256x256 tiles, column block nb contracts over (nb+1)*256."""
+    bn = 256
+    nbk, mbk = (in_f + bn - 1) // bn, (out_f + bn - 1) // bn
+    return 2.0 * (mbk * bn) * bn * bn * nbk * (nbk + 1) / 2
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` on `workload` from profiles/traffic.txt ("<kernel>/<workload> <bytes>
+    <commit the counters were read at>" per line; FETCH_SIZE and WRITE_SIZE of two rocprofv3 --pmc runs of this
+    command, scaled by a plain copy's readings): (bytes, commit) or (None, None) when not measured."""
+    tpath = os.path.join(ROOT, "profiles", "traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            f = line.split()
+            if len(f) >= 2 and f[0] == f"{kernel}/{workload}":
+                return float(f[1]), (f[2] if len(f) > 2 else None)
+    return None, None
+
+
+def _blas_threads() -> int:
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count() or 1
+        return os.cpu_count() or 1
+
+
+def cpu_baseline(layer_list, X_of, tokens, bits_list, group, n_clips=1, budget_flops=3.0e11, quant_budget=48_000_000):
+    """Times the CPU oracle, as it stands, on a bounded sample of the workload and scales to the whole of it, twice:
+    with the BLAS threads the box gives (`cores`) and single-threaded.
+
+    layer_list: [(W fp16 host array, count)]: one layer per distinct shape and how many layers of that shape (times
+    precisions are counted through bits_list); X_of(width, t) -> the first t tokens of that width's activations.
+    Sampled: the fp64 Gram matrix on as many tokens as cost `budget_flops`, scaled to `tokens`; the fp64 loss on as
+    many output rows as cost `budget_flops`, scaled to all rows (extrapolated); both quantizations of each distinct
+    shape on the first whole row groups that hold at most `quant_budget` weights (all rows of the 7B shapes), for the
+    first precision (numpy, one thread whatever the setting), scaled to all rows, layers, precisions and clip ratios.  Returns the cpu_baseline object."""
+    import oracle
+    from threadpoolctl import threadpool_limits
+    widths = sorted({W.shape[1] for W, _ in layer_list})
+    n_weights = sum(W.size * c for W, c in layer_list)
+    t_quant, quant_done = 0.0, {}
+    legs = {}
+    for label, limit, scale in (("all", None, 1.0), ("single", 1, 1.0 / 8)):
+        with threadpool_limits(limits=limit):
+            t_h, H = 0.0, {}
+            for w in widths:
+                t_s = int(max(64, min(tokens, budget_flops * scale / (2.0 * w * w))))
+                Xs = X_of(w, t_s)
+                t0 = time.perf_counter()
+                H[w] = oracle.hessian(Xs)
+                t_h += (time.perf_counter() - t0) * tokens / t_s
+            t_l = 0.0
+            for W, count in layer_list:
+                out_f, in_f = W.shape
+                g_rows = group if group else out_f
+                q_rows = int(min(out_f, max(g_rows, (quant_budget // in_f) // g_rows * g_rows)))
+                if label == "all":
+                    t0 = time.perf_counter()
+                    quant_done[W.shape] = [oracle.quantize(W[:q_rows], dim, bits_list[0], group)["dW"]
+                                           for dim in (oracle.OC, oracle.IC)]
+                    t_quant += (time.perf_counter() - t0) * (out_f / q_rows) * count * len(bits_list) * n_clips
+                rows = int(max(8, min(q_rows, budget_flops * scale / (2.0 * in_f * in_f) / 2)))
+                t0 = time.perf_counter()
+                losses = [float(oracle.layer_error_rows(dW[:rows], H[in_f]).sum()) for dW in quant_done[W.shape]]
+                oracle.select(losses)
+                t_l += (time.perf_counter() - t0) * (out_f / rows) * count * len(bits_list) * n_clips
+            legs[label] = {"gram_s": t_h, "loss_s": t_l}
+    out = {}
+    for label in ("all", "single"):
+        total = legs[label]["gram_s"] + legs[label]["loss_s"] + t_quant
+        out[label] = {"value": n_weights * len(bits_list) / total, "seconds_extrapolated": total,
+                      "gram_s": legs[label]["gram_s"], "loss_s": legs[label]["loss_s"], "quantize_s": t_quant}
+    cores = _blas_threads()
     return {
-        "value": W.size / total, "unit": "weights/s", "cores": int(cores), "kind": "oracle",
-        "sample": f"fp64 Gram matrix on the first {t_sample} of {X.shape[0]} tokens ({t_h:.2f} s, scaled x"
-                  f"{X.shape[0] / t_sample:.0f}); both quantizations and both fp64 losses in full ({t_q:.2f} s)"
-                  + (f", scaled x{len(clips)} for the clip ratios" if len(clips) > 1 else ""),
-        "seconds_extrapolated": total,
+        "value": out["all"]["value"], "unit": "weights/s", "cores": int(cores), "kind": "oracle",
+        "sample": ("per input width the fp64 Gram matrix on the first tokens worth %.0e flop, scaled to %d tokens; per "
+                   "distinct layer shape both quantizations of the first row groups holding up to %d weights (numpy, one "
+                   "thread) and both fp64 losses on the first rows worth %.0e flop, scaled to all rows, layers, "
+                   "precisions and clip ratios; repeated with one BLAS thread on an eighth of the sample"
+                   % (budget_flops, tokens, quant_budget, budget_flops)),
+        "seconds_extrapolated": out["all"]["seconds_extrapolated"],
+        "parts_s": {k: out["all"][k] for k in ("gram_s", "loss_s", "quantize_s")},
+        "single_thread": {"value": out["single"]["value"], "cores": 1,
+                          "seconds_extrapolated": out["single"]["seconds_extrapolated"],
+                          "parts_s": {k: out["single"][k] for k in ("gram_s", "loss_s", "quantize_s")}},
+        "host_cpus": os.cpu_count(),
     }
 
 
@@ -210,13 +281,187 @@ def gptq_bench(args):
     }))
 
 
+def block_bench(args):
+    """Whole decoder blocks.  block7b: the seven layers of the LLaMA-7B-shaped block, INT4 and INT3, per step two Gram
+    matrices (one per input width) and 14 searches; stream13b: blocks of the 40-block 13B-shaped model, weights of
+    every layer regenerated on the device per block from seed + layer id, results appended to a JSON-lines file,
+    block b + 1 queued while block b's answers travel to the host; block70b: the 70B-shaped GQA block with the
+    20-ratio clip grid (40 candidates per layer and precision).  One step = one block.  The activation matrices are
+    drawn once per input width and shared by the layers of that width and by every block (each block still forms
+    its own Gram matrices from them)."""
+    import tempfile
+
+    import torch
+    from paper_2309_15531_amd import binding as B
+    from paper_2309_15531_amd import search as S
+    from paper_2309_15531_amd import stream as ST
+    from paper_2309_15531_amd import synth
+    B.load_library()
+    cfg_id = BLOCK_WORKLOADS[args.workload]
+    cfg = synth.CONFIGS[cfg_id]
+    layers, tokens = cfg["layers"], cfg["tokens"]
+    group = cfg["group"] if args.group is None else args.group
+    bits_list = (args.bits,) if args.bits is not None else tuple(cfg["bits"])
+    clips = tuple(S.clip_grid(cfg["clips"])) if cfg["clips"] > 1 else (1.0,)
+    n_blocks_model = cfg.get("blocks", 1)
+    streaming = n_blocks_model > 1
+    if streaming and args.warmup + args.steps > n_blocks_model:
+        print(f"bench.py: {args.workload} has {n_blocks_model} blocks; --warmup + --steps must not exceed that", file=sys.stderr)
+        sys.exit(2)
+    widths = sorted({i for _, i in layers.values()})
+    Xd = {w: synth.config_activations_device(cfg_id, w) for w in widths}
+    block_weights = sum(o * i for o, i in layers.values())
+    ctx = B.Context()
+    shapes = sorted(set(layers.values()))
+
+    # weights: two buffer sets when they are regenerated per block (block b's are read while block b + 1's are drawn)
+    n_sets = 2 if streaming else 1
+    bufs = [{n: torch.empty(sh, dtype=torch.float16, device="cuda") for n, sh in layers.items()} for _ in range(n_sets)]
+    scratch = {sh: torch.empty(sh, dtype=torch.float32, device="cuda") for sh in shapes}
+    for n in layers:
+        synth.config_weight_device(cfg_id, n, block=0, out=bufs[0][n], scratch=scratch[layers[n]])
+
+    def weights_of(b, slot):
+        if not streaming:
+            return bufs[0]
+        for n in layers:
+            synth.config_weight_device(cfg_id, n, block=b, out=bufs[slot][n], scratch=scratch[layers[n]])
+        return bufs[slot]
+
+    if len(clips) == 1:
+        bs = ST.BlockSearch(ctx, layers, bits_list, group)
+        tmp = None
+        if args.log is None:
+            tmp = tempfile.NamedTemporaryFile(prefix="adadim_stream_", suffix=".jsonl", delete=False)
+            tmp.close()
+            log_path = tmp.name
+        else:
+            log_path = args.log
+            if not args.resume and os.path.exists(log_path):
+                os.remove(log_path)
+        log = ST.ResultsLog(log_path)
+        next_block = [max([k[1] for k in log.records] + [-1]) + 1 if args.resume else 0]
+
+        def run(n):
+            """Searches the next n blocks (a streamed model: its next blocks; a single block: the same block again
+            under a new step number); returns the records written."""
+            b0 = next_block[0]
+            next_block[0] += n
+            return ST.run_stream(bs, log, cfg["seed"], range(b0, b0 + n), weights_of, lambda b: Xd)
+    else:
+        # clip grid: 2 x 20 candidates per layer and precision, scored in batches of eight; the winner is quantized
+        # again once it is known, so every layer waits for its answer
+        hps = {w: S.PreparedHessian(ctx, w) for w in widths}
+        searches = {(sh, b): S.LayerSearch(ctx, sh[0], sh[1], b, group, clips=clips) for sh in shapes for b in bits_list}
+        results = []
+
+        def run(n):
+            for _ in range(n):
+                for w in widths:
+                    hps[w].update_prepared(Xd[w])
+                for b in bits_list:
+                    for name, sh in layers.items():
+                        best, dim, clip = searches[(sh, b)].run(bufs[0][name], hps[sh[1]])
+                        results.append({"layer": name, "bits": b, "dim": "ic" if dim == 1 else "oc", "clip": clip})
+            return n * len(layers) * len(bits_list)
+        log = None
+
+    def profiled(n, only=None):
+        ctx.adadim_profile_only(only)
+        ctx.adadim_profile(True)
+        t_begin = time.perf_counter()
+        run(n)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t_begin
+        ctx.adadim_profile(False)
+        ctx.adadim_profile_only(None)
+        return dt, {k: {"total_us": v[0] * 1e3, "launches": v[1], "steps": n} for k, v in ctx.adadim_profile_read().items()}
+
+    run(max(1, args.warmup))
+    torch.cuda.synchronize()
+    # the timed region brackets the dominant kernel only (see the single-layer path); the others from a second pass
+    elapsed, live = profiled(args.steps, only="gram_tiles" if len(clips) == 1 else "error_tiles")
+    recs = list(log.records.values()) if log is not None else []
+    if streaming and args.log is None:
+        # the per-kernel pass re-runs one block of the model; the log would skip a block it holds, so it starts afresh
+        log.close()
+        os.remove(log_path)
+        log = ST.ResultsLog(log_path)
+        next_block[0] %= n_blocks_model
+    _, kern = profiled(1)
+    kern.update(live)
+
+    def per_step(k):
+        return kern[k]["total_us"] / kern[k]["steps"] * 1e-6 if k in kern else 0.0
+
+    gram_flops = sum(gram_issued_flops(w, tokens) for w in widths)
+    err_flops = sum(error_issued_flops(o, i) for o, i in layers.values()) * 2 * len(clips) * len(bits_list)
+    gram_s, err_s = per_step("gram_tiles"), per_step("error_tiles")
+    comps = {k: {"us_per_step": v["total_us"] / v["steps"], "launches_per_step": v["launches"] / v["steps"]} for k, v in kern.items()}
+    comps["gram_tiles"].update(tflops_issued=gram_flops / gram_s / 1e12, frac_mfma=gram_flops / gram_s / MFMA_F16_PEAK)
+    comps["error_tiles"].update(tflops_issued=err_flops / err_s / 1e12, frac_mfma=err_flops / err_s / MFMA_F16_PEAK)
+    dom = "gram_tiles" if gram_s >= err_s else "error_tiles"
+    traffic, traffic_at = read_traffic(dom, args.workload)
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": comps[dom]["tflops_issued"], "peak": MFMA_F16_PEAK / 1e12,
+                "unit": "TFLOP/s", "frac": comps[dom]["frac_mfma"], "traffic": traffic, "traffic_measured_at": traffic_at,
+                "note": "issued flops of all the kernel's launches in a step over their summed durations (a step holds "
+                        "launches of several sizes); traffic likewise summed over a step"}
+    # quantizer: bytes both dimensions move per weight (W read for each, two fp16 dW, packed codes, scale + zero)
+    q_s = per_step("quant_both") + per_step("quant_oc") + per_step("quant_ic")
+    q_bytes = sum(block_weights * (2 * (2 + 2 + b / 8.0) + 2 * 5.0 / group) for b in bits_list) * len(clips)
+    if q_s > 0:
+        comps["quantizers"] = {"us_per_step": q_s * 1e6, "GBps_algorithmic": q_bytes / q_s / 1e9, "frac_hbm": q_bytes / q_s / HBM_PEAK,
+                               "note": "in-step launches, the bytes of the two dimensions added up (W read for each)"}
+    searched = block_weights * len(bits_list)
+    sec_per_step = elapsed / args.steps
+    result = {
+        "metric": "weight params quantized+scored (both dims)/s", "value": searched / sec_per_step, "unit": "weights/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: one step = one decoder block, {len(layers)} layers "
+                               f"({', '.join(f'{n}[{o},{i}]' for n, (o, i) in layers.items())}), X[{tokens},w] per input width "
+                               f"w in {widths}, int{'/int'.join(str(b) for b in bits_list)} g{group} both dims"
+                               + (f" x {len(clips)} clip ratios" if len(clips) > 1 else "") + " + selection"
+                               + (f"; blocks streamed, weights regenerated per block ({n_blocks_model}-block model)" if streaming else ""),
+                   "bits": list(bits_list), "group": group, "tokens": tokens, "weights_per_block": block_weights,
+                   "searches_per_step": len(layers) * len(bits_list)},
+        "roofline": roofline, "kernels": comps,
+        "gram_share_of_step": gram_s / sec_per_step,
+        "weights_per_s_without_gram": searched / max(sec_per_step - gram_s - per_step("gram_reduce"), 1e-9),
+    }
+    if log is not None:
+        result["results_log"] = {"records": len(recs), "sample": recs[-2:], "ic_chosen": sum(r["dim"] == "ic" for r in recs),
+                                 "note": "one JSON line per (seed, block, layer, bits, group), warm-up blocks included; a "
+                                         "rerun with --log PATH --resume skips the keys the file holds"}
+        log.close()
+        if args.log is None:
+            os.remove(log_path)
+    else:
+        result["results_sample"] = results[-2:]
+    if not args.no_cpu_baseline:
+        by_shape = {}
+        for n, sh in layers.items():
+            by_shape.setdefault(sh, []).append(n)
+        host_layers = [(bufs[0][names[0]].cpu().numpy(), len(names)) for sh, names in by_shape.items()]
+        Xs = {}
+
+        def X_of(w, t):
+            if w not in Xs or Xs[w].shape[0] < t:
+                Xs[w] = Xd[w][:t].cpu().numpy()
+            return Xs[w][:t]
+        result["cpu_baseline"] = cpu_baseline(host_layers, X_of, tokens, bits_list, group, n_clips=len(clips), budget_flops=2.0e11)
+    print(json.dumps(result))
+
+
 # (warm-up, timed) steps when the flags are absent.  The chip needs some tens of milliseconds of load before its
 # clocks settle (the first 20 q_proj steps of a process run 5 % slower than the 200 after them), so the defaults
 # time a few tenths of a second of sustained work; clip_grid has 50 launches per step and stays within the
 # library's 8192 timed launches.
 SETTLE_SECONDS = 0.15
 DEFAULT_STEPS = {"toy": (20, 200), "q_proj": (20, 200), "gate_proj": (20, 200), "down_proj": (10, 100), "qkv": (20, 200),
-                 "clip_grid": (5, 50), "gemv_ic": (100, 2000), "gptq": (3, 30)}
+                 "clip_grid": (5, 50), "gemv_ic": (100, 2000), "gptq": (3, 30), "block7b": (2, 10), "stream13b": (1, 4),
+                 "block70b": (1, 2)}
+BLOCK_WORKLOADS = {"block7b": 2, "stream13b": 3, "block70b": 4}      # name: config id in synth.CONFIGS
 
 
 def main():
@@ -224,7 +469,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: by workload, see DEFAULT_STEPS)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them")
-    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["gemv_ic", "gptq"])
+    ap.add_argument("--workload", default="down_proj",
+                    choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + ["gemv_ic", "gptq"])
+    ap.add_argument("--log", default=None, help="stream13b: the JSON-lines results file (default: a fresh temporary file)")
+    ap.add_argument("--resume", action="store_true", help="stream13b: keep the records --log already holds and skip their layers")
     ap.add_argument("--bits", type=int, default=None)
     ap.add_argument("--group", type=int, default=None, help="group size (0 = whole channel); default: the config's")
     ap.add_argument("--meta16", action="store_true",
@@ -259,6 +507,9 @@ def main():
         return
     if args.workload == "gptq":
         gptq_bench(args)
+        return
+    if args.workload in BLOCK_WORKLOADS:
+        block_bench(args)
         return
     B.load_library()  # fails loudly if the HIP library has not been built
 
@@ -377,23 +628,15 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
 
-    # roofline of the dominant kernel: the Gram-matrix tiles.  MFMA flops
-    # actually issued = upper-triangular tiles x 2*BT*BT*tokens.
-    bt, n_tiles = gram_tiling(in_f)
-    gram_flops = 2.0 * n_tiles * bt * bt * tokens
+    # roofline of the dominant kernel: the Gram-matrix tiles.  MFMA flops actually issued = upper-triangular
+    # tiles x 2*BT*BT*tokens.  HBM bytes per launch of that kernel from profiles/traffic.txt (null when not measured).
+    gram_flops = gram_issued_flops(in_f, tokens)
     gram_s = kern["gram_tiles"]["avg_us"] * 1e-6
-    # HBM bytes per launch of that kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
-    # command (profiles/traffic.txt: "<kernel>/<workload> <bytes>" per line); null when not measured
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.txt")
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            f = line.split()
-            if len(f) >= 2 and f[0] == f"gram_tiles/{args.workload}":
-                traffic = float(f[1])
+    traffic, traffic_at = read_traffic("gram_tiles", args.workload)
     roofline = {
         "kernel": "gram_tiles", "bound": "mfma", "achieved": gram_flops / gram_s / 1e12, "peak": MFMA_F16_PEAK / 1e12,
-        "unit": "TFLOP/s", "frac": gram_flops / gram_s / MFMA_F16_PEAK, "traffic": traffic,
+        "unit": "TFLOP/s", "frac": gram_flops / gram_s / MFMA_F16_PEAK, "traffic": traffic, "traffic_measured_at": traffic_at,
+        "must_move_bytes": 2.0 * tokens * in_f + 4.0 * in_f * in_f,
         "dense_equivalent": 2.0 * tokens * in_f * in_f / gram_s / 1e12,
     }
 
@@ -401,12 +644,8 @@ def main():
     comps = {}
     if "error_tiles" in kern:
         s = kern["error_tiles"]["avg_us"] * 1e-6
-        bn = 256
-        nbk = (in_f + bn - 1) // bn
-        mbk = (out_f + bn - 1) // bn
         per_launch = len(ls.cands) * kern["error_tiles"]["steps"] / kern["error_tiles"]["launches"]   # candidates per launch
-        # MFMA flops issued: 256x256 tiles, column block nb contracts over (nb+1)*256
-        issued = per_launch * 2.0 * (mbk * bn) * bn * bn * nbk * (nbk + 1) / 2
+        issued = per_launch * error_issued_flops(out_f, in_f)
         comps["error_tiles"] = {
             "avg_us": s * 1e6, "candidates_per_launch": per_launch, "tflops_issued": issued / s / 1e12,
             "frac_mfma": issued / s / MFMA_F16_PEAK,
@@ -415,9 +654,12 @@ def main():
     # with many candidates per layer (clip grid) the error GEMM, not the Gram matrix, is the dominant kernel
     et = comps.get("error_tiles")
     if et and dominant == "error_tiles":
+        traffic, traffic_at = read_traffic("error_tiles", args.workload)
         roofline = {"kernel": "error_tiles", "bound": "mfma", "achieved": et["tflops_issued"], "peak": MFMA_F16_PEAK / 1e12,
-                    "unit": "TFLOP/s", "frac": et["frac_mfma"], "traffic": None,
+                    "unit": "TFLOP/s", "frac": et["frac_mfma"], "traffic": traffic, "traffic_measured_at": traffic_at,
                     "dense_equivalent": et["tflops_dense_equivalent"]}
+    if et:
+        et["traffic"], et["traffic_measured_at"] = read_traffic("error_tiles", args.workload)
     # W read + fp16 dW written + scale/zero (one pair per group of the larger of the two group counts)
     qbytes = out_f * in_f * (2 + 2) + 5.0 * (out_f * in_f / group if group else max(out_f, in_f))
     for k in ("quant_oc", "quant_ic"):
@@ -498,7 +740,8 @@ def main():
         "kernels": comps,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(W, X, bits, group, clips=clips)
+        Ws_host = [(W, 1)] + [(synth.config_weight(cfg_id, l), 1) for l in layers[1:]]
+        result["cpu_baseline"] = cpu_baseline(Ws_host, lambda w, t: X[:t], tokens, (bits,), group, n_clips=len(clips))
     print(json.dumps(result))
 
 

@@ -16,8 +16,11 @@
  *     argument is documented as a host pointer.  The library never frees or
  *     keeps caller memory.  Internal scratch lives in the context.
  *   - Calls are asynchronous on the context's HIP stream; results are ready
- *     when that stream has caught up.  Only adadim_select with a host output
- *     synchronises.
+ *     when that stream has caught up.  Three things wait for the stream:
+ *     adadim_select with a host output; adadim_profile_read; and any call
+ *     that finds one of the context's scratch buffers too small (it waits for
+ *     the kernels that may still read the old buffer, frees it and allocates
+ *     a larger one: the first call of a shape, never a repeat of it).
  *   - Return value: ADADIM_OK or a negative ADADIM_E* code; the library does
  *     not throw or abort.  Arguments are validated before any device work, so
  *     a rejected call has touched nothing.  adadim_last_error gives a text.

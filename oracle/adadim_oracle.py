@@ -217,11 +217,15 @@ def layer_error_rows_from_X(X, dW_rows) -> np.ndarray:
 
 def select(losses) -> int:
     """Index of the first minimum: a later candidate wins only if strictly
-    lower (App. B procedure, candidates ordered oc then ic)."""
-    best = 0
-    for i in range(1, len(losses)):
-        if losses[i] < losses[best]:
-            best = i
+    lower (App. B procedure, candidates ordered oc then ic).  The procedure starts
+    from a best error of +infinity and replaces it on `err < best_err`, so a NaN loss
+    never becomes the best (every comparison with it is false) and an infinite one
+    never replaces anything; if no candidate ever wins (all NaN or +inf) the first
+    candidate is returned."""
+    best, best_err = 0, float("inf")
+    for i in range(len(losses)):
+        if losses[i] < best_err:
+            best, best_err = i, losses[i]
     return best
 
 

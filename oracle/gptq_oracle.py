@@ -6,13 +6,13 @@ no code with the HIP sources.
 
 What it computes (paper Sec. 3.3, "Augmenting RTN and GPTQ", App. A.1
 "Activation reordering for free", App. B `gptq_ada`, Table 2b): once RTN has
-chosen the dimension, GPTQ is run in that dimension.  GPTQ (Frantar et al. 2022,
-the paper's reference [frantar2022gptq]) quantizes the input channels of the layer one
-after the other and, after each, spreads that channel's rounding error over the
-channels not yet quantized, using the inverse of the (damped) Hessian
-H = X^T X of the layer input; the paper's per-IC variant "simply requires
-executing the quantization step with per-IC RTN".  The configuration the paper
-settles on (green cells of Table 2b):
+chosen the dimension, GPTQ is run in that dimension.  GPTQ (Frantar et al. 2022)
+quantizes the input channels of the layer one after the other and, after each,
+spreads that channel's rounding error over the channels not yet quantized, using
+the inverse of the (damped) Hessian H = X^T X of the layer input; per-IC GPTQ is
+the same sweep with each channel's parameters taken per row group when the channel
+is visited (Sec. 3.3).  The configuration the paper settles on (green cells of
+Table 2b):
 
 * per-IC: activation reordering (channels visited in the order of decreasing
   diag(H)), quantization parameters of each (row group, channel) taken from the

@@ -147,6 +147,24 @@ def _ptr(t):
     return c_void_p(t.data_ptr())
 
 
+def _need(t, what: str, dtype: str | None = None, pitched: bool = False):
+    """Raises unless the torch tensor `t` can be handed to the library as `what`: on the GPU, of the element type
+    the ABI documents (`dtype`: "float16", "float32", ...; None = any), unit stride along the last axis and, unless
+    `pitched` (X: the row pitch travels as ldx), contiguous.  The library sees only an address: a transposed view
+    or a tensor of another type would be read as something it is not.  None and raw addresses pass."""
+    if t is None or isinstance(t, int):
+        return
+    if not t.is_cuda:
+        raise TypeError(f"{what}: expected a device tensor, got one on {t.device}")
+    if dtype is not None and str(t.dtype) != "torch." + dtype:
+        raise TypeError(f"{what}: expected {dtype}, got {t.dtype}")
+    if t.dim() >= 1 and t.numel() > 0 and t.stride(-1) != 1:
+        raise ValueError(f"{what}: the last axis must have unit stride (strides {tuple(t.stride())}); pass a contiguous "
+                         "tensor, not a transposed view")
+    if not pitched and not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous (shape {tuple(t.shape)}, strides {tuple(t.stride())})")
+
+
 class Context:
     """One adadim_ctx bound to a HIP stream (default: torch's current stream)."""
 
@@ -187,12 +205,18 @@ class Context:
     # -- the ABI, one method per entry point ----------------------------
     def adadim_hessian(self, X, H, accumulate: bool = False, tokens: int | None = None):
         t = X.shape[0] if tokens is None else tokens
+        _need(X, "X", "float16", pitched=True)
+        _need(H, "H", "float32")
         self._check(self._lib.adadim_hessian(self._h, _ptr(X), t, X.shape[1], X.stride(0), _ptr(H),
                                              1 if accumulate else 0))
 
     def adadim_quantize(self, W, dim: int, bits: int, group: int, clip: float = 1.0, codes=None, scales=None,
                         zeros=None, dW=None, dW_dtype: int = DW_F32, colscale=None, packed=None):
         out_f, in_f = W.shape
+        _need(W, "W", "float16")
+        _need(codes, "codes", "uint8"); _need(scales, "scales", "float32"); _need(zeros, "zeros", "uint8")
+        _need(dW, "dW", "float32" if dW_dtype == DW_F32 else "float16"); _need(colscale, "colscale", "float32")
+        _need(packed, "packed")
         self._check(self._lib.adadim_quantize(self._h, _ptr(W), out_f, in_f, dim, bits, group, c_float(clip),
                                               _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(dW), dW_dtype,
                                               _ptr(colscale), _ptr(packed)))
@@ -200,6 +224,10 @@ class Context:
     def adadim_quantize_meta16(self, W, dim: int, bits: int, group: int, clip: float = 1.0, codes=None, meta=None,
                                dW=None, dW_dtype: int = DW_F32, colscale=None, packed=None):
         out_f, in_f = W.shape
+        _need(W, "W", "float16")
+        _need(codes, "codes", "uint8"); _need(meta, "meta")
+        _need(dW, "dW", "float32" if dW_dtype == DW_F32 else "float16"); _need(colscale, "colscale", "float32")
+        _need(packed, "packed")
         self._check(self._lib.adadim_quantize_meta16(self._h, _ptr(W), out_f, in_f, dim, bits, group, c_float(clip),
                                                      _ptr(codes), _ptr(meta), _ptr(dW), dW_dtype, _ptr(colscale),
                                                      _ptr(packed)))
@@ -208,6 +236,13 @@ class Context:
                              meta16: bool = False):
         """oc / ic: dicts with any of codes, scales (or meta when meta16), zeros, dW, packed."""
         out_f, in_f = W.shape
+        _need(W, "W", "float16")
+        _need(colscale, "colscale", "float32")
+        for d in (oc, ic):
+            _need(d.get("codes"), "codes", "uint8"); _need(d.get("dW"), "dW", "float16"); _need(d.get("packed"), "packed")
+            _need(d.get("zeros"), "zeros", "uint8")
+            _need(d.get("meta") if meta16 else d.get("scales"), "scales", None if meta16 else "float32")
+
         def five(d):
             return [_ptr(d.get("codes")), _ptr(d.get("meta") if meta16 else d.get("scales")), _ptr(d.get("zeros")),
                     _ptr(d.get("dW")), _ptr(d.get("packed"))]
@@ -221,31 +256,46 @@ class Context:
 
     def adadim_hessian_prepared(self, X, H, Hs, hmeta, tokens: int | None = None):
         t = X.shape[0] if tokens is None else tokens
+        _need(X, "X", "float16", pitched=True)
+        _need(H, "H", "float32"); _need(Hs, "Hs", "float16"); _need(hmeta, "hmeta", "float32")
         self._check(self._lib.adadim_hessian_prepared(self._h, _ptr(X), t, X.shape[1], X.stride(0), _ptr(H), _ptr(Hs),
                                                       _ptr(hmeta)))
 
     def adadim_hessian_prepare(self, H, Hs, hmeta):
+        _need(H, "H", "float32"); _need(Hs, "Hs", "float16"); _need(hmeta, "hmeta", "float32")
         self._check(self._lib.adadim_hessian_prepare(self._h, _ptr(H), H.shape[0], _ptr(Hs), _ptr(hmeta)))
 
     def adadim_layer_error(self, dW, dW_dtype: int, H, loss, loss_rows=None):
         out_f, in_f = dW.shape
+        _need(dW, "dW", "float32" if dW_dtype == DW_F32 else "float16"); _need(H, "H", "float32")
+        _need(loss, "loss", "float32"); _need(loss_rows, "loss_rows", "float32")
         self._check(self._lib.adadim_layer_error(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(H),
                                                  _ptr(loss_rows), _ptr(loss)))
 
     def adadim_layer_error_prepared(self, dW, dW_dtype: int, Hs, hmeta, loss, loss_rows=None, shape=None):
         """shape = (out, in) when dW is a flat scoring-layout buffer (see alloc_score)."""
         out_f, in_f = dW.shape if shape is None else shape
+        _need(dW, "dW", "float32" if dW_dtype == DW_F32 else "float16"); _need(Hs, "Hs", "float16")
+        _need(hmeta, "hmeta", "float32"); _need(loss, "loss", "float32"); _need(loss_rows, "loss_rows", "float32")
         self._check(self._lib.adadim_layer_error_prepared(self._h, _ptr(dW), dW_dtype, out_f, in_f, _ptr(Hs),
                                                           _ptr(hmeta), _ptr(loss_rows), _ptr(loss)))
 
     def adadim_layer_error_batch(self, dWs, dW_dtype: int, Hs, hmeta, losses, loss_rows=None, shape=None):
         out_f, in_f = dWs[0].shape if shape is None else shape
+        for t in dWs:
+            _need(t, "dW", "float32" if dW_dtype == DW_F32 else "float16")
+        _need(Hs, "Hs", "float16"); _need(hmeta, "hmeta", "float32"); _need(losses, "losses", "float32")
+        _need(loss_rows, "loss_rows", "float32")
         arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
         self._check(self._lib.adadim_layer_error_batch(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
                                                        _ptr(hmeta), _ptr(loss_rows), _ptr(losses)))
 
     def adadim_layer_error_batch_select(self, dWs, dW_dtype: int, Hs, hmeta, losses, best_dev, loss_rows=None, shape=None):
         out_f, in_f = dWs[0].shape if shape is None else shape
+        for t in dWs:
+            _need(t, "dW", "float32" if dW_dtype == DW_F32 else "float16")
+        _need(Hs, "Hs", "float16"); _need(hmeta, "hmeta", "float32"); _need(losses, "losses", "float32")
+        _need(loss_rows, "loss_rows", "float32")
         arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
         self._check(self._lib.adadim_layer_error_batch_select(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
                                                               _ptr(hmeta), _ptr(loss_rows), _ptr(losses), _ptr(best_dev)))

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 
 #include "../../include/adadim.h"
 
@@ -116,6 +117,26 @@ __host__ __device__ inline int64_t score_index(int64_t row, int64_t col, int64_t
     return score_blocked(cols) ? (((row >> 8) * (cols >> 5) + (col >> 5)) * 256 + (row & 255)) * 32 + (col & 31)
                                : row * cols + col;
 }
+
+// Runs `fn` (a sequence of hipFuncSetAttribute calls returning hipError_t) once per device and thread-safely:
+// function attributes belong to the device that is current when they are set, and several host threads may
+// make their first call at the same time.  A failed run is tried again by the next call.
+struct PerDeviceOnce {
+    std::mutex m;
+    bool done[128] = {};
+    template <class F>
+    hipError_t run(F fn) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 128) return hipErrorInvalidDevice;
+        std::lock_guard<std::mutex> lock(m);
+        if (done[dev]) return hipSuccess;
+        e = fn();
+        if (e == hipSuccess) done[dev] = true;
+        return e;
+    }
+};
 
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 

@@ -886,19 +886,22 @@ int launch_gptq_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
     const int rpl = ic ? g / 64 : 1;                                   // rows per lane
     const unsigned blocks = static_cast<unsigned>(ic ? out / g : (out + 63) / 64);
     const size_t smem = (size_t(GB) * GB + size_t(64) * rpl * (GB + 1) + size_t(2) * 64 * rpl * 17) * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 2>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 1>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<false, 1>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024));
+    static PerDeviceOnce once;
+    ADADIM_HIP_TRY(ctx, once.run([] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 2>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<true, 1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gq_sweep<false, 1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         // a row of W in LDS: up to 46340 halves
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gq_gather_w),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-        attr_set = true;
-    }
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(gq_gather_w),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        return e;
+    }));
     {
         ProfScope prof(ctx, "gptq_gather");
         hipLaunchKernelGGL(gq_gather_w, dim3(static_cast<unsigned>(out)), dim3(256), static_cast<size_t>(in) * 2, ctx->stream, W, out,

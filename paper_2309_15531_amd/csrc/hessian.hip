@@ -356,12 +356,11 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         const size_t zero_bytes = size_t(32) * size_t(ldx) * 2 + 512;
         void* zero16 = adadim_workspace(ctx, WS_ZERO, zero_bytes);
         if (!zero16) return ADADIM_EHIP;
-        static bool attr_set = false;
-        if (!attr_set) {
-            ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(dma::gram_tiles_dma<2, 2>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, dma::SMEM_BYTES));
-            attr_set = true;
-        }
+        static PerDeviceOnce once;
+        ADADIM_HIP_TRY(ctx, once.run([] {
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(dma::gram_tiles_dma<2, 2>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, dma::SMEM_BYTES);
+        }));
         if (ctx->zero_ready_bytes != ctx->ws_bytes[WS_ZERO]) {
             const int64_t n = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
             hipLaunchKernelGGL(zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
@@ -379,12 +378,11 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     } else {
         constexpr int smem = 4 * BT * ROW_BYTES;
-        static bool attr_set = false;
-        if (!attr_set) {
-            ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(gram_tiles<BT>),
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-            attr_set = true;
-        }
+        static PerDeviceOnce once;
+        ADADIM_HIP_TRY(ctx, once.run([] {
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(gram_tiles<BT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        }));
         {
             ProfScope prof(ctx, "gram_tiles");
             hipLaunchKernelGGL(gram_tiles<BT>, dim3(n_tiles, n_split), dim3(THREADS), smem, ctx->stream, X, tokens,

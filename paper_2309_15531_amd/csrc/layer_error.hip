@@ -15,6 +15,7 @@
 #include "mfma_tile.h"
 #include "error_dma.h"
 
+
 namespace {
 
 using namespace mfma;
@@ -182,14 +183,101 @@ __global__ void select_first_min(const float* __restrict__ losses, int n, int32_
     *best = b < 0 ? 0 : b;
 }
 
+// Scratch of one scoring launch, wherever it lives (the context's growing slots, or the fixed device array of the
+// entry point that may not allocate).
+struct ErrScratch {
+    float* part;             // per candidate [n_slots, out] row partials
+    float* diag;             // per candidate [out] diagonal terms (prologue path only)
+    double* block_tot;       // per candidate one double per 256 rows
+    unsigned int* ticket;    // 64 counters, zero between launches
+    const void* zero16;      // at least 256 zero bytes
+    __half* dW16;            // per candidate scaled copy of dW (prologue path only)
+};
+
+// Contraction chunk of a launch of nc candidates, in 256-k blocks, and the number of (chunk, column block) slots:
+// whole contractions (one workgroup per tile, the cheapest in prologues and epilogues) unless that leaves fewer
+// than two workgroups per compute unit; then the largest chunk that gives that many.
+void error_slots(int nc, int MB, int NB, int64_t in, int& kb, int& n_slots) {
+    constexpr int BT = edma::BT;
+    kb = NB;
+    for (;;) {
+        n_slots = 0;
+        for (int nb = 0; nb < NB; ++nb) {
+            const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
+            n_slots += static_cast<int>((kend + int64_t(kb) * BT - 1) / (int64_t(kb) * BT));
+        }
+        if (kb == 1 || int64_t(nc) * MB * n_slots >= 512) break;
+        kb = kb > 2 ? kb / 2 : 1;
+    }
+}
+
+int set_error_attr(adadim_ctx* ctx) {
+    static PerDeviceOnce once;
+    const hipError_t err = once.run([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(edma::error_tiles_dma<0>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, edma::SMEM_BYTES);
+    });
+    if (err != hipSuccess)
+        return adadim_fail(ctx, ADADIM_EHIP, "hipFuncSetAttribute(error_tiles): %s", hipGetErrorString(err));
+    return ADADIM_OK;
+}
+
+// One launch group: nc <= MAX_BATCH candidates dW[0..nc) scored against Hs; losses_all / n_all are the whole
+// call's loss array (for the fused selection, taken when best_dev is given).
+int run_error_batch(adadim_ctx* ctx, int nc, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
+                    const __half* Hs, const float* hmeta, float* loss_rows, float* losses, const float* losses_all,
+                    int n_all, int32_t* best_dev, const ErrScratch& sc, int kb, int n_slots) {
+    constexpr int BT = edma::BT;
+    const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
+    const int kc_len = kb * BT;
+    const unsigned fin_blocks = static_cast<unsigned>((out + 255) / 256);
+    SrcBatch src;
+    edma::Batch batch;
+    batch.n = nc;
+    for (int c = 0; c < edma::MAX_BATCH; ++c) {
+        src.dW[c] = c < nc ? dW[c] : nullptr;
+        batch.A[c] = c < nc ? (sc.dW16 ? sc.dW16 + size_t(c) * size_t(score_elems(out, in))
+                                       : static_cast<const __half*>(dW[c]))
+                            : nullptr;
+    }
+    // Column-scaled fp16 input is consumed as it is and the tile kernel adds the diagonal term;
+    // other inputs go through the prologue, which scales them and takes that term in fp32.
+    const bool direct = dW_dtype == ADADIM_DW_F16_SCALED;
+    if (!direct) {
+        ProfScope prof(ctx, "error_prologue");
+        hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out), nc), dim3(256), 0, ctx->stream, src,
+                           dW_dtype, out, in, hmeta, sc.dW16, sc.diag);
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
+    {
+        ProfScope prof(ctx, "error_tiles");
+        // units of 4 slots x 8 (candidate, row block) pairs, 32 workgroups each, dealt to 8 XCDs
+        const int n_units = ((n_slots + 3) / 4) * ((nc * MB + 7) / 8);
+        const unsigned grid = 8u * static_cast<unsigned>((n_units + 7) / 8) * 32u;
+        hipLaunchKernelGGL(edma::error_tiles_dma<0>, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
+                           out, in, MB, NB, kc_len, n_slots, sc.zero16, direct ? hmeta : nullptr, sc.part);
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
+    {
+        ProfScope prof(ctx, "error_finish");
+        hipLaunchKernelGGL(error_finish, dim3(fin_blocks, nc), dim3(256), 0, ctx->stream,
+                           direct ? static_cast<const float*>(nullptr) : sc.diag, sc.part, out, n_slots, loss_rows,
+                           losses, sc.block_tot, sc.ticket, losses_all, n_all, best_dev);
+    }
+    ADADIM_LAUNCH_CHECK(ctx, "error_finish");
+    return ADADIM_OK;
+}
+
 }  // namespace
 
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
                        const __half* Hs, const float* hmeta, float* loss_rows, float* losses, int32_t* best_dev) {
     constexpr int BT = edma::BT;
     const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
+    ErrScratch sc{};
     void* zero16 = adadim_workspace(ctx, WS_ZERO, 256);
     if (!zero16) return ADADIM_EHIP;
+    sc.zero16 = zero16;
     if (ctx->zero_ready_bytes != ctx->ws_bytes[WS_ZERO]) {
         // a fill kernel rather than a memset node, so that the call stays safe to capture in a graph
         const int64_t nz = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
@@ -198,87 +286,39 @@ int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dty
         ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
         ctx->zero_ready_bytes = ctx->ws_bytes[WS_ZERO];
     }
-    static bool attr_set = false;
-    if (!attr_set) {
-        ADADIM_HIP_TRY(ctx, hipFuncSetAttribute(reinterpret_cast<const void*>(edma::error_tiles_dma<0>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, edma::SMEM_BYTES));
-        attr_set = true;
-    }
+    int rc = set_error_attr(ctx);
+    if (rc != ADADIM_OK) return rc;
     for (int c0 = 0; c0 < n; c0 += edma::MAX_BATCH) {
         const int nc = n - c0 < edma::MAX_BATCH ? n - c0 : edma::MAX_BATCH;
-        // Contraction chunk, in 256-k blocks: whole contractions (one workgroup per tile, the
-        // cheapest in prologues and epilogues) unless that leaves fewer than two workgroups per
-        // compute unit; then the largest chunk that gives that many.
-        int kb = NB, n_slots = 0;
-        for (;;) {
-            n_slots = 0;
-            for (int nb = 0; nb < NB; ++nb) {
-                const int64_t kend = in < int64_t(nb + 1) * BT ? in : int64_t(nb + 1) * BT;
-                n_slots += static_cast<int>((kend + int64_t(kb) * BT - 1) / (int64_t(kb) * BT));
-            }
-            if (kb == 1 || int64_t(nc) * MB * n_slots >= 512) break;
-            kb = kb > 2 ? kb / 2 : 1;
-        }
-        const int kc_len = kb * BT;
+        int kb = 0, n_slots = 0;
+        error_slots(nc, MB, NB, in, kb, n_slots);
         // scratch: per candidate [n_slots, out] row partials; then per candidate [out] diagonal terms
-        float* part = static_cast<float*>(adadim_workspace(
+        sc.part = static_cast<float*>(adadim_workspace(
             ctx, WS_ERR_PART, size_t(nc) * size_t(n_slots + 1) * size_t(out) * sizeof(float)));
-        if (!part) return ADADIM_EHIP;
-        float* diag = part + size_t(nc) * size_t(n_slots) * size_t(out);
+        if (!sc.part) return ADADIM_EHIP;
+        sc.diag = sc.part + size_t(nc) * size_t(n_slots) * size_t(out);
         // scratch of the final reduction: per candidate one double per 256 rows; then the tickets
         const unsigned fin_blocks = static_cast<unsigned>((out + 255) / 256);
         const size_t fin_bytes = size_t(edma::MAX_BATCH) * fin_blocks * sizeof(double) + 256;
         const bool fin_fresh = ctx->ws_bytes[WS_ERR_FIN] < fin_bytes;
-        double* block_tot = static_cast<double*>(adadim_workspace(ctx, WS_ERR_FIN, fin_bytes));
-        if (!block_tot) return ADADIM_EHIP;
-        unsigned int* ticket =
-            reinterpret_cast<unsigned int*>(block_tot + (ctx->ws_bytes[WS_ERR_FIN] - 256) / sizeof(double));
+        sc.block_tot = static_cast<double*>(adadim_workspace(ctx, WS_ERR_FIN, fin_bytes));
+        if (!sc.block_tot) return ADADIM_EHIP;
+        sc.ticket = reinterpret_cast<unsigned int*>(sc.block_tot + (ctx->ws_bytes[WS_ERR_FIN] - 256) / sizeof(double));
         if (fin_fresh) {
-            hipLaunchKernelGGL(fill_zero_f32, dim3(1), dim3(64), 0, ctx->stream, reinterpret_cast<float*>(ticket),
+            hipLaunchKernelGGL(fill_zero_f32, dim3(1), dim3(64), 0, ctx->stream, reinterpret_cast<float*>(sc.ticket),
                                int64_t(64));
             ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
         }
-        SrcBatch src;
-        edma::Batch batch;
-        batch.n = nc;
-        __half* dW16 = nullptr;
+        sc.dW16 = nullptr;
         if (dW_dtype != ADADIM_DW_F16_SCALED) {
-            dW16 = static_cast<__half*>(
+            sc.dW16 = static_cast<__half*>(
                 adadim_workspace(ctx, WS_DW16, size_t(nc) * size_t(score_elems(out, in)) * sizeof(__half)));
-            if (!dW16) return ADADIM_EHIP;
+            if (!sc.dW16) return ADADIM_EHIP;
         }
-        for (int c = 0; c < edma::MAX_BATCH; ++c) {
-            src.dW[c] = c < nc ? dW[c0 + c] : nullptr;
-            batch.A[c] = c < nc ? (dW16 ? dW16 + size_t(c) * size_t(score_elems(out, in))
-                                        : static_cast<const __half*>(dW[c0 + c]))
-                                : nullptr;
-        }
-        // Column-scaled fp16 input is consumed as it is and the tile kernel adds the diagonal term;
-        // other inputs go through the prologue, which scales them and takes that term in fp32.
-        const bool direct = dW_dtype == ADADIM_DW_F16_SCALED;
-        if (!direct) {
-            ProfScope prof(ctx, "error_prologue");
-            hipLaunchKernelGGL(error_prologue, dim3(static_cast<unsigned>(out), nc), dim3(256), 0, ctx->stream, src,
-                               dW_dtype, out, in, hmeta, dW16, diag);
-        }
-        ADADIM_LAUNCH_CHECK(ctx, "error_prologue");
-        {
-            ProfScope prof(ctx, "error_tiles");
-            // units of 4 slots x 8 (candidate, row block) pairs, 32 workgroups each, dealt to 8 XCDs
-            const int n_units = ((n_slots + 3) / 4) * ((nc * MB + 7) / 8);
-            const unsigned grid = 8u * static_cast<unsigned>((n_units + 7) / 8) * 32u;
-            hipLaunchKernelGGL(edma::error_tiles_dma<0>, dim3(grid), dim3(256), edma::SMEM_BYTES, ctx->stream, batch, Hs,
-                               out, in, MB, NB, kc_len, n_slots, zero16, direct ? hmeta : nullptr, part);
-        }
-        ADADIM_LAUNCH_CHECK(ctx, "error_tiles");
-        {
-            ProfScope prof(ctx, "error_finish");
-            hipLaunchKernelGGL(error_finish, dim3(fin_blocks, nc), dim3(256), 0, ctx->stream,
-                               direct ? static_cast<const float*>(nullptr) : diag, part, out, n_slots,
-                               loss_rows ? loss_rows + size_t(c0) * size_t(out) : nullptr, losses + c0, block_tot,
-                               ticket, losses, n, c0 + nc == n ? best_dev : nullptr);
-        }
-        ADADIM_LAUNCH_CHECK(ctx, "error_finish");
+        rc = run_error_batch(ctx, nc, dW + c0, dW_dtype, out, in, Hs, hmeta,
+                             loss_rows ? loss_rows + size_t(c0) * size_t(out) : nullptr, losses + c0, losses, n,
+                             c0 + nc == n ? best_dev : nullptr, sc, kb, n_slots);
+        if (rc != ADADIM_OK) return rc;
     }
     return ADADIM_OK;
 }

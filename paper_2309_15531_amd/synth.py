@@ -123,9 +123,7 @@ CONFIGS = {
 def config_weight(cfg_id: int, layer: str, block: int = 0) -> np.ndarray:
     cfg = CONFIGS[cfg_id]
     out_f, in_f = cfg["layers"][layer]
-    lid = sorted(cfg["layers"]).index(layer)
-    seed = cfg["seed"] * 100003 + block * 101 + lid
-    return make_weight(out_f, in_f, seed, cfg["heavy_cols"], cfg["heavy_scale"])
+    return make_weight(out_f, in_f, layer_seed(cfg_id, layer, block), cfg["heavy_cols"], cfg["heavy_scale"])
 
 
 def config_activations(cfg_id: int, in_f: int, tokens: int | None = None) -> np.ndarray:
@@ -134,3 +132,76 @@ def config_activations(cfg_id: int, in_f: int, tokens: int | None = None) -> np.
     t = cfg["tokens"] if tokens is None else tokens
     return make_activations(t, in_f, cfg["seed"] * 100003 + 7 * in_f, n, lo, hi,
                             relu=in_f in cfg["relu_widths"])
+
+
+# ---------------------------------------------------------------------------------------------
+# The same recipes drawn on the device, for inputs too large to draw on the host per use (the
+# streamed 40-block workload regenerates 317 M weights per block; its 131072 x 13824 activation
+# matrix is 3.6 GB).  torch's seeded device generator replaces numpy's; the structure (which
+# channels are heavy, their factors) is still drawn on the host from the same seeded streams as
+# above (for weights, on the device as well).  A test that needs the values on the host copies the tensor back: the bits the oracle
+# sees are the bits the device holds.
+
+def device_weight(out_f: int, in_f: int, seed: int, heavy_cols, heavy_scale: float, sigma: float = 0.02,
+                  out=None, scratch=None, device="cuda"):
+    """W fp16 [out, in] on the device, same law as make_weight (different random bits).  `out` (fp16
+    [out, in]) and `scratch` (fp32 [out, in]) let a streaming caller reuse its buffers."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) & 0x7FFFFFFFFFFFFFFF)
+    buf = scratch if scratch is not None else torch.empty((out_f, in_f), dtype=torch.float32, device=device)
+    buf.normal_(0.0, float(sigma), generator=g)
+    # the heavy columns are drawn on the device too (a host-drawn scale vector would cost a blocking copy per
+    # layer, and the streaming driver must be able to queue a block without waiting for the GPU)
+    n_heavy = int(round(heavy_cols * in_f)) if 0 < heavy_cols < 1 else int(heavy_cols)
+    if n_heavy:
+        cols = torch.randperm(in_f, generator=g, device=device)[:n_heavy]
+        buf[:, cols] *= float(heavy_scale)
+    if out is None:
+        return buf.to(torch.float16)
+    out.copy_(buf)
+    return out
+
+
+def device_activations(tokens: int, in_f: int, seed: int, n_outliers: int, scale_lo: float, scale_hi: float,
+                       relu: bool = False, device="cuda", chunk_rows: int = 16384):
+    """X fp16 [tokens, in] on the device, same law as make_activations (different random bits)."""
+    import torch
+    rng = _rng(seed, 2)
+    ch = np.sort(rng.choice(in_f, size=n_outliers, replace=False)) if n_outliers else np.zeros(0, np.int64)
+    ch_scale = np.ones(in_f, dtype=np.float32)
+    ch_scale[ch] = rng.uniform(scale_lo, scale_hi, size=n_outliers).astype(np.float32)
+    cs = torch.from_numpy(ch_scale).to(device)[None, :]
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed) & 0x7FFFFFFFFFFFFFFF)
+    X = torch.empty((tokens, in_f), dtype=torch.float16, device=device)
+    buf = torch.empty((min(chunk_rows, tokens), in_f), dtype=torch.float32, device=device)
+    for r0 in range(0, tokens, chunk_rows):
+        r1 = min(tokens, r0 + chunk_rows)
+        b = buf[:r1 - r0]
+        b.normal_(0.0, 1.0, generator=g)
+        if relu:
+            b.clamp_(min=0.0)
+        b.mul_(cs)
+        X[r0:r1].copy_(b)
+    return X
+
+
+def layer_seed(cfg_id: int, layer: str, block: int = 0) -> int:
+    """Seed of one layer's weight: the workload's seed plus the layer's id within the model."""
+    cfg = CONFIGS[cfg_id]
+    return cfg["seed"] * 100003 + block * 101 + sorted(cfg["layers"]).index(layer)
+
+
+def config_weight_device(cfg_id: int, layer: str, block: int = 0, out=None, scratch=None):
+    cfg = CONFIGS[cfg_id]
+    out_f, in_f = cfg["layers"][layer]
+    return device_weight(out_f, in_f, layer_seed(cfg_id, layer, block), cfg["heavy_cols"], cfg["heavy_scale"],
+                         out=out, scratch=scratch)
+
+
+def config_activations_device(cfg_id: int, in_f: int, tokens: int | None = None):
+    cfg = CONFIGS[cfg_id]
+    n, lo, hi = cfg["outliers"][in_f]
+    t = cfg["tokens"] if tokens is None else tokens
+    return device_activations(t, in_f, cfg["seed"] * 100003 + 7 * in_f, n, lo, hi, relu=in_f in cfg["relu_widths"])

@@ -221,3 +221,34 @@ def test_fast_division_matches_ieee(tmp_path):
     res = subprocess.run([str(exe), "12", "8"], capture_output=True, text=True)
     assert res.returncode == 0, res.stdout
     assert " 0 mismatches" in res.stdout
+
+
+def test_binding_refuses_tensors_the_library_would_misread():
+    """The library sees addresses only; the binding must stop a transposed view, a wrong element type or a host
+    tensor before its address goes in."""
+    import torch
+    from paper_2309_15531_amd.binding import _need
+
+    class Dev:                                    # a device tensor's attributes without a device
+        def __init__(self, t):
+            self.t = t
+        is_cuda, device = True, "cuda:0"
+        dtype = property(lambda s: s.t.dtype)
+        shape = property(lambda s: s.t.shape)
+        def dim(self): return self.t.dim()
+        def numel(self): return self.t.numel()
+        def stride(self, *a): return self.t.stride(*a)
+        def is_contiguous(self): return self.t.is_contiguous()
+
+    w = torch.zeros((8, 16), dtype=torch.float16)
+    _need(Dev(w), "W", "float16")
+    _need(None, "W", "float16")
+    _need(Dev(w[:, :8]), "X", "float16", pitched=True)           # a row pitch is fine where ldx carries it
+    with pytest.raises(TypeError):
+        _need(w, "W", "float16")                                  # host tensor
+    with pytest.raises(TypeError):
+        _need(Dev(w.float()), "W", "float16")                     # wrong element type
+    with pytest.raises(ValueError):
+        _need(Dev(w.t()), "W", "float16")                         # transposed view
+    with pytest.raises(ValueError):
+        _need(Dev(w[:, :8]), "W", "float16")                      # pitched where the ABI takes none

@@ -135,3 +135,101 @@ def test_down_proj_sampled(ctx):
     words = in_f * bits // 32                                   # per-OC stream: one row = `words` words
     oc_stream = ls._packed[0][:out_f * words].view(out_f, words)[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint32)
     assert np.array_equal(oc_stream, single_packed[0])
+
+
+# ---- the other full-size cases of the 7B block: INT4 on both 4096 x 11008 layers and the [11008, 4096]
+# gate_proj at INT3 (its per-IC pass reads 128-byte pieces at a pitch of 8 KB).  X and H are made once per
+# input width and shared by the cases.
+_BLOCK_CACHE = {}
+
+
+def _block_input(ctx, in_f):
+    if in_f not in _BLOCK_CACHE:
+        _BLOCK_CACHE.clear()                                  # one width at a time: the 11008-wide X is 1.4 GB
+        X = synth.config_activations(2, in_f)
+        hp = S.PreparedHessian(ctx, in_f).update_prepared(dev(X))
+        torch.cuda.synchronize()
+        _BLOCK_CACHE[in_f] = (X, hp)
+    return _BLOCK_CACHE[in_f]
+
+
+@pytest.mark.parametrize("layer,bits", [("down_proj", 4), ("gate_proj", 4), ("gate_proj", 3)])
+def test_block_layer_sampled(ctx, layer, bits):
+    """One layer of the LLaMA-7B-shaped block through the calls the benchmark times (both candidates in one
+    quantizer call, scoring + selection in one call): the winner's parameters and packed stream in full, both
+    candidates' codes / scales / zeros in full through the single-dimension call, both losses on sampled
+    output rows against L_o = ||X dW_o||^2 in fp64."""
+    group = 128
+    out_f, in_f = synth.CONFIGS[2]["layers"][layer]
+    tokens = synth.CONFIGS[2]["tokens"]
+    W = synth.config_weight(2, layer)
+    X, hp = _block_input(ctx, in_f)
+    print("inputs ready", layer, bits, flush=True)
+    Wd = dev(W)
+    ls = S.LayerSearch(ctx, out_f, in_f, bits, group)
+    ls.launch(Wd, hp)
+    best, dim, _ = ls.result()
+    got = ls.losses.cpu().numpy().astype(np.float64)
+    rng = np.random.default_rng(5 + bits)
+    rows = np.sort(rng.choice(out_f, 16, replace=False))
+    ref_tot = []
+    for dm in (OC, IC):
+        q = oracle.quantize(W, dm, bits, group)
+        meta = (out_f, in_f // group) if dm == OC else (out_f // group, in_f)
+        codes = torch.empty((out_f, in_f), dtype=torch.uint8, device="cuda")
+        scales = torch.empty(meta, dtype=torch.float32, device="cuda")
+        zeros = torch.empty(meta, dtype=torch.uint8, device="cuda")
+        dW = ctx.alloc_score(out_f, in_f)
+        ctx.adadim_quantize(Wd, dm, bits, group, 1.0, codes=codes, scales=scales, zeros=zeros, dW=dW,
+                            dW_dtype=B.DW_F16_SCALED, colscale=hp.colscale)
+        loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        lrows = torch.zeros(out_f, dtype=torch.float32, device="cuda")
+        ctx.adadim_layer_error_prepared(dW, B.DW_F16_SCALED, hp.Hs, hp.hmeta, loss, loss_rows=lrows, shape=(out_f, in_f))
+        torch.cuda.synchronize()
+        assert np.array_equal(codes.cpu().numpy(), q["codes"])
+        assert np.array_equal(scales.cpu().numpy(), q["scales"])
+        assert np.array_equal(zeros.cpu().numpy(), q["zeros"])
+        # the one-call search's own outputs for this candidate: parameters and the packed stream, in full
+        n_meta = q["scales"].size
+        assert np.array_equal(ls._scales[dm][:n_meta].cpu().numpy(), q["scales"].ravel())
+        assert np.array_equal(ls._zeros[dm][:n_meta].cpu().numpy(), q["zeros"].ravel())
+        pk = oracle.pack(q["codes"], dm, bits)
+        assert np.array_equal(ls._packed[dm][:pk.size].cpu().numpy().view(np.uint32), pk.ravel())
+        ref_rows = np.zeros(len(rows))
+        for t0 in range(0, tokens, 8192):
+            ref_rows += oracle.layer_error_rows_from_X(X[t0:t0 + 8192], q["dW"][rows])
+        g = lrows.cpu().numpy().astype(np.float64)
+        assert g[rows] == pytest.approx(ref_rows, rel=LOSS_RTOL)
+        assert loss.item() == pytest.approx(g.sum(), rel=1e-5)
+        assert got[dm] == pytest.approx(loss.item(), rel=1e-5)
+        ref_tot.append(loss.item())
+        print("dim", dm, "loss", loss.item(), flush=True)
+    if abs(ref_tot[0] - ref_tot[1]) / min(ref_tot) > 0.01:
+        assert best == int(np.argmin(ref_tot)) and dim == best
+
+
+def test_gptq_factor_11008_wide(ctx):
+    """adadim_gptq_prepare on the down_proj input width against the fp64 oracle factor (the 256-wide outer panels
+    and the side-stream update only come into play above 4096): 12288 calibration tokens, visiting order and dead
+    flags exact, U to fp32 rounding."""
+    from oracle import gptq_oracle as G
+    in_f = 11008
+    X = synth.config_activations(2, in_f, tokens=12288)
+    H32 = oracle.hessian(X).astype(np.float32)
+    print("H ready", flush=True)
+    Hp, perm_ref, dead_ref = G.prepare(H32, 0.01, True)
+    U_ref = G.factor(Hp)
+    print("oracle factor ready", flush=True)
+    perm = torch.full((in_f,), -1, dtype=torch.int32, device="cuda")
+    dead = torch.full((in_f,), 7, dtype=torch.uint8, device="cuda")
+    U = torch.full((in_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.adadim_gptq_prepare(dev(H32), perm, dead, U, 0.01, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(perm.cpu().numpy().astype(np.int64), perm_ref)
+    assert np.array_equal(dead.cpu().numpy().astype(bool), dead_ref)
+    Ug = U.cpu().numpy().astype(np.float64)
+    bound = 4e-6 * np.abs(U_ref) + 2e-7 * np.abs(U_ref).max()
+    worst = float((np.abs(Ug - U_ref) / bound).max())
+    print("max |dU| / bound =", worst, flush=True)
+    assert worst <= 1.0
+    assert not np.tril(Ug, -1).any()

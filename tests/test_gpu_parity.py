@@ -272,12 +272,12 @@ def test_layer_error_zero_and_identity(ctx):
 
 def test_select(ctx):
     for vals, want in [([1.0, 1.0], 0), ([2.0, 1.0], 1), ([3.0, 2.0, 2.0, 5.0], 1),
-                       ([float("nan"), 4.0, 3.0], 2), ([5.0] * 40, 0)]:
+                       ([float("nan"), 4.0, 3.0], 2), ([5.0] * 40, 0), ([float("nan"), 2.0], 1), ([2.0, float("nan")], 0),
+                       ([float("nan"), float("nan")], 0), ([float("inf"), 2.0], 1), ([float("inf"), float("inf")], 0)]:
         t = torch.tensor(vals, dtype=torch.float32, device="cuda")
         best_dev = torch.full((1,), -7, dtype=torch.int32, device="cuda")
         assert ctx.adadim_select(t, best_dev=best_dev) == want
-        if not any(v != v for v in vals):
-            assert oracle.select(vals) == want
+        assert oracle.select(vals) == want
         assert ctx.adadim_select(t) == want
         assert best_dev.item() == want
 

@@ -276,6 +276,14 @@ def test_select_first_minimum():
     assert oracle.select([2.0, 1.0]) == 1
     assert oracle.select([1.0, 2.0]) == 0
     assert oracle.select([3.0, 2.0, 2.0, 5.0]) == 1
+    # App. B starts from best_err = inf and tests err < best_err: NaN never wins, wherever it stands
+    nan, inf = float("nan"), float("inf")
+    assert oracle.select([nan, 2.0]) == 1
+    assert oracle.select([2.0, nan]) == 0
+    assert oracle.select([nan, 3.0, 2.0, nan]) == 2
+    assert oracle.select([nan, nan]) == 0           # nothing ever wins: the first candidate stands
+    assert oracle.select([inf, 2.0]) == 1
+    assert oracle.select([inf, inf]) == 0
     # the argmin is the same for Eq. 1's norm, the listing's mean and the squared sum
     L = [7.3, 4.1, 9.9]
     assert oracle.select(L) == oracle.select([np.sqrt(v) for v in L]) == oracle.select([v / 1234 for v in L])
