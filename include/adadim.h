@@ -21,6 +21,7 @@
  *     that finds one of the context's scratch buffers too small (it waits for
  *     the kernels that may still read the old buffer, frees it and allocates
  *     a larger one: the first call of a shape, never a repeat of it).
+ *     adadim_layer_error_batch_select_noalloc has no scratch to grow.
  *   - Return value: ADADIM_OK or a negative ADADIM_E* code; the library does
  *     not throw or abort.  Arguments are validated before any device work, so
  *     a rejected call has touched nothing.  adadim_last_error gives a text.
@@ -221,6 +222,29 @@ int adadim_layer_error_batch(adadim_ctx* ctx, int n, const void* const* dW, int 
 int adadim_layer_error_batch_select(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out,
                                     int64_t in, const void* Hs, const float* hmeta, float* loss_rows, float* losses,
                                     int32_t* best_dev);
+
+/*
+ * adadim_layer_error_batch_select for callers that cannot allocate device memory: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The call above keeps its row partials, block
+ * totals and counters in scratch that the context allocates and grows on demand; this one keeps them in a fixed
+ * 16 MiB device array inside the library (one per GPU the library runs on, held until the process ends) and
+ * calls no hipMalloc, hipFree or other allocating routine.  Same kernels, same launch shape, same results bit
+ * for bit.
+ *   n       1..8 candidates (one launch);  dW[c]  column-scaled fp16 in the scoring layout (ADADIM_DW_F16_SCALED),
+ *           as adadim_quantize / adadim_quantize_both write it: the other dW types need a scaled copy of dW, which
+ *           does not fit a fixed array.
+ *   Sizes whose scratch exceeds the array are rejected with ADADIM_EINVAL and touch nothing;
+ *   adadim_noalloc_scratch_bytes(n, out, in) gives the need (-1 for arguments out of range), the limit is
+ *   16 MiB = 16777216 bytes: 512 + 64*ceil(out/256) + 4*n*slots*out with slots about ceil(in/256), e.g. 1.4 MB for
+ *   two candidates of a 4096 x 11008 layer, 8.4 MB for eight of an 8192 x 8192 layer.
+ *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *   contexts, two threads) race and give undefined losses; calls on one stream, one after the other, are safe.
+ * Everything else as in adadim_layer_error_batch_select.
+ */
+int adadim_layer_error_batch_select_noalloc(adadim_ctx* ctx, int n, const void* const* dW, int64_t out, int64_t in,
+                                            const void* Hs, const float* hmeta, float* loss_rows, float* losses,
+                                            int32_t* best_dev);
+int64_t adadim_noalloc_scratch_bytes(int n, int64_t out, int64_t in);
 
 /*
  * Eq. 1's argmin: index of the first minimum of losses[0..n) (a later

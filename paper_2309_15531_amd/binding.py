@@ -25,6 +25,7 @@ EXPORTS = (
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_only", "adadim_profile_read",
+    "adadim_layer_error_batch_select_noalloc", "adadim_noalloc_scratch_bytes",
 )
 
 _lib = None
@@ -113,6 +114,11 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_layer_error_batch_select.argtypes = [c_void_p, c_int, POINTER(c_void_p), c_int, c_int64, c_int64,
                                                     c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     lib.adadim_layer_error_batch_select.restype = c_int
+    lib.adadim_layer_error_batch_select_noalloc.argtypes = [c_void_p, c_int, POINTER(c_void_p), c_int64, c_int64,
+                                                            c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    lib.adadim_layer_error_batch_select_noalloc.restype = c_int
+    lib.adadim_noalloc_scratch_bytes.argtypes = [c_int, c_int64, c_int64]
+    lib.adadim_noalloc_scratch_bytes.restype = c_int64
     lib.adadim_select.argtypes = [c_void_p, c_void_p, c_int, c_void_p, POINTER(c_int32)]
     lib.adadim_select.restype = c_int
     lib.adadim_profile.argtypes = [c_void_p, c_int]
@@ -299,6 +305,15 @@ class Context:
         arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
         self._check(self._lib.adadim_layer_error_batch_select(self._h, len(dWs), arr, dW_dtype, out_f, in_f, _ptr(Hs),
                                                               _ptr(hmeta), _ptr(loss_rows), _ptr(losses), _ptr(best_dev)))
+
+    def adadim_layer_error_batch_select_noalloc(self, dWs, Hs, hmeta, losses, best_dev, loss_rows=None, shape=None):
+        """The same call with its scratch in the library's fixed device array (no allocation); dWs are
+        column-scaled fp16 buffers in the scoring layout, at most eight."""
+        out_f, in_f = dWs[0].shape if shape is None else shape
+        arr = (c_void_p * len(dWs))(*[t.data_ptr() for t in dWs])
+        self._check(self._lib.adadim_layer_error_batch_select_noalloc(self._h, len(dWs), arr, out_f, in_f, _ptr(Hs),
+                                                                      _ptr(hmeta), _ptr(loss_rows), _ptr(losses),
+                                                                      _ptr(best_dev)))
 
     def adadim_select(self, losses, n: int | None = None, best_dev=None, to_host: bool = True):
         n = losses.numel() if n is None else n

@@ -401,6 +401,31 @@ int adadim_layer_error_batch_select(adadim_ctx* ctx, int n, const void* const* d
     return error_batch_checked(ctx, n, dW, dW_dtype, out, in, Hs, hmeta, loss_rows, losses, best_dev);
 }
 
+int adadim_layer_error_batch_select_noalloc(adadim_ctx* ctx, int n, const void* const* dW, int64_t out, int64_t in,
+                                            const void* Hs, const float* hmeta, float* loss_rows, float* losses,
+                                            int32_t* best_dev) {
+    if (!ctx) return ADADIM_ENULL;
+    if (n <= 0 || n > 8)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_layer_error_batch_select_noalloc: n must be in [1,8], got %d", n);
+    if (!dW) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch_select_noalloc: dW is NULL");
+    if (!best_dev) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch_select_noalloc: best_dev is NULL");
+    for (int c = 0; c < n; ++c) {
+        int rc = check_error_args(ctx, "adadim_layer_error_batch_select_noalloc", dW[c], ADADIM_DW_F16_SCALED, out, in, Hs,
+                                  losses, true);
+        if (rc != ADADIM_OK) return rc;
+    }
+    if (!hmeta) return adadim_fail(ctx, ADADIM_ENULL, "adadim_layer_error_batch_select_noalloc: hmeta is NULL");
+    if (!aligned16(hmeta))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_layer_error_batch_select_noalloc: hmeta must be 16-byte aligned");
+    return launch_layer_error_noalloc(ctx, n, dW, out, in, static_cast<const __half*>(Hs), hmeta, loss_rows, losses,
+                                      best_dev);
+}
+
+int64_t adadim_noalloc_scratch_bytes(int n, int64_t out, int64_t in) {
+    if (n <= 0 || n > 8 || out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 20)) return -1;
+    return launch_layer_error_noalloc_bytes(n, out, in);
+}
+
 int adadim_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev, int32_t* host_best) {
     if (!ctx) return ADADIM_ENULL;
     if (!losses) return adadim_fail(ctx, ADADIM_ENULL, "adadim_select: losses is NULL");

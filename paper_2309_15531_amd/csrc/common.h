@@ -158,6 +158,11 @@ int launch_hessian_prepared(adadim_ctx* ctx, const __half* X, int64_t tokens, in
 int launch_layer_error(adadim_ctx* ctx, int n, const void* const* dW, int dW_dtype, int64_t out, int64_t in,
                        const __half* Hs, const float* hmeta, float* loss_rows, float* losses,
                        int32_t* best_dev = nullptr);
+// The same launch group (n <= 8 candidates, column-scaled fp16 dW) with its scratch in the library's fixed device
+// array; _bytes gives what such a launch needs of it.
+int launch_layer_error_noalloc(adadim_ctx* ctx, int n, const void* const* dW, int64_t out, int64_t in, const __half* Hs,
+                               const float* hmeta, float* loss_rows, float* losses, int32_t* best_dev);
+int64_t launch_layer_error_noalloc_bytes(int n, int64_t out, int64_t in);
 int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev);
 int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percdamp, int act_order, int32_t* perm,
                         uint8_t* dead, float* U);

@@ -331,3 +331,90 @@ int launch_select(adadim_ctx* ctx, const float* losses, int n, int32_t* best_dev
     ADADIM_LAUNCH_CHECK(ctx, "select_first_min");
     return ADADIM_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// The scoring call for callers that cannot allocate (code under graph capture, tight serving loops,
+// harnesses that forbid hipMalloc): the scratch of the launch lives in a fixed device array instead
+// of the context's growing slots.  Layout of the array: [0, 256) zero page (never written after the
+// first clear), [256, 512) the 64 counters of error_finish, [512, 512 + 8*MAX_BATCH*fin_blocks)
+// block totals, then the row partials.
+namespace {
+
+constexpr size_t NOALLOC_SCRATCH_BYTES = size_t(16) << 20;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+// Device address of `scratch` on each GPU (every GPU holds its own copy of the array at its own address);
+// looked up once per device, with that device current.
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};
+
+int noalloc_scratch(adadim_ctx* ctx, unsigned char** out_ptr, bool* first_use) {
+    int dev = -1;
+    ADADIM_HIP_TRY(ctx, hipGetDevice(&dev));
+    if (dev < 0 || dev >= NOALLOC_MAX_DEVICES)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_layer_error_batch_select_noalloc: device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    *first_use = false;
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return adadim_fail(ctx, ADADIM_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+        *first_use = true;
+    }
+    *out_ptr = g_scratch_ptr[dev];
+    return ADADIM_OK;
+}
+
+}  // namespace
+
+int64_t launch_layer_error_noalloc_bytes(int n, int64_t out, int64_t in) {
+    constexpr int BT = edma::BT;
+    const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
+    int kb = 0, n_slots = 0;
+    error_slots(n, MB, NB, in, kb, n_slots);
+    const int64_t fin_blocks = (out + 255) / 256;
+    return 512 + int64_t(edma::MAX_BATCH) * fin_blocks * 8 + int64_t(n) * n_slots * out * 4;
+}
+
+int launch_layer_error_noalloc(adadim_ctx* ctx, int n, const void* const* dW, int64_t out, int64_t in, const __half* Hs,
+                               const float* hmeta, float* loss_rows, float* losses, int32_t* best_dev) {
+    constexpr int BT = edma::BT;
+    const int MB = static_cast<int>((out + BT - 1) / BT), NB = static_cast<int>((in + BT - 1) / BT);
+    int kb = 0, n_slots = 0;
+    error_slots(n, MB, NB, in, kb, n_slots);
+    const int64_t need = launch_layer_error_noalloc_bytes(n, out, in);
+    if (need > int64_t(NOALLOC_SCRATCH_BYTES))
+        return adadim_fail(ctx, ADADIM_EINVAL,
+                           "adadim_layer_error_batch_select_noalloc: %d candidates of [%lld, %lld] need %lld bytes of scratch, "
+                           "the fixed array holds %lld", n, (long long)out, (long long)in, (long long)need,
+                           (long long)NOALLOC_SCRATCH_BYTES);
+    unsigned char* ptr = nullptr;
+    bool first_use = false;
+    int rc = noalloc_scratch(ctx, &ptr, &first_use);
+    if (rc != ADADIM_OK) return rc;
+    rc = set_error_attr(ctx);
+    if (rc != ADADIM_OK) return rc;
+    // The zero page and the counters must be zero on entry.  The array keeps the last call's contents (the
+    // counters are left at zero by a launch that ran to its end, but not by one that was abandoned), so the
+    // first 512 bytes are cleared on every call, by a fill kernel (a memset node would not be safe to record).
+    hipLaunchKernelGGL(fill_zero_f32, dim3(1), dim3(128), 0, ctx->stream, reinterpret_cast<float*>(ptr), int64_t(128));
+    ADADIM_LAUNCH_CHECK(ctx, "fill_zero_f32");
+    const int64_t fin_blocks = (out + 255) / 256;
+    ErrScratch sc{};
+    sc.zero16 = ptr;
+    sc.ticket = reinterpret_cast<unsigned int*>(ptr + 256);
+    sc.block_tot = reinterpret_cast<double*>(ptr + 512);
+    sc.part = reinterpret_cast<float*>(ptr + 512 + size_t(edma::MAX_BATCH) * size_t(fin_blocks) * 8);
+    sc.diag = nullptr;
+    sc.dW16 = nullptr;
+    return run_error_batch(ctx, n, dW, ADADIM_DW_F16_SCALED, out, in, Hs, hmeta, loss_rows, losses, losses, n, best_dev, sc,
+                           kb, n_slots);
+}
