@@ -7,7 +7,7 @@ dimensions, selection, and the winner's packed codes / scales / zeros.
 Prints ONE JSON line: metric, value, unit, ms_per_step, config, and the roofline / cpu_baseline objects.
 
     python bench.py [--steps K] [--warmup W]
-                    [--workload down_proj|gate_proj|q_proj|qkv|clip_grid|toy|block7b|stream13b|block70b|gemv_ic|gptq]
+                    [--workload down_proj|gate_proj|q_proj|qkv|clip_grid|toy|block7b|stream13b|block70b|gemv_ic|gptq|mfma_ceiling]
                     [--bits B] [--group G] [--meta16]
 
 The default workload is the layer the targets are stated on: W[4096, 11008] (the FFN down projection of the
@@ -84,7 +84,7 @@ def _blas_threads() -> int:
         return os.cpu_count() or 1
 
 
-def cpu_baseline(layer_list, X_of, tokens, bits_list, group, n_clips=1, budget_flops=3.0e11, quant_budget=48_000_000):
+def cpu_baseline(layer_list, X_of, tokens, bits_list, group, n_clips=1, budget_flops=5.0e11, quant_budget=48_000_000):
     """Times the CPU oracle, as it stands, on a bounded sample of the workload and scales to the whole of it, twice:
     with the BLAS threads the box gives (`cores`) and single-threaded.
 
@@ -453,6 +453,54 @@ def block_bench(args):
     print(json.dumps(result))
 
 
+def ceiling_bench(args):
+    """What the matrix cores sustain on this chip, beside the published peak: (a) a register-resident loop of the MFMA
+    instruction the two matrix kernels use, on all-zero and on random fp16 operands (adadim_probe_mfma); (b) the Gram
+    kernel itself on [65536, in] inputs of zeros, of positive parts of normal deviates (half the entries zero, as the
+    FFN-down input) and of normal deviates.  Same instruction streams, different operand bits: the rates differ
+    because the chip lowers its clock to hold its power limit.  One JSON line."""
+    import torch
+    from paper_2309_15531_amd import binding as B
+    B.load_library()
+    ctx = B.Context()
+    probe = {}
+    for name, rnd in (("zeros", False), ("random", True), ("zeros_again", False), ("random_again", True)):
+        runs = [ctx.adadim_probe_mfma(rnd, 4000) for _ in range(3)]
+        probe[name] = {"tflops": [round(r[0], 1) for r in runs], "clock_mhz": [round(r[1]) for r in runs]}
+    T = 65536
+    gram = {}
+    for n in (11008, 4096):
+        H = torch.empty(n, n, dtype=torch.float32, device="cuda")
+        g = torch.Generator(device="cuda").manual_seed(n)
+        Xn = torch.randn(T, n, device="cuda", generator=g).half()
+        for kind in ("normal", "relu", "zeros", "normal_again"):
+            X = Xn if kind.startswith("normal") else (torch.relu(Xn) if kind == "relu" else torch.zeros_like(Xn))
+            for _ in range(30 if n == 4096 else 8):
+                ctx.adadim_hessian(X, H)
+            torch.cuda.synchronize()
+            ctx.adadim_profile_only("gram_tiles")
+            ctx.adadim_profile(True)
+            for _ in range(10):
+                ctx.adadim_hessian(X, H)
+            torch.cuda.synchronize()
+            ctx.adadim_profile(False)
+            ctx.adadim_profile_only(None)
+            tot_ms, launches = ctx.adadim_profile_read()["gram_tiles"]
+            us = tot_ms / launches * 1e3
+            gram[f"in{n}_{kind}"] = {"gram_tiles_us": round(us, 1), "tflops_issued": round(gram_issued_flops(n, T) / us / 1e6, 1),
+                                     "frac_of_published_peak": round(gram_issued_flops(n, T) / (us * 1e-6) / MFMA_F16_PEAK, 4)}
+            del X
+        del Xn, H
+    worst = min(probe["random"]["tflops"] + probe["random_again"]["tflops"])
+    print(json.dumps({
+        "metric": "sustained fp16 MFMA rate (register-resident loop, random operands)", "value": worst, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": 3, "warmup": 0, "ms_per_step": None, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "matrix-core ceiling probe: v_mfma_f32_32x32x16_f16 loop on zero / random operands; Gram kernel on "
+                               "[65536, 11008] and [65536, 4096] inputs of zeros / relu(normal) / normal"},
+        "published_peak_tflops": MFMA_F16_PEAK / 1e12, "mfma_loop": probe, "gram_kernel_by_input": gram}))
+
+
 # (warm-up, timed) steps when the flags are absent.  The chip needs some tens of milliseconds of load before its
 # clocks settle (the first 20 q_proj steps of a process run 5 % slower than the 200 after them), so the defaults
 # time a few tenths of a second of sustained work; clip_grid has 50 launches per step and stays within the
@@ -470,7 +518,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: by workload, see DEFAULT_STEPS)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them")
     ap.add_argument("--workload", default="down_proj",
-                    choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + ["gemv_ic", "gptq"])
+                    choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + ["gemv_ic", "gptq", "mfma_ceiling"])
     ap.add_argument("--log", default=None, help="stream13b: the JSON-lines results file (default: a fresh temporary file)")
     ap.add_argument("--resume", action="store_true", help="stream13b: keep the records --log already holds and skip their layers")
     ap.add_argument("--bits", type=int, default=None)
@@ -510,6 +558,9 @@ def main():
         return
     if args.workload in BLOCK_WORKLOADS:
         block_bench(args)
+        return
+    if args.workload == "mfma_ceiling":
+        ceiling_bench(args)
         return
     B.load_library()  # fails loudly if the HIP library has not been built
 

@@ -364,6 +364,15 @@ void adadim_graph_destroy(void* graph);
  * it changes no records and may be called while timing is on or off.
  */
 int adadim_profile(adadim_ctx* ctx, int enable);
+/*
+ * Measurement aid: the rate the chip's matrix cores sustain on nothing but v_mfma_f32_32x32x16_f16 with
+ * register-resident operands (1024 workgroups of four waves, 64 * iters instructions per wave), for all-zero
+ * operands (random_operands = 0) or random fp16 operands in [-2, 2) (1).  The chip holds its power limit by
+ * lowering the clock and the power depends on the operand bits, so the two rates differ; the second is the
+ * ceiling a real fp16 contraction works under.  Waits for the stream.  tflops: the rate in TFLOP/s;
+ * clock_mhz: the shader clock the loop ran at (clock64 against the 100 MHz wall_clock64).  Host pointers.
+ */
+int adadim_probe_mfma(adadim_ctx* ctx, int random_operands, int iters, double* tflops, double* clock_mhz);
 int adadim_profile_only(adadim_ctx* ctx, const char* name);
 int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches);
 

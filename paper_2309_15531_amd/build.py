@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libadadim.so")
-SOURCES = ["api.hip", "quantize.hip", "hessian.hip", "layer_error.hip", "gemv_ic.hip", "gptq.hip"]
+SOURCES = ["api.hip", "quantize.hip", "hessian.hip", "layer_error.hip", "gemv_ic.hip", "gptq.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-ffp-contract=off",                      # one rounding per operation in the quantizer

@@ -33,6 +33,7 @@ enum {
     WS_GPTQ_E,          // fp32 propagated errors in visiting order
     WS_GPTQ_Q,          // u8 codes in visiting order
     WS_GPTQ_V,          // int32 position of each original channel in the visiting order
+    WS_PROBE,           // output of the matrix-core rate probe
     WS_COUNT
 };
 
@@ -59,9 +60,10 @@ struct adadim_ctx {
     void* ws[WS_COUNT];
     size_t ws_bytes[WS_COUNT];
     size_t zero_ready_bytes;         // size of WS_ZERO when it was last cleared
-    int64_t gram_key_tokens;         // token count and tile count the cached Gram split length was chosen for
-    int gram_key_tiles;
-    int64_t gram_t_per_split;
+    // Gram split lengths already chosen, keyed by (token count, tile count): choosing one simulates the launch's
+    // schedule (tens of milliseconds of host time), and a model driver alternates between a few input widths
+    struct GramSplit { int64_t tokens; int tiles; int64_t t_per_split; } gram_split[8];
+    int gram_split_n, gram_split_next;
     bool capturing;                  // between adadim_capture_begin and adadim_capture_end
     hipStream_t side;                // second stream for work that may overlap the main one (created on first use)
     hipEvent_t side_ev[2];           // main -> side and side -> main hand-overs

@@ -308,8 +308,11 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         // that schedule for "n full splits plus a shorter remainder", the remainder's items filling
         // the gaps of the last round.  Unit: one 32-token stage; an item costs about 12 stages of
         // prologue and epilogue, a partial tile about 0.1 stage of write and reduction traffic.
-        if (ctx->gram_key_tokens == tokens && ctx->gram_key_tiles == n_tiles) {
-            t_per_split = ctx->gram_t_per_split;
+        int hit = -1;
+        for (int k = 0; k < ctx->gram_split_n; ++k)
+            if (ctx->gram_split[k].tokens == tokens && ctx->gram_split[k].tiles == n_tiles) hit = k;
+        if (hit >= 0) {
+            t_per_split = ctx->gram_split[hit].t_per_split;
         } else {
             double best = 0.0;
             int64_t best_per = stages;
@@ -339,9 +342,10 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
                 }
             }
             t_per_split = best_per * STAGE;
-            ctx->gram_key_tokens = tokens;
-            ctx->gram_key_tiles = n_tiles;
-            ctx->gram_t_per_split = t_per_split;
+            const int slot = ctx->gram_split_next;                  // the oldest entry makes room
+            ctx->gram_split[slot] = {tokens, n_tiles, t_per_split};
+            ctx->gram_split_next = (slot + 1) % 8;
+            if (ctx->gram_split_n < 8) ++ctx->gram_split_n;
         }
     }
     n_split = static_cast<int>((tokens + t_per_split - 1) / t_per_split);

@@ -785,10 +785,13 @@ __global__ __launch_bounds__(RW <= 4 ? 256 : 64 * RW) void quant_ic_stream(
                                      dW_dtype, colscale, packed, n_words);
 }
 
-// Both grouping dimensions of one weight in one launch (groups of 8*LPG in either direction, at most
-// 128): the first n_oc workgroups are per-OC tiles, the rest per-IC tiles.  Short kernels spend a
-// good part of their time filling and draining the chip; one launch does that once, and the
-// per-IC tiles start while the last per-OC ones finish.
+// Both grouping dimensions of one weight in one launch (groups of g = 8*LPG in either direction, at most
+// 128).  Short kernels spend a good part of their time filling and draining the chip; one launch does
+// that once.  The two passes over W are arranged so that HBM is read once: W is cut into regions of g rows
+// x 512 columns, a region's g/16 per-OC tiles (16 rows x 512 columns) and g/16 per-IC tiles (g rows x
+// 512*16/g columns) are consecutive workgroups of ONE XCD (workgroups go to the eight XCDs round-robin by
+// launch index, so XCD x takes the regions x, x + 8, ...), and they run at the same time: whichever tile
+// asks for a line first brings it into that XCD's L2, the other finds it there.
 struct QuantOut {
     uint8_t* codes;
     float* scales;
@@ -799,17 +802,21 @@ struct QuantOut {
 template <int LPG, int PB>
 __global__ __launch_bounds__(256) void quant_both(const __half* __restrict__ W, int64_t out, int64_t in, float clip,
                                                   float qmax, float rqmax, int mfmt, QuantOut oc, QuantOut ic,
-                                                  const float* __restrict__ colscale, int64_t n_words_ic, unsigned gx_oc,
-                                                  unsigned n_oc, unsigned gx_ic) {
+                                                  const float* __restrict__ colscale, int64_t n_words_ic, unsigned regions_x,
+                                                  unsigned n_regions) {
     constexpr int U = LPG < 4 ? LPG : 4, RW = LPG / U;
-    static_assert(RW <= 4, "256 threads per workgroup in both halves");
-    if (blockIdx.x < n_oc) {
-        quant_oc_body<LPG, PB, true>(blockIdx.x % gx_oc, blockIdx.x / gx_oc, reinterpret_cast<const uint4*>(W), out,
+    static_assert(RW <= 4 && LPG >= 4, "256 threads per workgroup in both halves; groups of 32 and up");
+    constexpr unsigned PER = LPG / 2;                         // per-OC tiles per region = per-IC tiles per region = g/16
+    const unsigned xcd = blockIdx.x % 8, seq = blockIdx.x / 8;
+    const unsigned region = (seq / (2 * PER)) * 8 + xcd, within = seq % (2 * PER);
+    if (region >= n_regions) return;                          // whole workgroup
+    const unsigned rx = region % regions_x, ry = region / regions_x;
+    if (within < PER) {
+        quant_oc_body<LPG, PB, true>(rx, ry * PER + within, reinterpret_cast<const uint4*>(W), out,
                                      static_cast<int>(in / 8), clip, qmax, rqmax, mfmt, oc.codes, oc.scales, oc.zeros, oc.dW,
                                      ADADIM_DW_F16_SCALED, colscale, oc.packed);
     } else {
-        const unsigned b = blockIdx.x - n_oc;
-        quant_ic_body<U, RW, true, PB>(b % gx_ic, b / gx_ic, W, out, in, clip, qmax, rqmax, mfmt, ic.codes, ic.scales,
+        quant_ic_body<U, RW, true, PB>(rx * PER + (within - PER), ry, W, out, in, clip, qmax, rqmax, mfmt, ic.codes, ic.scales,
                                        ic.zeros, ic.dW, ADADIM_DW_F16_SCALED, colscale, ic.packed, n_words_ic);
     }
 }
@@ -1161,17 +1168,17 @@ int launch_quantize_both(adadim_ctx* ctx, const __half* W, int64_t out, int64_t 
                                ADADIM_DW_F16_SCALED, colscale, packed_ic, mfmt);
     }
     const float qmax = static_cast<float>((1 << bits) - 1);
-    const int rw = lpg / 4, csw = 4 / rw;
-    const unsigned gx_oc = static_cast<unsigned>((in / 8 + 63) / 64), gy_oc = static_cast<unsigned>((out + 15) / 16);
-    const unsigned gx_ic = static_cast<unsigned>((in + 64 * csw - 1) / (64 * csw)), gy_ic = static_cast<unsigned>(out / g_ic);
-    const unsigned n_oc = gx_oc * gy_oc, n_ic = gx_ic * gy_ic;
+    // regions of g rows x 512 columns, 2 * (g / 16) workgroups each, dealt to the XCDs round-robin
+    const unsigned regions_x = static_cast<unsigned>((in + 511) / 512), regions_y = static_cast<unsigned>(out / g_oc);
+    const unsigned n_regions = regions_x * regions_y, per_region = 2u * static_cast<unsigned>(lpg / 2);
+    const unsigned grid = 8u * ((n_regions + 7u) / 8u) * per_region;
     const QuantOut oc = {codes_oc, scales_oc, zeros_oc, dW_oc, packed_oc}, ic = {codes_ic, scales_ic, zeros_ic, dW_ic, packed_ic};
     const int64_t n_words_ic = (out * bits + 31) / 32;
     {
         ProfScope prof(ctx, "quant_both");
 #define QB_GO(L, PB)                                                                                                  \
-    hipLaunchKernelGGL((quant_both<L, PB>), dim3(n_oc + n_ic), dim3(256), 0, ctx->stream, W, out, in, clip, qmax,     \
-                       1.0f / qmax, mfmt, oc, ic, colscale, n_words_ic, gx_oc, n_oc, gx_ic)
+    hipLaunchKernelGGL((quant_both<L, PB>), dim3(grid), dim3(256), 0, ctx->stream, W, out, in, clip, qmax,            \
+                       1.0f / qmax, mfmt, oc, ic, colscale, n_words_ic, regions_x, n_regions)
 #define QB_PB(L)                                                                                                      \
     do {                                                                                                              \
         if (!want_pack) QB_GO(L, 0);                                                                                  \

@@ -252,3 +252,27 @@ def test_binding_refuses_tensors_the_library_would_misread():
         _need(Dev(w.t()), "W", "float16")                         # transposed view
     with pytest.raises(ValueError):
         _need(Dev(w[:, :8]), "W", "float16")                      # pitched where the ABI takes none
+
+
+def test_host_checks_under_sanitizers(tmp_path):
+    """The host builds of the device headers (fast division, code-field plan) compiled with the address and
+    undefined-behaviour sanitizers: the constexpr plans and the bit manipulation the kernels share with these
+    checks must be free of out-of-bounds indexing, signed overflow and shifts past the width."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    san = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan", "-g", "-O1", "-std=c++17"]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)                   # the sanitizer runtime has to be first in the process
+    for name, extra, argv, want in (("code_fields_check", [], [], "2 bits: 0, 3 bits: 0, 4 bits: 0 mismatches"),
+                                    ("fastdiv_check", ["-mfma", "-ffp-contract=off", "-pthread"], ["10", "4"], " 0 mismatches")):
+        exe = tmp_path / (name + "_san")
+        build = subprocess.run(["g++", *san, *extra, os.path.join(ROOT, "tests", "host", name + ".cpp"), "-o", str(exe)],
+                               capture_output=True, text=True)
+        if build.returncode != 0 and "asan" in build.stderr.lower() and "cannot find" in build.stderr.lower():
+            pytest.skip("the sanitizer runtime is not installed")
+        assert build.returncode == 0, build.stderr
+        res = subprocess.run([str(exe), *argv], capture_output=True, text=True, env=env)
+        assert res.returncode == 0, res.stdout + res.stderr
+        assert want in res.stdout and "runtime error" not in res.stderr
