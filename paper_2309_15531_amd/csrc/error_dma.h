@@ -32,6 +32,22 @@
 // barrier per stage, DMA and LDS reads interleaved with the MFMAs in a pinned
 // order, the ragged remainder of the contraction range taken by the first
 // stage through per-lane predicates.
+//
+// Epilogue inside the main loop.  The row sums need E[o,n] * dW'[o,n] for the n
+// of the column block.  When the workgroup's contraction range ends with the
+// block's own 256 k (the diagonal block of Hs: always, unless the contraction is
+// cut into chunks), those dW' values pass through the ring as operand 1 of the
+// last eight stages: stage i of the eight brings dW'[o, 32i .. 32i+31].  Hs is
+// strictly lower triangular, so the accumulators of columns 32i .. 32i+31 are
+// final once that stage's products are in (later stages add exact zeros).  The
+// waves that own those columns therefore copy the stage's dW' entries from the
+// ring into registers while the stage is computed and fold them into the row
+// sums during the next stage, between its MFMAs.  No separate fetch of the
+// 128 KB dW' tile, no pass over the accumulators after the loop: on 4096-wide
+// layers, where a workgroup computes for 6 to 100 us, that fetch and pass were
+// 8 to 10 us of every workgroup.  Workgroups whose range does not hold the
+// diagonal block, row-major operands and ragged widths take the separate
+// epilogue further down.
 #pragma once
 
 #include "common.h"
@@ -75,6 +91,13 @@ struct Frags {
     half8 v[TM + TN];
 };
 
+// fma(half HI of a packed fp16 pair, b, c): the conversion rides on the instruction (v_fma_mix_f32)
+typedef _Float16 f16x2v __attribute__((ext_vector_type(2)));
+template <int HI>
+__device__ __forceinline__ float fma_h(uint32_t pair, float b, float c) {
+    return __builtin_fmaf(static_cast<float>(__builtin_bit_cast(f16x2v, pair)[HI]), b, c);
+}
+
 // Candidates scored by one launch: their (column-scaled fp16) dW matrices share H.
 constexpr int MAX_BATCH = 8;
 struct Batch {
@@ -92,6 +115,8 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
                                                        float* __restrict__ part) {
     extern __shared__ __align__(16) char smem[];
     __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
+    __shared__ __align__(16) float s_hd[2][BT];   // in-loop epilogue: column scales d and diag(H) of the block's columns ...
+    __shared__ __align__(16) float s_hq[BT];      // ... and H_nn / d_n^2 / 2 (0 when this workgroup does not add the diagonal term)
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
     // Workgroups go to the eight XCDs round-robin by launch index, and a compute unit holds one
@@ -109,9 +134,11 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     const int round = seq / 32, within = seq % 32;
     const int unit = round * 8 + ((round & 1) ? 7 - xcd : xcd);
     if (unit >= n_sg * n_rs) return;
-    const int slot = (unit / n_rs) * 4 + (within & 3), pair = (unit % n_rs) * 8 + (within >> 2);
+    // (workgroup-uniform values: kept in scalar registers, where there is room)
+    const int slot = __builtin_amdgcn_readfirstlane((unit / n_rs) * 4 + (within & 3));
+    const int pair = __builtin_amdgcn_readfirstlane((unit % n_rs) * 8 + (within >> 2));
     if (slot >= n_slots || pair >= n_pairs) return;
-    const int cand = pair / MB, mb = pair % MB;
+    const int cand = __builtin_amdgcn_readfirstlane(pair / MB), mb = __builtin_amdgcn_readfirstlane(pair % MB);
     const __half* __restrict__ A = batch.A[cand];
     const int kb = kc_len / BT;
     int chunk = 0, rem = slot;
@@ -143,6 +170,15 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     // matrix re-read the block's first row: they only feed entries of E that the epilogue skips.
     const int lr = lane >> 2, p = lane & 3;
     const bool blocked = score_blocked(in);
+    // in-loop epilogue (see the head of the file): the contraction range ends with the column block's own 256 k
+    const bool fused = !(DBG & 1) && blocked && (in % BT) == 0 && k_begin <= col0 && col0 < k_begin + kc_len;
+    const bool add_diag = hmeta_diag != nullptr && chunk == 0;
+    if (fused && add_diag && wave == 0) {
+        // column scales and diag(H) of the block's 256 columns, 1 KB each, straight into LDS; issued before the
+        // first stage so that the wait for that stage covers them
+        g2l16(hmeta_diag + col0 + 4 * lane, static_cast<uint32_t>(reinterpret_cast<uintptr_t>(&s_hd[0][0])));
+        g2l16(hmeta_diag + in + col0 + 4 * lane, static_cast<uint32_t>(reinterpret_cast<uintptr_t>(&s_hd[1][0])));
+    }
     uint32_t goff[LOADS], gdst[LOADS];
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
@@ -241,18 +277,69 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     asm volatile("s_waitcnt vmcnt(16)" ::: "memory");   // stage 0 landed
     __builtin_amdgcn_s_barrier();
     read_frags(F0, 0, 0);
+    if (fused) {
+        // H_nn / d_n^2 / 2 for the block's columns (d = 2^e: the bit pattern of 1/d is 0x7F000000 minus that of d);
+        // read again only in the last eight stages, many barriers from here
+        float hq = 0.0f;
+        if (add_diag) {
+            const float r = __uint_as_float(0x7F000000u - __float_as_uint(s_hd[0][tid]));
+            hq = 0.5f * s_hd[1][tid] * r * r;
+        }
+        s_hq[tid] = hq;
+    }
     constexpr int PRE = NMMA / 4;
-    auto stage_body = [&](auto buf_tag) {
+    // in-loop epilogue state: the dW' entries of one 32-column sub-block (copied during the second sweep of its
+    // stage, used during the first sweep of the next) and the row sums
+    uint2 cap[TN * 4];
+    float sum[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) sum[j] = 0.0f;
+    // this lane's 8 bytes in row ol = wn*128 + 32 j + (lane & 31) of an operand-1 stage tile: j adds 32 rows, the
+    // chunk swizzle (ol >> 2) & 3 does not depend on j
+    const uint32_t cap_base = lds0 + OP_BYTES + (wn * WN + (lane & 31)) * ROWB + (lane >> 5) * 8;
+    const int cap_swz = ((lane & 31) >> 2) & 3;
+    // copy: item m = (j = m / 4, g = m % 4) of the sub-block whose stage sits in ring slot B
+    auto capture = [&](auto buf_tag, int m) {
         constexpr int B = decltype(buf_tag)::value;
+        const int j = m >> 2, g = m & 3;
+        cap[m] = lds_read_u2(cap_base + B * STAGE_BYTES + j * 32 * ROWB + ((g ^ cap_swz) << 4));
+    };
+    // fold: sum[j] += (E + hq * dW') * dW' for the four n of item m of sub-block IP (accumulator block i = IP % 4)
+    auto fold = [&](auto ip_tag, int m) {
+        constexpr int IP = decltype(ip_tag)::value, i = IP & 3;
+        const int j = m >> 2, g = m & 3;
+        const uint2 raw = cap[m];
+        const float4 h4 = *reinterpret_cast<const float4*>(&s_hq[(IP >> 2) * WM + 32 * i + 8 * g + 4 * (lane >> 5)]);
+        sum[j] = fma_h<0>(raw.x, fma_h<0>(raw.x, h4.x, acc[i][j][4 * g + 0]), sum[j]);
+        sum[j] = fma_h<1>(raw.x, fma_h<1>(raw.x, h4.y, acc[i][j][4 * g + 1]), sum[j]);
+        sum[j] = fma_h<0>(raw.y, fma_h<0>(raw.y, h4.z, acc[i][j][4 * g + 2]), sum[j]);
+        sum[j] = fma_h<1>(raw.y, fma_h<1>(raw.y, h4.w, acc[i][j][4 * g + 3]), sum[j]);
+    };
+    // IP < 0: a plain stage.  IP = 0..7: stage IP of the diagonal block with the in-loop epilogue: the waves that
+    // own sub-block IP - 1 (wm == (IP - 1) / 4) fold the entries copied a stage ago into the row sums, one item
+    // per MFMA of the first sweep; the waves that own sub-block IP copy its dW' entries from this stage's
+    // operand-1 tile, one item per MFMA of the second sweep (the tile stays in its ring slot until the next
+    // stage's barrier).
+    auto stage_body = [&](auto buf_tag, auto ip_tag) {
+        constexpr int B = decltype(buf_tag)::value, IP = decltype(ip_tag)::value;
+        static_assert(NMMA == TN * 4, "one epilogue item per MFMA of a sweep");
 #pragma unroll
         for (int m = 0; m < NMMA; ++m) {
 #pragma unroll
             for (int r = m * NRD / NMMA; r < (m + 1) * NRD / NMMA; ++r) read_one(F1, B, 1, r);
+            if constexpr (IP >= 1) {
+                if (wm == (IP - 1) / 4) fold(std::integral_constant<int, IP - 1>{}, m);
+            }
             mma(F0, m);
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int m = 0; m < PRE; ++m) mma(F1, m);
+        for (int m = 0; m < PRE; ++m) {
+            if constexpr (IP >= 0) {
+                if (wm == IP / 4) capture(buf_tag, m);
+            }
+            mma(F1, m);
+        }
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // next stage landed
         __builtin_amdgcn_s_barrier();
@@ -266,18 +353,39 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
             for (int r = q * NRD / REST; r < (q + 1) * NRD / REST; ++r) read_one(F0, (B + 1) & 3, 0, r);
 #pragma unroll
             for (int j = q * LOADS / REST; j < (q + 1) * LOADS / REST; ++j) issue_one(j, (B + 3) & 3);
+            if constexpr (IP >= 0) {
+                if (wm == IP / 4) capture(buf_tag, m);
+            }
             mma(F1, m);
             __builtin_amdgcn_sched_barrier(0);
         }
         stage_issued();
     };
     if constexpr (DBG & 8) dbg_t[1] = wall_clock64();
-    // four stages per trip (constant ring slots); surplus stages multiply zeros
-    for (int s = 0; s < n_st; s += 4) {
-        stage_body(std::integral_constant<int, 0>{});
-        stage_body(std::integral_constant<int, 1>{});
-        stage_body(std::integral_constant<int, 2>{});
-        stage_body(std::integral_constant<int, 3>{});
+    // four stages per trip (constant ring slots); surplus stages multiply zeros.  With the in-loop epilogue the
+    // range is a whole number of 256-k blocks (n_st a multiple of 8, no surplus stages) and its last eight stages
+    // are the diagonal block.
+    constexpr std::integral_constant<int, -1> plain{};
+    const int n_main = fused ? n_st - 8 : n_st;
+    for (int s = 0; s < n_main; s += 4) {
+        stage_body(std::integral_constant<int, 0>{}, plain);
+        stage_body(std::integral_constant<int, 1>{}, plain);
+        stage_body(std::integral_constant<int, 2>{}, plain);
+        stage_body(std::integral_constant<int, 3>{}, plain);
+    }
+    if (fused) {
+        stage_body(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        stage_body(std::integral_constant<int, 1>{}, std::integral_constant<int, 1>{});
+        stage_body(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{});
+        stage_body(std::integral_constant<int, 3>{}, std::integral_constant<int, 3>{});
+        stage_body(std::integral_constant<int, 0>{}, std::integral_constant<int, 4>{});
+        stage_body(std::integral_constant<int, 1>{}, std::integral_constant<int, 5>{});
+        stage_body(std::integral_constant<int, 2>{}, std::integral_constant<int, 6>{});
+        stage_body(std::integral_constant<int, 3>{}, std::integral_constant<int, 7>{});
+        if (wm == 1) {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) fold(std::integral_constant<int, 7>{}, m);
+        }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
     if constexpr (DBG & 8) dbg_t[2] = wall_clock64();
@@ -291,7 +399,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     // With hmeta_diag (column scales d then diag H, as adadim_hessian_prepare writes them) the
     // workgroup of a column block's first chunk also adds half the diagonal term,
     // dW'[o,n]^2 H_nn / d_n^2 / 2: the final reduction doubles the row sums.
-    if (blocked) {
+    if (blocked && !fused) {
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();                        // every wave is done with the ring
         const char* ebase = reinterpret_cast<const char*>(A + score_index(row0, col0, out, in));
@@ -307,10 +415,6 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
     }
-    const bool add_diag = hmeta_diag != nullptr && chunk == 0;
-    float sum[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) sum[j] = 0.0f;
     // Rows past `out` need no test on the LDS path: they hold a valid row's data and their sums
     // are never stored.  Columns past `in` are skipped (their accumulators are not zero).
     auto reduce = [&](auto from_lds) {
@@ -355,8 +459,10 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
             }
         }
     };
-    if (blocked) reduce(std::true_type{});
-    else reduce(std::false_type{});
+    if (!fused) {
+        if (blocked) reduce(std::true_type{});
+        else reduce(std::false_type{});
+    }
     float v[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) v[j] = sum[j] + __shfl_xor(sum[j], 32, 64);
