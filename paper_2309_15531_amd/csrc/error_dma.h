@@ -108,12 +108,14 @@ struct Batch {
 // Column block nb contracts over k < kend(nb) = min(in, (nb+1)*256), cut into
 // chunks of kc_len (a multiple of 256).  Slots enumerate (chunk, nb): chunk
 // ascending, nb descending over the column blocks that reach the chunk.
-template <int DBG = 0>
-__global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half* __restrict__ Hs, int64_t out,
-                                                       int64_t in, int MB, int NB, int kc_len, int n_slots,
-                                                       const void* zero16, const float* __restrict__ hmeta_diag,
-                                                       float* __restrict__ part) {
-    extern __shared__ __align__(16) char smem[];
+// One work item: position `seq` in the list of XCD `xcd` (see below).  Returns 0 after computing the item, 1 for a
+// padding position inside the list, 2 when the list of that XCD is exhausted (so is every later position).
+// rec: index of the item's timeline record (DBG 8).
+template <int DBG>
+__device__ __forceinline__ int error_item(const Batch& batch, const __half* __restrict__ Hs, int64_t out, int64_t in,
+                                          int MB, int NB, int kc_len, int n_slots, const void* zero16,
+                                          const float* __restrict__ hmeta_diag, float* __restrict__ part, int xcd, int seq,
+                                          int64_t rec, char* smem) {
     __shared__ float s_rows[2][BT];   // [wm][output row within the tile]
     __shared__ __align__(16) float s_hd[2][BT];   // in-loop epilogue: column scales d and diag(H) of the block's columns ...
     __shared__ __align__(16) float s_hq[BT];      // ... and H_nn / d_n^2 / 2 (0 when this workgroup does not add the diagonal term)
@@ -128,16 +130,15 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     // slots of a unit cover the same contraction range; units are dealt to the XCDs in serpentine
     // order (0..7, 7..0, ...), which evens out the totals, slot group by slot group, so that
     // neighbouring XCDs work on the same Hs tiles at the same time.
-    const int xcd = static_cast<int>(blockIdx.x % 8), seq = static_cast<int>(blockIdx.x / 8);
     const int n_pairs = batch.n * MB;                        // (candidate, row block) pairs
     const int n_rs = (n_pairs + 7) / 8, n_sg = (n_slots + 3) / 4;
     const int round = seq / 32, within = seq % 32;
     const int unit = round * 8 + ((round & 1) ? 7 - xcd : xcd);
-    if (unit >= n_sg * n_rs) return;
+    if (unit >= n_sg * n_rs) return 2;
     // (workgroup-uniform values: kept in scalar registers, where there is room)
     const int slot = __builtin_amdgcn_readfirstlane((unit / n_rs) * 4 + (within & 3));
     const int pair = __builtin_amdgcn_readfirstlane((unit % n_rs) * 8 + (within >> 2));
-    if (slot >= n_slots || pair >= n_pairs) return;
+    if (slot >= n_slots || pair >= n_pairs) return 1;
     const int cand = __builtin_amdgcn_readfirstlane(pair / MB), mb = __builtin_amdgcn_readfirstlane(pair % MB);
     const __half* __restrict__ A = batch.A[cand];
     const int kb = kc_len / BT;
@@ -304,31 +305,49 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         const int j = m >> 2, g = m & 3;
         cap[m] = lds_read_u2(cap_base + B * STAGE_BYTES + j * 32 * ROWB + ((g ^ cap_swz) << 4));
     };
-    // fold: sum[j] += (E + hq * dW') * dW' for the four n of item m of sub-block IP (accumulator block i = IP % 4)
-    auto fold = [&](auto ip_tag, int m) {
+    // fold, at MFMA slot m of a first sweep: sum[j] += (E + hq * dW') * dW' for the four n of one item (j, g) of
+    // sub-block IP (accumulator block row i = IP % 4).  That sweep's MFMAs for row i sit at slots 4 i .. 4 i + 3 and
+    // add exact zeros to the finished accumulators; the items of column j are taken at slots 4 (i + 1 + j) + g
+    // (mod 16), so that no item reads an accumulator block whose MFMA has just been issued.
+    auto fold = [&](auto ip_tag, int m, const float4 (&hq4)[4]) {
         constexpr int IP = decltype(ip_tag)::value, i = IP & 3;
-        const int j = m >> 2, g = m & 3;
-        const uint2 raw = cap[m];
-        const float4 h4 = *reinterpret_cast<const float4*>(&s_hq[(IP >> 2) * WM + 32 * i + 8 * g + 4 * (lane >> 5)]);
-        sum[j] = fma_h<0>(raw.x, fma_h<0>(raw.x, h4.x, acc[i][j][4 * g + 0]), sum[j]);
-        sum[j] = fma_h<1>(raw.x, fma_h<1>(raw.x, h4.y, acc[i][j][4 * g + 1]), sum[j]);
-        sum[j] = fma_h<0>(raw.y, fma_h<0>(raw.y, h4.z, acc[i][j][4 * g + 2]), sum[j]);
-        sum[j] = fma_h<1>(raw.y, fma_h<1>(raw.y, h4.w, acc[i][j][4 * g + 3]), sum[j]);
+        const int t = (m - 4 * (i + 1)) & 15, j = t >> 2, g = t & 3;
+        const uint2 raw = cap[t];
+        // the four accumulator entries are fetched here and nowhere earlier (the empty asm pins the copy out of the
+        // accumulator registers to this place; hoisted to the head of the sweep they would cost 64 registers)
+        float e0 = acc[i][j][4 * g + 0], e1 = acc[i][j][4 * g + 1], e2 = acc[i][j][4 * g + 2], e3 = acc[i][j][4 * g + 3];
+        asm volatile("" : "+v"(e0), "+v"(e1), "+v"(e2), "+v"(e3));
+        sum[j] = fma_h<0>(raw.x, fma_h<0>(raw.x, hq4[g].x, e0), sum[j]);
+        sum[j] = fma_h<1>(raw.x, fma_h<1>(raw.x, hq4[g].y, e1), sum[j]);
+        sum[j] = fma_h<0>(raw.y, fma_h<0>(raw.y, hq4[g].z, e2), sum[j]);
+        sum[j] = fma_h<1>(raw.y, fma_h<1>(raw.y, hq4[g].w, e3), sum[j]);
     };
-    // IP < 0: a plain stage.  IP = 0..7: stage IP of the diagonal block with the in-loop epilogue: the waves that
-    // own sub-block IP - 1 (wm == (IP - 1) / 4) fold the entries copied a stage ago into the row sums, one item
-    // per MFMA of the first sweep; the waves that own sub-block IP copy its dW' entries from this stage's
-    // operand-1 tile, one item per MFMA of the second sweep (the tile stays in its ring slot until the next
-    // stage's barrier).
+    auto load_hq = [&](auto ip_tag, float4 (&hq4)[4]) {
+        constexpr int IP = decltype(ip_tag)::value;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            hq4[g] = *reinterpret_cast<const float4*>(&s_hq[(IP >> 2) * WM + 32 * (IP & 3) + 8 * g + 4 * (lane >> 5)]);
+    };
+    // One stage in ring slot B.  IP < 0: a plain stage.  IP = 0..7: stage IP of the diagonal block with the in-loop
+    // epilogue: the waves that own sub-block IP - 1 (wm == (IP - 1) / 4) fold the entries copied a stage ago into
+    // the row sums, one item per MFMA of the first sweep; the waves that own sub-block IP copy its dW' entries from
+    // this stage's operand-1 tile, one item per MFMA of the second sweep (the tile stays in its ring slot until
+    // the next stage's barrier).  The branches hold no MFMA: the accumulators are only read inside them.
     auto stage_body = [&](auto buf_tag, auto ip_tag) {
         constexpr int B = decltype(buf_tag)::value, IP = decltype(ip_tag)::value;
+        constexpr int IPF = IP >= 1 ? IP - 1 : 0;
         static_assert(NMMA == TN * 4, "one epilogue item per MFMA of a sweep");
+        float4 hq4[4] = {};
+        const bool do_fold = IP >= 1 && wm == IPF / 4, do_cap = IP >= 0 && wm == (IP >= 0 ? IP : 0) / 4;
+        if constexpr (IP >= 1) {
+            if (do_fold) load_hq(std::integral_constant<int, IPF>{}, hq4);
+        }
 #pragma unroll
         for (int m = 0; m < NMMA; ++m) {
 #pragma unroll
             for (int r = m * NRD / NMMA; r < (m + 1) * NRD / NMMA; ++r) read_one(F1, B, 1, r);
             if constexpr (IP >= 1) {
-                if (wm == (IP - 1) / 4) fold(std::integral_constant<int, IP - 1>{}, m);
+                if (do_fold) fold(std::integral_constant<int, IPF>{}, m, hq4);
             }
             mma(F0, m);
             __builtin_amdgcn_sched_barrier(0);
@@ -336,7 +355,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
 #pragma unroll
         for (int m = 0; m < PRE; ++m) {
             if constexpr (IP >= 0) {
-                if (wm == IP / 4) capture(buf_tag, m);
+                if (do_cap) capture(buf_tag, m);
             }
             mma(F1, m);
         }
@@ -354,7 +373,7 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
 #pragma unroll
             for (int j = q * LOADS / REST; j < (q + 1) * LOADS / REST; ++j) issue_one(j, (B + 3) & 3);
             if constexpr (IP >= 0) {
-                if (wm == IP / 4) capture(buf_tag, m);
+                if (do_cap) capture(buf_tag, m);
             }
             mma(F1, m);
             __builtin_amdgcn_sched_barrier(0);
@@ -383,8 +402,10 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
         stage_body(std::integral_constant<int, 2>{}, std::integral_constant<int, 6>{});
         stage_body(std::integral_constant<int, 3>{}, std::integral_constant<int, 7>{});
         if (wm == 1) {
+            float4 hq4[4];
+            load_hq(std::integral_constant<int, 7>{}, hq4);
 #pragma unroll
-            for (int m = 0; m < NMMA; ++m) fold(std::integral_constant<int, 7>{}, m);
+            for (int m = 0; m < NMMA; ++m) fold(std::integral_constant<int, 7>{}, m, hq4);
         }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no DMA may outlive the workgroup
@@ -476,15 +497,36 @@ __global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half
     if constexpr (DBG & 8) {
         if (tid == 0) {
             dbg_t[3] = wall_clock64();
-            uint32_t* d = reinterpret_cast<uint32_t*>(part + int64_t(batch.n) * n_slots * out) + int64_t(blockIdx.x) * 8;
+            uint32_t* d = reinterpret_cast<uint32_t*>(part + int64_t(batch.n) * n_slots * out) + rec * 8;
 #pragma unroll
             for (int q = 0; q < 4; ++q) d[q] = static_cast<uint32_t>(dbg_t[q]);
             d[4] = static_cast<uint32_t>(n_st);
             d[5] = static_cast<uint32_t>(slot);
-            d[6] = static_cast<uint32_t>(pair);
+            // where it ran: XCC id (hardware register 20) in bits 16..19 above the SE / SH / CU fields of HW_ID (register 4)
+            const uint32_t hw = __builtin_amdgcn_s_getreg((4 << 0) | (0 << 6) | (31 << 11));
+            const uint32_t xcc = __builtin_amdgcn_s_getreg((20 << 0) | (0 << 6) | (3 << 11));
+            d[6] = (xcc << 16) | (hw & 0xff00u);
             d[7] = 1u;
         }
     }
+    return 0;
+}
+
+// The launch: one workgroup per list position, XCD = launch index % 8 (workgroups go to the eight XCDs round-robin
+// by launch index).  (Tried and not kept: persistent workgroups, one per compute unit, taking positions from
+// per-XCD counters.  Between two workgroups of a launch the hardware leaves a compute unit idle for 6 to 8 us on
+// average, and a persistent workgroup goes on within 3 us; but the time a compute unit is busy with the same
+// items then grows by about as much as the gaps shrink, 778 -> 832 us per compute unit on the 4096 x 11008
+// layer: the matrix cores run against the chip's power limit, and idle time between workgroups is time at a
+// higher clock afterwards.  Whole launches moved by -2 % to +9 %.)
+template <int DBG = 0>
+__global__ __launch_bounds__(256) void error_tiles_dma(Batch batch, const __half* __restrict__ Hs, int64_t out,
+                                                       int64_t in, int MB, int NB, int kc_len, int n_slots,
+                                                       const void* zero16, const float* __restrict__ hmeta_diag,
+                                                       float* __restrict__ part) {
+    extern __shared__ __align__(16) char smem[];
+    (void)error_item<DBG>(batch, Hs, out, in, MB, NB, kc_len, n_slots, zero16, hmeta_diag, part,
+                          static_cast<int>(blockIdx.x % 8), static_cast<int>(blockIdx.x / 8), int64_t(blockIdx.x), smem);
 }
 
 }  // namespace edma
