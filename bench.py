@@ -50,6 +50,18 @@ def gram_tiling(in_f: int):
     return bt, nb * (nb + 1) // 2
 
 
+def copy_calibration():
+    """One plain elementwise kernel that reads 256 MiB and writes 256 MiB (one vectorized_elementwise_kernel dispatch
+    with a MulFunctor in a counter file): the dispatch of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE."""
+    import torch
+    src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    torch.mul(src, 2.0, out=dst)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def gram_issued_flops(in_f: int, tokens: int) -> float:
     """MFMA flops the Gram kernel issues: upper-triangular tiles (full diagonal tiles) x 2*BT*BT*tokens."""
     bt, n_tiles = gram_tiling(in_f)
@@ -379,6 +391,8 @@ def block_bench(args):
 
     run(max(1, args.warmup))
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        copy_calibration()
     # the timed region brackets the dominant kernel only (see the single-layer path); the others from a second pass
     elapsed, live = profiled(args.steps, only="gram_tiles" if len(clips) == 1 else "error_tiles")
     recs = list(log.records.values()) if log is not None else []
@@ -634,14 +648,7 @@ def main():
         timed_step()
     torch.cuda.synchronize()
     if args.copy_calibration:
-        # an elementwise kernel that reads 256 MiB and writes 256 MiB (shows up as one
-        # vectorized_elementwise_kernel dispatch in the counter file)
-        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        torch.mul(src, 2.0, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration()
     # Per-kernel durations come from the library's event pair around each launch, and a pair costs the stream about
     # 7 us: bracketing all five kernels of a q_proj step takes 3 % off the figure being measured.  So the timed
     # region brackets one kernel, the dominant one (found in one untimed step with every kernel bracketed), which

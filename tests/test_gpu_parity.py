@@ -533,3 +533,27 @@ def test_profile_only_one_kernel(ctx):
     ctx.adadim_profile(False)
     rec = ctx.adadim_profile_read()
     assert "gram_tiles" in rec and "error_tiles" in rec and len(rec) >= 4
+
+
+@pytest.mark.parametrize("log2_scale", [-10, 0, 6])
+def test_search_losses_over_the_activation_range(ctx, log2_scale):
+    """The scoring operands are fp16 after the power-of-two column scaling (dW * d, d ~ sqrt(H_jj)), so the loss is
+    accurate while |dW| sqrt(H_jj) stays inside fp16's normal range (the header of adadim_hessian_prepare states the
+    range).  Activations 2^-10 and 2^6 times the usual size, outlier channels included, are inside it: both losses
+    to 1e-3 of the fp64 oracle, as at the usual size, through the calls the search makes."""
+    out_f, in_f, tokens, bits, group = 512, 768, 4096, 3, 128
+    W = rand_w(out_f, in_f, seed=77)
+    X = synth.make_activations(tokens, in_f, seed=78, n_outliers=4, scale_lo=50, scale_hi=100)
+    X = (X.astype(np.float32) * np.float32(2.0 ** log2_scale)).astype(np.float16)      # exact: a power of two, no overflow
+    assert np.isfinite(X).all()
+    H64 = oracle.hessian(X)
+    hp = S.PreparedHessian(ctx, in_f).update_prepared(dev(X))
+    ls = S.LayerSearch(ctx, out_f, in_f, bits, group)
+    ls.launch(dev(W), hp)
+    best, dim, _ = ls.result()
+    got = ls.losses.cpu().numpy().astype(np.float64)
+    ref = [oracle.layer_error(oracle.quantize(W, dm, bits, group)["dW"], H64) for dm in (OC, IC)]
+    assert np.isfinite(got).all()
+    assert got == pytest.approx(ref, rel=LOSS_RTOL)
+    if abs(ref[0] - ref[1]) / min(ref) > 0.01:
+        assert best == oracle.select(ref)
