@@ -481,6 +481,9 @@ def ceiling_bench(args):
     for name, rnd in (("zeros", False), ("random", True), ("zeros_again", False), ("random_again", True)):
         runs = [ctx.adadim_probe_mfma(rnd, 4000) for _ in range(3)]
         probe[name] = {"tflops": [round(r[0], 1) for r in runs], "clock_mhz": [round(r[1]) for r in runs]}
+    runs64 = [ctx.adadim_probe_mfma_f64(20000) for _ in range(3)]
+    probe64 = {"tflops": [round(r[0], 1) for r in runs64], "clock_mhz": [round(r[1]) for r in runs64],
+               "published_peak_tflops": 78.6}
     T = 65536
     gram = {}
     for n in (11008, 4096):
@@ -512,7 +515,8 @@ def ceiling_bench(args):
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": "matrix-core ceiling probe: v_mfma_f32_32x32x16_f16 loop on zero / random operands; Gram kernel on "
                                "[65536, 11008] and [65536, 4096] inputs of zeros / relu(normal) / normal"},
-        "published_peak_tflops": MFMA_F16_PEAK / 1e12, "mfma_loop": probe, "gram_kernel_by_input": gram}))
+        "published_peak_tflops": MFMA_F16_PEAK / 1e12, "mfma_loop": probe, "mfma_f64_loop": probe64,
+        "gram_kernel_by_input": gram}))
 
 
 # (warm-up, timed) steps when the flags are absent.  The chip needs some tens of milliseconds of load before its

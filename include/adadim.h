@@ -380,6 +380,13 @@ int adadim_profile(adadim_ctx* ctx, int enable);
  * clock_mhz: the shader clock the loop ran at (clock64 against the 100 MHz wall_clock64).  Host pointers.
  */
 int adadim_probe_mfma(adadim_ctx* ctx, int random_operands, int iters, double* tflops, double* clock_mhz);
+/*
+ * The same for the fp64 instruction the GPTQ factorization runs on: v_mfma_f64_16x16x4_f64, eight independent
+ * accumulator chains per wave, 1024 workgroups of four waves, 8 * iters instructions per wave, operands near 1.
+ * Outputs as above.  (On this chip the loop stays well below the published fp64 figure whatever the operands; the
+ * factor's products are to be read against this rate.)
+ */
+int adadim_probe_mfma_f64(adadim_ctx* ctx, int iters, double* tflops, double* clock_mhz);
 int adadim_profile_only(adadim_ctx* ctx, const char* name);
 int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches);
 

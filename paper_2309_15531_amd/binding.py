@@ -25,7 +25,7 @@ EXPORTS = (
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_only", "adadim_profile_read",
-    "adadim_layer_error_batch_select_noalloc", "adadim_noalloc_scratch_bytes", "adadim_probe_mfma",
+    "adadim_layer_error_batch_select_noalloc", "adadim_noalloc_scratch_bytes", "adadim_probe_mfma", "adadim_probe_mfma_f64",
 )
 
 _lib = None
@@ -121,6 +121,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_noalloc_scratch_bytes.restype = c_int64
     lib.adadim_probe_mfma.argtypes = [c_void_p, c_int, c_int, POINTER(ctypes.c_double), POINTER(ctypes.c_double)]
     lib.adadim_probe_mfma.restype = c_int
+    lib.adadim_probe_mfma_f64.argtypes = [c_void_p, c_int, POINTER(ctypes.c_double), POINTER(ctypes.c_double)]
+    lib.adadim_probe_mfma_f64.restype = c_int
     lib.adadim_select.argtypes = [c_void_p, c_void_p, c_int, c_void_p, POINTER(c_int32)]
     lib.adadim_select.restype = c_int
     lib.adadim_profile.argtypes = [c_void_p, c_int]
@@ -365,6 +367,12 @@ class Context:
         self._check(self._lib.adadim_gptq_quantize(self._h, _ptr(W), out_f, in_f, dim, bits, group, _ptr(U), _ptr(perm),
                                                    _ptr(dead), _ptr(static_scales), _ptr(static_zeros), _ptr(codes),
                                                    _ptr(scales), _ptr(zeros), _ptr(dW), _ptr(packed)))
+
+    def adadim_probe_mfma_f64(self, iters: int = 20000):
+        """(TFLOP/s, shader clock in MHz) of a register-resident fp64 MFMA loop; waits for the stream."""
+        tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
+        self._check(self._lib.adadim_probe_mfma_f64(self._h, iters, byref(tf), byref(mhz)))
+        return tf.value, mhz.value
 
     def adadim_probe_mfma(self, random_operands: bool, iters: int = 4000):
         """(TFLOP/s, shader clock in MHz) of a register-resident MFMA loop; waits for the stream."""

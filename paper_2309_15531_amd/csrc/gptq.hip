@@ -221,103 +221,170 @@ __device__ __forceinline__ void dgemm_each(const double4_t (&acc)[TS / 32][TS / 
 }
 
 // ------------------------------------------------------------------ Cholesky, lower, in place
-// Diagonal block A[k0.., k0..] of width w <= NB, factored and inverted by one wavefront.  Lane r
-// keeps row r in registers.  Right-looking: once column c is final (pivot broadcast by a lane
-// read, reciprocal square root plus two Newton steps), the lanes post it in LDS and every lane
-// subtracts l_rc l_jc from its later columns j: independent broadcast reads and independent
-// fmas, nothing waits on a chain.  The inverse likewise (column j of inv(L) by lane j: y_k final,
-// then a_r -= l_rk y_k for the later rows) goes to the diagonal block of M: it turns the panel's
-// triangular solve into a product and is the first level of the triangular inverse.
-// the value `v` has in lane `src_lane` (a constant), in every lane
+// Diagonal block A[k0.., k0..] of width w <= NB = 64, factored and inverted by one workgroup of four
+// waves, blocked by 16.  The whole factorization waits for this kernel, so what counts is the length
+// of its dependency chain, not its flops:
+//  * Cholesky, four panels of 16 columns.  Wave 0 holds the panel with lane r = row r (16 registers):
+//    column c is final once its pivot is (broadcast by a lane read; reciprocal square root plus two
+//    Newton steps), the later columns of the panel receive l_rc l_jc with l_jc read from lane j.  No
+//    LDS and no barrier inside a panel, at most 15 updates per column.  The columns behind the panel
+//    get the panel's rank-16 update from the fp64 matrix cores, the (at most six) 16 x 16 tiles dealt
+//    to the four waves.
+//  * inv(L) by doubling: the four 16 x 16 diagonal blocks at once, one per wave (lane j solves for
+//    column j, L's entries by lane reads), then the level-16 and level-32 off-diagonal blocks as
+//    -inv(B) C inv(A), two matrix-core products each.
+// inv(L) goes to the diagonal block of M: it turns the panel's triangular solve into a product and is
+// the first level of the triangular inverse.
+// the value `v` has in lane `src_lane` (wave-uniform), in every lane
 __device__ __forceinline__ double lane_read(double v, int src_lane) {
     const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
     const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
     return __hiloint2double(hi, lo);
 }
+// LDS writes of this wave before, its LDS reads after: a wave's LDS accesses are served in order
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
-__global__ __launch_bounds__(64) void chol_diag_inv(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0,
-                                                    int w) {
-    __shared__ double t[NB][NB + 1];
-    __shared__ double col[2][NB];                             // the column just finished, two buffers in turn
-    __shared__ double rd[NB];                                 // reciprocals of the diagonal of L
-    const int lane = threadIdx.x;
-    // one wave that the whole factorization waits for: ahead of the trailing update that may share its SIMD
+// LDS of the diagonal block's factorization: 75.5 KB
+struct DiagLds {
+    static constexpr int LD = NB + 1;
+    double t[NB][LD];                                         // the block, then L (zeros above the diagonal)
+    double mi[NB][LD];                                        // inv(L)
+    double tt[NB / 2][NB / 2 + 1];                            // C inv(A) of the inverse's levels
+    double rd[NB];                                            // reciprocals of the diagonal of L
+};
+__device__ __forceinline__ void diag_factor(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0, int w,
+                                            DiagLds& lds) {
+    constexpr int P = 16;
+    auto& t = lds.t;
+    auto& mi = lds.mi;
+    auto& tt = lds.tt;
+    auto& rd = lds.rd;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, h16 = lane >> 4;
+    // one workgroup that the whole factorization waits for: ahead of the trailing update that may share its SIMDs
     __builtin_amdgcn_s_setprio(3);
-    for (int e = lane; e < NB * NB; e += 64) {
+    for (int e = tid; e < NB * NB; e += 256) {
         const int r = e / NB, c = e % NB;
         t[r][c] = (r < w && c < w) ? A[(k0 + r) * n + k0 + c] : (r == c ? 1.0 : 0.0);   // identity padding
+        mi[r][c] = 0.0;
     }
     __syncthreads();
-    {
-        double x[NB];
+    // the pivot's reciprocal square root: the same in every lane
+    auto rsqrt_of = [](double piv) {
+        double inv = __builtin_amdgcn_rsq(piv);
+        inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
+        return inv * fma(-0.5 * piv * inv, inv, 1.5);
+    };
+    for (int p = 0; p < NB / P; ++p) {
+        if (wave == 0) {
+            double x[P];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) x[c] = t[lane][c];
-        // the pivot's reciprocal square root: the same in every lane
-        auto rsqrt_of = [](double piv) {
-            double inv = __builtin_amdgcn_rsq(piv);
-            inv = inv * fma(-0.5 * piv * inv, inv, 1.5);
-            return inv * fma(-0.5 * piv * inv, inv, 1.5);
-        };
-        double piv = lane_read(x[0], 0), inv = rsqrt_of(piv);
+            for (int j = 0; j < P; ++j) x[j] = t[lane][P * p + j];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            const double l = lane == c ? piv * inv : (lane > c ? x[c] * inv : 0.0);
-            x[c] = l;
-            col[c & 1][lane] = l;
-            if (lane == c) rd[c] = inv;
-            // The next pivot first, by lane reads, so that its chain (update, read, reciprocal square root, two
-            // Newton steps) runs under this column's broadcast reads and updates instead of behind them.
-            if (c + 1 < NB) {
-                x[c + 1] = fma(-l, lane_read(l, c + 1), x[c + 1]);
-                piv = lane_read(x[c + 1], c + 1);
-                inv = rsqrt_of(piv);
+            for (int c = 0; c < P; ++c) {
+                const int gc = P * p + c;
+                const double piv = lane_read(x[c], gc), inv = rsqrt_of(piv);
+                const double l = lane == gc ? piv * inv : (lane > gc ? x[c] * inv : 0.0);
+                x[c] = l;
+                if (lane == gc) rd[gc] = inv;
+#pragma unroll
+                for (int j = c + 1; j < P; ++j) x[j] = fma(-l, lane_read(l, P * p + j), x[j]);
             }
-            __syncthreads();
-            // sixteen broadcast reads in flight at a time: the fences keep the scheduler from issuing
-            // them all at once, which would not leave registers for the row
 #pragma unroll
-            for (int j0 = (c + 2) & ~15; j0 < NB; j0 += 16) {
-#pragma unroll
-                for (int j = j0 > c + 2 ? j0 : c + 2; j < j0 + 16; ++j) x[j] = fma(-l, col[c & 1][j], x[j]);
-                asm volatile("" ::: "memory");
-            }
+            for (int j = 0; j < P; ++j) t[lane][P * p + j] = x[j];
         }
+        __syncthreads();
+        int idx = 0;
+        for (int ti = p + 1; ti < NB / P; ++ti)
+            for (int tj = p + 1; tj <= ti; ++tj, ++idx) {
+                if ((idx & 3) != wave) continue;              // whole waves
+                double4_t acc;
 #pragma unroll
-        for (int c = 0; c < NB; ++c) t[lane][c] = x[c];
+                for (int r = 0; r < 4; ++r) acc[r] = t[P * ti + 4 * r + h16][P * tj + l16];
+#pragma unroll
+                for (int kk = 0; kk < P; kk += 4)
+                    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-t[P * ti + l16][P * p + kk + h16], t[P * tj + l16][P * p + kk + h16],
+                                                               acc, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) t[P * ti + 4 * r + h16][P * tj + l16] = acc[r];
+            }
+        __syncthreads();
     }
-    __syncthreads();
-    for (int e = lane; e < w * w; e += 64) A[(k0 + e / w) * n + k0 + e % w] = t[e / w][e % w];
+    // diagonal blocks of inv(L): wave b's lanes 0..15 hold rows and solve for columns of block b (the other
+    // lanes repeat them)
     {
-        const double my_rd = rd[lane];
-        double a[NB];
+        const int b = P * wave;
+        double xr[P], a[P];
 #pragma unroll
-        for (int r = 0; r < NB; ++r) {
-            a[r] = r == lane ? 1.0 : 0.0;
-            asm volatile("" : "+v"(a[r]));                    // a register now, not a lane compare kept for later
+        for (int k = 0; k < P; ++k) {
+            xr[k] = t[b + l16][b + k];
+            a[k] = k == l16 ? 1.0 : 0.0;
         }
 #pragma unroll
-        for (int k = 0; k < NB; ++k) {
-            // column k of L, with the reciprocal pivot in the diagonal's place, posted like the columns above
-            // (reading it where it lies, t[r][k], one address for the whole wave, was a third slower)
-            col[k & 1][lane] = lane == k ? my_rd : t[lane][k];
-            __syncthreads();
-            const double yk = a[k] * col[k & 1][k];
+        for (int k = 0; k < P; ++k) {
+            const double yk = a[k] * rd[b + k];
             a[k] = yk;
 #pragma unroll
-            for (int r0 = (k + 1) & ~15; r0 < NB; r0 += 16) {
-#pragma unroll
-                for (int r = r0 > k + 1 ? r0 : k + 1; r < r0 + 16; ++r) a[r] = fma(-col[k & 1][r], yk, a[r]);
-                asm volatile("" ::: "memory");
-            }
+            for (int r = k + 1; r < P; ++r) a[r] = fma(-lane_read(xr[k], r), yk, a[r]);
         }
-        // out through LDS (t is free now): sixty-four global stores from here would each want their
-        // address computed ahead of time, and those registers are not to be had
-        __syncthreads();
+        if (lane < P) {
 #pragma unroll
-        for (int r = 0; r < NB; ++r) t[r][lane] = r >= lane ? a[r] : 0.0;
+            for (int r = 0; r < P; ++r) mi[b + r][b + lane] = r >= lane ? a[r] : 0.0;
+        }
     }
     __syncthreads();
-    for (int e = lane; e < w * w; e += 64) M[(k0 + e / w) * n + k0 + e % w] = t[e / w][e % w];
+    // level 16: blocks (1, 0) and (3, 2), one wave each
+    if (wave < 2) {
+        const int ra = 2 * P * wave, rb = ra + P;            // first rows of inv(A)'s and inv(B)'s blocks
+        double4_t acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < P; kk += 4)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(t[rb + l16][ra + kk + h16], mi[ra + kk + h16][ra + l16], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tt[P * wave + 4 * r + h16][l16] = acc[r];
+        wave_lds_sync();
+        acc = double4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < P; kk += 4)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-mi[rb + l16][rb + kk + h16], tt[P * wave + kk + h16][l16], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mi[rb + 4 * r + h16][ra + l16] = acc[r];
+    }
+    __syncthreads();
+    // level 32: the 32 x 32 block below the diagonal, one 16 x 16 tile per wave
+    {
+        const int ti = wave >> 1, tj = wave & 1;
+        double4_t acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < 2 * P; kk += 4)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(t[2 * P + P * ti + l16][kk + h16], mi[kk + h16][P * tj + l16], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tt[P * ti + 4 * r + h16][P * tj + l16] = acc[r];
+        __syncthreads();
+        acc = double4_t{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int kk = 0; kk < 2 * P; kk += 4)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-mi[2 * P + P * ti + l16][2 * P + kk + h16], tt[kk + h16][P * tj + l16], acc,
+                                                       0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mi[2 * P + P * ti + 4 * r + h16][P * tj + l16] = acc[r];
+    }
+    __syncthreads();
+    for (int e = tid; e < w * w; e += 256) {
+        const int r = e / w, c = e % w;
+        A[(k0 + r) * n + k0 + c] = t[r][c];
+        M[(k0 + r) * n + k0 + c] = mi[r][c];
+    }
+}
+
+__global__ __launch_bounds__(256) void chol_diag_inv(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0,
+                                                     int w) {
+    __shared__ DiagLds lds;
+    diag_factor(A, M, n, k0, w, lds);
 }
 
 // rows below the diagonal block: L21 = A21 inv(L11)^T, 64 rows per block, in place (a block reads
@@ -351,6 +418,30 @@ __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t
     dgemm_each<TS>(acc, [&](int i, int j, double v) {
         if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] -= v;
     });
+}
+
+// The same update with 64 x 64 tiles, and the workgroup of the first tile (the diagonal block at k1, final once
+// this update has reached it) goes on to factor and invert that block: the next step's chol_diag_inv without its
+// launch, and under the other tiles' products.  The product's staging buffers and the factorization's LDS share
+// their space.
+__global__ __launch_bounds__(256) void chol_syrk_diag(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0, int w,
+                                                      int64_t k1) {
+    if (blockIdx.x > blockIdx.y) return;
+    __shared__ __align__(16) char smem[sizeof(DiagLds) > 2 * GK * (GT + 4) * sizeof(double) ? sizeof(DiagLds)
+                                                                                             : 2 * GK * (GT + 4) * sizeof(double)];
+    double(*As)[GT + 4] = reinterpret_cast<double(*)[GT + 4]>(smem);
+    double(*Bs)[GT + 4] = As + GK;
+    const int64_t r0 = k1 + int64_t(blockIdx.y) * GT, c0 = k1 + int64_t(blockIdx.x) * GT;
+    const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT), n_valid = static_cast<int>(n - c0 < GT ? n - c0 : GT);
+    double4_t acc[GT / 32][GT / 32] = {};
+    dgemm_tile<GT, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
+    dgemm_each<GT>(acc, [&](int i, int j, double v) {
+        if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] -= v;
+    });
+    if (blockIdx.x == 0 && blockIdx.y == 0) {                 // whole workgroup
+        __syncthreads();                                      // the tile is in memory and the staging buffers are free
+        diag_factor(A, M, n, k1, static_cast<int>(n - k1 < NB ? n - k1 : NB), *reinterpret_cast<DiagLds*>(smem));
+    }
 }
 
 // ------------------------------------------------------------------ M = inv(L), lower, by doubling
@@ -820,36 +911,44 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
     const bool overlap = n > 2 * NBO;
     if (overlap && !adadim_side_stream(ctx)) return ADADIM_EHIP;
     bool side_busy = false;
+    bool diag_ready = false;                                  // the block at the next k0 is already factored (chol_syrk_diag)
+    static_assert(GT == NB, "chol_syrk_diag's first tile is the next diagonal block");
     for (int64_t K0 = 0; K0 < n; K0 += NBO) {
         const int64_t W = n - K0 < NBO ? n - K0 : NBO;
         for (int64_t k0 = K0; k0 < K0 + W; k0 += NB) {
             const int w = static_cast<int>(n - k0 < NB ? n - k0 : NB);
-            hipLaunchKernelGGL(chol_diag_inv, dim3(1), dim3(64), 0, ctx->stream, A, M, n, k0, w);
+            if (!diag_ready) hipLaunchKernelGGL(chol_diag_inv, dim3(1), dim3(256), 0, ctx->stream, A, M, n, k0, w);
+            diag_ready = false;
             const int64_t rest = n - k0 - w;
             if (rest > 0) {
                 const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
                 hipLaunchKernelGGL(chol_panel, dim3(t), dim3(256), 0, ctx->stream, A, M, n, k0, w);
                 const unsigned tc = static_cast<unsigned>((K0 + W - (k0 + w) + GT - 1) / GT);
-                if (tc > 0) hipLaunchKernelGGL(chol_syrk<GT>, dim3(tc, t), dim3(256), 0, ctx->stream, A, n, k0, w, k0 + w, 0);
+                if (tc > 0) {
+                    hipLaunchKernelGGL(chol_syrk_diag, dim3(tc, t), dim3(256), 0, ctx->stream, A, M, n, k0, w, k0 + w);
+                    diag_ready = true;
+                }
             }
         }
         const int64_t rest = n - K0 - W;
         if (rest > 0) {
             // The panel's update of everything behind it.  The next panel's own columns first, on the main
-            // stream: its 64-wide steps need nothing else.  The columns behind those on the side stream, under
-            // those steps (which are chains of small launches that leave the chip idle).  Every element still
-            // receives the panels' updates in panel order: the side stream applies them in order, and the main
-            // stream waits for the side stream's last launch before it updates columns that launch wrote.
-            // (The overlap is partial: chol_diag_inv needs 400 registers per lane, so its one wave starts only on
-            // a SIMD that holds nothing else, and waits for the side launch to drain when it finds none.)
+            // stream (its first tile's workgroup factors the next diagonal block as well): the panel's 64-wide
+            // steps need nothing else.  The columns behind those on the side stream, under those steps (which are
+            // chains of small launches that leave the chip idle).  Every element still receives the panels'
+            // updates in panel order: the side stream applies them in order, and the main stream waits for the
+            // side stream's last launch before it updates columns that launch wrote.
             const unsigned t = static_cast<unsigned>((rest + GT - 1) / GT);
             const unsigned tn = static_cast<unsigned>(((rest < NBO ? rest : NBO) + GT - 1) / GT);
             if (side_busy) ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->stream, ctx->side_ev[1], 0));
             side_busy = false;
-            hipLaunchKernelGGL(chol_syrk<GT>, dim3(overlap ? tn : t, t), dim3(256), 0, ctx->stream, A, n, K0, static_cast<int>(W),
-                               K0 + W, 0);
+            // both launches need the finished panel, and write different tile columns: the side stream starts with
+            // the main stream's launch, not behind it
+            if (overlap && t > tn) ADADIM_HIP_TRY(ctx, hipEventRecord(ctx->side_ev[0], ctx->stream));
+            hipLaunchKernelGGL(chol_syrk_diag, dim3(overlap ? tn : t, t), dim3(256), 0, ctx->stream, A, M, n, K0,
+                               static_cast<int>(W), K0 + W);
+            diag_ready = true;
             if (overlap && t > tn) {
-                ADADIM_HIP_TRY(ctx, hipEventRecord(ctx->side_ev[0], ctx->stream));
                 ADADIM_HIP_TRY(ctx, hipStreamWaitEvent(ctx->side, ctx->side_ev[0], 0));
                 hipLaunchKernelGGL(chol_syrk<GT>, dim3(t - tn, t), dim3(256), 0, ctx->side, A, n, K0, static_cast<int>(W),
                                    K0 + W, static_cast<int>(tn));

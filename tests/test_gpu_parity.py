@@ -557,3 +557,15 @@ def test_search_losses_over_the_activation_range(ctx, log2_scale):
     assert got == pytest.approx(ref, rel=LOSS_RTOL)
     if abs(ref[0] - ref[1]) / min(ref) > 0.01:
         assert best == oracle.select(ref)
+
+
+@pytest.mark.gpu
+def test_matrix_core_probes_report_a_rate_below_the_published_peaks(ctx):
+    """The two measurement aids run, wait for the stream and return a rate and a clock that make sense for this
+    chip: above a tenth of the published dense peaks (fp16 2.5 PFLOP/s, fp64 78.6 TFLOP/s) and not above them."""
+    tf16, mhz16 = ctx.adadim_probe_mfma(True, 500)
+    tf64, mhz64 = ctx.adadim_probe_mfma_f64(2000)
+    assert 250.0 < tf16 <= 2500.0 and 7.8 < tf64 <= 78.6
+    assert 500.0 < mhz16 < 3000.0 and 500.0 < mhz64 < 3000.0
+    with pytest.raises(B.AdaDimError):
+        ctx.adadim_probe_mfma_f64(0)
