@@ -30,7 +30,7 @@
 namespace {
 
 constexpr int NB = 64;        // panel width of the factorization
-constexpr int NBO = 256;      // its outer panel: trailing updates are applied 256 columns at a time
+constexpr int NBO = 512;      // its outer panel: trailing updates are applied 512 columns at a time
 constexpr int GB = 128;       // channels per sweep block
 
 // ------------------------------------------------------------------ prepare: order and matrix
@@ -129,12 +129,12 @@ constexpr int GT = 64, GK = 32;                  // tile edge, contraction chunk
 // (128 x 128 tiles were measured too: one workgroup per compute unit instead of four, and the
 // products ran a third slower; the matrix pipe wants the other workgroups' waves to fill its gaps.)
 
-// acc += A B for one TS x TS tile (TS = 64 or 128) and k in [k_lo, k_hi), 256 threads: 2 x 2 waves,
+// acc += A B (acc -= A B with NEG_A) for one TS x TS tile (TS = 64 or 128) and k in [k_lo, k_hi), 256 threads: 2 x 2 waves,
 // each TS/2 x TS/2 = MT x MT matrix-core tiles of 16 x 16.
 //   A(i, k) = Ap[i * lda + k], rows i < m_valid;
 //   B(k, j) = B_KC ? Bp[j * ldb + k] : Bp[k * ldb + j], columns j < n_valid;
 // everything outside the valid ranges reads as zero.  As, Bs: [GK][TS + 4] doubles each.
-template <int TS, bool B_KC>
+template <int TS, bool B_KC, bool NEG_A = false>
 __device__ __forceinline__ void dgemm_tile(const double* __restrict__ Ap, int64_t lda, int m_valid,
                                            const double* __restrict__ Bp, int64_t ldb, int n_valid, int64_t k_lo,
                                            int64_t k_hi, double (*As)[TS + 4], double (*Bs)[TS + 4],
@@ -196,6 +196,7 @@ __device__ __forceinline__ void dgemm_tile(const double* __restrict__ Ap, int64_
 #pragma unroll
             for (int u = 0; u < MT; ++u) {
                 a[u] = As[ks + (lane >> 4)][wm * (TS / 2) + u * 16 + (lane & 15)];
+                if constexpr (NEG_A) a[u] = -a[u];
                 b[u] = Bs[ks + (lane >> 4)][wn * (TS / 2) + u * 16 + (lane & 15)];
             }
 #pragma unroll
@@ -218,6 +219,20 @@ __device__ __forceinline__ void dgemm_each(const double4_t (&acc)[TS / 32][TS / 
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 f(wm * (TS / 2) + u * 16 + 4 * r + (lane >> 4), wn * (TS / 2) + v * 16 + (lane & 15), acc[u][v][r]);
+}
+
+// fills the lane's elements of a tile: acc = f(row in tile, column in tile)
+template <int TS, typename F>
+__device__ __forceinline__ void dgemm_fill(double4_t (&acc)[TS / 32][TS / 32], F f) {
+    constexpr int MT = TS / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+#pragma unroll
+    for (int u = 0; u < MT; ++u)
+#pragma unroll
+        for (int v = 0; v < MT; ++v)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[u][v][r] = f(wm * (TS / 2) + u * 16 + 4 * r + (lane >> 4), wn * (TS / 2) + v * 16 + (lane & 15));
 }
 
 // ------------------------------------------------------------------ Cholesky, lower, in place
@@ -248,19 +263,19 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// LDS of the diagonal block's factorization: 75.5 KB
+// LDS of the diagonal block's factorization: 41 KB.  inv(L) grows in the upper triangle of the block that holds L
+// (transposed; its diagonal is rd), so that the workgroup fits beside three of the trailing update's workgroups on
+// a compute unit: one that needed more than a freed slot's share of LDS would wait for that launch to drain.
 struct DiagLds {
     static constexpr int LD = NB + 1;
-    double t[NB][LD];                                         // the block, then L (zeros above the diagonal)
-    double mi[NB][LD];                                        // inv(L)
+    double t[NB][LD];                                         // the block, then L on and below the diagonal, inv(L)^T above
     double tt[NB / 2][NB / 2 + 1];                            // C inv(A) of the inverse's levels
-    double rd[NB];                                            // reciprocals of the diagonal of L
+    double rd[NB];                                            // reciprocals of the diagonal of L = diagonal of inv(L)
 };
 __device__ __forceinline__ void diag_factor(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0, int w,
                                             DiagLds& lds) {
     constexpr int P = 16;
     auto& t = lds.t;
-    auto& mi = lds.mi;
     auto& tt = lds.tt;
     auto& rd = lds.rd;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -270,9 +285,13 @@ __device__ __forceinline__ void diag_factor(double* __restrict__ A, double* __re
     for (int e = tid; e < NB * NB; e += 256) {
         const int r = e / NB, c = e % NB;
         t[r][c] = (r < w && c < w) ? A[(k0 + r) * n + k0 + c] : (r == c ? 1.0 : 0.0);   // identity padding
-        mi[r][c] = 0.0;
     }
     __syncthreads();
+    // element (r, c) of inv(L) once its block is there
+    auto mval = [&](int r, int c) {
+        const double up = t[c < r ? c : r][c < r ? r : c], dg = lds.rd[r];
+        return r > c ? up : (r == c ? dg : 0.0);
+    };
     // the pivot's reciprocal square root: the same in every lane
     auto rsqrt_of = [](double piv) {
         double inv = __builtin_amdgcn_rsq(piv);
@@ -333,7 +352,8 @@ __device__ __forceinline__ void diag_factor(double* __restrict__ A, double* __re
         }
         if (lane < P) {
 #pragma unroll
-            for (int r = 0; r < P; ++r) mi[b + r][b + lane] = r >= lane ? a[r] : 0.0;
+            for (int r = 0; r < P; ++r)
+                if (r > lane) t[b + lane][b + r] = a[r];      // the diagonal entry is rd
         }
     }
     __syncthreads();
@@ -343,16 +363,16 @@ __device__ __forceinline__ void diag_factor(double* __restrict__ A, double* __re
         double4_t acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int kk = 0; kk < P; kk += 4)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(t[rb + l16][ra + kk + h16], mi[ra + kk + h16][ra + l16], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(t[rb + l16][ra + kk + h16], mval(ra + kk + h16, ra + l16), acc, 0, 0, 0);
 #pragma unroll
         for (int r = 0; r < 4; ++r) tt[P * wave + 4 * r + h16][l16] = acc[r];
         wave_lds_sync();
         acc = double4_t{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int kk = 0; kk < P; kk += 4)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-mi[rb + l16][rb + kk + h16], tt[P * wave + kk + h16][l16], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-mval(rb + l16, rb + kk + h16), tt[P * wave + kk + h16][l16], acc, 0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mi[rb + 4 * r + h16][ra + l16] = acc[r];
+        for (int r = 0; r < 4; ++r) t[ra + l16][rb + 4 * r + h16] = acc[r];
     }
     __syncthreads();
     // level 32: the 32 x 32 block below the diagonal, one 16 x 16 tile per wave
@@ -361,23 +381,23 @@ __device__ __forceinline__ void diag_factor(double* __restrict__ A, double* __re
         double4_t acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int kk = 0; kk < 2 * P; kk += 4)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(t[2 * P + P * ti + l16][kk + h16], mi[kk + h16][P * tj + l16], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(t[2 * P + P * ti + l16][kk + h16], mval(kk + h16, P * tj + l16), acc, 0, 0, 0);
 #pragma unroll
         for (int r = 0; r < 4; ++r) tt[P * ti + 4 * r + h16][P * tj + l16] = acc[r];
         __syncthreads();
         acc = double4_t{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int kk = 0; kk < 2 * P; kk += 4)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-mi[2 * P + P * ti + l16][2 * P + kk + h16], tt[kk + h16][P * tj + l16], acc,
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(-mval(2 * P + P * ti + l16, 2 * P + kk + h16), tt[kk + h16][P * tj + l16], acc,
                                                        0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mi[2 * P + P * ti + 4 * r + h16][P * tj + l16] = acc[r];
+        for (int r = 0; r < 4; ++r) t[P * tj + l16][2 * P + P * ti + 4 * r + h16] = acc[r];
     }
     __syncthreads();
     for (int e = tid; e < w * w; e += 256) {
         const int r = e / w, c = e % w;
-        A[(k0 + r) * n + k0 + c] = t[r][c];
-        M[(k0 + r) * n + k0 + c] = mi[r][c];
+        A[(k0 + r) * n + k0 + c] = r >= c ? t[r][c] : 0.0;
+        M[(k0 + r) * n + k0 + c] = mval(r, c);
     }
 }
 
@@ -404,7 +424,7 @@ __global__ __launch_bounds__(256) void chol_panel(double* __restrict__ A, const 
 
 // trailing update: C[r][c] -= sum_t P[r][t] P[c][t] on the TS x TS tiles (blockIdx.y, blockIdx.x <= blockIdx.y)
 // of the rows/columns from k1 on; P = A[.., k0..k0+w).  gridDim.x limits the columns that are updated
-// (inside a 256-wide outer panel only the panel's own columns; behind it all, with w = 256).
+// (inside a 512-wide outer panel only the panel's own columns; behind it all, with w = 512).
 // ct0: first tile column of this launch (the update behind an outer panel goes out in two launches).
 template <int TS>
 __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t n, int64_t k0, int w, int64_t k1, int ct0) {
@@ -413,10 +433,13 @@ __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t
     __shared__ double As[GK][TS + 4], Bs[GK][TS + 4];
     const int64_t r0 = k1 + int64_t(blockIdx.y) * TS, c0 = k1 + int64_t(ct) * TS;
     const int m_valid = static_cast<int>(n - r0 < TS ? n - r0 : TS), n_valid = static_cast<int>(n - c0 < TS ? n - c0 : TS);
-    double4_t acc[TS / 32][TS / 32] = {};
-    dgemm_tile<TS, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
+    // the accumulators start as the tile of C (its loads travel with the first operand chunk's) and the products are
+    // subtracted: no read-modify-write behind the loop
+    double4_t acc[TS / 32][TS / 32];
+    dgemm_fill<TS>(acc, [&](int i, int j) { return (i < m_valid && j < n_valid) ? A[(r0 + i) * n + c0 + j] : 0.0; });
+    dgemm_tile<TS, true, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
     dgemm_each<TS>(acc, [&](int i, int j, double v) {
-        if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] -= v;
+        if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] = v;
     });
 }
 
@@ -433,10 +456,11 @@ __global__ __launch_bounds__(256) void chol_syrk_diag(double* __restrict__ A, do
     double(*Bs)[GT + 4] = As + GK;
     const int64_t r0 = k1 + int64_t(blockIdx.y) * GT, c0 = k1 + int64_t(blockIdx.x) * GT;
     const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT), n_valid = static_cast<int>(n - c0 < GT ? n - c0 : GT);
-    double4_t acc[GT / 32][GT / 32] = {};
-    dgemm_tile<GT, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
+    double4_t acc[GT / 32][GT / 32];
+    dgemm_fill<GT>(acc, [&](int i, int j) { return (i < m_valid && j < n_valid) ? A[(r0 + i) * n + c0 + j] : 0.0; });
+    dgemm_tile<GT, true, true>(A + r0 * n + k0, n, m_valid, A + c0 * n + k0, n, n_valid, 0, w, As, Bs, acc);
     dgemm_each<GT>(acc, [&](int i, int j, double v) {
-        if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] -= v;
+        if (i < m_valid && c0 + j <= r0 + i) A[(r0 + i) * n + c0 + j] = v;
     });
     if (blockIdx.x == 0 && blockIdx.y == 0) {                 // whole workgroup
         __syncthreads();                                      // the tile is in memory and the staging buffers are free
@@ -905,7 +929,7 @@ int launch_gptq_prepare(adadim_ctx* ctx, const float* H, int64_t n, float percda
         hipLaunchKernelGGL(gq_rank, dim3(nb1), dim3(256), 0, ctx->stream, dvec, n, act_order, perm);
     hipLaunchKernelGGL(gq_gather, dim3(nb2), dim3(256), 0, ctx->stream, H, n, perm, dvec, damp, A);
     ADADIM_LAUNCH_CHECK(ctx, "gptq prepare");
-    // Outer panels of 256 columns: inside a panel the 64-wide steps update the panel's own columns
+    // Outer panels of 512 columns: inside a panel the 64-wide steps update the panel's own columns
     // only; the columns behind it get the whole panel at once, a product with 256 contraction steps
     // per pass over the trailing matrix instead of 64.
     const bool overlap = n > 2 * NBO;
