@@ -62,7 +62,7 @@ struct adadim_ctx {
     size_t zero_ready_bytes;         // size of WS_ZERO when it was last cleared
     // Gram split lengths already chosen, keyed by (token count, tile count): choosing one simulates the launch's
     // schedule (tens of milliseconds of host time), and a model driver alternates between a few input widths
-    struct GramSplit { int64_t tokens; int tiles; int64_t t_per_split; } gram_split[8];
+    struct GramSplit { int64_t tokens; int tiles; int64_t t_per_split; int n_whole; bool whole_ok; } gram_split[8];
     int gram_split_n, gram_split_next;
     bool capturing;                  // between adadim_capture_begin and adadim_capture_end
     hipStream_t side;                // second stream for work that may overlap the main one (created on first use)

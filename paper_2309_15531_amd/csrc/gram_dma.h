@@ -87,7 +87,8 @@ template <int WGM, int WGN, int DBG = 0>
 __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* __restrict__ X, int64_t tokens,
                                                                  int64_t in, int64_t ldx, int nb, int n_split,
                                                                  int n_full, int64_t t_per_split, const void* zero16,
-                                                                 float* __restrict__ part) {
+                                                                 float* __restrict__ part, int n_whole,
+                                                                 float* __restrict__ H) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BT / WGM, WN = BT / WGN, TM = WM / 32, TN = WN / 32;
     constexpr int LOADS = 32 / NW;  // 1-KB transfers per wavefront per stage
@@ -95,31 +96,40 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
     extern __shared__ __align__(16) char smem[];
     const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
 
-    // Work item = (token split, tile), split-major.  Workgroups are handed to the eight XCDs
-    // round-robin by launch index, and each XCD has its own L2: give XCD x the x-th contiguous
-    // eighth of the work list, so that the workgroups resident on one XCD at a time stream the
-    // same token range and share row/column panels in its L2.
-    // The first n_full splits have full length, a last one (if any) is shorter: each XCD takes
-    // its eighth of the full-length items first and then its eighth of the short ones, so the
-    // short items fill the gaps of the last round on every XCD.
-    const int n_tiles = nb * (nb + 1) / 2;
-    const int total_big = n_tiles * n_full, total_small = n_tiles * (n_split - n_full);
-    const int per_big = (total_big + 7) / 8, per_small = (total_small + 7) / 8;
-    const int xcd = static_cast<int>(blockIdx.x % 8), q = static_cast<int>(blockIdx.x / 8);
-    int item;
-    if (q < per_big) {
-        item = xcd * per_big + q;
-        if (item >= total_big) return;
+    // Work items.  The first n_whole tiles (decode_tile's order) are taken whole: one workgroup runs the tile over
+    // all tokens and stores it straight into H, both halves.  The other tiles are items (token split, tile),
+    // split-major, each writing an fp32 partial tile that gram_reduce adds up: the first n_full splits have full
+    // length, a last one (if any) is shorter.  Workgroups are handed to the eight XCDs round-robin by launch
+    // index, and each XCD has its own L2: XCD x takes the x-th contiguous eighth of each of the three lists, the
+    // long items first, so that the workgroups resident on one XCD at a time stream the same token range and
+    // share row/column panels in its L2, and the short items fill the gaps of the last round on every XCD.
+    const int n_tiles = nb * (nb + 1) / 2, n_rest = n_tiles - n_whole;
+    const int total_big = n_rest * n_full, total_small = n_rest * (n_split - n_full);
+    const int per_whole = (n_whole + 7) / 8, per_big = (total_big + 7) / 8, per_small = (total_small + 7) / 8;
+    const int xcd = static_cast<int>(blockIdx.x % 8);
+    int q = static_cast<int>(blockIdx.x / 8);
+    int item = -1, tile, split = 0;                          // item: index of the partial tile; -1 for a whole tile
+    if (q < per_whole) {
+        tile = xcd * per_whole + q;
+        if (tile >= n_whole) return;
     } else {
-        const int sidx = xcd * per_small + (q - per_big);
-        if (q - per_big >= per_small || sidx >= total_small) return;
-        item = total_big + sidx;
+        q -= per_whole;
+        if (q < per_big) {
+            item = xcd * per_big + q;
+            if (item >= total_big) return;
+        } else {
+            const int sidx = xcd * per_small + (q - per_big);
+            if (q - per_big >= per_small || sidx >= total_small) return;
+            item = total_big + sidx;
+        }
+        split = item / n_rest;
+        tile = n_whole + (item - split * n_rest);
     }
-    const int split = item / n_tiles;
+    const bool whole = item < 0;                             // the same for the whole workgroup
     int I, J;
-    decode_tile(item - split * n_tiles, nb, I, J);
-    const int64_t t_begin = int64_t(split) * t_per_split;
-    const int64_t t_end = min(tokens, t_begin + t_per_split);
+    decode_tile(tile, nb, I, J);
+    const int64_t t_begin = whole ? 0 : int64_t(split) * t_per_split;
+    const int64_t t_end = whole ? tokens : min(tokens, t_begin + t_per_split);
     const int t_len = static_cast<int>(t_end - t_begin);
     const int n_st = t_len > 0 ? (t_len + KT - 1) / KT : 1;  // an empty range still runs one all-zero stage
 
@@ -302,6 +312,47 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gram_tiles_dma(const __half* _
     // holds accumulator registers 4q..4q+3 of block (i, j), so every store instruction writes one
     // contiguous kilobyte per wave; gram_reduce reads it back in the same order.
     static_assert(WGM == 2 && WGN == 2, "register-order partials assume 2 x 2 waves of 4 x 4 blocks");
+    if (whole) {
+        // Straight into H, one row of four 32x32 blocks per pass: the blocks go to a private LDS patch with constant
+        // offsets (the only code that names accumulator registers), then a rolled loop stores each block row by row
+        // (lanes 0..31 take 32 consecutive columns of one row: 128-byte pieces), its mirror image below the diagonal
+        // from the turned patch, and a block on the diagonal with its lower half taken from its upper half, so H is
+        // exactly symmetric.  Blocks below the diagonal of a diagonal tile are their mirror images' business.
+        __builtin_amdgcn_s_barrier();                        // every wave has read its last fragments: the ring is free
+        float* sp = reinterpret_cast<float*>(smem) + wave * (TN * 32 * 33);
+        const int half = lane >> 5, l32 = lane & 31;
+        const int64_t Rw = int64_t(I) * BT + wm * WM, Cw = int64_t(J) * BT + wn * WN;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sp[j * (32 * 33) + acc_row(r, lane) * 33 + l32] = acc[i][j][r];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int64_t R0 = Rw + 32 * i;
+#pragma unroll 1
+            for (int j = 0; j < TN; ++j) {
+                const int64_t C0 = Cw + 32 * j;
+                if (R0 > C0 || R0 >= in || C0 >= in) continue;   // wave-uniform
+                const float* sb = sp + j * (32 * 33);
+                const bool dg = R0 == C0;
+#pragma unroll 1
+                for (int pz = 0; pz < 16; ++pz) {
+                    const int row = 2 * pz + half;
+                    const float up = sb[row * 33 + l32], tr = sb[l32 * 33 + row];
+                    const bool ok_u = R0 + row < in && C0 + l32 < in;
+                    if (ok_u) H[(R0 + row) * in + C0 + l32] = (dg && l32 < row) ? tr : up;
+                    if (!dg && C0 + row < in && R0 + l32 < in) H[(C0 + row) * in + R0 + l32] = tr;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
     float4* dst = reinterpret_cast<float4*>(part + int64_t(item) * (int64_t(BT) * BT));
 #pragma unroll
     for (int i = 0; i < TM; ++i)

@@ -4,12 +4,15 @@
 // into a quadratic form in dW.  It is a symmetric rank-k update whose
 // contraction runs over the tokens, the slow axis of X, so both operands are
 // transposed on their way into LDS.  Only tiles on or above the diagonal are
-// computed; the token range is split over workgroups to fill the chip, each
-// (tile, split) writes an fp32 partial tile, and a second kernel adds the
-// partials in a fixed order, mirrors the result and stores or accumulates H.
+// computed.  As many tiles as fill whole rounds of the chip run over all tokens
+// and store their part of H themselves, both halves; for the others the token
+// range is split over workgroups to fill the last round, each (tile, split)
+// writes an fp32 partial tile, and a second kernel adds the partials in a
+// fixed order, mirrors the result and stores or accumulates H.
 // No atomics: the result is bit-reproducible and exactly symmetric.
 #include "common.h"
 
+#include <algorithm>
 #include <cmath>
 #include "mfma_tile.h"
 #include "gram_dma.h"
@@ -96,7 +99,7 @@ __global__ __launch_bounds__(THREADS) void gram_tiles(const __half* __restrict__
 // that entry, hence to the same bits.
 
 // index of the diagonal tile (I, I) in decode_tile's order
-__device__ __forceinline__ int diag_tile_index(int I, int nb) {
+__host__ __device__ inline int diag_tile_index(int I, int nb) {
     const int s = I >> 2;
     int base = 0;
     for (int t = 0; t < s; ++t) {
@@ -122,20 +125,34 @@ __device__ __forceinline__ float jacobi_scale(float h) {
 template <int BT, bool REGMAJOR = false, bool PREP = false>
 __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ part, int n_tiles, int n_split,
                                                    int nb, int64_t in, float* __restrict__ H, int accumulate,
-                                                   __half* __restrict__ Hs, float* __restrict__ hmeta) {
+                                                   __half* __restrict__ Hs, float* __restrict__ hmeta, int n_whole) {
     constexpr int SB = BT / 32;
     __shared__ float s[32][33];
     __shared__ float s_rd[2][32];                             // PREP: 1/d of the block's rows and columns
-    const int tile = blockIdx.x / (SB * SB), sub = blockIdx.x % (SB * SB);
+    // the grid holds the tiles with partials (n_whole .. n_tiles - 1) and, behind them when PREP, the diagonal tiles
+    // among the whole ones (the first ones in diagonal order: diag_tile_index grows with the tile's row)
+    const int slot = blockIdx.x / (SB * SB), sub = blockIdx.x % (SB * SB);
+    const int tile = slot < n_tiles - n_whole ? n_whole + slot : diag_tile_index(slot - (n_tiles - n_whole), nb);
     int I, J;
     decode_tile(tile, nb, I, J);
     const int sr = sub / SB, sc = sub % SB;
     const int64_t R0 = int64_t(I) * BT + sr * 32, C0 = int64_t(J) * BT + sc * 32;
     if (R0 > C0 || R0 >= in || C0 >= in) return;  // below the diagonal or outside H
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    const float* src = part + int64_t(tile) * (int64_t(BT) * BT);
-    const int64_t split_stride = int64_t(n_tiles) * BT * BT;
-    if constexpr (REGMAJOR) {
+    // The first n_whole tiles are in H already, both halves (the tile kernel ran them over all tokens and stored
+    // them itself): nothing to add up, only the prepared form to derive, from H (here for the diagonal tiles among
+    // them, which also yield hmeta).  The others have n_split partial tiles each.
+    const bool whole = tile < n_whole;
+    if (whole && (!PREP || I != J)) return;                   // prepared form of whole off-diagonal tiles: gram_prep_whole
+    const float* src = part + int64_t(tile - n_whole) * (int64_t(BT) * BT);
+    const int64_t split_stride = int64_t(n_tiles - n_whole) * BT * BT;
+    if (whole) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const int r = ty * 4 + rr;
+            s[r][tx] = (R0 + r < in && C0 + tx < in) ? H[(R0 + r) * in + C0 + tx] : 0.0f;
+        }
+    } else if constexpr (REGMAJOR) {
         static_assert(!REGMAJOR || BT == 256, "register-major partials come from the 256-wide DMA kernel");
         const int wave = (sr >> 2) * 2 + (sc >> 2);
         const int64_t idx = (((sr & 3) * 4 + (sc & 3)) * 4 + (ty >> 1)) * 256 + wave * 64 + (ty & 1) * 32 + tx;
@@ -172,8 +189,13 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
                 } else {
                     off = int64_t(sb * 32 + a) * BT + sb * 32 + a;
                 }
-                const float* dsrc = part + int64_t(diag_tile_index(T, nb)) * (int64_t(BT) * BT) + off;
-                for (int sp = 0; sp < n_split; ++sp) h += dsrc[sp * split_stride];
+                const int dtile = diag_tile_index(T, nb);
+                if (dtile < n_whole) {
+                    h = H[j * in + j];
+                } else {
+                    const float* dsrc = part + int64_t(dtile - n_whole) * (int64_t(BT) * BT) + off;
+                    for (int sp = 0; sp < n_split; ++sp) h += dsrc[sp * split_stride];
+                }
             }
             const float d = jacobi_scale(h);
             s_rd[which][a] = 1.0f / d;                        // exact: a power of two
@@ -207,6 +229,7 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
             if (n < in && k < in) *reinterpret_cast<uint4*>(Hs + score_index(n, k, in, in)) = make_uint4(0, 0, 0, 0);
         }
     }
+    if (whole) return;                                        // H holds the tile already
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
         const int r = ty * 4 + rr;
@@ -221,6 +244,64 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
             const float v = s[tx][r];
             float* p = H + (C0 + r) * in + R0 + tx;
             *p = accumulate ? *p + v : v;
+        }
+    }
+}
+
+// Prepared form of the off-diagonal tiles that the tile kernel stored whole (256 x 256): Hs[n, k] = H[k, n] / (d_n d_k) for the tile's rows k and columns n, and zeros in the mirrored
+// place.  A block takes 32 rows of the tile: it reads 32 x 1 KB of H, turns them through LDS and writes the 16 KB
+// that these 32 k and the tile's 256 n occupy in the scoring layout in one piece, then 8 x 2 KB of zeros.  d comes
+// from hmeta, which gram_reduce has written by then.
+__global__ __launch_bounds__(256) void gram_prep_whole(const float* __restrict__ H, int nb, int64_t in, const float* __restrict__ hmeta,
+                                                       __half* __restrict__ Hs) {
+    constexpr int BT = 256;
+    __shared__ float s[BT][33];
+    __shared__ float s_rk[32];
+    int I, J;
+    decode_tile(blockIdx.x >> 3, nb, I, J);
+    if (I == J) return;
+    const int strip = blockIdx.x & 7, t = threadIdx.x;
+    const int64_t R0 = int64_t(I) * BT + strip * 32, C0 = int64_t(J) * BT;
+    // (a ragged last tile: rows and columns past the end read as zero and are not stored; in % 8 == 0)
+    if (t < 32) s_rk[t] = R0 + t < in ? 1.0f / hmeta[R0 + t] : 1.0f;   // exact: powers of two
+    const float rn = C0 + t < in ? 1.0f / hmeta[C0 + t] : 1.0f;
+    {
+        const int c4 = (t & 63) * 4, r_first = t >> 6;
+        float4 v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            v[q] = (R0 + r_first + 4 * q < in && C0 + c4 < in)
+                       ? *reinterpret_cast<const float4*>(H + (R0 + r_first + 4 * q) * in + C0 + c4)
+                       : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int r = r_first + 4 * q;
+            s[c4][r] = v[q].x; s[c4 + 1][r] = v[q].y; s[c4 + 2][r] = v[q].z; s[c4 + 3][r] = v[q].w;
+        }
+    }
+    __syncthreads();
+    // thread t = column n of the tile: its 32 k are 64 contiguous bytes, the block's 256 n x 64 bytes one 16 KB piece
+    {
+        uint4 o[4];
+        __half2* h = reinterpret_cast<__half2*>(o);
+#pragma unroll
+        for (int e = 0; e < 32; e += 2)
+            h[e / 2] = __floats2half2_rn(s[t][e] * rn * s_rk[e], s[t][e + 1] * rn * s_rk[e + 1]);
+        if (C0 + t < in) {
+            uint4* dst = reinterpret_cast<uint4*>(Hs + score_index(C0 + t, R0, in, in));
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (R0 + 8 * q < in) dst[q] = o[q];
+        }
+    }
+    // zeros above the diagonal: rows n = R0 .. R0 + 31, the tile's 8 column blocks of 32 k, 64 bytes per row and block
+    {
+        const int kb = t >> 5, nl = t & 31;
+        if (R0 + nl < in && C0 + 32 * kb < in) {
+            uint4* dst = reinterpret_cast<uint4*>(Hs + score_index(R0 + nl, C0 + 32 * kb, in, in));
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (C0 + 32 * kb + 8 * q < in) dst[q] = make_uint4(0, 0, 0, 0);
         }
     }
 }
@@ -301,56 +382,90 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         }
     }
     int64_t t_per_split = ((stages + n_split - 1) / n_split) * STAGE;
+    int n_whole = 0;
     if constexpr (BT == 256) {
-        // The 256-wide kernel runs one workgroup per compute unit, 32 per XCD, each XCD working through
-        // its own share of the items, long ones first.  Equal splits leave the last round partly
-        // empty (952 items on 256 units: 3.7 rounds), so the split length is chosen by simulating
-        // that schedule for "n full splits plus a shorter remainder", the remainder's items filling
-        // the gaps of the last round.  Unit: one 32-token stage; an item costs about 12 stages of
-        // prologue and epilogue, a partial tile about 0.1 stage of write and reduction traffic.
+        // The 256-wide kernel runs one workgroup per compute unit, 32 per XCD, each XCD working through its own
+        // share of the items, long ones first.  Equal splits leave the last round partly empty (952 items on 256
+        // units: 3.7 rounds), so the schedule is chosen by simulating it: the first n_whole tiles (a multiple of
+        // 256: whole rounds) run over all tokens and store H themselves, the others get "n full splits plus a
+        // shorter remainder", the remainder's items filling the gaps of the last round.  Unit: one 32-token stage;
+        // an item costs about 12 stages of prologue and epilogue, a partial tile about 0.2 stage of reduction traffic
+        // behind the tile kernel, a whole tile 0.15 (its prepared form is made from H).  Whole tiles need a plain
+        // store (accumulate == 0).
         int hit = -1;
         for (int k = 0; k < ctx->gram_split_n; ++k)
-            if (ctx->gram_split[k].tokens == tokens && ctx->gram_split[k].tiles == n_tiles) hit = k;
+            if (ctx->gram_split[k].tokens == tokens && ctx->gram_split[k].tiles == n_tiles &&
+                ctx->gram_split[k].whole_ok == (accumulate == 0))
+                hit = k;
         if (hit >= 0) {
             t_per_split = ctx->gram_split[hit].t_per_split;
+            n_whole = ctx->gram_split[hit].n_whole;
         } else {
             double best = 0.0;
             int64_t best_per = stages;
-            for (int nf = 1; nf <= 32 && nf <= stages; ++nf) {
-                for (int f = 0; f <= 10; ++f) {
-                    const int64_t per = static_cast<int64_t>(std::ceil(double(stages) / (nf + 0.1 * f)));
-                    if (per <= 0 || stages / per != nf) continue;
-                    const int64_t rem = stages - nf * per;
-                    const int64_t big = (int64_t(n_tiles) * nf + 7) / 8, small = rem > 0 ? (int64_t(n_tiles) + 7) / 8 : 0;
-                    if (big + small > 4096) continue;
-                    double slot[32] = {};                          // finish times of one XCD's 32 units
-                    auto place = [&](double dur) {
-                        int m = 0;
-                        for (int k = 1; k < 32; ++k)
-                            if (slot[k] < slot[m]) m = k;
-                        slot[m] += dur;
-                    };
-                    for (int64_t i = 0; i < big; ++i) place(double(per) + 12.0);
-                    for (int64_t i = 0; i < small; ++i) place(double(rem) + 12.0);
+            int best_whole = 0;
+            const int top = accumulate ? 0 : (n_tiles / 256) * 256;
+            for (int nw = top; nw >= 0 && nw >= top - 512; nw -= 256) {
+                const int n_rest = n_tiles - nw;
+                const int64_t wq = (int64_t(nw) + 7) / 8;
+                double slot0[32] = {};                              // one XCD's 32 units after its whole tiles
+                for (int64_t i = 0; i < wq; ++i) {
+                    int m = 0;
+                    for (int k = 1; k < 32; ++k)
+                        if (slot0[k] < slot0[m]) m = k;
+                    slot0[m] += double(stages) + 12.0;
+                }
+                if (n_rest == 0) {
                     double span = 0.0;
-                    for (int k = 0; k < 32; ++k) span = slot[k] > span ? slot[k] : span;
-                    const double cost = span + 0.10 * double(n_tiles) * double(nf + (rem > 0 ? 1 : 0));
+                    for (int k = 0; k < 32; ++k) span = slot0[k] > span ? slot0[k] : span;
+                    const double cost = span + 0.15 * double(nw);
                     if (best == 0.0 || cost < best) {
                         best = cost;
-                        best_per = per;
+                        best_per = stages;
+                        best_whole = nw;
+                    }
+                    continue;
+                }
+                for (int nf = 1; nf <= 32 && nf <= stages; ++nf) {
+                    for (int f = 0; f <= 10; ++f) {
+                        const int64_t per = static_cast<int64_t>(std::ceil(double(stages) / (nf + 0.1 * f)));
+                        if (per <= 0 || stages / per != nf) continue;
+                        const int64_t rem = stages - nf * per;
+                        const int64_t big = (int64_t(n_rest) * nf + 7) / 8, small = rem > 0 ? (int64_t(n_rest) + 7) / 8 : 0;
+                        if (big + small > 4096) continue;
+                        double slot[32];
+                        for (int k = 0; k < 32; ++k) slot[k] = slot0[k];
+                        auto place = [&](double dur) {
+                            int m = 0;
+                            for (int k = 1; k < 32; ++k)
+                                if (slot[k] < slot[m]) m = k;
+                            slot[m] += dur;
+                        };
+                        for (int64_t i = 0; i < big; ++i) place(double(per) + 12.0);
+                        for (int64_t i = 0; i < small; ++i) place(double(rem) + 12.0);
+                        double span = 0.0;
+                        for (int k = 0; k < 32; ++k) span = slot[k] > span ? slot[k] : span;
+                        const double cost = span + 0.20 * double(n_rest) * double(nf + (rem > 0 ? 1 : 0)) + 0.15 * double(nw);
+                        if (best == 0.0 || cost < best) {
+                            best = cost;
+                            best_per = per;
+                            best_whole = nw;
+                        }
                     }
                 }
             }
             t_per_split = best_per * STAGE;
+            n_whole = best_whole;
             const int slot = ctx->gram_split_next;                  // the oldest entry makes room
-            ctx->gram_split[slot] = {tokens, n_tiles, t_per_split};
+            ctx->gram_split[slot] = {tokens, n_tiles, t_per_split, n_whole, accumulate == 0};
             ctx->gram_split_next = (slot + 1) % 8;
             if (ctx->gram_split_n < 8) ++ctx->gram_split_n;
         }
     }
-    n_split = static_cast<int>((tokens + t_per_split - 1) / t_per_split);
-    const int n_full = static_cast<int>(tokens / t_per_split);       // splits of full length; at most one shorter
-    const size_t part_bytes = size_t(n_split) * n_tiles * BT * BT * sizeof(float);
+    const int n_rest = n_tiles - n_whole;
+    n_split = n_rest > 0 ? static_cast<int>((tokens + t_per_split - 1) / t_per_split) : 0;
+    const int n_full = n_rest > 0 ? static_cast<int>(tokens / t_per_split) : 0;   // splits of full length; at most one shorter
+    const size_t part_bytes = std::max<size_t>(256, size_t(n_split) * n_rest * BT * BT * sizeof(float));
     float* part = static_cast<float*>(adadim_workspace(ctx, WS_HESS_PART, part_bytes));
     if (!part) return ADADIM_EHIP;
 
@@ -374,10 +489,11 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         }
         {
             ProfScope prof(ctx, "gram_tiles");
-            const int per_big = (n_tiles * n_full + 7) / 8, per_small = (n_tiles * (n_split - n_full) + 7) / 8;
-            const unsigned grid = 8u * static_cast<unsigned>(per_big + per_small);
+            const int per_whole = (n_whole + 7) / 8, per_big = (n_rest * n_full + 7) / 8,
+                      per_small = (n_rest * (n_split - n_full) + 7) / 8;
+            const unsigned grid = 8u * static_cast<unsigned>(per_whole + per_big + per_small);
             hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2>), dim3(grid), dim3(256), dma::SMEM_BYTES, ctx->stream, X,
-                               tokens, in, ldx, nb, n_split, n_full, t_per_split, zero16, part);
+                               tokens, in, ldx, nb, n_split, n_full, t_per_split, zero16, part, n_whole, H);
         }
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     } else {
@@ -395,16 +511,27 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     }
     constexpr int SB = BT / 32;
-    {
+    int whole_diag = 0;                                       // diagonal tiles among the whole ones
+    while (Hs && whole_diag < nb && diag_tile_index(whole_diag, nb) < n_whole) ++whole_diag;
+    const unsigned reduce_tiles = static_cast<unsigned>(n_rest + whole_diag);
+    if (reduce_tiles > 0) {
         ProfScope prof(ctx, "gram_reduce");
         if (Hs)
-            hipLaunchKernelGGL((gram_reduce<BT, BT == 256, true>), dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream,
-                               part, n_tiles, n_split, nb, in, H, 0, Hs, hmeta);
+            hipLaunchKernelGGL((gram_reduce<BT, BT == 256, true>), dim3(SB * SB * reduce_tiles), dim3(256), 0, ctx->stream,
+                               part, n_tiles, n_split, nb, in, H, 0, Hs, hmeta, n_whole);
         else
-            hipLaunchKernelGGL((gram_reduce<BT, BT == 256, false>), dim3(SB * SB * n_tiles), dim3(256), 0, ctx->stream,
-                               part, n_tiles, n_split, nb, in, H, accumulate, Hs, hmeta);
+            hipLaunchKernelGGL((gram_reduce<BT, BT == 256, false>), dim3(SB * SB * reduce_tiles), dim3(256), 0, ctx->stream,
+                               part, n_tiles, n_split, nb, in, H, accumulate, Hs, hmeta, n_whole);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gram_reduce");
+    if (Hs && n_whole > 0) {
+        {
+            ProfScope prof(ctx, "gram_prep_whole");
+            hipLaunchKernelGGL(gram_prep_whole, dim3(8u * static_cast<unsigned>(n_whole)), dim3(256), 0, ctx->stream, H, nb, in, hmeta,
+                               Hs);
+        }
+        ADADIM_LAUNCH_CHECK(ctx, "gram_prep_whole");
+    }
     return ADADIM_OK;
 }
 

@@ -170,7 +170,8 @@ def check_hessian(Hg, Href):
     assert np.array_equal(Hg, Hg.T)
 
 
-@pytest.mark.parametrize("tokens,in_f", [(256, 512), (1000, 264), (77, 1288), (4096, 128), (3000, 2056), (1, 64)])
+@pytest.mark.parametrize("tokens,in_f", [(256, 512), (1000, 264), (77, 1288), (4096, 128), (3000, 2056), (1, 64),
+                                         (70, 6144), (200, 6008)])   # the last two: 300 tiles, 256 of them stored whole
 def test_hessian(ctx, tokens, in_f):
     X = synth.make_activations(tokens, in_f, seed=tokens + in_f, n_outliers=3, scale_lo=50, scale_hi=100)
     check_hessian(gpu_hessian(ctx, X), oracle.hessian(X))
@@ -181,6 +182,9 @@ def test_hessian_accumulate_and_pitch(ctx):
     Href = oracle.hessian(X)
     check_hessian(gpu_hessian(ctx, X, accumulate_chunks=3), Href)
     check_hessian(gpu_hessian(ctx, X, ld_pad=24), Href)
+    # wide enough for whole-tile stores: the first chunk takes them, the accumulating second one may not
+    Xw = synth.make_activations(90, 6144, seed=10, n_outliers=4, scale_lo=30, scale_hi=60)
+    check_hessian(gpu_hessian(ctx, Xw, accumulate_chunks=2), oracle.hessian(Xw))
     # tokens == 0 clears H
     H = torch.ones((64, 64), dtype=torch.float32, device="cuda")
     ctx.adadim_hessian(torch.empty((0, 64), dtype=torch.float16, device="cuda"), H)
@@ -394,7 +398,7 @@ def test_shared_input_search(ctx):
 
 
 @pytest.mark.parametrize("tokens,in_f", [(300, 512), (2500, 264), (77, 1288), (5000, 2080), (9000, 4096), (1, 64),
-                                         (0, 256)])
+                                         (0, 256), (130, 6144), (64, 6008)])
 def test_hessian_prepared_equals_the_two_calls(ctx, tokens, in_f):
     """adadim_hessian_prepared against adadim_hessian + adadim_hessian_prepare: H, hmeta and Hs bit for bit (both
     tile widths, one and several token splits, both scoring layouts, ragged last tiles)."""
