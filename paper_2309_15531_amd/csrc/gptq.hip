@@ -412,6 +412,8 @@ __global__ __launch_bounds__(256) void chol_diag_inv(double* __restrict__ A, dou
 __global__ __launch_bounds__(256) void chol_panel(double* __restrict__ A, const double* __restrict__ M, int64_t n,
                                                   int64_t k0, int w) {
     __shared__ double As[GK][GT + 4], Bs[GK][GT + 4];
+    // a link of the chain the factorization waits for: its waves issue ahead of the bulk update's on a shared SIMD
+    __builtin_amdgcn_s_setprio(3);
     const int64_t r0 = k0 + w + int64_t(blockIdx.x) * GT;
     const int m_valid = static_cast<int>(n - r0 < GT ? n - r0 : GT);
     double4_t acc[2][2] = {};
@@ -450,6 +452,7 @@ __global__ __launch_bounds__(256) void chol_syrk(double* __restrict__ A, int64_t
 __global__ __launch_bounds__(256) void chol_syrk_diag(double* __restrict__ A, double* __restrict__ M, int64_t n, int64_t k0, int w,
                                                       int64_t k1) {
     if (blockIdx.x > blockIdx.y) return;
+    __builtin_amdgcn_s_setprio(3);                            // a link of the chain, as chol_panel
     __shared__ __align__(16) char smem[sizeof(DiagLds) > 2 * GK * (GT + 4) * sizeof(double) ? sizeof(DiagLds)
                                                                                              : 2 * GK * (GT + 4) * sizeof(double)];
     double(*As)[GT + 4] = reinterpret_cast<double(*)[GT + 4]>(smem);
