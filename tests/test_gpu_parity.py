@@ -171,7 +171,7 @@ def check_hessian(Hg, Href):
 
 
 @pytest.mark.parametrize("tokens,in_f", [(256, 512), (1000, 264), (77, 1288), (4096, 128), (3000, 2056), (1, 64),
-                                         (70, 6144), (200, 6008)])   # the last two: 300 tiles, 256 of them stored whole
+                                         (70, 6144), (200, 6008), (40, 6016)])   # the last three: 300 tiles, 256 of them stored whole
 def test_hessian(ctx, tokens, in_f):
     X = synth.make_activations(tokens, in_f, seed=tokens + in_f, n_outliers=3, scale_lo=50, scale_hi=100)
     check_hessian(gpu_hessian(ctx, X), oracle.hessian(X))
@@ -398,7 +398,7 @@ def test_shared_input_search(ctx):
 
 
 @pytest.mark.parametrize("tokens,in_f", [(300, 512), (2500, 264), (77, 1288), (5000, 2080), (9000, 4096), (1, 64),
-                                         (0, 256), (130, 6144), (64, 6008)])
+                                         (0, 256), (130, 6144), (64, 6008), (50, 6016)])
 def test_hessian_prepared_equals_the_two_calls(ctx, tokens, in_f):
     """adadim_hessian_prepared against adadim_hessian + adadim_hessian_prepare: H, hmeta and Hs bit for bit (both
     tile widths, one and several token splits, both scoring layouts, ragged last tiles)."""
