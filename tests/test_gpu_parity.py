@@ -99,6 +99,29 @@ def test_quantize_bit_exact(ctx, dim, out_f, in_f, bits, group):
     assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, bits))
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_quantize_random_shapes(ctx, seed):
+    """Seeded random shapes, precisions, group lengths and clip ratios, both dimensions: whatever kernel path the
+    shape selects, every output bit for bit."""
+    rng = np.random.default_rng(1000 + seed)
+    out_f, in_f = 8 * int(rng.integers(4, 120)), 8 * int(rng.integers(4, 160))
+    bits = int(rng.choice([2, 3, 4, 5, 8]))
+    clip = 1.0 if seed % 3 else float(np.float32(rng.uniform(0.6, 1.0)))
+    W = rand_w(out_f, in_f, seed=2000 + seed)
+    for dim in (OC, IC):
+        axis = in_f if dim == OC else out_f
+        fits = [g for g in (8, 16, 32, 64, 128, 256) if axis % g == 0]
+        group = int(rng.choice(fits + [0]))
+        ref = oracle.quantize(W, dim, bits, group, clip)
+        got = gpu_quantize(ctx, W, dim, bits, group, clip)
+        what = f"out={out_f} in={in_f} bits={bits} group={group} dim={dim} clip={clip}"
+        assert np.array_equal(got["scales"].view(np.uint32), ref["scales"].view(np.uint32)), what
+        assert np.array_equal(got["zeros"], ref["zeros"]), what
+        assert np.array_equal(got["codes"], ref["codes"]), what
+        assert np.array_equal(got["dW"], ref["dW"]), what
+        assert np.array_equal(got["packed"], oracle.pack(ref["codes"], dim, bits)), what
+
+
 @pytest.mark.parametrize("dim", [OC, IC])
 @pytest.mark.parametrize("clip", [0.5, 0.7368421, 0.97])
 def test_quantize_clip_and_fp16_outputs(ctx, dim, clip):
