@@ -396,6 +396,28 @@ def test_group_size_sweep(ctx, bits, group):
     _check_winner(ls.scales, ls.zeros, ls.packed, W, dim, bits, group)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_search_random_shapes(ctx, seed):
+    """The whole search on seeded random layer shapes, token counts, precisions and group lengths (ragged tiles of
+    every kernel on the path): both losses against the fp64 oracle, the winner when it is clear, and the winner's
+    stored outputs bit for bit."""
+    rng = np.random.default_rng(3000 + seed)
+    group = int(rng.choice([32, 64, 128]))
+    out_f, in_f = group * int(rng.integers(2, 1536 // group)), group * int(rng.integers(2, 2560 // group))
+    tokens, bits = int(rng.integers(50, 3000)), int(rng.choice([2, 3, 4]))
+    W = rand_w(out_f, in_f, seed=4000 + seed)
+    X = synth.make_activations(tokens, in_f, seed=5000 + seed, n_outliers=int(rng.integers(0, 6)), scale_lo=30, scale_hi=100,
+                               relu=bool(seed & 1))
+    ref = oracle.search(W, X, bits, group)
+    ls, best, dim, clip = run_search(ctx, W, X, bits, group)
+    what = f"out={out_f} in={in_f} tokens={tokens} bits={bits} group={group}"
+    assert ls.losses.cpu().numpy() == pytest.approx(ref["losses"], rel=LOSS_RTOL), what
+    lo, hi = min(ref["losses"]), max(ref["losses"])
+    if (hi - lo) / lo > 0.01:
+        assert best == ref["best"], what
+    _check_winner(ls.scales, ls.zeros, ls.packed, W, dim, bits, group)
+
+
 def test_shared_input_search(ctx):
     """Three layers that see the same input (q, k, v): one H, one scoring launch for all six
     candidates; every layer's losses equal the single-layer search's, winners bit-exact."""
