@@ -923,11 +923,13 @@ __global__ __launch_bounds__(256) void wide_params(const uint32_t* __restrict__ 
 }
 
 // element-wise pass: one thread per 16-byte chunk of W
-template <bool IC, bool SCALED>
+// PB != 0 (per-OC only; 2, 3, 4 or 8 bits, in % 32 == 0): the bit stream is written here too, as in the lane kernel.
+template <bool IC, bool SCALED, int PB = 0>
 __global__ __launch_bounds__(256) void wide_apply(const uint4* __restrict__ W, int64_t out, int cpr, int g,
                                                   int64_t n_groups, const float* __restrict__ par, float qmax,
                                                   uint8_t* __restrict__ codes, void* __restrict__ dW, int dW_dtype,
-                                                  const float* __restrict__ colscale) {
+                                                  const float* __restrict__ colscale, uint32_t* __restrict__ packed) {
+    static_assert(PB == 0 || !IC, "the per-IC stream runs across rows");
     const int64_t c = int64_t(blockIdx.x) * 256 + threadIdx.x;
     const bool valid = c < out * cpr;
     const int64_t row = valid ? c / cpr : 0;
@@ -968,6 +970,12 @@ __global__ __launch_bounds__(256) void wide_apply(const uint4* __restrict__ W, i
     const uint32_t v[4] = {raw.x, raw.y, raw.z, raw.w};
     float k[8];
     quant_k8(v, qc, slow, k);
+    if constexpr (PB != 0) {                                  // all lanes take part in the DPP
+        float q[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) q[i] = k[i] - qc[i].nz;
+        pack8_store<PB>(q, c, valid, packed);
+    }
     if (!valid) return;
     if (codes) {
         uint32_t lo = 0, hi = 0;
@@ -1096,8 +1104,10 @@ void launch_ic_stream(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in,
 }
 
 // wide-group path (see wide_minmax_oc): in % 8 == 0; per-OC also g % 8 == 0
+// pb: bits of the per-OC stream to write into `packed` along with the rest (0: none)
 int launch_wide(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int dim, int g, float clip, float qmax, int mfmt,
-                uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale) {
+                uint8_t* codes, float* scales, uint8_t* zeros, void* dW, int dW_dtype, const float* colscale,
+                int pb = 0, uint32_t* packed = nullptr) {
     const bool ic = dim == ADADIM_DIM_IC;
     const int64_t n_groups = ic ? (out / g) * in : out * (in / g);
     const int cpr = static_cast<int>(in / 8);
@@ -1116,15 +1126,25 @@ int launch_wide(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, int d
     }
     hipLaunchKernelGGL(wide_params, dim3(static_cast<unsigned>((n_groups + 255) / 256)), dim3(256), 0, ctx->stream, part,
                        n_groups, n_pieces, in, ic ? 1 : 0, clip, qmax, 1.0f / qmax, mfmt, par, scales, zeros);
-    if (codes || dW) {
+    if (codes || dW || pb) {
         const unsigned blocks = static_cast<unsigned>((out * cpr + 255) / 256);
         const bool scaled = dW && dW_dtype == ADADIM_DW_F16_SCALED;
         const uint4* W4 = reinterpret_cast<const uint4*>(W);
-#define WIDE_GO(IC, S)                                                                                          \
-    hipLaunchKernelGGL((wide_apply<IC, S>), dim3(blocks), dim3(256), 0, ctx->stream, W4, out, cpr, g, n_groups, \
-                       par, qmax, codes, dW, dW_dtype, colscale)
-        if (ic) { if (scaled) WIDE_GO(true, true); else WIDE_GO(true, false); }
-        else { if (scaled) WIDE_GO(false, true); else WIDE_GO(false, false); }
+#define WIDE_GO(IC, S, PB)                                                                                          \
+    hipLaunchKernelGGL((wide_apply<IC, S, PB>), dim3(blocks), dim3(256), 0, ctx->stream, W4, out, cpr, g, n_groups, \
+                       par, qmax, codes, dW, dW_dtype, colscale, packed)
+#define WIDE_OC(PB)                                                                                                 \
+    do {                                                                                                            \
+        if (scaled) WIDE_GO(false, true, PB);                                                                       \
+        else WIDE_GO(false, false, PB);                                                                             \
+    } while (0)
+        if (ic) { if (scaled) WIDE_GO(true, true, 0); else WIDE_GO(true, false, 0); }
+        else if (pb == 2) WIDE_OC(2);
+        else if (pb == 3) WIDE_OC(3);
+        else if (pb == 4) WIDE_OC(4);
+        else if (pb == 8) WIDE_OC(8);
+        else WIDE_OC(0);
+#undef WIDE_OC
 #undef WIDE_GO
     }
     return ADADIM_OK;
@@ -1206,8 +1226,10 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
                           out <= 16 * 65535;
     const bool ic_stream = dim == ADADIM_DIM_IC && vec && (g % 8) == 0 && lpg <= 32 && (lpg & (lpg - 1)) == 0;
     // the fast kernels assemble the bit stream themselves for these widths
+    const bool oc_wide = dim == ADADIM_DIM_OC && !oc_lanes && vec && (g % 8) == 0 && g >= 512 &&
+                         out * (in / g) <= (int64_t(1) << 30);
     const bool fused_pack =
-        packed && ((oc_lanes && (in % 32) == 0 && (bits == 2 || bits == 3 || bits == 4 || bits == 8)) ||
+        packed && (((oc_lanes || oc_wide) && (in % 32) == 0 && (bits == 2 || bits == 3 || bits == 4 || bits == 8)) ||
                    (ic_stream && ic_stream_pack_ok(lpg, bits)));
     if (packed && !fused_pack && !codes) {
         codes = static_cast<uint8_t*>(adadim_workspace(ctx, WS_CODES, size_t(out) * size_t(in)));
@@ -1223,8 +1245,9 @@ int launch_quantize(adadim_ctx* ctx, const __half* W, int64_t out, int64_t in, i
 #undef OC_CASE
             }
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_fast");
-        } else if (vec && (g % 8) == 0 && g >= 512 && out * (in / g) <= (int64_t(1) << 30)) {
-            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale);
+        } else if (oc_wide) {
+            const int rc = launch_wide(ctx, W, out, in, dim, g, clip, qmax, mfmt, codes, scales, zeros, dW, dW_dtype, colscale,
+                                       fused_pack ? bits : 0, fused_pack ? packed : nullptr);
             if (rc != ADADIM_OK) return rc;
             ADADIM_LAUNCH_CHECK(ctx, "quant_oc_wide");
         } else {

@@ -80,6 +80,10 @@ QUANT_CASES = [
     (100, 70, 4, 10),           # in % 8 != 0 -> scalar paths for both dims
     (128, 128, 3, 16),
     (64, 4096, 3, 32),
+    (72, 1024, 3, 0),           # wide groups: three passes, the per-OC bit stream written by the last
+    (64, 2048, 2, 1024),
+    (40, 1536, 8, 768),
+    (48, 1056, 4, 528),
 ]
 
 
