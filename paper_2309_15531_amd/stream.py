@@ -15,6 +15,7 @@ Call order and bookkeeping only; all arithmetic happens in libadadim.so.
 from __future__ import annotations
 
 import json
+import math
 import os
 
 
@@ -216,8 +217,13 @@ class BlockSearch:
         for name, bits in self._launched[slot]:
             r = self.slot_of[(name, bits)]
             l = self.h_losses[slot][r].tolist()
-            out.append({"layer": name, "bits": int(bits), "dim": "ic" if int(self.h_best[slot][r]) == 1 else "oc",
-                        "L_oc": float(l[0]), "L_ic": float(l[1])})
+            rec = {"layer": name, "bits": int(bits), "dim": "ic" if int(self.h_best[slot][r]) == 1 else "oc",
+                   "L_oc": float(l[0]), "L_ic": float(l[1])}
+            if not (math.isfinite(l[0]) and math.isfinite(l[1])):
+                # |dW| sqrt(H_jj) left fp16's range for some column (the header of adadim_hessian_prepare gives the
+                # range): the choice between the two dimensions is then not to be trusted
+                rec["nonfinite_loss"] = True
+            out.append(rec)
         return out
 
     def outputs(self, name: str, dim: int):

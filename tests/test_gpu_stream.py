@@ -116,3 +116,27 @@ def test_two_blocks_streamed_and_resumed(tmp_path):
     finally:
         torch.cuda.synchronize()
         ctx.close()
+
+
+def test_records_flag_losses_outside_the_scoring_range():
+    """A column whose |dW| sqrt(H_jj) exceeds fp16's largest number makes the scoring operand infinite: the block
+    search's record then says so instead of passing a choice on silently; an ordinary layer carries no flag."""
+    out_f, in_f, tokens, bits, group = 256, 512, 4096, 3, 128
+    ctx = B.Context()
+    try:
+        bs = ST.BlockSearch(ctx, {"fine": (out_f, in_f)}, (bits,), group)
+        rng = np.random.default_rng(5)
+        W = (rng.standard_normal((out_f, in_f)) * 0.02).astype(np.float16)
+        X = rng.standard_normal((tokens, in_f)).astype(np.float16)
+        for huge in (False, True):
+            Wd, Xd = torch.from_numpy(W).cuda(), torch.from_numpy(X).cuda()
+            if huge:
+                Wd[:, 7] *= 30000.0                               # |dW| in the hundreds in this column ...
+                Xd[:, 7] = torch.sign(Xd[:, 7]) * 30000.0         # ... against sqrt(H_77) ~ 2e6
+                assert torch.isfinite(Wd).all() and torch.isfinite(Xd).all()
+            bs.hessians({in_f: Xd})
+            bs.launch(0, {"fine": Wd})
+            rec, = bs.collect(0)
+            assert rec.get("nonfinite_loss", False) == huge, rec
+    finally:
+        ctx.close()
