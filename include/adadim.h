@@ -169,21 +169,21 @@ int adadim_quantize_both(adadim_ctx* ctx, const void* W, int64_t out, int64_t in
 
 /*
  * Prepares H for scoring on the matrix cores.  With the power-of-two column
- * scales d_j ~ sqrt(H_jj):
+ * scales d_j = 2^(round(log2(H_jj)/2) - 6), i.e. about sqrt(H_jj)/64 (1 where H_jj <= 0):
  *   Hs     fp16 [in, in] in the scoring layout (adadim_score_elems(in, in) elements):
  *          Hs[n,k] = H[n,k]/(d_n d_k) for k < n, 0 elsewhere
  *   hmeta  f32  [2, in]:  hmeta[0,j] = d_j (the colscale of adadim_quantize),
  *                         hmeta[1,j] = H_jj
  * so that tr(dW H dW^T) = sum_o ( sum_j H_jj dW_oj^2 + 2 sum_{k<n} dW'_ok Hs_nk dW'_on ),
- * dW'_oj = dW_oj d_j.  The scaling keeps |Hs| <= 2 whatever the activation
+ * dW'_oj = dW_oj d_j.  The scaling keeps |Hs| <= 2^13 whatever the activation
  * outliers are.  Hs 16-byte aligned; in a multiple of 8.
  * Range: dW' is fp16, so a candidate is scored accurately while |dW_oj| sqrt(H_jj) lies
- * inside fp16's normal range, 6e-5 .. 6e4, for the entries that matter (an entry's share of
- * the loss is about that number squared).  With N(0, 0.02^2) weights, 65536 tokens and x100
- * outlier channels the largest products are near 3e2: activations up to 2^7 times larger or
- * 2^10 times smaller than that stay inside.  Beyond the upper end dW' becomes inf and the
- * loss inf or NaN, which never wins the selection (adadim_select); beyond the lower end
- * small entries are rounded to fp16 subnormals or zero and the loss reads low.
+ * between 4e-3 and 4e6 for the entries that matter (an entry's share of the loss is about
+ * that number squared).  With N(0, 0.02^2) weights, 65536 tokens and x100 outlier channels
+ * the largest products are near 3e2 and the ordinary columns' near 1: activations 2^13 times
+ * larger (fp16 cannot hold them) or 2^8 times smaller stay inside.  Beyond the upper end dW'
+ * becomes inf and the loss inf or NaN, which never wins the selection (adadim_select); beyond
+ * the lower end small entries are rounded to fp16 subnormals or zero and the loss reads low.
  */
 int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs, float* hmeta);
 

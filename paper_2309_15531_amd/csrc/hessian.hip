@@ -110,12 +110,16 @@ __host__ __device__ inline int diag_tile_index(int I, int nb) {
     return base + c * (c + 1) / 2 + c;
 }
 
-// d = 2^round(log2(h)/2) (1 if h <= 0): any power of two near sqrt(h) serves; the exponent is clamped
-// so that d, 1/d and d*d stay normal fp32 numbers
+// d = 2^(round(log2(h)/2) - 6) (1 if h <= 0): a power of two near sqrt(h) / 64.  Any power of two serves (the
+// scaling is undone exactly); this one splits fp16's 30 binades between the two scoring operands so that neither
+// leaves them for any fp16 input: Hs = H / (d d) stays below 2^13, and dW' = dW d stays finite up to
+// |dW| sqrt(h) = 4e6, which weights of ordinary size do not reach even on activations at fp16's largest value
+// in every token.  The exponent is clamped so that d, 1/d and d*d stay normal fp32 numbers.
+constexpr int SCORE_SHIFT = 6;
 __device__ __forceinline__ float jacobi_scale(float h) {
     float d = 1.0f;
     if (h > 0.0f && h < 3.0e38f) {
-        int e = static_cast<int>(rintf(0.5f * log2f(h)));
+        int e = static_cast<int>(rintf(0.5f * log2f(h))) - SCORE_SHIFT;
         e = max(-30, min(30, e));
         d = ldexpf(1.0f, e);
     }

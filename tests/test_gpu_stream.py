@@ -119,7 +119,7 @@ def test_two_blocks_streamed_and_resumed(tmp_path):
 
 
 def test_records_flag_losses_outside_the_scoring_range():
-    """A column whose |dW| sqrt(H_jj) exceeds fp16's largest number makes the scoring operand infinite: the block
+    """A column whose |dW| sqrt(H_jj) / 64 exceeds fp16's largest number makes the scoring operand infinite: the block
     search's record then says so instead of passing a choice on silently; an ordinary layer carries no flag."""
     out_f, in_f, tokens, bits, group = 256, 512, 4096, 3, 128
     ctx = B.Context()
