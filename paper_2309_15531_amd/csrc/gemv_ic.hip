@@ -23,11 +23,13 @@
 namespace {
 
 constexpr int GV_WAVES = 8, GV_OUT_PER_BLOCK = 64 * 32;
-// Two blocks fit a compute unit (registers and LDS), 512 on the chip.  The columns are dealt to
-// blocks so that one launch is a whole number of such rounds as nearly as can be: a grid a little
-// larger than that would run a second, mostly empty round (576 blocks took two rounds for the work
-// of 1.1), and the kernel is short enough for that to cost a third of its time.
-constexpr int GV_BLOCK_SLOTS = 512, GV_MIN_COLS_PER_WAVE = 32;
+// One block per compute unit, 256 on the chip (two would fit by registers and LDS, but half as many blocks with
+// twice the columns each are 5 % faster on the App. D shape: half the dispatches, half the partial sums, and eight
+// waves with two steps in flight each already keep the memory system busy).  The columns are dealt to blocks so
+// that one launch is a whole number of such rounds as nearly as can be: a grid a little larger than that would run
+// a second, mostly empty round, and the kernel is short enough for that to cost a third of its time.
+constexpr int GV_BLOCK_SLOTS = 256, GV_MIN_COLS_PER_WAVE = 32;
+constexpr int GV_NBUF = 3;                 // load buffers taken in turn (4 to 6 were measured: no faster)
 
 template <int PB>
 struct Words {
@@ -165,20 +167,19 @@ __global__ __launch_bounds__(64 * GV_WAVES, 4) void gemv_ic_tiles(const uint32_t
         }
     };
     if (valid && j_begin < j_end) {
-        // three buffers, no copies: one is consumed while the other two are in flight (two steps of 2 to 4 KB per
-        // wave are too little to keep the memory system busy with 2- and 3-bit codes).  Fetches past the end
+        // GV_NBUF buffers taken in turn, no copies: one is consumed while the others are in flight (a step is 2 to
+        // 4 KB per wave; the memory system wants several of them outstanding per wave).  Fetches past the end
         // re-read the chunk's last columns and are not consumed.
         const int64_t j_last = j_end - 4;
-        Step A, B2, C;
-        fetch(A, j_begin);
-        fetch(B2, min(j_begin + 4, j_last));
-        for (int64_t j0 = j_begin; j0 < j_end; j0 += 12) {   // in % 4 == 0
-            fetch(C, min(j0 + 8, j_last));
-            consume(A);
-            fetch(A, min(j0 + 12, j_last));
-            if (j0 + 4 < j_end) consume(B2);
-            fetch(B2, min(j0 + 16, j_last));
-            if (j0 + 8 < j_end) consume(C);
+        Step st[GV_NBUF];
+#pragma unroll
+        for (int b = 0; b < GV_NBUF - 1; ++b) fetch(st[b], min(j_begin + 4 * b, j_last));
+        for (int64_t j0 = j_begin; j0 < j_end; j0 += 4 * GV_NBUF) {   // in % 4 == 0
+#pragma unroll
+            for (int b = 0; b < GV_NBUF; ++b) {
+                fetch(st[(b + GV_NBUF - 1) % GV_NBUF], min(j0 + 4 * (b + GV_NBUF - 1), j_last));
+                if (j0 + 4 * b < j_end) consume(st[b]);
+            }
         }
     }
     // OFFSET: the codes were read as code + code_offset(k)
