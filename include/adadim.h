@@ -189,7 +189,8 @@ int adadim_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, void* Hs
 
 /*
  * adadim_hessian (accumulate = 0) and adadim_hessian_prepare in one call: the pass that adds up the Gram
- * matrix's token-split partial tiles also writes Hs and hmeta, so H is not read back.  Same outputs, bit for
+ * matrix's token-split partial tiles also writes Hs and hmeta for those tiles, and the tiles that were formed
+ * whole get theirs from one read of their block of H, not of the full matrix.  Same outputs, bit for
  * bit, as the two calls one after the other.  For a calibration set fed in chunks use adadim_hessian with
  * accumulate = 1 and adadim_hessian_prepare after the last chunk.
  */
