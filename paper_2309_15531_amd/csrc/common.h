@@ -10,6 +10,7 @@
 #include <mutex>
 
 #include "../../include/adadim.h"
+#include "gram_plan.h"
 
 // Scratch slots owned by a context; each grows on demand and is reused.
 enum {
@@ -60,9 +61,10 @@ struct adadim_ctx {
     void* ws[WS_COUNT];
     size_t ws_bytes[WS_COUNT];
     size_t zero_ready_bytes;         // size of WS_ZERO when it was last cleared
-    // Gram split lengths already chosen, keyed by (token count, tile count): choosing one simulates the launch's
-    // schedule (tens of milliseconds of host time), and a model driver alternates between a few input widths
-    struct GramSplit { int64_t tokens; int tiles; int64_t t_per_split; int n_whole; bool whole_ok; } gram_split[8];
+    // Gram launch plans already chosen, keyed by (token count, tile count, whether whole tiles may store): choosing
+    // one simulates the launch's schedule (milliseconds of host time), and a model driver alternates between a few
+    // input widths
+    struct GramSplit { GramPlan plan; GramOrder order; bool whole_ok; } gram_split[8];
     int gram_split_n, gram_split_next;
     bool capturing;                  // between adadim_capture_begin and adadim_capture_end
     hipStream_t side;                // second stream for work that may overlap the main one (created on first use)

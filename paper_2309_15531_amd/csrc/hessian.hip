@@ -127,14 +127,15 @@ __device__ __forceinline__ float jacobi_scale(float h) {
 }
 
 template <int BT, bool REGMAJOR = false, bool PREP = false>
-__global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ part, int n_tiles, int n_split,
-                                                   int nb, int64_t in, float* __restrict__ H, int accumulate,
-                                                   __half* __restrict__ Hs, float* __restrict__ hmeta, int n_whole) {
+__global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ part, GramPlan plan, int nb, int64_t in,
+                                                   float* __restrict__ H, int accumulate, __half* __restrict__ Hs,
+                                                   float* __restrict__ hmeta) {
     constexpr int SB = BT / 32;
     __shared__ float s[32][33];
     __shared__ float s_rd[2][32];                             // PREP: 1/d of the block's rows and columns
     // the grid holds the tiles with partials (n_whole .. n_tiles - 1) and, behind them when PREP, the diagonal tiles
     // among the whole ones (the first ones in diagonal order: diag_tile_index grows with the tile's row)
+    const int n_tiles = plan.n_tiles, n_whole = plan.n_whole;
     const int slot = blockIdx.x / (SB * SB), sub = blockIdx.x % (SB * SB);
     const int tile = slot < n_tiles - n_whole ? n_whole + slot : diag_tile_index(slot - (n_tiles - n_whole), nb);
     int I, J;
@@ -145,11 +146,24 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     // The first n_whole tiles are in H already, both halves (the tile kernel ran them over all tokens and stored
     // them itself): nothing to add up, only the prepared form to derive, from H (here for the diagonal tiles among
-    // them, which also yield hmeta).  The others have n_split partial tiles each.
+    // them, which also yield hmeta).  The others have the plan's partial tiles, added in the order of their tokens.
     const bool whole = tile < n_whole;
     if (whole && (!PREP || I != J)) return;                   // prepared form of whole off-diagonal tiles: gram_prep_whole
-    const float* src = part + int64_t(tile - n_whole) * (int64_t(BT) * BT);
-    const int64_t split_stride = int64_t(n_tiles - n_whole) * BT * BT;
+    // A tile's partials are two runs of slots with a constant stride each: the full pieces (one per split, a
+    // split apart) and the pieces of the rest (next to each other).
+    constexpr int64_t TILE = int64_t(BT) * BT;
+    struct Runs { const float* a; int na; int64_t sa; const float* b; int nb; };
+    auto runs_of = [&](int tile_r) {
+        const int n = gram_plan_parts(plan, tile_r);
+        Runs r;
+        r.a = part + int64_t(tile_r) * TILE;
+        r.na = plan.n_full;
+        r.sa = int64_t(gram_plan_rest(plan)) * TILE;
+        r.nb = n - plan.n_full;
+        r.b = r.nb > 0 ? part + int64_t(gram_plan_slot(plan, tile_r, plan.n_full)) * TILE : part;
+        return r;
+    };
+    const Runs mine = whole ? Runs{part, 0, 0, part, 0} : runs_of(tile - n_whole);
     if (whole) {
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
@@ -161,8 +175,12 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
         const int wave = (sr >> 2) * 2 + (sc >> 2);
         const int64_t idx = (((sr & 3) * 4 + (sc & 3)) * 4 + (ty >> 1)) * 256 + wave * 64 + (ty & 1) * 32 + tx;
         float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        for (int sp = 0; sp < n_split; ++sp) {
-            const float4 p = *reinterpret_cast<const float4*>(src + sp * split_stride + idx * 4);
+        for (int sp = 0; sp < mine.na; ++sp) {
+            const float4 p = *reinterpret_cast<const float4*>(mine.a + sp * mine.sa + idx * 4);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+        }
+        for (int sp = 0; sp < mine.nb; ++sp) {
+            const float4 p = *reinterpret_cast<const float4*>(mine.b + sp * TILE + idx * 4);
             v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
         }
         s[ty * 4 + 0][tx] = v.x;
@@ -174,7 +192,9 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
         for (int rr = 0; rr < 4; ++rr) {
             const int r = ty * 4 + rr;
             float v = 0.0f;
-            for (int sp = 0; sp < n_split; ++sp) v += src[sp * split_stride + (sr * 32 + r) * BT + sc * 32 + tx];
+            const int64_t at = (sr * 32 + r) * BT + sc * 32 + tx;
+            for (int sp = 0; sp < mine.na; ++sp) v += mine.a[sp * mine.sa + at];
+            for (int sp = 0; sp < mine.nb; ++sp) v += mine.b[sp * TILE + at];
             s[r][tx] = v;
         }
     }
@@ -197,8 +217,9 @@ __global__ __launch_bounds__(256) void gram_reduce(const float* __restrict__ par
                 if (dtile < n_whole) {
                     h = H[j * in + j];
                 } else {
-                    const float* dsrc = part + int64_t(dtile - n_whole) * (int64_t(BT) * BT) + off;
-                    for (int sp = 0; sp < n_split; ++sp) h += dsrc[sp * split_stride];
+                    const Runs dg = runs_of(dtile - n_whole);
+                    for (int sp = 0; sp < dg.na; ++sp) h += dg.a[sp * dg.sa + off];
+                    for (int sp = 0; sp < dg.nb; ++sp) h += dg.b[sp * TILE + off];
                 }
             }
             const float d = jacobi_scale(h);
@@ -367,109 +388,46 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
              __half* Hs, float* hmeta) {
     const int nb = static_cast<int>((in + BT - 1) / BT);
     const int n_tiles = nb * (nb + 1) / 2;
-    // Token split: every (tile, split) is one workgroup and one workgroup fits a compute unit, so
-    // the tile kernel runs in about ceil(workgroups / 256) rounds of stages/n_split stages each,
-    // while every split adds one partial tile per tile to write and to read back.  Take the split
-    // count with the lowest estimate (unit: the time of one 32-token stage; a 256x256 partial
-    // costs about a fifth of that per split in traffic).
-    constexpr int STAGE = BT == 256 ? dma::KT : KT;
-    const int64_t stages = (tokens + STAGE - 1) / STAGE;
-    int n_split = 1;
-    double best_cost = 0.0;
-    for (int n = 1; n <= 32 && n <= stages; ++n) {
-        const int64_t per = (stages + n - 1) / n;
-        const int64_t rounds = (int64_t(n_tiles) * n + 255) / 256;
-        const double cost = double(rounds) * double(per) + 0.19 * double(n) * double(n_tiles) * (BT * BT / 65536.0);
-        if (n == 1 || cost < best_cost) {
-            best_cost = cost;
-            n_split = n;
-        }
-    }
-    int64_t t_per_split = ((stages + n_split - 1) / n_split) * STAGE;
-    int n_whole = 0;
+    // The 128-wide kernel takes a grid of (tile, token split): about ceil(workgroups / 256) rounds of stages/n_split
+    // stages each, while every split adds one partial tile per tile to write and to read back.  Take the split
+    // count with the lowest estimate (unit: the time of one stage; a partial costs about a fifth of that per split
+    // in traffic).  The 256-wide kernel's launch is planned by simulation (gram_plan.h); plans are kept per context.
+    GramPlan plan;
+    const GramOrder* order = nullptr;
     if constexpr (BT == 256) {
-        // The 256-wide kernel runs one workgroup per compute unit, 32 per XCD, each XCD working through its own
-        // share of the items, long ones first.  Equal splits leave the last round partly empty (952 items on 256
-        // units: 3.7 rounds), so the schedule is chosen by simulating it: the first n_whole tiles (a multiple of
-        // 256: whole rounds) run over all tokens and store H themselves, the others get "n full splits plus a
-        // shorter remainder", the remainder's items filling the gaps of the last round.  Unit: one 32-token stage;
-        // an item costs about 12 stages of prologue and epilogue, a partial tile about 0.2 stage of reduction traffic
-        // behind the tile kernel, a whole tile 0.15 (its prepared form is made from H).  Whole tiles need a plain
-        // store (accumulate == 0).
         int hit = -1;
         for (int k = 0; k < ctx->gram_split_n; ++k)
-            if (ctx->gram_split[k].tokens == tokens && ctx->gram_split[k].tiles == n_tiles &&
+            if (ctx->gram_split[k].plan.tokens == tokens && ctx->gram_split[k].plan.n_tiles == n_tiles &&
                 ctx->gram_split[k].whole_ok == (accumulate == 0))
                 hit = k;
-        if (hit >= 0) {
-            t_per_split = ctx->gram_split[hit].t_per_split;
-            n_whole = ctx->gram_split[hit].n_whole;
-        } else {
-            double best = 0.0;
-            int64_t best_per = stages;
-            int best_whole = 0;
-            const int top = accumulate ? 0 : (n_tiles / 256) * 256;
-            for (int nw = top; nw >= 0 && nw >= top - 512; nw -= 256) {
-                const int n_rest = n_tiles - nw;
-                const int64_t wq = (int64_t(nw) + 7) / 8;
-                double slot0[32] = {};                              // one XCD's 32 units after its whole tiles
-                for (int64_t i = 0; i < wq; ++i) {
-                    int m = 0;
-                    for (int k = 1; k < 32; ++k)
-                        if (slot0[k] < slot0[m]) m = k;
-                    slot0[m] += double(stages) + 12.0;
-                }
-                if (n_rest == 0) {
-                    double span = 0.0;
-                    for (int k = 0; k < 32; ++k) span = slot0[k] > span ? slot0[k] : span;
-                    const double cost = span + 0.15 * double(nw);
-                    if (best == 0.0 || cost < best) {
-                        best = cost;
-                        best_per = stages;
-                        best_whole = nw;
-                    }
-                    continue;
-                }
-                for (int nf = 1; nf <= 32 && nf <= stages; ++nf) {
-                    for (int f = 0; f <= 10; ++f) {
-                        const int64_t per = static_cast<int64_t>(std::ceil(double(stages) / (nf + 0.1 * f)));
-                        if (per <= 0 || stages / per != nf) continue;
-                        const int64_t rem = stages - nf * per;
-                        const int64_t big = (int64_t(n_rest) * nf + 7) / 8, small = rem > 0 ? (int64_t(n_rest) + 7) / 8 : 0;
-                        if (big + small > 4096) continue;
-                        double slot[32];
-                        for (int k = 0; k < 32; ++k) slot[k] = slot0[k];
-                        auto place = [&](double dur) {
-                            int m = 0;
-                            for (int k = 1; k < 32; ++k)
-                                if (slot[k] < slot[m]) m = k;
-                            slot[m] += dur;
-                        };
-                        for (int64_t i = 0; i < big; ++i) place(double(per) + 12.0);
-                        for (int64_t i = 0; i < small; ++i) place(double(rem) + 12.0);
-                        double span = 0.0;
-                        for (int k = 0; k < 32; ++k) span = slot[k] > span ? slot[k] : span;
-                        const double cost = span + 0.20 * double(n_rest) * double(nf + (rem > 0 ? 1 : 0)) + 0.15 * double(nw);
-                        if (best == 0.0 || cost < best) {
-                            best = cost;
-                            best_per = per;
-                            best_whole = nw;
-                        }
-                    }
-                }
-            }
-            t_per_split = best_per * STAGE;
-            n_whole = best_whole;
-            const int slot = ctx->gram_split_next;                  // the oldest entry makes room
-            ctx->gram_split[slot] = {tokens, n_tiles, t_per_split, n_whole, accumulate == 0};
-            ctx->gram_split_next = (slot + 1) % 8;
+        if (hit < 0) {
+            hit = ctx->gram_split_next;                             // the oldest entry makes room
+            ctx->gram_split[hit].plan = gram_plan_choose(tokens, n_tiles, accumulate == 0);
+            gram_plan_order(ctx->gram_split[hit].plan, ctx->gram_split[hit].order);
+            ctx->gram_split[hit].whole_ok = accumulate == 0;
+            ctx->gram_split_next = (hit + 1) % 8;
             if (ctx->gram_split_n < 8) ++ctx->gram_split_n;
         }
+        plan = ctx->gram_split[hit].plan;
+        order = &ctx->gram_split[hit].order;
+    } else {
+        const int64_t stages = (tokens + KT - 1) / KT;
+        int n_split = 1;
+        double best_cost = 0.0;
+        for (int n = 1; n <= 32 && n <= stages; ++n) {
+            const int64_t per = (stages + n - 1) / n;
+            const int64_t rounds = (int64_t(n_tiles) * n + 255) / 256;
+            const double cost = double(rounds) * double(per) + 0.19 * double(n) * double(n_tiles) * (BT * BT / 65536.0);
+            if (n == 1 || cost < best_cost) {
+                best_cost = cost;
+                n_split = n;
+            }
+        }
+        const int64_t t_per_split = ((stages + n_split - 1) / n_split) * KT;
+        plan = {n_tiles, 0, static_cast<int>(tokens / t_per_split), 0, 1, tokens, t_per_split, KT};
     }
-    const int n_rest = n_tiles - n_whole;
-    n_split = n_rest > 0 ? static_cast<int>((tokens + t_per_split - 1) / t_per_split) : 0;
-    const int n_full = n_rest > 0 ? static_cast<int>(tokens / t_per_split) : 0;   // splits of full length; at most one shorter
-    const size_t part_bytes = std::max<size_t>(256, size_t(n_split) * n_rest * BT * BT * sizeof(float));
+    const int n_whole = plan.n_whole, n_rest = n_tiles - n_whole;
+    const size_t part_bytes = std::max<size_t>(256, size_t(gram_plan_slots(plan)) * BT * BT * sizeof(float));
     float* part = static_cast<float*>(adadim_workspace(ctx, WS_HESS_PART, part_bytes));
     if (!part) return ADADIM_EHIP;
 
@@ -493,11 +451,10 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         }
         {
             ProfScope prof(ctx, "gram_tiles");
-            const int per_whole = (n_whole + 7) / 8, per_big = (n_rest * n_full + 7) / 8,
-                      per_small = (n_rest * (n_split - n_full) + 7) / 8;
-            const unsigned grid = 8u * static_cast<unsigned>(per_whole + per_big + per_small);
-            hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2>), dim3(grid), dim3(256), dma::SMEM_BYTES, ctx->stream, X,
-                               tokens, in, ldx, nb, n_split, n_full, t_per_split, zero16, part, n_whole, H);
+            // 32 workgroups per XCD walking their own items, or one workgroup per item where there is no order
+            const unsigned grid = 8u * static_cast<unsigned>(order->n ? 32 : gram_plan_per_xcd(plan));
+            hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2>), dim3(grid), dim3(256), dma::SMEM_BYTES, ctx->stream, X, in,
+                               ldx, nb, plan, *order, zero16, part, H);
         }
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     } else {
@@ -509,8 +466,9 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         }));
         {
             ProfScope prof(ctx, "gram_tiles");
+            const int n_split = plan.n_full + (gram_plan_has_rem(plan) ? 1 : 0);   // partial [split][tile]: the plan's slots
             hipLaunchKernelGGL(gram_tiles<BT>, dim3(n_tiles, n_split), dim3(THREADS), smem, ctx->stream, X, tokens,
-                               in, ldx, nb, t_per_split, part);
+                               in, ldx, nb, plan.t_per_split, part);
         }
         ADADIM_LAUNCH_CHECK(ctx, "gram_tiles");
     }
@@ -522,10 +480,10 @@ int run_gram(adadim_ctx* ctx, const __half* X, int64_t tokens, int64_t in, int64
         ProfScope prof(ctx, "gram_reduce");
         if (Hs)
             hipLaunchKernelGGL((gram_reduce<BT, BT == 256, true>), dim3(SB * SB * reduce_tiles), dim3(256), 0, ctx->stream,
-                               part, n_tiles, n_split, nb, in, H, 0, Hs, hmeta, n_whole);
+                               part, plan, nb, in, H, 0, Hs, hmeta);
         else
             hipLaunchKernelGGL((gram_reduce<BT, BT == 256, false>), dim3(SB * SB * reduce_tiles), dim3(256), 0, ctx->stream,
-                               part, n_tiles, n_split, nb, in, H, accumulate, Hs, hmeta, n_whole);
+                               part, plan, nb, in, H, accumulate, Hs, hmeta);
     }
     ADADIM_LAUNCH_CHECK(ctx, "gram_reduce");
     if (Hs && n_whole > 0) {

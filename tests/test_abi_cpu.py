@@ -191,6 +191,28 @@ def test_code_field_plan_on_the_host(tmp_path):
     assert "2 bits: 0, 3 bits: 0, 4 bits: 0 mismatches" in res.stdout
 
 
+def test_gram_launch_plans_cover_every_tile_once(tmp_path):
+    """csrc/gram_plan.h (which workgroup of the Gram kernel runs which tile over which tokens, and where its partial
+    tile goes): for the plans the library chooses over many shapes, and for hand-made ones at the corners of the
+    arithmetic, every tile is taken whole once or covered by its pieces exactly once, no two pieces share a
+    partial slot, and the reduction reads exactly the slots the pieces wrote.  The chosen plan for the 4096-wide
+    layer at 65536 tokens must keep the 32 units of an XCD within 5 % of the even share."""
+    import shutil
+    import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler")
+    exe = tmp_path / "gram_plan_check"
+    src = os.path.join(ROOT, "tests", "host", "gram_plan_check.cpp")
+    subprocess.run(["g++", "-O2", "-std=c++17", src, "-o", str(exe)], check=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout
+    assert " 0 mistakes" in res.stdout
+    res = subprocess.run([str(exe), "65536", "4096"], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout
+    share = [float(m) for m in re.findall(r"even share \d+ \(([0-9.]+)\)", res.stdout)]
+    assert len(share) == 2 and min(share) >= 0.95, res.stdout
+
+
 def test_product_does_not_import_oracle():
     """The product package must never reach into the oracle (and vice versa)."""
     pkg = os.path.join(ROOT, "paper_2309_15531_amd")
@@ -255,7 +277,7 @@ def test_binding_refuses_tensors_the_library_would_misread():
 
 
 def test_host_checks_under_sanitizers(tmp_path):
-    """The host builds of the device headers (fast division, code-field plan) compiled with the address and
+    """The host builds of the device headers (fast division, code-field plan, Gram launch plan) compiled with the address and
     undefined-behaviour sanitizers: the constexpr plans and the bit manipulation the kernels share with these
     checks must be free of out-of-bounds indexing, signed overflow and shifts past the width."""
     import shutil
@@ -266,7 +288,8 @@ def test_host_checks_under_sanitizers(tmp_path):
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1")
     env.pop("LD_PRELOAD", None)                   # the sanitizer runtime has to be first in the process
     for name, extra, argv, want in (("code_fields_check", [], [], "2 bits: 0, 3 bits: 0, 4 bits: 0 mismatches"),
-                                    ("fastdiv_check", ["-mfma", "-ffp-contract=off", "-pthread"], ["10", "4"], " 0 mismatches")):
+                                    ("fastdiv_check", ["-mfma", "-ffp-contract=off", "-pthread"], ["10", "4"], " 0 mismatches"),
+                                    ("gram_plan_check", [], [], " 0 mistakes")):
         exe = tmp_path / (name + "_san")
         build = subprocess.run(["g++", *san, *extra, os.path.join(ROOT, "tests", "host", name + ".cpp"), "-o", str(exe)],
                                capture_output=True, text=True)

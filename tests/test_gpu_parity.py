@@ -219,6 +219,33 @@ def test_hessian_accumulate_and_pitch(ctx):
     assert not H.cpu().numpy().any()
 
 
+def test_hessian_with_cut_rests(ctx):
+    """A shape whose launch plan cuts the token range three ways (17 tiles per XCD on 32 units: one full piece per
+    tile, the rest whole for most tiles and in four short pieces for sixteen of them; tests/host/gram_plan_check
+    prints the plan with arguments "8232 4096"), with a ragged last stage: plain, accumulated over two chunks, and
+    through the call that also prepares H for scoring."""
+    tokens, in_f = 8232, 4096
+    X = synth.make_activations(tokens, in_f, seed=77, n_outliers=6, scale_lo=30, scale_hi=80)
+    Href = oracle.hessian(X)
+    check_hessian(gpu_hessian(ctx, X), Href)
+    Xd = dev(X)
+    H = torch.zeros((in_f, in_f), dtype=torch.float32, device="cuda")
+    ctx.adadim_hessian(Xd[:4000], H)                              # a different plan
+    ctx.adadim_hessian(Xd[4000:], H, accumulate=True)
+    torch.cuda.synchronize()
+    check_hessian(H.cpu().numpy(), Href)
+    H1 = torch.full((in_f, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    Hs = ctx.alloc_score(in_f, in_f).fill_(float("nan"))
+    hmeta = torch.full((2, in_f), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.adadim_hessian_prepared(Xd, H1, Hs, hmeta)
+    H2 = torch.empty_like(H1)
+    ctx.adadim_hessian(Xd, H2)
+    torch.cuda.synchronize()
+    assert np.array_equal(H1.cpu().numpy().view(np.uint32), H2.cpu().numpy().view(np.uint32))
+    check_hessian(H1.cpu().numpy(), Href)
+    assert np.array_equal(hmeta[1].cpu().numpy(), np.diag(H1.cpu().numpy()))
+
+
 def test_hessian_reproducible(ctx):
     X = synth.make_activations(5000, 776, seed=4, n_outliers=2, scale_lo=50, scale_hi=50)
     a, b = gpu_hessian(ctx, X), gpu_hessian(ctx, X)
