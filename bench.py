@@ -668,8 +668,9 @@ def main():
         dt = time.perf_counter() - t_begin
         ctx.adadim_profile(False)
         ctx.adadim_profile_only(None)
-        return dt, {k: {"avg_us": v[0] / max(v[1], 1) * 1e3, "launches": v[1], "steps": n}
-                    for k, v in ctx.adadim_profile_read().items()}
+        return dt, {k: {"avg_us": v[0] / max(v[1], 1) * 1e3, "launches": v[1], "steps": n,
+                        "min_us": v[2] * 1e3, "median_us": v[3] * 1e3, "max_us": v[4] * 1e3}
+                    for k, v in ctx.adadim_profile_read(spread=True).items()}
 
     _, probe = profiled(1, step)
     dominant = max(probe, key=lambda k: probe[k]["avg_us"] * probe[k]["launches"])
@@ -684,6 +685,9 @@ def main():
     else:
         elapsed, live = profiled(args.steps, timed_step, only=dominant)
     best, dim, clip = finish()
+    # What the chip's matrix cores sustain right now on nothing but the MFMA instruction, random operands: the
+    # ceiling the two matrix kernels work under on this machine (power-limited clock), beside the published peak.
+    loop = [ctx.adadim_probe_mfma(1, 4000) for _ in range(2)][-1]
     _, kern = profiled(min(args.steps, 50), step)
     kern.update(live)                                         # the dominant kernel: as measured in the timed region
     losses = ls.losses.cpu().numpy().tolist()
@@ -701,6 +705,7 @@ def main():
         "must_move_bytes": 2.0 * tokens * in_f + 4.0 * in_f * in_f,
         "dense_equivalent": 2.0 * tokens * in_f * in_f / gram_s / 1e12,
     }
+    spread = {k: kern["gram_tiles"][k] for k in ("min_us", "median_us", "max_us") if k in kern["gram_tiles"]}
 
     # the error GEMM (MFMA) and the quantizers (HBM)
     comps = {}
@@ -720,6 +725,12 @@ def main():
         roofline = {"kernel": "error_tiles", "bound": "mfma", "achieved": et["tflops_issued"], "peak": MFMA_F16_PEAK / 1e12,
                     "unit": "TFLOP/s", "frac": et["frac_mfma"], "traffic": traffic, "traffic_measured_at": traffic_at,
                     "dense_equivalent": et["tflops_dense_equivalent"]}
+        spread = {k: kern["error_tiles"][k] for k in ("min_us", "median_us", "max_us") if k in kern["error_tiles"]}
+    roofline.update(spread)                                   # of the same launches `achieved` averages over
+    roofline["chip_mfma_loop"] = {"tflops": round(loop[0], 1), "clock_mhz": round(loop[1]),
+                                  "frac_of_peak": round(loop[0] * 1e12 / MFMA_F16_PEAK, 3),
+                                  "note": "v_mfma_f32_32x32x16_f16 alone, register-resident random fp16 operands, right "
+                                          "after the timed region"}
     if et:
         et["traffic"], et["traffic_measured_at"] = read_traffic("error_tiles", args.workload)
     # W read + fp16 dW written + scale/zero (one pair per group of the larger of the two group counts)
@@ -733,6 +744,9 @@ def main():
     for k, v in kern.items():
         comps.setdefault(k, {"avg_us": v["avg_us"]})
         comps[k]["launches_per_step"] = v["launches"] / v["steps"]
+        for f in ("min_us", "median_us"):
+            if f in v:
+                comps[k][f] = v[f]
 
     # The quantizer on its own, with HBM-resident inputs: back-to-back launches between two events
     # while rotating over enough weight / dW buffers (> 512 MB) that the 256 MB Infinity Cache

@@ -365,7 +365,9 @@ void adadim_graph_destroy(void* graph);
  * adadim_profile_read waits for the stream and returns the idx-th kernel's
  * record: name (host buffer of `cap` bytes), total milliseconds and number of
  * recorded launches.  Returns ADADIM_OK, or ADADIM_EINVAL when idx is past the
- * last record (use this to stop iterating).
+ * last record (use this to stop iterating).  adadim_profile_read_spread gives the
+ * smallest, the median and the largest duration of the same launches (0 when there
+ * are none).
  * An event pair costs a few microseconds of the stream's time (about 7 us per launch on an MI355X: 3 % of a
  * five-kernel step of 1.1 ms).  adadim_profile_only(ctx, name) restricts the bracketing to the kernel of that
  * name (as adadim_profile_read reports it, at most 31 characters) until it is called with NULL or "";
@@ -390,6 +392,7 @@ int adadim_probe_mfma(adadim_ctx* ctx, int random_operands, int iters, double* t
 int adadim_probe_mfma_f64(adadim_ctx* ctx, int iters, double* tflops, double* clock_mhz);
 int adadim_profile_only(adadim_ctx* ctx, const char* name);
 int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches);
+int adadim_profile_read_spread(adadim_ctx* ctx, int idx, double* min_ms, double* median_ms, double* max_ms);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,7 @@ EXPORTS = (
     "adadim_gemv_ic", "adadim_gptq_prepare", "adadim_gptq_quantize",
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
-    "adadim_profile", "adadim_profile_only", "adadim_profile_read",
+    "adadim_profile", "adadim_profile_only", "adadim_profile_read", "adadim_profile_read_spread",
     "adadim_layer_error_batch_select_noalloc", "adadim_noalloc_scratch_bytes", "adadim_probe_mfma", "adadim_probe_mfma_f64",
 )
 
@@ -132,6 +132,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_profile_read.argtypes = [c_void_p, c_int, ctypes.c_char_p, c_int, POINTER(ctypes.c_double),
                                         POINTER(c_int64)]
     lib.adadim_profile_read.restype = c_int
+    lib.adadim_profile_read_spread.argtypes = [c_void_p, c_int] + [POINTER(ctypes.c_double)] * 3
+    lib.adadim_profile_read_spread.restype = c_int
     lib.adadim_gemv_ic.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
                                    c_void_p]
     lib.adadim_gemv_ic.restype = c_int
@@ -387,8 +389,9 @@ class Context:
         """Bracket only the kernel of that name with events (None: every kernel again)."""
         self._check(self._lib.adadim_profile_only(self._h, name.encode() if name else None))
 
-    def adadim_profile_read(self) -> dict:
-        """All per-kernel records: {kernel name: (total ms, launches)}."""
+    def adadim_profile_read(self, spread: bool = False) -> dict:
+        """All per-kernel records: {kernel name: (total ms, launches)}; with spread, (total ms, launches, smallest,
+        median and largest ms of a launch)."""
         out, idx = {}, 0
         while True:
             name = ctypes.create_string_buffer(64)
@@ -397,5 +400,10 @@ class Context:
             if rc == EINVAL:
                 return out
             self._check(rc)
-            out[name.value.decode()] = (ms.value, n.value)
+            rec = (ms.value, n.value)
+            if spread:
+                lo, mid, hi = ctypes.c_double(0.0), ctypes.c_double(0.0), ctypes.c_double(0.0)
+                self._check(self._lib.adadim_profile_read_spread(self._h, idx, byref(lo), byref(mid), byref(hi)))
+                rec += (lo.value, mid.value, hi.value)
+            out[name.value.decode()] = rec
             idx += 1

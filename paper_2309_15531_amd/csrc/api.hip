@@ -2,6 +2,9 @@
 // runs before the first HIP call so that a rejected call touches no device.
 #include "common.h"
 
+#include <algorithm>
+#include <vector>
+
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -151,6 +154,27 @@ int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* t
     }
     if (total_ms) *total_ms = tot;
     if (launches) *launches = n;
+    return ADADIM_OK;
+}
+
+int adadim_profile_read_spread(adadim_ctx* ctx, int idx, double* min_ms, double* median_ms, double* max_ms) {
+    if (!ctx) return ADADIM_ENULL;
+    adadim_prof& p = ctx->prof;
+    if (idx < 0 || idx >= p.n_kernels)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_profile_read_spread: no record %d", idx);
+    ADADIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    std::vector<float> ms;
+    for (int i = 0; i < p.n_used; ++i) {
+        if (p.kernel_of[i] != idx) continue;
+        float t = 0.0f;
+        ADADIM_HIP_TRY(ctx, hipEventElapsedTime(&t, p.start[i], p.stop[i]));
+        ms.push_back(t);
+    }
+    std::sort(ms.begin(), ms.end());
+    const size_t n = ms.size();
+    if (min_ms) *min_ms = n ? ms.front() : 0.0;
+    if (max_ms) *max_ms = n ? ms.back() : 0.0;
+    if (median_ms) *median_ms = n ? 0.5 * (double(ms[(n - 1) / 2]) + double(ms[n / 2])) : 0.0;
     return ADADIM_OK;
 }
 

@@ -607,6 +607,9 @@ def test_profile_only_one_kernel(ctx):
     ctx.adadim_profile(False)
     rec = ctx.adadim_profile_read()
     assert list(rec) == ["gram_tiles"] and rec["gram_tiles"][1] == 2 and rec["gram_tiles"][0] > 0
+    total, n, lo, mid, hi = ctx.adadim_profile_read(spread=True)["gram_tiles"]
+    assert n == 2 and 0 < lo <= mid <= hi                     # two launches: the median is their mean
+    assert lo + hi == pytest.approx(total, rel=1e-5) and mid == pytest.approx(total / 2, rel=1e-5)
     ctx.adadim_profile_only(None)
     ctx.adadim_profile(True)
     step()
