@@ -213,6 +213,14 @@ def test_gram_launch_plans_cover_every_tile_once(tmp_path):
     assert len(share) == 2 and min(share) >= 0.95, res.stdout
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU per box: bench.py --gpus 2 says so and exits before anything touches a GPU."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2 and "one GPU only" in res.stderr and res.stdout == ""
+
+
 def test_product_does_not_import_oracle():
     """The product package must never reach into the oracle (and vice versa)."""
     pkg = os.path.join(ROOT, "paper_2309_15531_amd")
