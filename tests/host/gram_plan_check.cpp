@@ -5,7 +5,8 @@
 //   * every piece but the first of its token range starts on a stage boundary (the kernel puts a ragged length
 //     into the piece's first stage) and full pieces have the plan's length;
 //   * no two pieces share a partial slot, every slot is below gram_plan_slots, and the slots the reduction reads
-//     for a tile (gram_plan_parts / gram_plan_slot) are exactly the ones its pieces wrote, in token order.
+//     for a tile (gram_plan_parts / gram_plan_slot) are exactly the ones its pieces wrote, in token order;
+//   * the fixed order of a plan with short pieces (gram_plan_order) names every place of an XCD's lists once.
 // With arguments "tokens in" it prints the plan chosen for that shape and its simulated balance.
 #include "../../paper_2309_15531_amd/csrc/gram_plan.h"
 
@@ -58,6 +59,21 @@ static long check(const GramPlan& p) {
             at = hit->e;
         }
         bad += at != p.tokens;
+    }
+    // the fixed order, where the plan has one: every place of an XCD's lists exactly once, units in ascending runs
+    GramOrder o;
+    gram_plan_order(p, o);
+    if (o.n) {
+        bad += o.n != per || o.first[0] != 0 || o.first[32] != o.n;
+        std::vector<int> seen(per, 0);
+        for (int c = 0; c < 32; ++c) {
+            bad += o.first[c] > o.first[c + 1];
+            for (int k = o.first[c]; k < o.first[c + 1] && k < GRAM_ORDER_MAX; ++k) {
+                if (o.pos[k] >= per) { ++bad; continue; }
+                ++seen[o.pos[k]];
+            }
+        }
+        for (int q = 0; q < per; ++q) bad += seen[q] != 1;
     }
     return bad;
 }
