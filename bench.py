@@ -792,7 +792,23 @@ def main():
                                "rotating_buffers": n_rot,
                                "note": "bytes of the two dimensions added up (W read for each), as for the single launches"}
         del dW2
-    del Ws, dWs
+    # For scale: what a plain device copy of one weight matrix reaches on this machine in the same arrangement
+    # (torch's elementwise copy of W into a buffer of the same size, the same rotation; bytes = read + written).
+    # The quantizers read W and write as many bytes again, so this is the rate to hold their fractions against.
+    dsts = [torch.empty_like(Wd) for _ in range(n_rot)]
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(2):                                      # the first sweep warms up
+        ev0.record()
+        for _ in range(3 if rep else 1):
+            for i in range(n_rot):
+                dsts[i].copy_(Ws[i])
+        ev1.record()
+        torch.cuda.synchronize()
+    copy_sec = ev0.elapsed_time(ev1) * 1e-3 / (3 * n_rot)
+    quant["plain_copy"] = {"us_per_launch": copy_sec * 1e6, "GBps": 4.0 * out_f * in_f / copy_sec / 1e9,
+                           "frac_hbm": 4.0 * out_f * in_f / copy_sec / HBM_PEAK, "rotating_buffers": n_rot,
+                           "note": "back-to-back copies between two events: includes the gaps between launches"}
+    del Ws, dWs, dsts
 
     result = {
         "metric": "weight params quantized+scored (both dims)/s",
