@@ -198,7 +198,8 @@ def check_hessian(Hg, Href):
 
 
 @pytest.mark.parametrize("tokens,in_f", [(256, 512), (1000, 264), (77, 1288), (4096, 128), (3000, 2056), (1, 64),
-                                         (70, 6144), (200, 6008), (40, 6016)])   # the last three: 300 tiles, 256 of them stored whole
+                                         (70, 6144), (200, 6008), (40, 6016),    # 300 tiles, 256 of them stored whole
+                                         (12000, 4096), (9999, 3080), (4097, 5128)])   # token ranges cut two and three ways, ragged
 def test_hessian(ctx, tokens, in_f):
     X = synth.make_activations(tokens, in_f, seed=tokens + in_f, n_outliers=3, scale_lo=50, scale_hi=100)
     check_hessian(gpu_hessian(ctx, X), oracle.hessian(X))
