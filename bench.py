@@ -333,11 +333,27 @@ def block_bench(args):
     for n in layers:
         synth.config_weight_device(cfg_id, n, block=0, out=bufs[0][n], scratch=scratch[layers[n]])
 
+    # A streamed model's next block is drawn on a stream of its own, under the Gram kernels just queued for it on the
+    # context's stream (in a real job the block's weights arrive by DMA meanwhile).  The draw may start once the
+    # kernels that read this slot's buffers two blocks ago are done: everything queued before the previous draw.
+    gen_stream = torch.cuda.Stream() if streaming else None
+    queued_before = [None, None]
+
     def weights_of(b, slot):
         if not streaming:
             return bufs[0]
-        for n in layers:
-            synth.config_weight_device(cfg_id, n, block=b, out=bufs[slot][n], scratch=scratch[layers[n]])
+        main = torch.cuda.current_stream()
+        mark = torch.cuda.Event()
+        mark.record(main)
+        with torch.cuda.stream(gen_stream):
+            if queued_before[slot ^ 1] is not None:
+                gen_stream.wait_event(queued_before[slot ^ 1])
+            for n in layers:
+                synth.config_weight_device(cfg_id, n, block=b, out=bufs[slot][n], scratch=scratch[layers[n]])
+            drawn = torch.cuda.Event()
+            drawn.record(gen_stream)
+        queued_before[slot] = mark
+        main.wait_event(drawn)
         return bufs[slot]
 
     if len(clips) == 1:
