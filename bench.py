@@ -7,7 +7,7 @@ dimensions, selection, and the winner's packed codes / scales / zeros.
 Prints ONE JSON line: metric, value, unit, ms_per_step, config, and the roofline / cpu_baseline objects.
 
     python bench.py [--steps K] [--warmup W]
-                    [--workload down_proj|gate_proj|q_proj|qkv|clip_grid|toy|block7b|stream13b|block70b|gemv_ic|gptq|mfma_ceiling]
+                    [--workload down_proj|gate_proj|q_proj|qkv|clip_grid|toy|block7b|stream13b|block70b|gemv_ic|gptq|mfma_ceiling|gram_timeline]
                     [--bits B] [--group G] [--meta16]
 
 The default workload is the layer the targets are stated on: W[4096, 11008] (the FFN down projection of the
@@ -483,6 +483,51 @@ def block_bench(args):
     print(json.dumps(result))
 
 
+def timeline_bench(args):
+    """Where the Gram tile kernel's time goes on the narrow layers, piece by piece (adadim_probe_gram_timeline): the
+    4096-wide input of the q_proj workload and the 5120-wide one of the streamed model at 65536 tokens, once with the fixed
+    order the library uses for plans with short pieces and once with one workgroup per piece left to the hardware's
+    dispatcher.  Per run: the plan, the span from the first start to the last end, the mean duration and shader
+    clock of each list's pieces, when the last piece of each XCD's lists ends, and how many short pieces started
+    more than 20 us after the first short piece of their XCD.  One JSON line."""
+    import torch
+    from paper_2309_15531_amd import binding as B
+    from paper_2309_15531_amd import synth
+    B.load_library()
+    ctx = B.Context()
+    runs = []
+    for cfg_id, width in ((1, 4096), (3, 5120)):
+        X = synth.config_activations_device(cfg_id, width, tokens=65536)
+        for dispatcher in (False, True, False, True):
+            rec, plan = ctx.adadim_probe_gram_timeline(X, dispatcher=dispatcher)
+            lists = {}
+            for name, c in (("full", 0), ("rest", 1), ("short", 2)):
+                r = rec[rec[:, 0] == c]
+                if len(r):
+                    dur = r[:, 3] - r[:, 2]
+                    lists[name] = {"pieces": int(len(r)), "mean_us": round(float(dur.mean()), 1),
+                                   "clock_mhz": round(float((r[:, 4] / dur).mean()))}
+            xcd_end = [round(float(rec[rec[:, 1] == x][:, 3].max()), 1) for x in range(8)]
+            late = 0
+            short = rec[rec[:, 0] == 2]
+            for x in range(8):
+                sx = short[short[:, 1] == x]
+                if len(sx):
+                    late += int((sx[:, 2] > sx[:, 2].min() + 20.0).sum())
+            runs.append({"in": width, "order": "dispatcher" if dispatcher else ("fixed" if plan[6] else "dispatcher (plan has no short pieces)"),
+                         "plan": {"tiles": plan[0], "full_pieces_per_tile": plan[1], "full_piece_stages": plan[2],
+                                  "tiles_with_cut_rest": plan[3], "short_pieces_per_cut_rest": plan[4],
+                                  "short_piece_stages": plan[5], "places_per_xcd": plan[7]},
+                         "span_us": round(float(rec[:, 3].max()), 1), "lists": lists, "last_end_per_xcd_us": xcd_end,
+                         "short_pieces_started_late": late})
+        del X
+    print(json.dumps({
+        "metric": "span of one Gram tile launch, first start to last end", "value": runs[0]["span_us"], "unit": "us",
+        "n_gpus": 1, "steps": 1, "warmup": 2, "ms_per_step": runs[0]["span_us"] / 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "time-stamped Gram tile launches, X[65536, 4096] and X[65536, 5120]"}, "runs": runs}))
+
+
 def ceiling_bench(args):
     """What the matrix cores sustain on this chip, beside the published peak: (a) a register-resident loop of the MFMA
     instruction the two matrix kernels use, on all-zero and on random fp16 operands (adadim_probe_mfma); (b) the Gram
@@ -552,7 +597,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: by workload, see DEFAULT_STEPS)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them")
     ap.add_argument("--workload", default="down_proj",
-                    choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + ["gemv_ic", "gptq", "mfma_ceiling"])
+                    choices=sorted(WORKLOADS) + sorted(BLOCK_WORKLOADS) + ["gemv_ic", "gptq", "mfma_ceiling", "gram_timeline"])
     ap.add_argument("--log", default=None, help="stream13b: the JSON-lines results file (default: a fresh temporary file)")
     ap.add_argument("--resume", action="store_true", help="stream13b: keep the records --log already holds and skip their layers")
     ap.add_argument("--bits", type=int, default=None)
@@ -592,6 +637,9 @@ def main():
         return
     if args.workload in BLOCK_WORKLOADS:
         block_bench(args)
+        return
+    if args.workload == "gram_timeline":
+        timeline_bench(args)
         return
     if args.workload == "mfma_ceiling":
         ceiling_bench(args)

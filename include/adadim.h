@@ -390,6 +390,21 @@ int adadim_probe_mfma(adadim_ctx* ctx, int random_operands, int iters, double* t
  * factor's products are to be read against this rate.)
  */
 int adadim_probe_mfma_f64(adadim_ctx* ctx, int iters, double* tflops, double* clock_mhz);
+/*
+ * Measurement aid: where the time of the Gram tile kernel goes, piece by piece.  Runs the 256-wide tile kernel of
+ * adadim_hessian three times on X (device, fp16 [tokens, in], row pitch ldx; in > 1024) in a build that stamps the
+ * 100 MHz clock around every piece, with the launch plan of an accumulating call (no whole tiles: those carry no
+ * stamps), and reads the last launch's stamps back.  dispatcher = 1 launches one workgroup per piece in list order
+ * whatever the plan, 0 as adadim_hessian would (a fixed order where the plan has short pieces).  H is not written and
+ * the context's scratch for partial tiles is left with the stamps in it.  Waits for the stream.
+ * records (host, cap * 8 floats): per piece {list (0 full piece, 1 rest, 2 short piece of a cut rest), XCD whose list
+ * it is on, start and end in us from the first start, shader cycles, prologue us, main loop us, 0}.  n_records: the
+ * number of pieces (also set when cap is too small, which is ADADIM_EINVAL).  plan_out (host, 8 ints): tiles, full
+ * pieces per tile, their length in 32-token stages, tiles with a cut rest, pieces per cut rest, their length, whether
+ * the order was fixed, places per XCD.
+ */
+int adadim_probe_gram_timeline(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx,
+                               int dispatcher, float* records, int cap, int* n_records, int* plan_out);
 int adadim_profile_only(adadim_ctx* ctx, const char* name);
 int adadim_profile_read(adadim_ctx* ctx, int idx, char* name, int cap, double* total_ms, int64_t* launches);
 int adadim_profile_read_spread(adadim_ctx* ctx, int idx, double* min_ms, double* median_ms, double* max_ms);

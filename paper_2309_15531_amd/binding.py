@@ -25,6 +25,7 @@ EXPORTS = (
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_only", "adadim_profile_read", "adadim_profile_read_spread",
+    "adadim_probe_gram_timeline",
     "adadim_layer_error_batch_select_noalloc", "adadim_noalloc_scratch_bytes", "adadim_probe_mfma", "adadim_probe_mfma_f64",
 )
 
@@ -132,6 +133,9 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_profile_read.argtypes = [c_void_p, c_int, ctypes.c_char_p, c_int, POINTER(ctypes.c_double),
                                         POINTER(c_int64)]
     lib.adadim_profile_read.restype = c_int
+    lib.adadim_probe_gram_timeline.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int,
+                                               POINTER(ctypes.c_float), c_int, POINTER(c_int), POINTER(c_int)]
+    lib.adadim_probe_gram_timeline.restype = c_int
     lib.adadim_profile_read_spread.argtypes = [c_void_p, c_int] + [POINTER(ctypes.c_double)] * 3
     lib.adadim_profile_read_spread.restype = c_int
     lib.adadim_gemv_ic.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int, c_int,
@@ -375,6 +379,18 @@ class Context:
         tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
         self._check(self._lib.adadim_probe_mfma_f64(self._h, iters, byref(tf), byref(mhz)))
         return tf.value, mhz.value
+
+    def adadim_probe_gram_timeline(self, X, dispatcher: bool = False):
+        """(records [pieces, 8] as a numpy array, plan as 8 ints) of one time-stamped launch of the Gram tile kernel."""
+        import numpy as np
+        _need(X, "X", "float16", pitched=True)
+        cap = 8192
+        rec = np.zeros((cap, 8), dtype=np.float32)
+        n, plan = c_int(0), (c_int * 8)()
+        self._check(self._lib.adadim_probe_gram_timeline(
+            self._h, _ptr(X), X.shape[0], X.shape[1], X.stride(0), 1 if dispatcher else 0,
+            rec.ctypes.data_as(POINTER(ctypes.c_float)), cap, byref(n), plan))
+        return rec[:n.value].copy(), [int(v) for v in plan]
 
     def adadim_probe_mfma(self, random_operands: bool, iters: int = 4000):
         """(TFLOP/s, shader clock in MHz) of a register-resident MFMA loop; waits for the stream."""

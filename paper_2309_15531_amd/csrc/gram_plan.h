@@ -72,6 +72,14 @@ GRAM_PLAN_FN int gram_plan_per_xcd(const GramPlan& p) {
     return (p.n_whole + 7) / 8 + (gram_plan_big(p) + 7) / 8 + (gram_plan_small(p) + 7) / 8 + (gram_plan_sub(p) + 7) / 8;
 }
 
+// XCD x's share of a list of n items begins at item x * ceil(n / 8): contiguous eighths, the last one (or ones)
+// short.  (Shares that differ by one item at most were measured on the 5120-wide input, 27 x 7 + 21 tiles against
+// 26 or 27 each: no faster.  A short XCD leaves its part of the chip's power to the others.)
+GRAM_PLAN_FN int gram_plan_share_begin(int n, int xcd) {
+    const int b = xcd * ((n + 7) / 8);
+    return b < n ? b : n;
+}
+
 // Item of workgroup q (0 .. gram_plan_per_xcd - 1) on XCD xcd; false if that place of the launch is empty.
 GRAM_PLAN_FN bool gram_plan_item(const GramPlan& p, int xcd, int q, GramItem& it) {
     const int n_rest = gram_plan_rest(p), total_big = gram_plan_big(p), n_small = gram_plan_small(p),
@@ -79,16 +87,16 @@ GRAM_PLAN_FN bool gram_plan_item(const GramPlan& p, int xcd, int q, GramItem& it
     const int per_whole = (p.n_whole + 7) / 8, per_big = (total_big + 7) / 8, per_small = (n_small + 7) / 8,
               per_sub = (n_sub + 7) / 8;
     if (q < per_whole) {
-        it.tile = xcd * per_whole + q;
+        it.tile = gram_plan_share_begin(p.n_whole, xcd) + q;
         it.slot = -1;
         it.t_begin = 0;
         it.t_end = p.tokens;
-        return it.tile < p.n_whole;
+        return it.tile < gram_plan_share_begin(p.n_whole, xcd + 1);
     }
     q -= per_whole;
     if (q < per_big) {
-        const int i = xcd * per_big + q;
-        if (i >= total_big) return false;
+        const int i = gram_plan_share_begin(total_big, xcd) + q;
+        if (i >= gram_plan_share_begin(total_big, xcd + 1)) return false;
         const int split = i / n_rest;
         it.tile = p.n_whole + (i - split * n_rest);
         it.slot = i;
@@ -99,8 +107,8 @@ GRAM_PLAN_FN bool gram_plan_item(const GramPlan& p, int xcd, int q, GramItem& it
     q -= per_big;
     const int64_t rem_begin = int64_t(p.n_full) * p.t_per_split;
     if (q < per_small) {
-        const int s = xcd * per_small + q;
-        if (s >= n_small) return false;
+        const int s = gram_plan_share_begin(n_small, xcd) + q;
+        if (s >= gram_plan_share_begin(n_small, xcd + 1)) return false;
         it.tile = p.n_whole + p.n_cut + s;
         it.slot = total_big + s;
         it.t_begin = rem_begin;
@@ -109,8 +117,8 @@ GRAM_PLAN_FN bool gram_plan_item(const GramPlan& p, int xcd, int q, GramItem& it
     }
     q -= per_small;
     if (q >= per_sub) return false;
-    const int u = xcd * per_sub + q;
-    if (u >= n_sub) return false;
+    const int u = gram_plan_share_begin(n_sub, xcd) + q;
+    if (u >= gram_plan_share_begin(n_sub, xcd + 1)) return false;
     const int t = u / p.m, j = u - t * p.m;
     it.tile = p.n_whole + t;
     it.slot = total_big + n_small + u;

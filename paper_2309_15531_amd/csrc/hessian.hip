@@ -14,6 +14,8 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstring>
+#include <vector>
 #include "mfma_tile.h"
 #include "gram_dma.h"
 
@@ -526,6 +528,93 @@ int launch_hessian_prepared(adadim_ctx* ctx, const __half* X, int64_t tokens, in
     }
     if (in <= 1024) return run_gram<128>(ctx, X, tokens, in, ldx, H, 0, Hs, hmeta);
     return run_gram<256>(ctx, X, tokens, in, ldx, H, 0, Hs, hmeta);
+}
+
+// Measurement aid: one launch of the 256-wide tile kernel built with time stamps around every piece.
+extern "C" int adadim_probe_gram_timeline(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx,
+                                          int dispatcher, float* records, int cap, int* n_records, int* plan_out) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!X || !records || !n_records || !plan_out)
+        return adadim_fail(ctx, ADADIM_ENULL, "adadim_probe_gram_timeline: NULL argument");
+    if (tokens <= 0 || tokens > (int64_t(1) << 24) || in <= 1024 || in > (int64_t(1) << 16) || ldx < in ||
+        (dispatcher != 0 && dispatcher != 1))
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_probe_gram_timeline: need 0 < tokens <= 2^24, 1024 < in <= 65536 "
+                                               "(the 256-wide kernel), ldx >= in, dispatcher 0 or 1");
+    if ((in % 8) != 0 || (ldx % 8) != 0 || !aligned16(X))
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_probe_gram_timeline: in and ldx multiples of 8, X 16-byte aligned");
+    if (ctx->capturing)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_probe_gram_timeline: not while a graph is being recorded");
+    constexpr int BT = 256;
+    const int nb = static_cast<int>((in + BT - 1) / BT), n_tiles = nb * (nb + 1) / 2;
+    const GramPlan plan = gram_plan_choose(tokens, n_tiles, false);   // no whole tiles: they carry no time stamps
+    GramOrder order;
+    gram_plan_order(plan, order);
+    if (dispatcher) order.n = 0;
+    const int slots = gram_plan_slots(plan);
+    *n_records = slots;
+    plan_out[0] = plan.n_tiles; plan_out[1] = plan.n_full; plan_out[2] = static_cast<int>(plan.t_per_split / GRAM_STAGE);
+    plan_out[3] = plan.n_cut; plan_out[4] = plan.m; plan_out[5] = static_cast<int>(plan.t_sub / GRAM_STAGE);
+    plan_out[6] = order.n ? 1 : 0; plan_out[7] = gram_plan_per_xcd(plan);
+    if (cap < slots)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_probe_gram_timeline: %d records needed, room for %d", slots, cap);
+    float* part = static_cast<float*>(adadim_workspace(ctx, WS_HESS_PART, size_t(slots) * BT * BT * sizeof(float)));
+    void* zero16 = adadim_workspace(ctx, WS_ZERO, size_t(32) * size_t(ldx) * 2 + 512);
+    if (!part || !zero16) return ADADIM_EHIP;
+    if (ctx->zero_ready_bytes != ctx->ws_bytes[WS_ZERO]) {
+        const int64_t n = static_cast<int64_t>(ctx->ws_bytes[WS_ZERO] / 4);
+        hipLaunchKernelGGL(zero_f32, dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                           static_cast<float*>(zero16), n);
+        ADADIM_LAUNCH_CHECK(ctx, "zero_f32");
+        ctx->zero_ready_bytes = ctx->ws_bytes[WS_ZERO];
+    }
+    static PerDeviceOnce once;
+    ADADIM_HIP_TRY(ctx, once.run([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(dma::gram_tiles_dma<2, 2, 8>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, dma::SMEM_BYTES);
+    }));
+    const unsigned grid = 8u * static_cast<unsigned>(order.n ? 32 : gram_plan_per_xcd(plan));
+    for (int rep = 0; rep < 3; ++rep) {                       // the last launch is the one read back
+        hipLaunchKernelGGL((dma::gram_tiles_dma<2, 2, 8>), dim3(grid), dim3(256), dma::SMEM_BYTES, ctx->stream,
+                           static_cast<const __half*>(X), in, ldx, nb, plan, order, zero16, part,
+                           static_cast<float*>(nullptr));
+        ADADIM_LAUNCH_CHECK(ctx, "gram_tiles (time stamps)");
+    }
+    ADADIM_HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    // a piece leaves its stamps in the first 16 bytes of its partial tile and 4 KB further on
+    std::vector<float> head(size_t(slots) * 4), phase(size_t(slots) * 4);
+    const size_t pitch = size_t(BT) * BT * sizeof(float);
+    ADADIM_HIP_TRY(ctx, hipMemcpy2D(head.data(), 16, part, pitch, 16, slots, hipMemcpyDeviceToHost));
+    ADADIM_HIP_TRY(ctx, hipMemcpy2D(phase.data(), 16, part + 1024, pitch, 16, slots, hipMemcpyDeviceToHost));
+    uint32_t t0 = 0;
+    for (int i = 0; i < slots; ++i) {
+        uint32_t st;
+        std::memcpy(&st, &head[size_t(i) * 4 + 2], 4);
+        if (i == 0 || static_cast<int32_t>(st - t0) < 0) t0 = st;
+    }
+    const int n_big = gram_plan_big(plan), n_small = gram_plan_small(plan), n_sub = gram_plan_sub(plan);
+    auto xcd_of = [](int n, int i) {                          // the XCD whose share of an n-item list holds item i
+        int x = 0;
+        while (x < 7 && gram_plan_share_begin(n, x + 1) <= i) ++x;
+        return x;
+    };
+    for (int i = 0; i < slots; ++i) {
+        uint32_t st, en;
+        std::memcpy(&st, &head[size_t(i) * 4 + 2], 4);
+        std::memcpy(&en, &head[size_t(i) * 4 + 3], 4);
+        const int cls = i < n_big ? 0 : i < n_big + n_small ? 1 : 2;
+        const int xcd = cls == 0 ? xcd_of(n_big, i) : cls == 1 ? xcd_of(n_small, i - n_big) : xcd_of(n_sub, i - n_big - n_small);
+        float* r = records + size_t(i) * 8;
+        r[0] = static_cast<float>(cls);
+        r[1] = static_cast<float>(xcd);
+        r[2] = static_cast<float>(st - t0) / 100.0f;            // 100 MHz ticks -> us
+        r[3] = static_cast<float>(en - t0) / 100.0f;
+        r[4] = head[size_t(i) * 4];                            // shader cycles
+        r[5] = phase[size_t(i) * 4] / 100.0f;                  // prologue
+        r[6] = phase[size_t(i) * 4 + 1] / 100.0f;              // main loop
+        r[7] = 0.0f;
+    }
+    (void)n_sub;
+    return ADADIM_OK;
 }
 
 int launch_hessian_prepare(adadim_ctx* ctx, const float* H, int64_t in, __half* Hs, float* hmeta) {

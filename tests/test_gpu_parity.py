@@ -677,3 +677,25 @@ def test_matrix_core_probes_report_a_rate_below_the_published_peaks(ctx):
     assert 500.0 < mhz16 < 3000.0 and 500.0 < mhz64 < 3000.0
     with pytest.raises(B.AdaDimError):
         ctx.adadim_probe_mfma_f64(0)
+
+
+def test_gram_timeline_probe_stamps_every_piece(ctx):
+    """The time-stamped launch of the Gram tile kernel (a measurement aid): one record per piece of the plan, each with
+    a list, an XCD, a start before its end, and a prologue and main loop that fit inside it; the pieces of a list
+    that share a tile's token range order themselves by list; H = X^T X computed afterwards is unharmed by the stamps
+    the probe left in the scratch buffer."""
+    tokens, in_f = 6000, 2048
+    X = synth.make_activations(tokens, in_f, seed=5, n_outliers=3, scale_lo=20, scale_hi=40)
+    Xd = dev(X)
+    for dispatcher in (False, True):
+        rec, plan = ctx.adadim_probe_gram_timeline(Xd, dispatcher=dispatcher)
+        n_tiles = (in_f // 256) * (in_f // 256 + 1) // 2
+        assert plan[0] == n_tiles and plan[1] >= 0 and plan[7] >= 1
+        assert len(rec) >= n_tiles                                # at least one piece per tile
+        assert set(np.unique(rec[:, 0])) <= {0.0, 1.0, 2.0} and rec[:, 1].min() >= 0 and rec[:, 1].max() <= 7
+        assert (rec[:, 2] >= 0).all() and (rec[:, 3] > rec[:, 2]).all() and rec[:, 2].min() == 0.0
+        assert (rec[:, 5] + rec[:, 6] <= rec[:, 3] - rec[:, 2] + 0.05).all()
+        assert (rec[:, 4] > 0).all()
+    check_hessian(gpu_hessian(ctx, X), oracle.hessian(X))
+    with pytest.raises(B.AdaDimError):
+        ctx.adadim_probe_gram_timeline(dev(X[:, :1024].copy()))  # the 128-wide kernel's widths carry no stamps
