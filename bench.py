@@ -213,6 +213,11 @@ def gemv_bench(args):
     torch.cuda.synchronize()
     ctx.adadim_profile(False)
     kern = dict({k: v[0] / max(v[1], 1) * 1e3 for k, v in ctx.adadim_profile_read().items()}, **kern)
+    # what reading the code stream in the kernel's pattern costs by itself, the two buffers taken in turn
+    for i in range(4):
+        ctx.adadim_probe_gemv_read(packs[i & 1], out_f, in_f, bits)
+    bare = [ctx.adadim_probe_gemv_read(packs[i & 1], out_f, in_f, bits) for i in range(10)]
+    bare_us = float(np.mean(bare))
     alg_bytes = out_f * in_f * bits / 8 + (2.0 if args.meta16 else 5.0) * (out_f // group) * in_f + 2 * in_f + 2 * out_f
     sec = kern["gemv_ic_tiles"] * 1e-6
     result = {
@@ -224,7 +229,10 @@ def gemv_bench(args):
                                + (", 16-bit group words" if args.meta16 else ""),
                    "bits": bits, "group": group},
         "roofline": {"kernel": "gemv_ic_tiles", "bound": "hbm", "achieved": alg_bytes / sec / 1e9, "peak": HBM_PEAK / 1e9,
-                     "unit": "GB/s", "frac": alg_bytes / sec / HBM_PEAK, "traffic": None},
+                     "unit": "GB/s", "frac": alg_bytes / sec / HBM_PEAK, "traffic": None,
+                     "bare_read": {"us": bare_us, "frac_hbm": out_f * in_f * bits / 8 / (bare_us * 1e-6) / HBM_PEAK,
+                                   "note": "the code words alone, read by the same grid and column ranges with one xor "
+                                           "per word (adadim_probe_gemv_read); event-timed launch by launch"}},
         "kernels_us": kern,
     }
     if not args.no_cpu_baseline:

@@ -403,6 +403,13 @@ int adadim_probe_mfma_f64(adadim_ctx* ctx, int iters, double* tflops, double* cl
  * pieces per tile, their length in 32-token stages, tiles with a cut rest, pieces per cut rest, their length, whether
  * the order was fixed, places per XCD.
  */
+/*
+ * Measurement aid: what the access pattern of adadim_gemv_ic alone costs.  One launch that reads the code words of
+ * `packed` (device, the [in][out * bits / 32] stream of adadim_gemv_ic, bits 2..4) with the grid, waves and column
+ * ranges of the product's tile kernel and one xor per word in place of everything else; us (host): its duration
+ * between two events on the context's stream.  Waits for the stream; uses the product's scratch for partial sums.
+ */
+int adadim_probe_gemv_read(adadim_ctx* ctx, const void* packed, int64_t out, int64_t in, int bits, double* us);
 int adadim_probe_gram_timeline(adadim_ctx* ctx, const void* X, int64_t tokens, int64_t in, int64_t ldx,
                                int dispatcher, float* records, int cap, int* n_records, int* plan_out);
 int adadim_profile_only(adadim_ctx* ctx, const char* name);

@@ -25,7 +25,7 @@ EXPORTS = (
     "adadim_quantize_meta16", "adadim_gemv_ic_meta16",
     "adadim_hessian_prepared", "adadim_layer_error_batch_select", "adadim_quantize_both", "adadim_gptq_quantize_meta16", "adadim_capture_begin", "adadim_capture_end", "adadim_graph_launch", "adadim_graph_destroy",
     "adadim_profile", "adadim_profile_only", "adadim_profile_read", "adadim_profile_read_spread",
-    "adadim_probe_gram_timeline",
+    "adadim_probe_gram_timeline", "adadim_probe_gemv_read",
     "adadim_layer_error_batch_select_noalloc", "adadim_noalloc_scratch_bytes", "adadim_probe_mfma", "adadim_probe_mfma_f64",
 )
 
@@ -133,6 +133,8 @@ def load_library(path: str | None = None) -> ctypes.CDLL:
     lib.adadim_profile_read.argtypes = [c_void_p, c_int, ctypes.c_char_p, c_int, POINTER(ctypes.c_double),
                                         POINTER(c_int64)]
     lib.adadim_profile_read.restype = c_int
+    lib.adadim_probe_gemv_read.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int, POINTER(ctypes.c_double)]
+    lib.adadim_probe_gemv_read.restype = c_int
     lib.adadim_probe_gram_timeline.argtypes = [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int,
                                                POINTER(ctypes.c_float), c_int, POINTER(c_int), POINTER(c_int)]
     lib.adadim_probe_gram_timeline.restype = c_int
@@ -379,6 +381,13 @@ class Context:
         tf, mhz = ctypes.c_double(0.0), ctypes.c_double(0.0)
         self._check(self._lib.adadim_probe_mfma_f64(self._h, iters, byref(tf), byref(mhz)))
         return tf.value, mhz.value
+
+    def adadim_probe_gemv_read(self, packed, out_f: int, in_f: int, bits: int) -> float:
+        """Microseconds of one launch that only reads the code stream the way the matrix-vector kernel does."""
+        _need(packed, "packed", "int32")
+        us = ctypes.c_double(0.0)
+        self._check(self._lib.adadim_probe_gemv_read(self._h, _ptr(packed), out_f, in_f, bits, byref(us)))
+        return us.value
 
     def adadim_probe_gram_timeline(self, X, dispatcher: bool = False):
         """(records [pieces, 8] as a numpy array, plan as 8 ints) of one time-stamped launch of the Gram tile kernel."""

@@ -223,7 +223,81 @@ __global__ __launch_bounds__(256) void gemv_ic_finish(const float* __restrict__ 
     *reinterpret_cast<uint2*>(y + o0) = o;
 }
 
+// Measurement aid: the same code words read by the same grid, waves and column ranges as gemv_ic_tiles, with one
+// xor per word in place of the arithmetic and no parameters, x, LDS reduction or partial sums: what the kernel's
+// access pattern alone costs.  Each thread leaves one word in `sink` so that the loads are not dropped.
+template <int PB>
+__global__ __launch_bounds__(64 * GV_WAVES, 4) void gemv_bare_read(const uint32_t* __restrict__ packed, int64_t out,
+                                                                int64_t in, int64_t n_words,
+                                                                uint32_t* __restrict__ sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t o_lane = int64_t(blockIdx.x) * GV_OUT_PER_BLOCK + lane * 32;
+    const bool valid = o_lane < out;
+    const uint32_t n_wv = gridDim.y * GV_WAVES, wv = blockIdx.y * GV_WAVES + wave, quads = static_cast<uint32_t>(in >> 2);
+    const uint32_t q_each = quads / n_wv, q_more = quads - q_each * n_wv;
+    const int64_t j_begin = int64_t(wv * q_each + min(wv, q_more)) << 2;
+    const int64_t j_end = int64_t((wv + 1) * q_each + min(wv + 1, q_more)) << 2;
+    const uint32_t* wp = packed + (valid ? (o_lane >> 5) * PB : 0);
+    uint32_t acc = 0;
+    if (valid) {
+        for (int64_t j0 = j_begin; j0 < j_end; j0 += 4) {
+            Words<PB> wd[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) wd[c] = load_words<PB>(wp + (j0 + c) * n_words);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int w = 0; w < PB; ++w) acc ^= wd[c].w[w];
+        }
+    }
+    sink[(int64_t(blockIdx.y) * gridDim.x + blockIdx.x) * (64 * GV_WAVES) + threadIdx.x] = acc;
+}
+
 }  // namespace
+
+extern "C" int adadim_probe_gemv_read(adadim_ctx* ctx, const void* packed, int64_t out, int64_t in, int bits,
+                                      double* us) {
+    if (!ctx) return ADADIM_ENULL;
+    if (!packed || !us) return adadim_fail(ctx, ADADIM_ENULL, "adadim_probe_gemv_read: NULL argument");
+    if (bits < 2 || bits > 4 || out <= 0 || in <= 0 || out > (int64_t(1) << 24) || in > (int64_t(1) << 24) ||
+        (out % 32) != 0 || (in % 4) != 0)
+        return adadim_fail(ctx, ADADIM_EINVAL, "adadim_probe_gemv_read: bits 2..4, out a multiple of 32, in of 4, both "
+                                               "at most 2^24");
+    if (reinterpret_cast<uintptr_t>(packed) & 15u)
+        return adadim_fail(ctx, ADADIM_EALIGN, "adadim_probe_gemv_read: packed must be 16-byte aligned");
+    if (ctx->capturing) return adadim_fail(ctx, ADADIM_EINVAL, "adadim_probe_gemv_read: not while a graph is being recorded");
+    // the grid of launch_gemv_ic
+    const int n_tiles = static_cast<int>((out + GV_OUT_PER_BLOCK - 1) / GV_OUT_PER_BLOCK);
+    const int64_t max_chunks = std::max<int64_t>(1, in / (GV_WAVES * GV_MIN_COLS_PER_WAVE));
+    const int64_t rounds = (n_tiles + GV_BLOCK_SLOTS - 1) / GV_BLOCK_SLOTS;
+    const int n_chunks = static_cast<int>(std::min<int64_t>(max_chunks, std::max<int64_t>(1, rounds * GV_BLOCK_SLOTS / n_tiles)));
+    uint32_t* sink = static_cast<uint32_t*>(
+        adadim_workspace(ctx, WS_GEMV_PART, size_t(n_tiles) * size_t(n_chunks) * 64 * GV_WAVES * sizeof(uint32_t)));
+    if (!sink) return ADADIM_EHIP;
+    const int64_t n_words = out * bits / 32;
+    const dim3 grid(static_cast<unsigned>(n_tiles), static_cast<unsigned>(n_chunks));
+    hipEvent_t e0, e1;
+    ADADIM_HIP_TRY(ctx, hipEventCreate(&e0));
+    ADADIM_HIP_TRY(ctx, hipEventCreate(&e1));
+    ADADIM_HIP_TRY(ctx, hipEventRecord(e0, ctx->stream));
+    const uint32_t* pk = static_cast<const uint32_t*>(packed);
+    switch (bits) {
+        case 2: hipLaunchKernelGGL(gemv_bare_read<2>, grid, dim3(64 * GV_WAVES), 0, ctx->stream, pk, out, in, n_words, sink); break;
+        case 3: hipLaunchKernelGGL(gemv_bare_read<3>, grid, dim3(64 * GV_WAVES), 0, ctx->stream, pk, out, in, n_words, sink); break;
+        default: hipLaunchKernelGGL(gemv_bare_read<4>, grid, dim3(64 * GV_WAVES), 0, ctx->stream, pk, out, in, n_words, sink); break;
+    }
+    const hipError_t le = hipGetLastError();
+    hipError_t e = hipEventRecord(e1, ctx->stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.0f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (le != hipSuccess) return adadim_fail(ctx, ADADIM_EHIP, "adadim_probe_gemv_read: launch: %s", hipGetErrorString(le));
+    if (e != hipSuccess) return adadim_fail(ctx, ADADIM_EHIP, "adadim_probe_gemv_read: %s", hipGetErrorString(e));
+    *us = double(ms) * 1e3;
+    return ADADIM_OK;
+}
 
 int launch_gemv_ic(adadim_ctx* ctx, const uint32_t* packed, const void* scales, const uint8_t* zeros, const __half* x,
                    int64_t out, int64_t in, int bits, int g, __half* y, bool meta16) {

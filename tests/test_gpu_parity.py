@@ -677,6 +677,13 @@ def test_matrix_core_probes_report_a_rate_below_the_published_peaks(ctx):
     assert 500.0 < mhz16 < 3000.0 and 500.0 < mhz64 < 3000.0
     with pytest.raises(B.AdaDimError):
         ctx.adadim_probe_mfma_f64(0)
+    # the matrix-vector product's read pattern by itself: runs on a stream of any bit pattern, every width
+    for bits in (2, 3, 4):
+        out_f, in_f = 4096, 520
+        packed = torch.randint(-2 ** 31, 2 ** 31 - 1, (in_f, out_f * bits // 32), dtype=torch.int32, device="cuda")
+        assert 0.0 < ctx.adadim_probe_gemv_read(packed, out_f, in_f, bits) < 1e5
+    with pytest.raises(B.AdaDimError):
+        ctx.adadim_probe_gemv_read(packed, 4096 + 8, 520, 4)
 
 
 def test_gram_timeline_probe_stamps_every_piece(ctx):
